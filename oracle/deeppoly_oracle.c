@@ -1,0 +1,322 @@
+/*
+ * CPU oracle for DeepPoly bound propagation -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain float64, neuron-at-a-time loops.  Nothing here is shared with the GPU
+ * library: no headers, helpers, tables or pre/post-processing.  Only tests,
+ * the smoke check and the benchmark's cpu_baseline leg may call it.
+ *
+ * What it computes, following the paper:
+ *   - abstract shape per neuron (l, u, L, U): concrete interval plus polyhedral
+ *     lower/upper expressions (Section 2.1; DeepPoly specification, Appendix C);
+ *   - a polyhedral expression is c0 + sum_i c_i * eta_i (Section 2.1); in a chain
+ *     network all non-zero coefficients of an expression sit in one layer at a
+ *     time (Section 3.1, "Generality"), so an expression is held as a constant
+ *     and one coefficient per neuron of that layer;
+ *   - Affine transformer: L = U = prev.dot(w) + b, l = backsubs_lower(L),
+ *     u = backsubs_upper(U) (Appendix C, DeepPoly, "Affine ->");
+ *   - ReLU transformer: l = relu(prev.l), u = relu(prev.u), L = relu_n(prev),
+ *     U = compute_upper(prev) (Appendix C, DeepPoly, "Relu ->");
+ *   - backsubs_* = traverse(backward, priority2 = -layer, stop_traverse = false,
+ *     replace_*) followed by map(simplify_*): every iteration replaces each term
+ *     c*eta of the deepest layer present by c*L_eta or c*U_eta chosen by the sign
+ *     of c ("coeff >= 0.0"), sums the results and adds the old constant back
+ *     (map semantics, Section 3.2 and Algorithm 2's final merge); the loop ends
+ *     when only input neurons remain, which have no L/U to substitute; then
+ *     simplify_* replaces c*eta by c*l or c*u by sign and sums to a real;
+ *   - a convolution layer is an affine layer whose weight matrix is the
+ *     expanded kernel (Section 3.3: "for a convolutional layer, it represents
+ *     an expanded convolution kernel"), zero padding, neurons flattened
+ *     (channel, row, column);
+ *   - property check: output constraints compared against psi (Section 2).  For
+ *     robustness psi is "logit[label] > every other logit"; each difference
+ *     logit[label] - logit[o] is itself an affine expression over the last
+ *     hidden layer and is lower-bounded with backsubs_lower; verified iff every
+ *     such bound is > 0.
+ *   - max_depth >= 0 gives the DeepPoly_p variant of Section 6.2: at most p
+ *     traverse iterations, then simplify_* against the stored l, u of the layer
+ *     reached.  max_depth < 0: full traversal.
+ *
+ * Build: gcc -O2 -fopenmp -shared -fPIC (see oracle/__init__.py).
+ */
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+enum { DPO_AFFINE = 0, DPO_CONV = 1, DPO_RELU = 2 };
+enum { DPO_LOWER = 0, DPO_UPPER = 1 };
+
+typedef struct {
+    int kind;
+    int n_in, n_out;
+    const float* W;          /* affine: [n_out, n_in]; conv: [Co, Ci, kh, kw] */
+    const float* b;          /* [n_out] or [Co] */
+    int Ci, H, Wd, Co, kh, kw, stride, pad, Ho, Wo;   /* conv only */
+} dpo_layer;
+
+/* Per-network, per-batch state: l,u of every layer, relaxation of ReLU layers.
+ * Layer index 0 is the input; index i (1-based) is the i-th network layer. */
+typedef struct {
+    int nlayers;
+    const dpo_layer* layers;     /* layers[i-1] describes layer index i */
+    int B;
+    double** l;                  /* [nlayers+1] -> [B, n_i] */
+    double** u;
+    double** lam;                /* ReLU layers only: L = lam * eta_prev            */
+    double** mu;                 /*                   U = mu * eta_prev + nu        */
+    double** nu;
+} dpo_state;
+
+static int layer_size(const dpo_state* st, int idx)
+{
+    if (idx == 0) return st->layers[0].n_in;
+    return st->layers[idx - 1].n_out;
+}
+
+/* One traverse iteration (replace_lower / replace_upper, Appendix C): every term
+ * c * eta_i with eta_i in layer `at` becomes c * L_i when (c >= 0) on the lower
+ * side, c * U_i otherwise (mirrored on the upper side); results are summed and
+ * the running constant is kept.  Output coefficients are over layer at-1. */
+static void replace_layer(const dpo_state* st, int bi, int at, int side,
+                          const double* cin, double* c0, double* cout)
+{
+    const dpo_layer* L = &st->layers[at - 1];
+    const int n_out = L->n_out, n_in = L->n_in;
+    for (int p = 0; p < n_in; ++p) cout[p] = 0.0;
+
+    if (L->kind == DPO_AFFINE) {
+        /* L_i = U_i = b_i + sum_p W[i,p] eta_p : the sign choice picks the same expression */
+        for (int i = 0; i < n_out; ++i) {
+            const double c = cin[i];
+            if (c == 0.0) continue;
+            *c0 += c * (double)L->b[i];
+            const float* w = L->W + (size_t)i * n_in;
+            for (int p = 0; p < n_in; ++p) cout[p] += c * (double)w[p];
+        }
+    } else if (L->kind == DPO_CONV) {
+        /* expanded kernel: W[(co,ho,wo),(ci,hi,wi)] = K[co,ci,hi-ho*s+pad,wi-wo*s+pad] */
+        for (int co = 0; co < L->Co; ++co)
+            for (int ho = 0; ho < L->Ho; ++ho)
+                for (int wo = 0; wo < L->Wo; ++wo) {
+                    const double c = cin[((size_t)co * L->Ho + ho) * L->Wo + wo];
+                    if (c == 0.0) continue;
+                    *c0 += c * (double)L->b[co];
+                    for (int ci = 0; ci < L->Ci; ++ci)
+                        for (int ky = 0; ky < L->kh; ++ky) {
+                            const int hi = ho * L->stride - L->pad + ky;
+                            if (hi < 0 || hi >= L->H) continue;
+                            for (int kx = 0; kx < L->kw; ++kx) {
+                                const int wi = wo * L->stride - L->pad + kx;
+                                if (wi < 0 || wi >= L->Wd) continue;
+                                const double k = (double)L->W[(((size_t)co * L->Ci + ci) * L->kh + ky) * L->kw + kx];
+                                cout[((size_t)ci * L->H + hi) * L->Wd + wi] += c * k;
+                            }
+                        }
+                }
+    } else {
+        /* ReLU neuron i over predecessor i: L_i = lam_i * eta_i, U_i = mu_i * eta_i + nu_i */
+        const double* lam = st->lam[at] + (size_t)bi * n_out;
+        const double* mu = st->mu[at] + (size_t)bi * n_out;
+        const double* nu = st->nu[at] + (size_t)bi * n_out;
+        for (int i = 0; i < n_out; ++i) {
+            const double c = cin[i];
+            const int use_L = (side == DPO_LOWER) ? (c >= 0.0) : !(c >= 0.0);
+            if (use_L) {
+                cout[i] += c * lam[i];
+            } else {
+                cout[i] += c * mu[i];
+                *c0 += c * nu[i];
+            }
+        }
+    }
+}
+
+/* simplify_lower / simplify_upper (Appendix C): c >= 0 ? c*l : c*u (mirrored). */
+static double simplify(const dpo_state* st, int bi, int at, int side, double c0, const double* c)
+{
+    const int n = layer_size(st, at);
+    const double* l = st->l[at] + (size_t)bi * n;
+    const double* u = st->u[at] + (size_t)bi * n;
+    double acc = c0;
+    for (int i = 0; i < n; ++i) {
+        const double ci = c[i];
+        if (side == DPO_LOWER) acc += (ci >= 0.0) ? ci * l[i] : ci * u[i];
+        else                   acc += (ci >= 0.0) ? ci * u[i] : ci * l[i];
+    }
+    return acc;
+}
+
+/* backsubs_lower / backsubs_upper.  `e` (constant *c0, coefficients in buf_a over
+ * layer `at`) is traversed backwards; returns the concrete bound.  If sym_c is
+ * not NULL and the traversal reached the input, the final input-level
+ * expression is copied out. */
+static double backsubs(const dpo_state* st, int bi, int at, int side, double c0,
+                       double* buf_a, double* buf_b, int max_depth,
+                       double* sym_c, double* sym_c0)
+{
+    int depth = 0;
+    double* cur = buf_a;
+    double* nxt = buf_b;
+    while (at > 0 && (max_depth < 0 || depth < max_depth)) {
+        replace_layer(st, bi, at, side, cur, &c0, nxt);
+        double* t = cur; cur = nxt; nxt = t;
+        --at;
+        ++depth;
+    }
+    if (sym_c && at == 0) {
+        memcpy(sym_c, cur, sizeof(double) * (size_t)layer_size(st, 0));
+        *sym_c0 = c0;
+    }
+    return simplify(st, bi, at, side, c0, cur);
+}
+
+/* The polyhedral expression prev.dot(w_r) + b_r of neuron r of an affine/conv
+ * layer, written over the previous layer. */
+static double neuron_expr(const dpo_layer* L, int r, double* coeff)
+{
+    for (int p = 0; p < L->n_in; ++p) coeff[p] = 0.0;
+    if (L->kind == DPO_AFFINE) {
+        const float* w = L->W + (size_t)r * L->n_in;
+        for (int p = 0; p < L->n_in; ++p) coeff[p] = (double)w[p];
+        return (double)L->b[r];
+    }
+    const int wo = r % L->Wo, ho = (r / L->Wo) % L->Ho, co = r / (L->Wo * L->Ho);
+    for (int ci = 0; ci < L->Ci; ++ci)
+        for (int ky = 0; ky < L->kh; ++ky) {
+            const int hi = ho * L->stride - L->pad + ky;
+            if (hi < 0 || hi >= L->H) continue;
+            for (int kx = 0; kx < L->kw; ++kx) {
+                const int wi = wo * L->stride - L->pad + kx;
+                if (wi < 0 || wi >= L->Wd) continue;
+                coeff[((size_t)ci * L->H + hi) * L->Wd + wi] =
+                    (double)L->W[(((size_t)co * L->Ci + ci) * L->kh + ky) * L->kw + kx];
+            }
+        }
+    return (double)L->b[co];
+}
+
+/*
+ * Run DeepPoly over the whole network.
+ *   l,u,lam,mu,nu : arrays of nlayers+1 pointers (index 0 = input layer); l[i],u[i]
+ *                   are [B, n_i] and written for every i; lam/mu/nu are written
+ *                   for ReLU layers only (other entries may be NULL).
+ *   label         : [B] or NULL.  With a label, margin [B, nK-1] and verdict [B]
+ *                   are written (last layer must be affine).
+ *   sym_layer     : layer index (>=1, affine/conv) whose input-level expressions
+ *                   are exported (needs full traversal), or -1.
+ *                   sym_cl/sym_cu: [B, n_sym, n0]; sym_kl/sym_ku: [B, n_sym].
+ * Returns 0 on success, non-zero on malformed input.
+ */
+int dpo_run(int nlayers, const dpo_layer* layers, int B,
+            const float* lo, const float* hi, const int* label,
+            double** l, double** u, double** lam, double** mu, double** nu,
+            double* margin, int* verdict,
+            int sym_layer, double* sym_cl, double* sym_kl, double* sym_cu, double* sym_ku,
+            int max_depth)
+{
+    if (nlayers < 1 || B < 0) return 1;
+    if (layers[0].kind == DPO_RELU) return 2;
+    int nmax = layers[0].n_in;
+    for (int i = 0; i < nlayers; ++i) {
+        if (i > 0 && layers[i].n_in != layers[i - 1].n_out) return 3;
+        if (layers[i].kind == DPO_RELU && layers[i].n_in != layers[i].n_out) return 3;
+        if (layers[i].n_out > nmax) nmax = layers[i].n_out;
+    }
+    if (label && layers[nlayers - 1].kind != DPO_AFFINE) return 4;
+
+    dpo_state st = { nlayers, layers, B, l, u, lam, mu, nu };
+    const int n0 = layers[0].n_in;
+
+    /* input layer: the box is the abstract shape of the input neurons */
+    for (size_t i = 0; i < (size_t)B * n0; ++i) {
+        if (!(lo[i] <= hi[i])) return 5;
+        l[0][i] = (double)lo[i];
+        u[0][i] = (double)hi[i];
+    }
+
+    for (int k = 1; k <= nlayers; ++k) {
+        const dpo_layer* L = &layers[k - 1];
+        const int n = L->n_out;
+        if (L->kind == DPO_RELU) {
+            for (int bi = 0; bi < B; ++bi)
+                for (int i = 0; i < n; ++i) {
+                    const size_t o = (size_t)bi * n + i;
+                    const double pl = l[k - 1][o], pu = u[k - 1][o];
+                    l[k][o] = pl >= 0.0 ? pl : 0.0;                 /* relu(prev[l]) */
+                    u[k][o] = pu >= 0.0 ? pu : 0.0;                 /* relu(prev[u]) */
+                    lam[k][o] = (pl + pu >= 0.0) ? 1.0 : 0.0;       /* relu_n        */
+                    if (pl >= 0.0)      { mu[k][o] = 1.0; nu[k][o] = 0.0; }   /* compute_upper */
+                    else if (pu <= 0.0) { mu[k][o] = 0.0; nu[k][o] = 0.0; }
+                    else { mu[k][o] = pu / (pu - pl); nu[k][o] = -(pu * pl) / (pu - pl); }
+                }
+            continue;
+        }
+        const int want_sym = (sym_layer == k);
+        int fail = 0;
+        #pragma omp parallel
+        {
+            double* buf_a = (double*)malloc(sizeof(double) * (size_t)nmax);
+            double* buf_b = (double*)malloc(sizeof(double) * (size_t)nmax);
+            if (!buf_a || !buf_b) {
+                #pragma omp atomic write
+                fail = 1;
+            }
+            #pragma omp for collapse(2) schedule(dynamic, 8)
+            for (int bi = 0; bi < B; ++bi)
+                for (int r = 0; r < n; ++r) {
+                    if (!buf_a || !buf_b) continue;
+                    const size_t o = (size_t)bi * n + r;
+                    double c0 = neuron_expr(L, r, buf_a);
+                    l[k][o] = backsubs(&st, bi, k - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth,
+                                       want_sym ? sym_cl + o * n0 : NULL, want_sym ? sym_kl + o : NULL);
+                    c0 = neuron_expr(L, r, buf_a);
+                    u[k][o] = backsubs(&st, bi, k - 1, DPO_UPPER, c0, buf_a, buf_b, max_depth,
+                                       want_sym ? sym_cu + o * n0 : NULL, want_sym ? sym_ku + o : NULL);
+                }
+            free(buf_a);
+            free(buf_b);
+        }
+        if (fail) return 6;
+    }
+
+    if (label) {
+        const dpo_layer* L = &layers[nlayers - 1];
+        const int nK = L->n_out, nP = L->n_in;
+        for (int bi = 0; bi < B; ++bi)
+            if (label[bi] < 0 || label[bi] >= nK) return 7;
+        int fail = 0;
+        #pragma omp parallel
+        {
+            double* buf_a = (double*)malloc(sizeof(double) * (size_t)nmax);
+            double* buf_b = (double*)malloc(sizeof(double) * (size_t)nmax);
+            if (!buf_a || !buf_b) {
+                #pragma omp atomic write
+                fail = 1;
+            }
+            #pragma omp for collapse(2) schedule(dynamic, 1)
+            for (int bi = 0; bi < B; ++bi)
+                for (int q = 0; q < nK - 1; ++q) {
+                    if (!buf_a || !buf_b) continue;
+                    const int t = label[bi];
+                    const int o = q < t ? q : q + 1;
+                    /* logit[t] - logit[o] as a polyhedral expression over the last hidden layer */
+                    for (int p = 0; p < nP; ++p)
+                        buf_a[p] = (double)L->W[(size_t)t * nP + p] - (double)L->W[(size_t)o * nP + p];
+                    const double c0 = (double)L->b[t] - (double)L->b[o];
+                    margin[(size_t)bi * (nK - 1) + q] =
+                        backsubs(&st, bi, nlayers - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth, NULL, NULL);
+                }
+            free(buf_a);
+            free(buf_b);
+        }
+        if (fail) return 6;
+        for (int bi = 0; bi < B; ++bi) {
+            int ok = 1;
+            for (int q = 0; q < nK - 1; ++q)
+                if (!(margin[(size_t)bi * (nK - 1) + q] > 0.0)) ok = 0;
+            verdict[bi] = ok;
+        }
+    }
+    return 0;
+}
+
+int dpo_layer_struct_size(void) { return (int)sizeof(dpo_layer); }
