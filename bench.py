@@ -1,0 +1,143 @@
+"""Benchmark of the DeepPoly back-substitution hot path on one MI355X.
+
+A step is one pass of the whole hot path (all layers' traversals, concretisations, margin rows and
+verdicts) over one batch of synthetic boxes of the named workload; for cfg2 that is the three
+perturbation sizes, 96 instances.  Inputs are resident in HBM before the timed region.  Prints ONE
+JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+DESCR = {
+    "cfg1": "cfg1: FC 784-100-100-100-10, B=1, eps=0.01",
+    "cfg2": "cfg2: FC 784-6x500-10, B=32, eps in {0.005,0.01,0.02} (96 instances per step)",
+    "cfg3": "cfg3: conv16 4x4s2 - conv32 4x4s2 - FC100 - FC10 on 3x32x32, B=32, eps=2/255",
+    "cfg4": "cfg4: conv32 3x3 - conv32 4x4s2 - conv64 3x3 - conv64 4x4s2 - FC512 - FC512 - FC10 on 3x32x32, B=16, eps=1/255",
+    "cfg5": "cfg5: FC 1024-9x1024-10, B=64, eps=0.005",
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(DESCR))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="inputs per eps given to the CPU oracle (0 = default)")
+    ap.add_argument("--variant", type=int, default=-1, help="contraction tile variant (tuning)")
+    ap.add_argument("--fuse", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2507_20055_amd import binding, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.variant >= 0:
+        binding.dpc_tuning_set("contract_variant", args.variant)
+
+    n_eps = len(wl.CONFIGS[args.workload]["eps"])
+    loads = [wl.make_workload(args.workload, eps_index=i) for i in range(n_eps)]
+    net = binding.Network(loads[0].net, device=0)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        dev = [(torch.from_numpy(w.lo).cuda(), torch.from_numpy(w.hi).cuda(), torch.from_numpy(w.label).cuda()) for w in loads]
+    stream.synchronize()
+    B = loads[0].lo.shape[0]
+    results = [None] * n_eps
+
+    def step(profile):
+        for i, (lo, hi, lab) in enumerate(dev):
+            results[i] = net.certify(lo, hi, lab, stream=stream.cuda_stream, profile=profile, fuse=args.fuse, reuse=results[i])
+
+    for _ in range(args.warmup):
+        step(0)
+    torch.cuda.synchronize()
+    prof_tot = None
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(1)                                   # HIP events around every kernel, on the launch stream
+        for r in results:
+            p = r.profile()
+            prof_tot = p if prof_tot is None else {k: prof_tot[k] + p[k] for k in p}
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # the same steps without per-kernel events, to show what the events cost
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step(0)
+    torch.cuda.synchronize()
+    dt_plain = time.perf_counter() - t1
+
+    inputs_per_step = B * n_eps
+    verified = int(sum(int(r.verdict()[0].sum()) for r in results))
+    min_abs_margin = float(min(float(np.abs(r.verdict()[1]).min()) for r in results))
+
+    P = prof_tot
+    contract_tflops = P["contract_flop"] / (P["contract_ms"] * 1e-3) / 1e12 if P["contract_ms"] > 0 else 0.0
+    relax_gbs = P["relax_bytes"] / (P["relax_ms"] * 1e-3) / 1e9 if P["relax_ms"] > 0 else 0.0
+    conc_gbs = P["concretise_bytes"] / (P["concretise_ms"] * 1e-3) / 1e9 if P["concretise_ms"] > 0 else 0.0
+
+    out = {
+        "metric": "certified inputs/sec",
+        "value": inputs_per_step * args.steps / dt,
+        "unit": "inputs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": DESCR[args.workload], "inputs_per_step": inputs_per_step,
+                   "verified": verified, "min_abs_margin": min_abs_margin, "fuse": args.fuse},
+        "roofline": {
+            "kernel": "contract (fp32 MFMA C*W of back-substitution)",
+            "bound": "mfma", "achieved": contract_tflops, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": contract_tflops / PEAK_FP32_MFMA_TFLOPS,
+            "launches": P["contract_launches"], "avg_launch_ms": P["contract_ms"] / max(P["contract_launches"], 1),
+            "flop_per_step": P["contract_flop"] / args.steps,
+            "traffic": None,
+        },
+        "hbm_passes": {
+            "relax_step": {"achieved": relax_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": relax_gbs / PEAK_HBM_GBS,
+                           "launches": P["relax_launches"], "ms_per_step": P["relax_ms"] / args.steps},
+            "concretise": {"achieved": conc_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": conc_gbs / PEAK_HBM_GBS,
+                           "launches": P["concretise_launches"], "ms_per_step": P["concretise_ms"] / args.steps},
+        },
+        "time_split_ms_per_step": {k: P[k] / args.steps for k in ("contract_ms", "relax_ms", "concretise_ms", "other_ms", "total_ms")},
+        "value_without_kernel_events": inputs_per_step * args.steps / dt_plain,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+        default_sample = {"cfg1": 1, "cfg2": 8, "cfg3": 8, "cfg4": 1, "cfg5": 2}[args.workload]
+        ns = min(B, args.cpu_sample or default_sample)
+        tc = time.perf_counter()
+        for w in loads:
+            oracle.run(w.net, w.lo[:ns], w.hi[:ns], label=w.label[:ns], threads=cores)
+        tcpu = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": ns * n_eps / tcpu, "unit": "inputs/s", "cores": cores, "kind": "oracle",
+                               "sample": f"first {ns} of {B} inputs of each of the {n_eps} eps settings, float64 oracle, {tcpu:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,199 @@
+/*
+ * dpcert -- DeepPoly-style symbolic bound propagation on one AMD MI355X (gfx950).
+ *
+ * C ABI.  Every function returns a dpc_status (0 = OK) and never throws; the
+ * text of the last error on the calling thread is available from
+ * dpc_last_error().  Unless a parameter says "device", pointers may be host or
+ * device memory: the library copies through hipMemcpy's default (address
+ * inferring) kind and never keeps a caller pointer after the call returns.
+ *
+ * Problem statement (paper, Section 2): a property is a pair (phi, psi); the
+ * certifier attaches an abstract shape (l, u, L, U) to every neuron -- concrete
+ * bounds l <= eta <= u and polyhedral bounds L <= eta <= U, each polyhedral
+ * expression being c0 + sum_i c_i * eta_i (Section 2.1) -- starting from phi on
+ * the input layer, propagates it with abstract transformers, and compares the
+ * output constraints with psi: the result is "verified" or "unknown".
+ * Here phi is an axis-aligned box [lo, hi] per input (an L-infinity ball) and
+ * psi is "logit[label] is larger than every other logit".
+ *
+ * Method (paper, Appendix C, DeepPoly specification):
+ *   Affine / convolution neuron:  L = U = prev.dot(w) + b;  l = backsubs_lower(L),
+ *     u = backsubs_upper(U): traverse the network backwards, replacing every
+ *     term c*eta by c*L_eta or c*U_eta according to the sign of c, layer after
+ *     layer until only input neurons remain, then replace c*eta by c*l_eta or
+ *     c*u_eta by sign and sum (Sections 2.1, 2.2; Appendix C).
+ *   ReLU neuron over predecessor p with bounds (l, u):
+ *     l' = max(l,0), u' = max(u,0);  L = (l + u >= 0) ? p : 0;
+ *     U = l >= 0 ? p : (u <= 0 ? 0 : u/(u-l) * p - u*l/(u-l)).
+ *   The library reports L of a ReLU neuron as lambda*p and U as mu*p + nu.
+ *
+ * Layer indices: 0 is the input layer, i >= 1 is the i-th dpc_network_add_* call.
+ * Neurons of a convolution layer are numbered (channel, row, column) row-major,
+ * on both sides of this interface (weights of a following affine layer use the
+ * same order); zero padding.
+ */
+#ifndef DPCERT_H
+#define DPCERT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t dpc_status;
+enum {
+    DPC_OK = 0,
+    DPC_EINVAL = 1,        /* null pointer, bad dimension, size chain mismatch, lo > hi, label out of range, non-finite value */
+    DPC_EUNSUPPORTED = 2,  /* ReLU as first layer, two ReLUs in a row, ReLU after the last affine layer */
+    DPC_ENOMEM = 3,        /* host or device allocation failed */
+    DPC_EHIP = 4,          /* a HIP call failed; dpc_last_error() holds its message */
+    DPC_ESTATE = 5         /* wrong call order (certify before finalize, add after finalize, ...) */
+};
+
+typedef struct dpc_network dpc_network;   /* opaque; owned by the library until dpc_network_destroy */
+typedef struct dpc_result dpc_result;     /* opaque; owned by the library until dpc_result_destroy  */
+
+/* ---- network description (host side; Section 2: the DNN is the graph the certifier walks) ---- */
+
+dpc_status dpc_network_create(dpc_network** out);
+
+/* Fully-connected layer y = W x + b.  W: [out_dim, in_dim] row-major, b: [out_dim];
+ * both are copied.  in_dim must equal the previous layer's size. */
+dpc_status dpc_network_add_affine(dpc_network* net, int32_t out_dim, int32_t in_dim,
+                                  const float* W, const float* b);
+
+/* 2-D convolution (cross-correlation, zero padding) on a (Ci, H, W) input.
+ * K: [Co, Ci, kh, kw] row-major, b: [Co]; copied.  Ci*H*W must equal the
+ * previous layer's size.  Output (Co, Ho, Wo), Ho = (H + 2*pad - kh)/stride + 1.
+ * The layer is an affine layer whose weight matrix is the expanded kernel
+ * (Section 3.3); the library never materialises that matrix. */
+dpc_status dpc_network_add_conv2d(dpc_network* net, int32_t Ci, int32_t H, int32_t W,
+                                  int32_t Co, int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                  const float* K, const float* b);
+
+/* ReLU over the previous layer (element-wise). */
+dpc_status dpc_network_add_relu(dpc_network* net);
+
+/* Validate the chain, upload weights to HIP device `device` in the layouts the
+ * kernels use.  After this call no layer can be added.  Synchronous. */
+dpc_status dpc_network_finalize(dpc_network* net, int32_t device);
+
+/* Frees host and device memory of the network (results must be destroyed first). */
+dpc_status dpc_network_destroy(dpc_network* net);
+
+/* ---- certification ---- */
+
+typedef struct {
+    int32_t struct_size;        /* = sizeof(dpc_options); rejects mismatching callers */
+    int32_t max_backsub_depth;  /* -1: traverse to the input (DeepPoly).  p >= 0: at most p traverse
+                                   iterations (each replaces one layer's neurons, ReLU layers
+                                   included), then concretise against the stored l,u of the layer
+                                   reached -- the DeepPoly_p family of Section 6.2; 0 = IBP */
+    int32_t keep_symbolic;      /* 0: none; 1: keep the input-level polyhedral bounds of the last layer
+                                   (needs max_backsub_depth = -1) */
+    int32_t fuse;               /* 1 (default): the ReLU step / concretisation that follows a
+                                   contraction runs in that contraction's epilogue where supported;
+                                   0: every step is its own kernel */
+    int32_t profile;            /* 1: time every kernel class with HIP events (see dpc_result_profile) */
+    int32_t reserved;
+    void*   stream;             /* hipStream_t all work is enqueued on (NULL = the null stream) */
+} dpc_options;
+
+/* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, null stream). */
+dpc_status dpc_options_default(dpc_options* opt);
+
+/* Runs the certifier on `batch` boxes.
+ *   lo, hi : [batch, n0] float32, lo <= hi element-wise (host or device).
+ *   label  : [batch] int32 target class in [0, nK), or NULL for bounds only.
+ *   *result: NULL -> a new result is allocated; a result returned by an earlier
+ *            call on the same network with the same batch and keep_symbolic ->
+ *            it is reused and no device memory is allocated.
+ * Work is enqueued on opt->stream; the call returns after the stream has been
+ * synchronised, so results are ready.  Calls on one network must not overlap
+ * (the network owns the coefficient workspace). */
+dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const float* hi,
+                       const int32_t* label, const dpc_options* opt, dpc_result** result);
+
+/* Concrete bounds l, u of every neuron of `layer` (0 = the box itself):
+ * [batch, n_layer] float32 each, caller-allocated (host or device); either may be NULL. */
+dpc_status dpc_result_concrete(const dpc_result* res, int32_t layer, float* l, float* u);
+
+/* Polyhedral bounds of the neurons of ReLU layer `relu_layer` over their
+ * predecessors: L = lambda*p, U = mu*p + nu.  [batch, n] float32 each; any may be NULL. */
+dpc_status dpc_result_relaxation(const dpc_result* res, int32_t relu_layer,
+                                 float* lambda, float* mu, float* nu);
+
+/* Input-level polyhedral bound of the last layer's neurons (keep_symbolic = 1):
+ * side 0 = lower, 1 = upper; coeff [batch, nK, n0], cst [batch, nK]. */
+dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t side,
+                               float* coeff, float* cst);
+
+/* verdict [batch]: 1 = verified, 0 = unknown.  margin_lb [batch, nK-1] (may be
+ * NULL): lower bound of logit[label] - logit[o] for o != label in ascending o.
+ * Verified iff every margin lower bound is > 0.  Needs a label at certify time. */
+dpc_status dpc_result_verdict(const dpc_result* res, int32_t* verdict, float* margin_lb);
+
+/* Per-kernel-class timing of the certify call that produced `res` (opt->profile = 1).
+ * Times are sums of HIP-event intervals on the call's stream, in milliseconds;
+ * flop / byte counts are the algorithmic ones of the launches made. */
+typedef struct {
+    int32_t struct_size;
+    int32_t contract_launches, relax_launches, concretise_launches, other_launches;
+    double  contract_ms, relax_ms, concretise_ms, other_ms, total_ms;
+    double  contract_flop;       /* 2*M*K*N per contraction (conv: compressed-core count) */
+    double  relax_bytes;         /* 8 B per coefficient (first step of a pass: 4 B) */
+    double  concretise_bytes;    /* 4 B per coefficient */
+} dpc_profile;
+dpc_status dpc_result_profile(const dpc_result* res, dpc_profile* out);
+
+dpc_status dpc_result_destroy(dpc_result* res);
+
+/* ---- the three hot kernels on caller-owned DEVICE buffers (unit tests, roofline runs) ---- */
+
+/* Affine contraction of a traverse iteration (Matmul rewrite, Section 4.3):
+ *   Cout[m, 0:N] = sum_k A[m, k] * W[k, 0:N],  m < M, k < K.
+ * A: [M, lda] device, W: [K, ldw] device, Cout: [M, ldc] device, all float32 row-major;
+ * lda >= K, ldw >= N, ldc >= N.  Columns N..ldc-1 of Cout are written as zero.
+ * Requirements (EINVAL otherwise): lda, ldw, ldc multiples of 4; buffers 16-byte aligned. */
+dpc_status dpc_op_contract(const float* A, int64_t M, int32_t K, int32_t lda,
+                           const float* W, int32_t N, int32_t ldw,
+                           float* Cout, int32_t ldc, void* stream);
+
+/* Sign-split ReLU step of a traverse iteration (replace_lower / replace_upper with the
+ * Ternary and Clamp rewrites of Section 4.3) followed by the bias fold of the affine
+ * layer below.  Rows are ordered [side][input][r]: m = (side*batch + b)*R + r, side 0 = lower.
+ *   lower rows: C'[m,i] = max(C,0)*lambda[b,i] + min(C,0)*mu[b,i];  c' = c + sum_i min(C,0)*nu[b,i]
+ *   upper rows: C'[m,i] = max(C,0)*mu[b,i] + min(C,0)*lambda[b,i];  c' = c + sum_i max(C,0)*nu[b,i]
+ *   both      : c' += sum_i C'[m,i] * bias[i]
+ * C: [nsides*batch*R, ldc] device float32, updated in place; cst: [nsides*batch*R] device float64,
+ * updated in place; lambda, mu, nu: [batch, n] device; bias: [n] device.  If shared_src is not
+ * NULL it is a [R, ld_src] matrix read instead of C for every (side, b) (the weight rows of the
+ * layer being bounded, which carry no batch dimension before the first ReLU step). */
+dpc_status dpc_op_relax_step(float* C, int32_t ldc, double* cst, int32_t nsides, int32_t batch, int32_t R,
+                             int32_t n, const float* lambda, const float* mu, const float* nu,
+                             const float* bias, const float* shared_src, int32_t ld_src, void* stream);
+
+/* Concretisation (simplify_lower / simplify_upper, Appendix C) against the box:
+ *   lower rows: out_l[b,r] = c + sum_i (C >= 0 ? C*lo[b,i] : C*hi[b,i])
+ *   upper rows: out_u[b,r] = c + sum_i (C >= 0 ? C*hi[b,i] : C*lo[b,i])
+ * Row order as in dpc_op_relax_step.  out_l, out_u: [batch, R] device float32
+ * (out_u unused when nsides = 1). */
+dpc_status dpc_op_concretise(const float* C, int32_t ldc, const double* cst, int32_t nsides, int32_t batch,
+                             int32_t R, int32_t n, const float* lo, const float* hi,
+                             float* out_l, float* out_u, void* stream);
+
+/* Tuning knob for experiments: key "contract_variant" selects the tile shape of the contraction
+ * kernel (0 = default).  Results do not depend on it beyond rounding order. */
+dpc_status dpc_tuning_set(const char* key, int32_t value);
+
+/* Text of the last error raised on the calling thread ("" if none). */
+const char* dpc_last_error(void);
+
+/* Library version string. */
+const char* dpc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPCERT_H */

@@ -1,0 +1,856 @@
+// C ABI of the dpcert library: network description, certify orchestration, result accessors.
+// The host loop mirrors the DeepPoly flow of the paper (Appendix C): layers in forward order; for
+// every affine / convolution layer one backward traversal of its neurons' polyhedral expressions
+// (ReLU step, contraction, ... down to the input) followed by concretisation.
+#include <stdarg.h>
+#include <string.h>
+
+#include <algorithm>
+#include <cmath>
+#include <memory>
+#include <vector>
+
+#include "common.h"
+#include "conv.h"
+
+namespace dpc {
+
+static thread_local std::string g_error;
+
+void set_error(const char* fmt, ...)
+{
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_error = buf;
+}
+
+void set_contract_variant(int v);
+
+namespace {
+
+enum Kind { AFFINE = 0, CONV = 1, RELU = 2 };
+
+struct DeviceGuard {
+    int prev = -1;
+    explicit DeviceGuard(int dev)
+    {
+        DPC_HIP(hipGetDevice(&prev));
+        if (prev != dev) DPC_HIP(hipSetDevice(dev));
+        else prev = -1;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+template <class T>
+struct DevBuf {
+    T* p = nullptr;
+    size_t count = 0;
+    void reserve(size_t n)
+    {
+        if (n <= count) return;
+        release();
+        DPC_HIP(hipMalloc(reinterpret_cast<void**>(&p), n * sizeof(T)));
+        count = n;
+    }
+    void release()
+    {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        count = 0;
+    }
+    ~DevBuf() { release(); }
+    DevBuf() = default;
+    DevBuf(const DevBuf&) = delete;
+    DevBuf& operator=(const DevBuf&) = delete;
+};
+
+struct Layer {
+    int kind = AFFINE;
+    int n_in = 0, n_out = 0;
+    ConvGeom g{};                          // CONV only
+    bool spatial_out = false;              // neurons of this layer carry a (C,H,W) shape (stored H,W,C)
+    int C = 0, H = 0, W = 0;               // that shape
+    std::vector<float> hW, hb;             // host copies in the caller's layout
+    // device, in the internal neuron order
+    DevBuf<float> dW;                      // AFFINE: [n_out, ldw]; CONV: see conv.h
+    int ldw = 0;
+    DevBuf<float> dBias;                   // [n_out] per neuron
+    ConvWeights cw;                        // CONV only
+};
+
+}  // namespace
+}  // namespace dpc
+
+using namespace dpc;
+
+struct dpc_network {
+    std::vector<std::unique_ptr<Layer>> layers;
+    int n0 = 0;
+    bool in_spatial = false;
+    int inC = 0, inH = 0, inW = 0;
+    bool finalized = false;
+    int device = 0;
+    int live_results = 0;
+    // traversal workspace, grown on demand, reused across certify calls
+    DevBuf<float> buf[2];
+    DevBuf<double> cst;
+    DevBuf<float> stage;                   // staging for layout permutations / margins
+
+    int size_of(int idx) const { return idx == 0 ? n0 : layers[idx - 1]->n_out; }
+    int ld_of(int idx) const { return (int)round_up(size_of(idx), kLdAlign); }
+    bool spatial(int idx, int* C, int* H, int* W) const
+    {
+        if (idx == 0) { *C = inC; *H = inH; *W = inW; return in_spatial; }
+        const Layer& L = *layers[idx - 1];
+        *C = L.C; *H = L.H; *W = L.W;
+        return L.spatial_out;
+    }
+};
+
+struct dpc_result {
+    dpc_network* net = nullptr;
+    int batch = 0;
+    int keep_symbolic = 0;
+    bool has_label = false, has_symbolic = false;
+    std::vector<float*> l, u, lam, mu, nu;   // per layer index, device, internal order (sub-allocations)
+    DevBuf<float> pool;
+    DevBuf<float> margin;                    // [B, nK-1]
+    DevBuf<int32_t> verdict, label;
+    DevBuf<float> sym_coeff;                 // [2][B*nK][ld0]
+    DevBuf<double> sym_cst;                  // [2][B*nK]
+    dpc_profile prof{};
+};
+
+namespace {
+
+struct Prof {
+    bool on = false;
+    hipStream_t s = nullptr;
+    struct Rec { int cls; hipEvent_t a, b; };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    size_t used = 0;
+    hipEvent_t get()
+    {
+        if (used == pool.size()) {
+            hipEvent_t e;
+            DPC_HIP(hipEventCreate(&e));
+            pool.push_back(e);
+        }
+        return pool[used++];
+    }
+    void begin(int cls)
+    {
+        if (!on) return;
+        Rec r{cls, get(), get()};
+        DPC_HIP(hipEventRecord(r.a, s));
+        recs.push_back(r);
+    }
+    void end()
+    {
+        if (!on) return;
+        DPC_HIP(hipEventRecord(recs.back().b, s));
+    }
+    ~Prof() { for (auto e : pool) (void)hipEventDestroy(e); }
+};
+enum { P_CONTRACT = 0, P_RELAX = 1, P_CONC = 2, P_OTHER = 3 };
+
+// Shape of the coefficient rows during a traversal: dense over a whole layer, or patch form
+// (rows of a convolution layer: a small window of the current layer, see conv.h).
+struct Form {
+    bool patch = false;
+    PatchGeom pg{};
+    int ld = 0;
+};
+
+Form start_form(const dpc_network* net, int at, const Layer* own)
+{
+    Form f;
+    if (own && own->kind == CONV) {
+        const ConvGeom& g = own->g;
+        f.patch = true;
+        f.pg = PatchGeom{g.Wo, g.Co, g.kh, g.kw, g.Ci, g.stride, g.pad, g.H, g.W};
+        f.ld = own->cw.ld_core;
+    } else {
+        f.ld = net->ld_of(at);
+    }
+    return f;
+}
+
+// Form after a traverse iteration through convolution layer g (patch form only).
+Form through_conv(const Form& f, const ConvGeom& g)
+{
+    Form o = f;
+    o.pg.ph = (f.pg.ph - 1) * g.stride + g.kh;
+    o.pg.pw = (f.pg.pw - 1) * g.stride + g.kw;
+    o.pg.C = g.Ci;
+    o.pg.S = f.pg.S * g.stride;
+    o.pg.P = f.pg.P * g.stride + g.pad;
+    o.pg.gh = g.H;
+    o.pg.gw = g.W;
+    o.ld = (int)round_up(o.pg.elems(), 4);
+    return o;
+}
+
+// Largest rows x leading-dimension product any traversal of this network needs, in floats.
+size_t workspace_floats(const dpc_network* net, int B, bool with_margin)
+{
+    size_t need = 1;
+    const int nl = (int)net->layers.size();
+    for (int i = 1; i <= nl; ++i) {
+        const Layer& own = *net->layers[i - 1];
+        if (own.kind == RELU) continue;
+        const size_t rows = 2 * (size_t)B * own.n_out;
+        Form f = start_form(net, i - 1, &own);
+        need = std::max(need, rows * f.ld);
+        for (int at = i - 1; at > 0; --at) {
+            const Layer& L = *net->layers[at - 1];
+            if (L.kind == CONV && f.patch) f = through_conv(f, L.g);
+            else if (L.kind != RELU) f.ld = net->ld_of(at - 1);
+            need = std::max(need, rows * f.ld);
+        }
+    }
+    if (with_margin) {
+        const size_t rows = (size_t)B * (net->layers[nl - 1]->n_out - 1);
+        for (int j = 0; j < nl; ++j) need = std::max(need, rows * net->ld_of(j));
+    }
+    return need;
+}
+
+// One backward traversal (backsubs_lower and backsubs_upper of R expressions per input) starting
+// from expressions over layer index `at`: either the shared weight rows of layer `own`, or per-input
+// rows already in net->buf[0] (own == NULL).
+struct Pass {
+    dpc_network* net;
+    dpc_result* res;
+    const dpc_options* opt;
+    hipStream_t s;
+    Prof* prof;
+    int B;
+};
+
+void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym)
+{
+    dpc_network* net = P.net;
+    dpc_result* res = P.res;
+    const int B = P.B;
+    const int maxd = P.opt->max_backsub_depth;
+    float* cur = net->buf[0].p;
+    float* nxt = net->buf[1].p;
+    double* cst = net->cst.p;
+    Form f = start_form(net, at, own);
+    // rows not yet per-input: the layer's own weight rows (dense) or kernel cores (patch form)
+    const float* shared = own ? (f.patch ? own->cw.core : own->dW.p) : nullptr;
+    const int ld_shared = own ? (f.patch ? own->cw.ld_core : own->ldw) : 0;
+    const float* cst_init = own ? (f.patch ? own->cw.bias_c : own->dBias.p) : nullptr;
+    bool bias_folded = false;
+    int depth = 0;
+    const int64_t M = (int64_t)nsides * B * R;
+
+    auto relax = [&](const float* la, const float* m, const float* v, const Layer* bias_of) {
+        const int n_at = net->size_of(at);
+        P.prof->begin(P_RELAX);
+        if (f.patch)
+            launch_relax_step_patch(cur, f.ld, cst, nsides, B, R, f.pg, la, m, v, bias_of ? bias_of->cw.bias_c : nullptr,
+                                    shared, ld_shared, cst_init, P.s);
+        else
+            launch_relax_step(cur, f.ld, cst, nsides, B, R, n_at, la, m, v, bias_of ? bias_of->dBias.p : nullptr,
+                              shared, ld_shared, shared ? cst_init : nullptr, P.s);
+        P.prof->end();
+        res->prof.relax_launches++;
+        res->prof.relax_bytes += (double)M * (f.patch ? f.pg.elems() : n_at) * (shared ? 4.0 : 8.0);
+        shared = nullptr;
+    };
+
+    while (at > 0 && (maxd < 0 || depth < maxd)) {
+        const Layer& L = *net->layers[at - 1];
+        if (L.kind == RELU) {
+            const Layer& below = *net->layers[at - 2];
+            const bool fold = (maxd < 0 || depth + 2 <= maxd);
+            relax(res->lam[at], res->mu[at], res->nu[at], fold ? &below : nullptr);
+            bias_folded = fold;
+        } else {
+            if (!bias_folded) relax(nullptr, nullptr, nullptr, &L);   // affine layer entered without a ReLU step above it
+            const int n_at = net->size_of(at), n_prev = net->size_of(at - 1);
+            P.prof->begin(P_CONTRACT);
+            if (L.kind == AFFINE) {
+                DPC_REQUIRE(!f.patch, DPC_EUNSUPPORTED, "patch-form rows cannot cross a fully-connected layer");
+                const int ld_prev = net->ld_of(at - 1);
+                launch_contract(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, P.s);
+                res->prof.contract_flop += 2.0 * (double)M * n_at * n_prev;
+                f.ld = ld_prev;
+            } else if (f.patch) {
+                const Form o = through_conv(f, L.g);
+                res->prof.contract_flop += launch_conv_transpose_rows(cur, M, f.ld, f.pg.ph, f.pg.pw, L.g, L.cw, nxt, o.ld,
+                                                                      o.pg.ph, o.pg.pw, 0, P.s);
+                f = o;
+            } else {
+                const int ld_prev = net->ld_of(at - 1);
+                res->prof.contract_flop += launch_conv_transpose_rows(cur, M, f.ld, L.g.Ho, L.g.Wo, L.g, L.cw, nxt, ld_prev,
+                                                                      L.g.H, L.g.W, L.g.pad, P.s);
+                f.ld = ld_prev;
+            }
+            P.prof->end();
+            res->prof.contract_launches++;
+            std::swap(cur, nxt);
+            bias_folded = false;
+        }
+        --at;
+        ++depth;
+    }
+
+    const int n_at = net->size_of(at);
+    if (keep_sym) {
+        DPC_REQUIRE(at == 0 && !f.patch, DPC_EUNSUPPORTED, "symbolic bounds are kept for dense rows at the input only");
+        if (!shared) {
+            DPC_HIP(hipMemcpyAsync(res->sym_coeff.p, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
+            DPC_HIP(hipMemcpyAsync(res->sym_cst.p, cst, (size_t)M * sizeof(double), hipMemcpyDeviceToDevice, P.s));
+        } else {
+            // single-layer network: the expression is the weight row itself for every input and side
+            launch_relax_step(res->sym_coeff.p, f.ld, res->sym_cst.p, nsides, B, R, n_at, nullptr, nullptr, nullptr,
+                              nullptr, shared, ld_shared, cst_init, P.s);
+        }
+        res->has_symbolic = true;
+    }
+    P.prof->begin(P_CONC);
+    if (f.patch)
+        launch_concretise_patch(cur, f.ld, cst, nsides, B, R, f.pg, res->l[at], res->u[at], out_l, out_u,
+                                shared, ld_shared, cst_init, P.s);
+    else
+        launch_concretise(cur, f.ld, cst, nsides, B, R, n_at, res->l[at], res->u[at], out_l, out_u,
+                          shared, ld_shared, shared ? cst_init : nullptr, P.s);
+    P.prof->end();
+    res->prof.concretise_launches++;
+    res->prof.concretise_bytes += (double)M * (f.patch ? f.pg.elems() : n_at) * 4.0;
+}
+
+void validate_chain(dpc_network* net)
+{
+    DPC_REQUIRE(!net->layers.empty(), DPC_EINVAL, "network has no layers");
+    DPC_REQUIRE(net->layers[0]->kind != RELU, DPC_EUNSUPPORTED, "ReLU cannot be the first layer");
+    DPC_REQUIRE(net->layers.back()->kind != RELU, DPC_EUNSUPPORTED, "ReLU after the last affine layer is not supported");
+    for (size_t i = 1; i < net->layers.size(); ++i) {
+        DPC_REQUIRE(!(net->layers[i]->kind == RELU && net->layers[i - 1]->kind == RELU), DPC_EUNSUPPORTED,
+                    "two ReLU layers in a row");
+        DPC_REQUIRE(net->layers[i]->n_in == net->layers[i - 1]->n_out, DPC_EINVAL,
+                    "layer %zu expects %d inputs but the previous layer has %d neurons", i + 1,
+                    net->layers[i]->n_in, net->layers[i - 1]->n_out);
+    }
+}
+
+bool all_finite(const float* p, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        if (!std::isfinite(p[i])) return false;
+    return true;
+}
+
+template <class F>
+dpc_status guarded(F&& f)
+{
+    try {
+        f();
+        return DPC_OK;
+    } catch (const Fail& e) {
+        return e.code;
+    } catch (const std::bad_alloc&) {
+        set_error("host allocation failed");
+        return DPC_ENOMEM;
+    } catch (...) {
+        set_error("unexpected internal error");
+        return DPC_EHIP;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dpc_last_error(void) { return g_error.c_str(); }
+const char* dpc_version(void) { return "dpcert 0.1 (gfx950)"; }
+
+dpc_status dpc_network_create(dpc_network** out)
+{
+    return guarded([&] {
+        DPC_REQUIRE(out, DPC_EINVAL, "dpc_network_create: out is NULL");
+        *out = new dpc_network();
+    });
+}
+
+dpc_status dpc_network_add_affine(dpc_network* net, int32_t out_dim, int32_t in_dim, const float* W, const float* b)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net && W && b, DPC_EINVAL, "dpc_network_add_affine: NULL argument");
+        DPC_REQUIRE(!net->finalized, DPC_ESTATE, "network already finalized");
+        DPC_REQUIRE(out_dim >= 1 && in_dim >= 1 && out_dim <= (1 << 24) && in_dim <= (1 << 24), DPC_EINVAL,
+                    "dpc_network_add_affine: bad dimensions %d x %d", out_dim, in_dim);
+        const int prev = net->layers.empty() ? 0 : net->layers.back()->n_out;
+        DPC_REQUIRE(net->layers.empty() || prev == in_dim, DPC_EINVAL,
+                    "dpc_network_add_affine: in_dim %d does not match previous layer size %d", in_dim, prev);
+        DPC_REQUIRE(all_finite(W, (size_t)out_dim * in_dim) && all_finite(b, out_dim), DPC_EINVAL,
+                    "dpc_network_add_affine: non-finite weight or bias");
+        auto L = std::make_unique<Layer>();
+        L->kind = AFFINE;
+        L->n_in = in_dim;
+        L->n_out = out_dim;
+        L->hW.assign(W, W + (size_t)out_dim * in_dim);
+        L->hb.assign(b, b + out_dim);
+        if (net->layers.empty()) net->n0 = in_dim;
+        net->layers.push_back(std::move(L));
+    });
+}
+
+dpc_status dpc_network_add_conv2d(dpc_network* net, int32_t Ci, int32_t H, int32_t W, int32_t Co, int32_t kh,
+                                  int32_t kw, int32_t stride, int32_t pad, const float* K, const float* b)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net && K && b, DPC_EINVAL, "dpc_network_add_conv2d: NULL argument");
+        DPC_REQUIRE(!net->finalized, DPC_ESTATE, "network already finalized");
+        DPC_REQUIRE(Ci >= 1 && H >= 1 && W >= 1 && Co >= 1 && kh >= 1 && kw >= 1 && stride >= 1 && pad >= 0 &&
+                        pad < kh && pad < kw && H + 2 * pad >= kh && W + 2 * pad >= kw,
+                    DPC_EINVAL, "dpc_network_add_conv2d: bad geometry");
+        DPC_REQUIRE((int64_t)Ci * H * W <= (1 << 24), DPC_EINVAL, "dpc_network_add_conv2d: input too large");
+        const int n_in = Ci * H * W;
+        const int prev = net->layers.empty() ? 0 : net->layers.back()->n_out;
+        DPC_REQUIRE(net->layers.empty() || prev == n_in, DPC_EINVAL,
+                    "dpc_network_add_conv2d: Ci*H*W = %d does not match previous layer size %d", n_in, prev);
+        if (!net->layers.empty()) {
+            const Layer& pl = *net->layers.back();
+            DPC_REQUIRE(!pl.spatial_out || (pl.C == Ci && pl.H == H && pl.W == W), DPC_EINVAL,
+                        "dpc_network_add_conv2d: input shape (%d,%d,%d) differs from the previous layer's (%d,%d,%d)",
+                        Ci, H, W, pl.C, pl.H, pl.W);
+            DPC_REQUIRE(pl.spatial_out, DPC_EUNSUPPORTED, "convolution after a fully-connected layer is not supported");
+        }
+        const size_t nk = (size_t)Co * Ci * kh * kw;
+        DPC_REQUIRE(all_finite(K, nk) && all_finite(b, Co), DPC_EINVAL, "dpc_network_add_conv2d: non-finite weight or bias");
+        auto L = std::make_unique<Layer>();
+        L->kind = CONV;
+        L->g = ConvGeom{Ci, H, W, Co, kh, kw, stride, pad, (H + 2 * pad - kh) / stride + 1, (W + 2 * pad - kw) / stride + 1};
+        DPC_REQUIRE((int64_t)Co * L->g.Ho * L->g.Wo <= (1 << 24), DPC_EINVAL, "dpc_network_add_conv2d: output too large");
+        L->n_in = n_in;
+        L->n_out = Co * L->g.Ho * L->g.Wo;
+        L->spatial_out = true;
+        L->C = Co; L->H = L->g.Ho; L->W = L->g.Wo;
+        L->hW.assign(K, K + nk);
+        L->hb.assign(b, b + Co);
+        if (net->layers.empty()) {
+            net->n0 = n_in;
+            net->in_spatial = true;
+            net->inC = Ci; net->inH = H; net->inW = W;
+        }
+        net->layers.push_back(std::move(L));
+    });
+}
+
+dpc_status dpc_network_add_relu(dpc_network* net)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net, DPC_EINVAL, "dpc_network_add_relu: NULL network");
+        DPC_REQUIRE(!net->finalized, DPC_ESTATE, "network already finalized");
+        DPC_REQUIRE(!net->layers.empty(), DPC_EUNSUPPORTED, "ReLU cannot be the first layer");
+        const Layer& pl = *net->layers.back();
+        DPC_REQUIRE(pl.kind != RELU, DPC_EUNSUPPORTED, "two ReLU layers in a row");
+        auto L = std::make_unique<Layer>();
+        L->kind = RELU;
+        L->n_in = L->n_out = pl.n_out;
+        L->spatial_out = pl.spatial_out;
+        L->C = pl.C; L->H = pl.H; L->W = pl.W;
+        net->layers.push_back(std::move(L));
+    });
+}
+
+dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net, DPC_EINVAL, "dpc_network_finalize: NULL network");
+        DPC_REQUIRE(!net->finalized, DPC_ESTATE, "network already finalized");
+        validate_chain(net);
+        int ndev = 0;
+        DPC_HIP(hipGetDeviceCount(&ndev));
+        DPC_REQUIRE(device >= 0 && device < ndev, DPC_EINVAL, "device %d out of range (%d devices)", device, ndev);
+        DeviceGuard guard(device);
+        net->device = device;
+        for (size_t i = 0; i < net->layers.size(); ++i) {
+            Layer& L = *net->layers[i];
+            if (L.kind == RELU) continue;
+            int pc, ph, pw;
+            const bool prev_spatial = net->spatial((int)i, &pc, &ph, &pw);
+            if (L.kind == AFFINE) {
+                L.ldw = (int)round_up(L.n_in, kLdAlign);
+                std::vector<float> w((size_t)L.n_out * L.ldw, 0.0f);
+                for (int r = 0; r < L.n_out; ++r)
+                    for (int c = 0; c < L.n_in; ++c) {
+                        int dst = c;                    // column c is a (C,H,W) index when the input is spatial
+                        if (prev_spatial) {
+                            const int x = c % pw, y = (c / pw) % ph, ch = c / (pw * ph);
+                            dst = (y * pw + x) * pc + ch;
+                        }
+                        w[(size_t)r * L.ldw + dst] = L.hW[(size_t)r * L.n_in + c];
+                    }
+                L.dW.reserve(w.size());
+                DPC_HIP(hipMemcpy(L.dW.p, w.data(), w.size() * sizeof(float), hipMemcpyHostToDevice));
+                L.dBias.reserve(L.n_out);
+                DPC_HIP(hipMemcpy(L.dBias.p, L.hb.data(), L.hb.size() * sizeof(float), hipMemcpyHostToDevice));
+            } else {
+                upload_conv_weights(L.g, L.hW.data(), L.hb.data(), L.cw);
+                std::vector<float> bias((size_t)L.n_out);
+                for (int i2 = 0; i2 < L.n_out; ++i2) bias[i2] = L.hb[i2 % L.g.Co];   // (H,W,C) order
+                L.dBias.reserve(L.n_out);
+                DPC_HIP(hipMemcpy(L.dBias.p, bias.data(), bias.size() * sizeof(float), hipMemcpyHostToDevice));
+            }
+        }
+        net->finalized = true;
+    });
+}
+
+dpc_status dpc_network_destroy(dpc_network* net)
+{
+    return guarded([&] {
+        if (!net) return;
+        DPC_REQUIRE(net->live_results == 0, DPC_ESTATE, "destroy the network's results first");
+        if (net->finalized) {
+            DeviceGuard guard(net->device);
+            delete net;
+        } else {
+            delete net;
+        }
+    });
+}
+
+dpc_status dpc_options_default(dpc_options* opt)
+{
+    return guarded([&] {
+        DPC_REQUIRE(opt, DPC_EINVAL, "dpc_options_default: NULL");
+        memset(opt, 0, sizeof *opt);
+        opt->struct_size = (int32_t)sizeof(dpc_options);
+        opt->max_backsub_depth = -1;
+        opt->keep_symbolic = 0;
+        opt->fuse = 1;
+        opt->profile = 0;
+        opt->stream = nullptr;
+    });
+}
+
+dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
+                       const dpc_options* opt_in, dpc_result** result)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net && lo && hi && result, DPC_EINVAL, "dpc_certify: NULL argument");
+        DPC_REQUIRE(net->finalized, DPC_ESTATE, "dpc_certify: network not finalized");
+        dpc_options opt;
+        if (opt_in) {
+            DPC_REQUIRE(opt_in->struct_size == (int32_t)sizeof(dpc_options), DPC_EINVAL,
+                        "dpc_certify: options struct_size %d, expected %zu", opt_in->struct_size, sizeof(dpc_options));
+            opt = *opt_in;
+        } else {
+            dpc_options_default(&opt);
+        }
+        DPC_REQUIRE(batch >= 0 && batch <= 16384, DPC_EINVAL, "dpc_certify: batch %d out of range [0, 16384]", batch);
+        DPC_REQUIRE(opt.max_backsub_depth >= -1, DPC_EINVAL, "dpc_certify: max_backsub_depth must be >= -1");
+        DPC_REQUIRE(opt.keep_symbolic == 0 || opt.keep_symbolic == 1, DPC_EINVAL, "dpc_certify: keep_symbolic must be 0 or 1");
+        DPC_REQUIRE(opt.keep_symbolic == 0 || opt.max_backsub_depth == -1, DPC_EINVAL,
+                    "dpc_certify: keep_symbolic needs a full traversal");
+        const int nl = (int)net->layers.size();
+        const Layer& last = *net->layers[nl - 1];
+        if (label) DPC_REQUIRE(last.kind == AFFINE && last.n_out >= 2, DPC_EUNSUPPORTED,
+                               "dpc_certify: a label needs a fully-connected last layer with >= 2 outputs");
+        DeviceGuard guard(net->device);
+        hipStream_t s = reinterpret_cast<hipStream_t>(opt.stream);
+        const int B = batch, n0 = net->n0, nK = last.n_out;
+
+        // ---- result object (reused when compatible) ----
+        dpc_result* res = *result;
+        if (res) DPC_REQUIRE(res->net == net && res->batch == batch && res->keep_symbolic == opt.keep_symbolic,
+                             DPC_EINVAL, "dpc_certify: the result passed in belongs to another network, batch or mode");
+        std::unique_ptr<dpc_result> fresh;
+        if (!res) {
+            fresh.reset(new dpc_result());
+            res = fresh.get();
+            res->net = net;
+            res->batch = batch;
+            res->keep_symbolic = opt.keep_symbolic;
+            size_t tot = 0;
+            for (int i = 0; i <= nl; ++i) {
+                tot += 2 * (size_t)B * net->size_of(i);
+                if (i > 0 && net->layers[i - 1]->kind == RELU) tot += 3 * (size_t)B * net->size_of(i);
+            }
+            res->pool.reserve(std::max<size_t>(tot, 1));
+            res->l.assign(nl + 1, nullptr); res->u.assign(nl + 1, nullptr);
+            res->lam.assign(nl + 1, nullptr); res->mu.assign(nl + 1, nullptr); res->nu.assign(nl + 1, nullptr);
+            float* p = res->pool.p;
+            for (int i = 0; i <= nl; ++i) {
+                const size_t c = (size_t)B * net->size_of(i);
+                res->l[i] = p; p += c;
+                res->u[i] = p; p += c;
+                if (i > 0 && net->layers[i - 1]->kind == RELU) {
+                    res->lam[i] = p; p += c;
+                    res->mu[i] = p; p += c;
+                    res->nu[i] = p; p += c;
+                }
+            }
+            res->margin.reserve(std::max<size_t>((size_t)B * (nK - 1), 1));
+            res->verdict.reserve(std::max(B, 1));
+            res->label.reserve(std::max(B, 1));
+            if (opt.keep_symbolic) {
+                res->sym_coeff.reserve(std::max<size_t>(2 * (size_t)B * nK * net->ld_of(0), 1));
+                res->sym_cst.reserve(std::max<size_t>(2 * (size_t)B * nK, 1));
+            }
+        }
+        res->has_label = label != nullptr;
+        res->has_symbolic = false;
+        memset(&res->prof, 0, sizeof res->prof);
+        res->prof.struct_size = (int32_t)sizeof(dpc_profile);
+
+        // ---- workspace ----
+        size_t need_rows = 1;
+        const size_t stage_need = 2 * (size_t)B * n0 + 16;   // box staging + one flag word
+        for (int i = 1; i <= nl; ++i)
+            if (net->layers[i - 1]->kind != RELU) need_rows = std::max(need_rows, 2 * (size_t)B * net->size_of(i));
+        const size_t need = workspace_floats(net, B, label != nullptr);
+        net->buf[0].reserve(need);
+        net->buf[1].reserve(need);
+        net->cst.reserve(need_rows);
+        net->stage.reserve(stage_need);
+
+        if (B == 0) {
+            if (fresh) { *result = fresh.release(); net->live_results++; }
+            return;
+        }
+
+        Prof prof;
+        prof.on = opt.profile != 0;
+        prof.s = s;
+        hipEvent_t t0 = nullptr, t1 = nullptr;
+        if (prof.on) { t0 = prof.get(); t1 = prof.get(); DPC_HIP(hipEventRecord(t0, s)); }
+
+        // ---- box and labels to the device, in the internal neuron order ----
+        const size_t box = (size_t)B * n0;
+        if (net->in_spatial) {
+            DPC_HIP(hipMemcpyAsync(net->stage.p, lo, box * 4, hipMemcpyDefault, s));
+            DPC_HIP(hipMemcpyAsync(net->stage.p + box, hi, box * 4, hipMemcpyDefault, s));
+            launch_chw_to_hwc(net->stage.p, res->l[0], B, net->inC, net->inH, net->inW, s);
+            launch_chw_to_hwc(net->stage.p + box, res->u[0], B, net->inC, net->inH, net->inW, s);
+        } else {
+            DPC_HIP(hipMemcpyAsync(res->l[0], lo, box * 4, hipMemcpyDefault, s));
+            DPC_HIP(hipMemcpyAsync(res->u[0], hi, box * 4, hipMemcpyDefault, s));
+        }
+        if (label) DPC_HIP(hipMemcpyAsync(res->label.p, label, (size_t)B * 4, hipMemcpyDefault, s));
+        {   // validate lo <= hi, finite, labels in range (on the device; one flag comes back)
+            int bad = check_inputs(res->l[0], res->u[0], box, label ? res->label.p : nullptr, B, nK,
+                                   reinterpret_cast<int32_t*>(net->stage.p + 2 * box), s);
+            DPC_REQUIRE(bad == 0, DPC_EINVAL,
+                        bad == 1 ? "dpc_certify: lo > hi or a non-finite bound" : "dpc_certify: label out of range");
+        }
+
+        Pass P{net, res, &opt, s, &prof, B};
+        for (int i = 1; i <= nl; ++i) {
+            Layer& L = *net->layers[i - 1];
+            if (L.kind == RELU) {
+                prof.begin(P_OTHER);
+                launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
+                                    (int64_t)B * L.n_out, s);
+                prof.end();
+                res->prof.other_launches++;
+                continue;
+            }
+            run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
+        }
+        if (label) {
+            const int nq = nK - 1;
+            prof.begin(P_OTHER);
+            launch_margin_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
+                               net->ld_of(nl - 1), net->cst.p, s);
+            prof.end();
+            res->prof.other_launches++;
+            run_pass(P, nl - 1, 1, nq, nullptr, res->margin.p, nullptr, false);
+            prof.begin(P_OTHER);
+            launch_verdict(res->margin.p, B, nq, res->verdict.p, s);
+            prof.end();
+            res->prof.other_launches++;
+        }
+        if (prof.on) DPC_HIP(hipEventRecord(t1, s));
+        DPC_HIP(hipStreamSynchronize(s));
+        if (prof.on) {
+            float ms = 0.f;
+            DPC_HIP(hipEventElapsedTime(&ms, t0, t1));
+            res->prof.total_ms = ms;
+            for (auto& r : prof.recs) {
+                DPC_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+                (r.cls == P_CONTRACT ? res->prof.contract_ms : r.cls == P_RELAX ? res->prof.relax_ms
+                 : r.cls == P_CONC ? res->prof.concretise_ms : res->prof.other_ms) += ms;
+            }
+        }
+        if (fresh) { *result = fresh.release(); net->live_results++; }
+    });
+}
+
+
+// ---- result accessors -------------------------------------------------------------------------
+
+namespace {
+
+// Copies a [batch, n] device array held in the internal neuron order to the caller, undoing the
+// (H,W,C) storage of spatial layers.
+void copy_out_layer(const dpc_result* res, int layer, const float* src, float* dst)
+{
+    if (!dst) return;
+    const dpc_network* net = res->net;
+    const size_t count = (size_t)res->batch * net->size_of(layer);
+    if (count == 0) return;
+    int C, H, W;
+    if (net->spatial(layer, &C, &H, &W)) {
+        DevBuf<float> tmp;
+        tmp.reserve(count);
+        launch_hwc_to_chw(src, tmp.p, res->batch, C, H, W, nullptr);
+        DPC_HIP(hipMemcpy(dst, tmp.p, count * sizeof(float), hipMemcpyDefault));
+    } else {
+        DPC_HIP(hipMemcpy(dst, src, count * sizeof(float), hipMemcpyDefault));
+    }
+}
+
+void require_result(const dpc_result* res, const char* who)
+{
+    DPC_REQUIRE(res && res->net, DPC_EINVAL, "%s: NULL result", who);
+}
+
+}  // namespace
+
+dpc_status dpc_result_concrete(const dpc_result* res, int32_t layer, float* l, float* u)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_concrete");
+        DPC_REQUIRE(layer >= 0 && layer <= (int)res->net->layers.size(), DPC_EINVAL,
+                    "dpc_result_concrete: layer %d out of range", layer);
+        DeviceGuard guard(res->net->device);
+        copy_out_layer(res, layer, res->l[layer], l);
+        copy_out_layer(res, layer, res->u[layer], u);
+    });
+}
+
+dpc_status dpc_result_relaxation(const dpc_result* res, int32_t relu_layer, float* lambda, float* mu, float* nu)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_relaxation");
+        DPC_REQUIRE(relu_layer >= 1 && relu_layer <= (int)res->net->layers.size() &&
+                        res->net->layers[relu_layer - 1]->kind == RELU,
+                    DPC_EINVAL, "dpc_result_relaxation: layer %d is not a ReLU layer", relu_layer);
+        DeviceGuard guard(res->net->device);
+        copy_out_layer(res, relu_layer, res->lam[relu_layer], lambda);
+        copy_out_layer(res, relu_layer, res->mu[relu_layer], mu);
+        copy_out_layer(res, relu_layer, res->nu[relu_layer], nu);
+    });
+}
+
+dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t side, float* coeff, float* cst)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_symbolic");
+        const dpc_network* net = res->net;
+        const int nl = (int)net->layers.size();
+        DPC_REQUIRE(res->keep_symbolic == 1 && res->has_symbolic, DPC_ESTATE,
+                    "dpc_result_symbolic: certify was not run with keep_symbolic = 1");
+        DPC_REQUIRE(layer == nl, DPC_EINVAL, "dpc_result_symbolic: only the last layer (%d) is kept", nl);
+        DPC_REQUIRE(side == 0 || side == 1, DPC_EINVAL, "dpc_result_symbolic: side must be 0 or 1");
+        DeviceGuard guard(net->device);
+        const int B = res->batch, nK = net->size_of(nl), n0 = net->n0, ld0 = net->ld_of(0);
+        const size_t rows = (size_t)B * nK;
+        if (rows == 0) return;
+        if (coeff) {
+            const float* src = res->sym_coeff.p + (size_t)side * rows * ld0;
+            int C, H, W;
+            if (net->spatial(0, &C, &H, &W)) {
+                DevBuf<float> a, b;
+                a.reserve(rows * n0);
+                b.reserve(rows * n0);
+                DPC_HIP(hipMemcpy2D(a.p, (size_t)n0 * 4, src, (size_t)ld0 * 4, (size_t)n0 * 4, rows, hipMemcpyDeviceToDevice));
+                DPC_REQUIRE(rows <= 0x7fffffff, DPC_EINVAL, "dpc_result_symbolic: too many rows");
+                launch_hwc_to_chw(a.p, b.p, (int)rows, C, H, W, nullptr);
+                DPC_HIP(hipMemcpy(coeff, b.p, rows * n0 * sizeof(float), hipMemcpyDefault));
+            } else {
+                DPC_HIP(hipMemcpy2D(coeff, (size_t)n0 * 4, src, (size_t)ld0 * 4, (size_t)n0 * 4, rows, hipMemcpyDefault));
+            }
+        }
+        if (cst) {
+            std::vector<double> h(rows);
+            DPC_HIP(hipMemcpy(h.data(), res->sym_cst.p + (size_t)side * rows, rows * sizeof(double), hipMemcpyDeviceToHost));
+            std::vector<float> hf(rows);
+            for (size_t i = 0; i < rows; ++i) hf[i] = (float)h[i];
+            DPC_HIP(hipMemcpy(cst, hf.data(), rows * sizeof(float), hipMemcpyDefault));
+        }
+    });
+}
+
+dpc_status dpc_result_verdict(const dpc_result* res, int32_t* verdict, float* margin_lb)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_verdict");
+        DPC_REQUIRE(res->has_label, DPC_ESTATE, "dpc_result_verdict: certify was run without labels");
+        DeviceGuard guard(res->net->device);
+        const int B = res->batch, nq = res->net->size_of((int)res->net->layers.size()) - 1;
+        if (B == 0) return;
+        if (verdict) DPC_HIP(hipMemcpy(verdict, res->verdict.p, (size_t)B * sizeof(int32_t), hipMemcpyDefault));
+        if (margin_lb) DPC_HIP(hipMemcpy(margin_lb, res->margin.p, (size_t)B * nq * sizeof(float), hipMemcpyDefault));
+    });
+}
+
+dpc_status dpc_result_profile(const dpc_result* res, dpc_profile* out)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_profile");
+        DPC_REQUIRE(out && out->struct_size == (int32_t)sizeof(dpc_profile), DPC_EINVAL,
+                    "dpc_result_profile: out is NULL or its struct_size is not %zu", sizeof(dpc_profile));
+        *out = res->prof;
+        out->struct_size = (int32_t)sizeof(dpc_profile);
+    });
+}
+
+dpc_status dpc_result_destroy(dpc_result* res)
+{
+    return guarded([&] {
+        if (!res) return;
+        DeviceGuard guard(res->net->device);
+        res->net->live_results--;
+        delete res;
+    });
+}
+
+// ---- the hot kernels on caller-owned device buffers --------------------------------------------
+
+dpc_status dpc_op_contract(const float* A, int64_t M, int32_t K, int32_t lda, const float* W, int32_t N, int32_t ldw,
+                           float* Cout, int32_t ldc, void* stream)
+{
+    return guarded([&] { launch_contract(A, M, K, lda, W, N, ldw, Cout, ldc, reinterpret_cast<hipStream_t>(stream)); });
+}
+
+dpc_status dpc_op_relax_step(float* C, int32_t ldc, double* cst, int32_t nsides, int32_t batch, int32_t R, int32_t n,
+                             const float* lambda, const float* mu, const float* nu, const float* bias,
+                             const float* shared_src, int32_t ld_src, void* stream)
+{
+    return guarded([&] {
+        launch_relax_step(C, ldc, cst, nsides, batch, R, n, lambda, mu, nu, bias, shared_src, ld_src, nullptr,
+                          reinterpret_cast<hipStream_t>(stream));
+    });
+}
+
+dpc_status dpc_op_concretise(const float* C, int32_t ldc, const double* cst, int32_t nsides, int32_t batch, int32_t R,
+                             int32_t n, const float* lo, const float* hi, float* out_l, float* out_u, void* stream)
+{
+    return guarded([&] {
+        launch_concretise(C, ldc, cst, nsides, batch, R, n, lo, hi, out_l, out_u, nullptr, 0, nullptr,
+                          reinterpret_cast<hipStream_t>(stream));
+    });
+}
+
+dpc_status dpc_tuning_set(const char* key, int32_t value)
+{
+    return guarded([&] {
+        DPC_REQUIRE(key, DPC_EINVAL, "dpc_tuning_set: NULL key");
+        if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
+        else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
+    });
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Shared host-side declarations of the dpcert library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+
+#include "dpcert.h"
+
+namespace dpc {
+
+// ---- error plumbing: no exception crosses the C ABI -------------------------------------------
+void set_error(const char* fmt, ...);
+struct Fail { dpc_status code; };          // thrown internally, caught at every extern "C" entry
+
+#define DPC_HIP(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e__ = (expr);                                                           \
+        if (e__ != hipSuccess) {                                                           \
+            dpc::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+            throw dpc::Fail{e__ == hipErrorOutOfMemory ? DPC_ENOMEM : DPC_EHIP};           \
+        }                                                                                  \
+    } while (0)
+
+#define DPC_REQUIRE(cond, code, ...)                                                       \
+    do {                                                                                   \
+        if (!(cond)) { dpc::set_error(__VA_ARGS__); throw dpc::Fail{code}; }               \
+    } while (0)
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+static inline int64_t ceil_div(int64_t x, int64_t m) { return (x + m - 1) / m; }
+
+// Leading dimensions of every coefficient matrix are multiples of this many floats, so that a row
+// is a whole number of 128-byte lines and the contraction's K loop needs no tail.
+constexpr int kLdAlign = 32;
+
+// ---- kernel launchers (each validates the shapes its kernel assumes before launching) ---------
+
+// Per-ReLU-neuron relaxation from the predecessor's concrete bounds (DeepPoly ReLU transformer).
+// l,u: [count]; writes lambda, mu, nu and the ReLU neuron's own bounds rl, ru: [count].
+void launch_relax_params(const float* l, const float* u, float* lambda, float* mu, float* nu,
+                         float* rl, float* ru, int64_t count, hipStream_t s);
+
+// Sign-split ReLU step + bias fold on dense rows; see dpc_op_relax_step.  cst_init (optional,
+// [R] float) replaces the incoming constant when shared_src is used.  lambda/mu/nu may be NULL
+// together (identity relaxation: only the bias fold); bias may be NULL.
+void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, int R, int n,
+                       const float* lambda, const float* mu, const float* nu, const float* bias,
+                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s);
+
+// Concretisation of dense rows against per-input bounds; see dpc_op_concretise.
+void launch_concretise(const float* C, int ldc, const double* cst, int nsides, int batch, int R, int n,
+                       const float* lo, const float* hi, float* out_l, float* out_u,
+                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s);
+
+// fp32 MFMA contraction Cout = A * W; see dpc_op_contract.  W must be padded with zeros to
+// [round_up(K,32), round_up(N,128)] so that tile loads need no bounds checks: ldw >= round_up(N,128)
+// and the allocation holds round_up(K,32) rows.
+void launch_contract(const float* A, int64_t M, int K, int lda, const float* Wpad, int N, int ldw,
+                     float* Cout, int ldc, hipStream_t s);
+
+// Margin rows of the robustness property: for input b and q-th other class o,
+// row = W[label_b] - W[o], constant = bias[label_b] - bias[o].
+void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch,
+                        int nK, int n, float* C, int ldc, double* cst, hipStream_t s);
+
+// verdict[b] = all margins of input b > 0.
+void launch_verdict(const float* margin, int batch, int nq, int32_t* verdict, hipStream_t s);
+
+// dst[b, perm(i)] = src[b, i] element permutation between (C,H,W) and (H,W,C) neuron orders.
+void launch_chw_to_hwc(const float* src, float* dst, int batch, int C, int H, int W, hipStream_t s);
+void launch_hwc_to_chw(const float* src, float* dst, int batch, int C, int H, int W, hipStream_t s);
+
+}  // namespace dpc

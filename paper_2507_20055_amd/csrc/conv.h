@@ -1,0 +1,77 @@
+// Convolution layers in the back-substitution: geometry, device weight layouts and launchers.
+//
+// A convolution layer is an affine layer whose weight matrix is the expanded kernel; in the
+// block-sparse picture its rows are a "Convolution block" (core = the kernel, shared by all
+// positions) and the coefficient rows of a convolution layer's neurons after the first ReLU step
+// are a "Patches block" (same sparsity pattern, distinct values per row; core = [rows, patch]).
+// Neither dense form is ever built: kernels work on the cores.
+//
+// Internal neuron order of spatial layers is (H, W, C) -- channel fastest -- so that a patch
+// position is a contiguous vector of channels.
+#pragma once
+
+#include "common.h"
+
+namespace dpc {
+
+struct ConvGeom {
+    int Ci, H, W;          // input (channels, rows, columns)
+    int Co, kh, kw, stride, pad;
+    int Ho, Wo;            // output rows, columns
+};
+
+struct ConvWeights {
+    float* core = nullptr;      // [Co][kh][kw][Ci] padded rows: row co has ld_core floats (the layer's own expressions)
+    int ld_core = 0;
+    float* taps = nullptr;      // [kh][kw][Co][Ci]  (transposed-convolution operand, Ci fastest)
+    float* bias_c = nullptr;    // [Co]
+    ~ConvWeights();
+    ConvWeights() = default;
+    ConvWeights(const ConvWeights&) = delete;
+    ConvWeights& operator=(const ConvWeights&) = delete;
+};
+
+void upload_conv_weights(const ConvGeom& g, const float* K /*[Co][Ci][kh][kw] host*/, const float* b, ConvWeights& out);
+
+// Geometry of patch-form rows: row r of a pass is neuron (ho, wo, co) of the layer being bounded,
+// r = (ho*rows_W + wo)*rows_C + co; its coefficients over the current layer (grid gh x gw x C) are a
+// ph x pw x C patch whose top-left corner sits at grid position (ho*S - P, wo*S - P).  Positions
+// outside the grid fall on zero padding and carry no neuron: their coefficients are kept at zero.
+struct PatchGeom {
+    int rows_W, rows_C;    // decomposition of the row index
+    int ph, pw, C;         // patch extent and channels at the current layer
+    int S, P;              // origin = index * S - P
+    int gh, gw;            // grid (rows, columns) of the current layer
+    int elems() const { return ph * pw * C; }
+};
+
+// Sign-split ReLU step + bias fold on patch-form rows (same arithmetic as the dense-row kernel;
+// lambda/mu/nu are [batch, gh*gw*C] in (H,W,C) order and are gathered by patch position).
+// bias_c: per-channel bias of the convolution layer below, or NULL.  shared_core: [rows_C][ld_core]
+// (initial expressions: the layer's own kernel, one core per output channel) or NULL.
+void launch_relax_step_patch(float* C, int ldc, double* cst, int nsides, int batch, int R, const PatchGeom& pg,
+                             const float* lambda, const float* mu, const float* nu, const float* bias_c,
+                             const float* shared_core, int ld_core, const float* cst_init_c, hipStream_t s);
+
+// Concretisation of patch-form rows against per-input bounds lo, hi: [batch, gh*gw*C] (H,W,C).
+void launch_concretise_patch(const float* C, int ldc, const double* cst, int nsides, int batch, int R,
+                             const PatchGeom& pg, const float* lo, const float* hi, float* out_l, float* out_u,
+                             const float* shared_core, int ld_core, const float* cst_init_c, hipStream_t s);
+
+// Transposed convolution of coefficient rows through convolution layer g (one traverse iteration):
+//   in : [M][ih][iw][g.Co] rows (ld_in floats apart)   -- coefficients over g's outputs
+//   out: [M][oh][ow][g.Ci] rows (ld_out floats apart)  -- coefficients over g's inputs
+//   out[m, y, x, ci] = sum over (ky, kx, co) with (y + off - ky) = py*stride, (x + off - kx) = px*stride,
+//                      0 <= py < ih, 0 <= px < iw, of in[m, py, px, co] * K[co, ci, ky, kx].
+// Dense rows: (ih, iw) = (Ho, Wo), (oh, ow) = (H, W), off = pad.  Patch rows: (oh, ow) =
+// ((ih-1)*stride + kh, (iw-1)*stride + kw), off = 0.  Columns oh*ow*Ci .. ld_out-1 are zeroed.
+// Returns the algorithmic flop count 2*M*ih*iw*Co*Ci*kh*kw.
+double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
+                                  const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
+
+// Validation of certify inputs on the device.  Returns 0 = fine, 1 = lo > hi or non-finite, 2 = bad label.
+// `flag` is a device int32 scratch word.  Synchronises the stream.
+int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
+                 int32_t* flag, hipStream_t s);
+
+}  // namespace dpc

@@ -1,0 +1,277 @@
+// Convolution-layer kernels of the back-substitution (patch-form rows, transposed convolution)
+// and input validation.
+#include <vector>
+
+#include "conv.h"
+
+namespace dpc {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+struct PatchArgs {
+    int rows_W, rows_C, ph, pw, C, S, P, gh, gw, elems;
+};
+
+// One wavefront per row; lanes stride over the patch elements (channel fastest, so a wavefront
+// reads contiguous runs of the row and contiguous channel vectors of the per-input parameters).
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void relax_step_patch_kernel(
+    float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, PatchArgs pa,
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
+    const float* __restrict__ bias_c, const float* __restrict__ core, int ld_core,
+    const float* __restrict__ cst_init_c, int rows_per_wave)
+{
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r0 = (blockIdx.x * kWaves + wave) * rows_per_wave;
+    const size_t pbase = (size_t)b * pa.gh * pa.gw * pa.C;
+    for (int q = 0; q < rows_per_wave; ++q) {
+        const int r = r0 + q;
+        if (r >= R) break;
+        const int co = r % pa.rows_C, wo = (r / pa.rows_C) % pa.rows_W, ho = r / (pa.rows_C * pa.rows_W);
+        const int oy = ho * pa.S - pa.P, ox = wo * pa.S - pa.P;
+        const size_t m = (size_t)sb * R + r;
+        const float* in = SHARED ? core + (size_t)co * ld_core : C + m * ldc;
+        float* out = C + m * ldc;
+        double a = 0.0;
+        for (int e = lane; e < ldc; e += 64) {
+            float y = 0.0f;
+            if (e < pa.elems) {
+                const int c = e % pa.C, pos = e / pa.C;
+                const int px = pos % pa.pw, py = pos / pa.pw;
+                const int gy = oy + py, gx = ox + px;
+                if (gy >= 0 && gy < pa.gh && gx >= 0 && gx < pa.gw) {
+                    const size_t idx = pbase + ((size_t)gy * pa.gw + gx) * pa.C + c;
+                    const float la = lambda ? lambda[idx] : 1.0f;
+                    const float mm = mu ? mu[idx] : 1.0f;
+                    const float v = nu ? nu[idx] : 0.0f;
+                    const float bj = bias_c ? bias_c[c] : 0.0f;
+                    const float x = in[e];
+                    const bool pos_c = x >= 0.0f;
+                    const float mult = pos_c ? (side == 0 ? la : mm) : (side == 0 ? mm : la);
+                    const float k = ((pos_c == (side != 0)) ? v : 0.0f) + mult * bj;
+                    y = x * mult;
+                    a += (double)x * (double)k;
+                }
+            }
+            out[e] = y;
+        }
+        const double t = wave_sum(a);
+        if (lane == 0) cst[m] = (SHARED ? (double)cst_init_c[co] : cst[m]) + t;
+    }
+}
+
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void concretise_patch_kernel(
+    const float* __restrict__ C, int ldc, const double* __restrict__ cst, int batch, int R, PatchArgs pa,
+    const float* __restrict__ lo, const float* __restrict__ hi, float* __restrict__ out_l, float* __restrict__ out_u,
+    const float* __restrict__ core, int ld_core, const float* __restrict__ cst_init_c, int rows_per_wave)
+{
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r0 = (blockIdx.x * kWaves + wave) * rows_per_wave;
+    const size_t pbase = (size_t)b * pa.gh * pa.gw * pa.C;
+    for (int q = 0; q < rows_per_wave; ++q) {
+        const int r = r0 + q;
+        if (r >= R) break;
+        const int co = r % pa.rows_C, wo = (r / pa.rows_C) % pa.rows_W, ho = r / (pa.rows_C * pa.rows_W);
+        const int oy = ho * pa.S - pa.P, ox = wo * pa.S - pa.P;
+        const size_t m = (size_t)sb * R + r;
+        const float* in = SHARED ? core + (size_t)co * ld_core : C + m * ldc;
+        double a = 0.0;
+        for (int e = lane; e < pa.elems; e += 64) {
+            const int c = e % pa.C, pos = e / pa.C;
+            const int px = pos % pa.pw, py = pos / pa.pw;
+            const int gy = oy + py, gx = ox + px;
+            if (gy >= 0 && gy < pa.gh && gx >= 0 && gx < pa.gw) {
+                const size_t idx = pbase + ((size_t)gy * pa.gw + gx) * pa.C + c;
+                const float x = in[e];
+                const float bound = (x >= 0.0f) == (side == 0) ? lo[idx] : hi[idx];
+                a += (double)x * (double)bound;
+            }
+        }
+        const double t = wave_sum(a);
+        if (lane == 0) {
+            const double v = (SHARED ? (double)cst_init_c[co] : cst[m]) + t;
+            (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)v;
+        }
+    }
+}
+
+// Transposed convolution of coefficient rows, one thread per output element (gather form: every
+// output is produced by exactly one thread, so the summation order is fixed).
+__global__ __launch_bounds__(kThreads) void conv_transpose_rows_kernel(
+    const float* __restrict__ in, int ld_in, int ih, int iw, int Co, int Ci, int kh, int kw, int stride,
+    const float* __restrict__ taps, float* __restrict__ out, int ld_out, int oh, int ow, int off)
+{
+    const size_t m = blockIdx.x;
+    const int o = blockIdx.y * kThreads + threadIdx.x;
+    if (o >= ld_out) return;
+    float acc = 0.0f;
+    if (o < oh * ow * Ci) {
+        const int ci = o % Ci, x = (o / Ci) % ow, y = o / (Ci * ow);
+        const float* row = in + m * ld_in;
+        for (int ky = 0; ky < kh; ++ky) {
+            const int ty = y + off - ky;
+            if (ty < 0 || ty % stride != 0) continue;
+            const int py = ty / stride;
+            if (py >= ih) continue;
+            for (int kx = 0; kx < kw; ++kx) {
+                const int tx = x + off - kx;
+                if (tx < 0 || tx % stride != 0) continue;
+                const int px = tx / stride;
+                if (px >= iw) continue;
+                const float* p = row + ((size_t)py * iw + px) * Co;
+                const float* t = taps + ((size_t)(ky * kw + kx) * Co) * Ci + ci;
+                for (int co = 0; co < Co; ++co) acc = fmaf(p[co], t[(size_t)co * Ci], acc);
+            }
+        }
+    }
+    out[m * ld_out + o] = acc;
+}
+
+__global__ void check_inputs_kernel(const float* __restrict__ lo, const float* __restrict__ hi, size_t count,
+                                    const int32_t* __restrict__ label, int batch, int nK, int32_t* __restrict__ flag)
+{
+    int bad = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+        const float a = lo[i], b = hi[i];
+        if (!(a <= b) || !isfinite(a) || !isfinite(b)) bad |= 1;
+    }
+    if (label)
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)batch; i += (size_t)gridDim.x * blockDim.x)
+            if (label[i] < 0 || label[i] >= nK) bad |= 2;
+    if (bad) atomicOr(flag, bad);
+}
+
+__global__ void zero_word_kernel(int32_t* p) { *p = 0; }
+
+PatchArgs to_args(const PatchGeom& g)
+{
+    return PatchArgs{g.rows_W, g.rows_C, g.ph, g.pw, g.C, g.S, g.P, g.gh, g.gw, g.elems()};
+}
+
+int rows_per_wave_for(int R, int groups)
+{
+    int rpw = 8;
+    while (rpw > 1 && ceil_div(R, rpw * kWaves) * groups < 2048) rpw >>= 1;
+    return rpw;
+}
+
+}  // namespace
+
+ConvWeights::~ConvWeights()
+{
+    if (core) (void)hipFree(core);
+    if (taps) (void)hipFree(taps);
+    if (bias_c) (void)hipFree(bias_c);
+}
+
+void upload_conv_weights(const ConvGeom& g, const float* K, const float* b, ConvWeights& out)
+{
+    const int patch = g.kh * g.kw * g.Ci;
+    out.ld_core = (int)round_up(patch, 4);
+    std::vector<float> core((size_t)g.Co * out.ld_core, 0.0f), taps((size_t)g.kh * g.kw * g.Co * g.Ci);
+    for (int co = 0; co < g.Co; ++co)
+        for (int ci = 0; ci < g.Ci; ++ci)
+            for (int ky = 0; ky < g.kh; ++ky)
+                for (int kx = 0; kx < g.kw; ++kx) {
+                    const float v = K[(((size_t)co * g.Ci + ci) * g.kh + ky) * g.kw + kx];
+                    core[(size_t)co * out.ld_core + ((size_t)ky * g.kw + kx) * g.Ci + ci] = v;
+                    taps[(((size_t)ky * g.kw + kx) * g.Co + co) * g.Ci + ci] = v;
+                }
+    DPC_HIP(hipMalloc(reinterpret_cast<void**>(&out.core), core.size() * sizeof(float)));
+    DPC_HIP(hipMalloc(reinterpret_cast<void**>(&out.taps), taps.size() * sizeof(float)));
+    DPC_HIP(hipMalloc(reinterpret_cast<void**>(&out.bias_c), (size_t)g.Co * sizeof(float)));
+    DPC_HIP(hipMemcpy(out.core, core.data(), core.size() * sizeof(float), hipMemcpyHostToDevice));
+    DPC_HIP(hipMemcpy(out.taps, taps.data(), taps.size() * sizeof(float), hipMemcpyHostToDevice));
+    DPC_HIP(hipMemcpy(out.bias_c, b, (size_t)g.Co * sizeof(float), hipMemcpyHostToDevice));
+}
+
+void launch_relax_step_patch(float* C, int ldc, double* cst, int nsides, int batch, int R, const PatchGeom& pg,
+                             const float* lambda, const float* mu, const float* nu, const float* bias_c,
+                             const float* shared_core, int ld_core, const float* cst_init_c, hipStream_t s)
+{
+    DPC_REQUIRE(C && cst && nsides >= 1 && nsides <= 2 && batch >= 0 && R >= 0, DPC_EINVAL, "relax_step_patch: bad arguments");
+    DPC_REQUIRE(ldc >= pg.elems() && R == R / (pg.rows_C * pg.rows_W) * (pg.rows_C * pg.rows_W), DPC_EINVAL,
+                "relax_step_patch: row geometry does not match R");
+    DPC_REQUIRE((lambda != nullptr) == (mu != nullptr) && (mu != nullptr) == (nu != nullptr), DPC_EINVAL,
+                "relax_step_patch: lambda, mu, nu must be given together");
+    if (shared_core) DPC_REQUIRE(ld_core >= pg.elems() && cst_init_c, DPC_EINVAL, "relax_step_patch: bad shared core");
+    DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "relax_step_patch: nsides*batch exceeds 65535");
+    if (batch == 0 || R == 0) return;
+    const int rpw = rows_per_wave_for(R, nsides * batch);
+    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
+    if (shared_core)
+        hipLaunchKernelGGL(relax_step_patch_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, to_args(pg),
+                           lambda, mu, nu, bias_c, shared_core, ld_core, cst_init_c, rpw);
+    else
+        hipLaunchKernelGGL(relax_step_patch_kernel<false>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, to_args(pg),
+                           lambda, mu, nu, bias_c, (const float*)nullptr, 0, (const float*)nullptr, rpw);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_concretise_patch(const float* C, int ldc, const double* cst, int nsides, int batch, int R,
+                             const PatchGeom& pg, const float* lo, const float* hi, float* out_l, float* out_u,
+                             const float* shared_core, int ld_core, const float* cst_init_c, hipStream_t s)
+{
+    DPC_REQUIRE(nsides >= 1 && nsides <= 2 && batch >= 0 && R >= 0 && lo && hi && out_l && (nsides == 1 || out_u),
+                DPC_EINVAL, "concretise_patch: bad arguments");
+    DPC_REQUIRE(R == R / (pg.rows_C * pg.rows_W) * (pg.rows_C * pg.rows_W), DPC_EINVAL,
+                "concretise_patch: row geometry does not match R");
+    if (shared_core) DPC_REQUIRE(ld_core >= pg.elems() && cst_init_c, DPC_EINVAL, "concretise_patch: bad shared core");
+    else DPC_REQUIRE(C && cst && ldc >= pg.elems(), DPC_EINVAL, "concretise_patch: bad rows");
+    DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "concretise_patch: nsides*batch exceeds 65535");
+    if (batch == 0 || R == 0) return;
+    const int rpw = rows_per_wave_for(R, nsides * batch);
+    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
+    if (shared_core)
+        hipLaunchKernelGGL(concretise_patch_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, to_args(pg),
+                           lo, hi, out_l, out_u, shared_core, ld_core, cst_init_c, rpw);
+    else
+        hipLaunchKernelGGL(concretise_patch_kernel<false>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, to_args(pg),
+                           lo, hi, out_l, out_u, (const float*)nullptr, 0, (const float*)nullptr, rpw);
+    DPC_HIP(hipGetLastError());
+}
+
+double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
+                                  const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s)
+{
+    DPC_REQUIRE(in && out && M >= 0 && w.taps, DPC_EINVAL, "conv_transpose_rows: bad arguments");
+    DPC_REQUIRE(ld_in >= ih * iw * g.Co && ld_out >= oh * ow * g.Ci, DPC_EINVAL,
+                "conv_transpose_rows: leading dimensions too small");
+    DPC_REQUIRE(M < ((int64_t)1 << 31), DPC_EINVAL, "conv_transpose_rows: too many rows");
+    if (M == 0) return 0.0;
+    dim3 grid((unsigned)M, (unsigned)ceil_div(ld_out, kThreads));
+    hipLaunchKernelGGL(conv_transpose_rows_kernel, grid, dim3(kThreads), 0, s, in, ld_in, ih, iw, g.Co, g.Ci, g.kh, g.kw,
+                       g.stride, w.taps, out, ld_out, oh, ow, off);
+    DPC_HIP(hipGetLastError());
+    return 2.0 * (double)M * ih * iw * g.Co * g.Ci * g.kh * g.kw;
+}
+
+int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
+                 int32_t* flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, s, flag);
+    const unsigned blocks = (unsigned)std::min<size_t>(1024, ceil_div((int64_t)std::max<size_t>(count, 1), 256));
+    hipLaunchKernelGGL(check_inputs_kernel, dim3(blocks), dim3(256), 0, s, lo, hi, count, label, batch, nK, flag);
+    DPC_HIP(hipGetLastError());
+    int32_t h = 0;
+    DPC_HIP(hipMemcpyAsync(&h, flag, sizeof h, hipMemcpyDeviceToHost, s));
+    DPC_HIP(hipStreamSynchronize(s));
+    return (h & 1) ? 1 : (h & 2) ? 2 : 0;
+}
+
+}  // namespace dpc

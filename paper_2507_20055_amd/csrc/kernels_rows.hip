@@ -1,0 +1,377 @@
+// Row-streaming kernels of the back-substitution: ReLU relaxation parameters, the sign-split
+// ReLU step (+ bias fold), concretisation, margin rows, verdict.  All HBM-bound: one wavefront
+// streams one coefficient row with 16-byte loads, per-input parameters sit in LDS, the per-row
+// constant is accumulated in fp64 and reduced with wavefront shuffles.
+#include "common.h"
+
+namespace dpc {
+
+namespace {
+
+constexpr int kThreads = 256;          // 4 wavefronts of 64
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxRowsPerWave = 8;
+constexpr int kChunk = 2048;           // columns of per-input parameters resident in LDS at a time
+
+typedef float vfloat4 __attribute__((ext_vector_type(4)));
+
+// Streaming (non-temporal) 16-byte accesses: coefficient rows are touched once per kernel.
+__device__ __forceinline__ float4 nt_load4(const float4* p)
+{
+    const vfloat4 v = __builtin_nontemporal_load(reinterpret_cast<const vfloat4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float4* p, float a, float b, float c, float d)
+{
+    vfloat4 v = {a, b, c, d};
+    __builtin_nontemporal_store(v, reinterpret_cast<vfloat4*>(p));
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// DeepPoly ReLU transformer (Appendix C: relu, relu_n, compute_upper), one thread per neuron.
+__global__ __launch_bounds__(kThreads) void relax_params_kernel(
+    const float* __restrict__ l, const float* __restrict__ u, float* __restrict__ lambda,
+    float* __restrict__ mu, float* __restrict__ nu, float* __restrict__ rl, float* __restrict__ ru,
+    int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= count) return;
+    const float lv = l[i], uv = u[i];
+    lambda[i] = (lv + uv >= 0.0f) ? 1.0f : 0.0f;
+    float m, v;
+    if (lv >= 0.0f) { m = 1.0f; v = 0.0f; }
+    else if (uv <= 0.0f) { m = 0.0f; v = 0.0f; }
+    else {
+        const float d = uv - lv;
+        m = uv / d;
+        v = -(uv * lv) / d;
+    }
+    mu[i] = m;
+    nu[i] = v;
+    rl[i] = lv >= 0.0f ? lv : 0.0f;
+    ru[i] = uv >= 0.0f ? uv : 0.0f;
+}
+
+// Sign-split ReLU step + bias fold (replace_lower / replace_upper through a ReLU layer, then the
+// constant part of the affine layer below).  grid = (row tiles, nsides*batch).  LDS per chunk of
+// columns: multiplier for C >= 0, multiplier for C < 0, and the constant picked up per unit of
+// C >= 0 / C < 0 (nu on the side that uses U, plus multiplier * bias).
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void relax_step_kernel(
+    float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
+    const float* __restrict__ bias, const float* __restrict__ src, int ld_src,
+    const float* __restrict__ cst_init, int rows_per_wave)
+{
+    __shared__ float4 s_pm[kChunk / 4], s_nm[kChunk / 4], s_pk[kChunk / 4], s_nk[kChunk / 4];
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r0 = blockIdx.x * (rows_per_wave * kWaves) + wave * rows_per_wave;
+
+    double acc[kMaxRowsPerWave];
+#pragma unroll
+    for (int q = 0; q < kMaxRowsPerWave; ++q) acc[q] = 0.0;
+
+    for (int c0 = 0; c0 < ldc; c0 += kChunk) {
+        const int cw = min(kChunk, ldc - c0);          // multiple of 4 (ldc is)
+        if (c0 > 0) __syncthreads();
+        for (int i = threadIdx.x; i < cw; i += kThreads) {
+            const int col = c0 + i;
+            float pm = 0.f, nm = 0.f, pk = 0.f, nk = 0.f;
+            if (col < n) {
+                const float la = lambda ? lambda[(size_t)b * n + col] : 1.0f;
+                const float m = mu ? mu[(size_t)b * n + col] : 1.0f;
+                const float v = nu ? nu[(size_t)b * n + col] : 0.0f;
+                const float bj = bias ? bias[col] : 0.0f;
+                pm = side == 0 ? la : m;               // lower rows: C>=0 takes L, C<0 takes U
+                nm = side == 0 ? m : la;
+                pk = (side == 0 ? 0.0f : v) + pm * bj;
+                nk = (side == 0 ? v : 0.0f) + nm * bj;
+            }
+            reinterpret_cast<float*>(s_pm)[i] = pm;
+            reinterpret_cast<float*>(s_nm)[i] = nm;
+            reinterpret_cast<float*>(s_pk)[i] = pk;
+            reinterpret_cast<float*>(s_nk)[i] = nk;
+        }
+        __syncthreads();
+        const int cw4 = cw >> 2;
+        const int nloc = n - c0;
+#pragma unroll
+        for (int q = 0; q < kMaxRowsPerWave; ++q) {
+            const int r = r0 + q;
+            if (q >= rows_per_wave || r >= R) break;
+            const size_t m = (size_t)sb * R + r;
+            const float4* in = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src + c0
+                                                                      : C + m * ldc + c0);
+            float4* out = reinterpret_cast<float4*>(C + m * ldc + c0);
+            double a = 0.0;
+            for (int base = 0; base < cw4; base += 64 * 4) {
+                float4 v[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int i4 = base + t * 64 + lane;
+                    if (i4 < cw4) v[t] = SHARED ? in[i4] : nt_load4(in + i4);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int i4 = base + t * 64 + lane;
+                    if (i4 >= cw4) continue;
+                    const float4 pm = s_pm[i4], nm = s_nm[i4], pk = s_pk[i4], nk = s_nk[i4];
+                    const float x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+                    const float pmv[4] = {pm.x, pm.y, pm.z, pm.w}, nmv[4] = {nm.x, nm.y, nm.z, nm.w};
+                    const float pkv[4] = {pk.x, pk.y, pk.z, pk.w}, nkv[4] = {nk.x, nk.y, nk.z, nk.w};
+                    float y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool pos = x[e] >= 0.0f;
+                        const bool live = i4 * 4 + e < nloc;     // padding columns come out as exact zeros
+                        y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
+                        a += live ? (double)x[e] * (double)(pos ? pkv[e] : nkv[e]) : 0.0;
+                    }
+                    nt_store4(out + i4, y[0], y[1], y[2], y[3]);
+                }
+            }
+            acc[q] += a;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kMaxRowsPerWave; ++q) {
+        const int r = r0 + q;
+        if (q >= rows_per_wave || r >= R) break;
+        const double t = wave_sum(acc[q]);
+        if (lane == 0) {
+            const size_t m = (size_t)sb * R + r;
+            cst[m] = (cst_init ? (double)cst_init[r] : cst[m]) + t;
+        }
+    }
+}
+
+// Concretisation (simplify_lower / simplify_upper): one wavefront per row, box of input b in LDS.
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void concretise_kernel(
+    const float* __restrict__ C, int ldc, const double* __restrict__ cst, int batch, int R, int n,
+    const float* __restrict__ lo, const float* __restrict__ hi, float* __restrict__ out_l,
+    float* __restrict__ out_u, const float* __restrict__ src, int ld_src,
+    const float* __restrict__ cst_init, int rows_per_wave)
+{
+    __shared__ float4 s_p[kChunk / 4], s_n[kChunk / 4];   // bound taken by C >= 0 / C < 0
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r0 = blockIdx.x * (rows_per_wave * kWaves) + wave * rows_per_wave;
+
+    double acc[kMaxRowsPerWave];
+#pragma unroll
+    for (int q = 0; q < kMaxRowsPerWave; ++q) acc[q] = 0.0;
+
+    for (int c0 = 0; c0 < ldc; c0 += kChunk) {
+        const int cw = min(kChunk, ldc - c0);
+        if (c0 > 0) __syncthreads();
+        for (int i = threadIdx.x; i < cw; i += kThreads) {
+            const int col = c0 + i;
+            float p = 0.f, q = 0.f;
+            if (col < n) {
+                const float lv = lo[(size_t)b * n + col], hv = hi[(size_t)b * n + col];
+                p = side == 0 ? lv : hv;
+                q = side == 0 ? hv : lv;
+            }
+            reinterpret_cast<float*>(s_p)[i] = p;
+            reinterpret_cast<float*>(s_n)[i] = q;
+        }
+        __syncthreads();
+        const int cw4 = cw >> 2;
+        const int nloc = n - c0;
+#pragma unroll
+        for (int q = 0; q < kMaxRowsPerWave; ++q) {
+            const int r = r0 + q;
+            if (q >= rows_per_wave || r >= R) break;
+            const size_t m = (size_t)sb * R + r;
+            const float4* in = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src + c0
+                                                                      : C + m * ldc + c0);
+            double a = 0.0;
+            for (int base = 0; base < cw4; base += 64 * 4) {
+                float4 v[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int i4 = base + t * 64 + lane;
+                    if (i4 < cw4) v[t] = SHARED ? in[i4] : nt_load4(in + i4);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int i4 = base + t * 64 + lane;
+                    if (i4 >= cw4) continue;
+                    const float4 p = s_p[i4], ng = s_n[i4];
+                    const float x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+                    const float pv[4] = {p.x, p.y, p.z, p.w}, nv[4] = {ng.x, ng.y, ng.z, ng.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (i4 * 4 + e < nloc) a += (double)x[e] * (double)(x[e] >= 0.0f ? pv[e] : nv[e]);
+                }
+            }
+            acc[q] += a;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kMaxRowsPerWave; ++q) {
+        const int r = r0 + q;
+        if (q >= rows_per_wave || r >= R) break;
+        const double t = wave_sum(acc[q]);
+        if (lane == 0) {
+            const size_t m = (size_t)sb * R + r;
+            const double v = (cst_init ? (double)cst_init[r] : cst[m]) + t;
+            (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void margin_rows_kernel(
+    const float* __restrict__ W, int ldw, const float* __restrict__ bias, const int32_t* __restrict__ label,
+    int nK, int n, float* __restrict__ C, int ldc, double* __restrict__ cst)
+{
+    const int m = blockIdx.x;                // b * (nK-1) + q
+    const int b = m / (nK - 1), q = m - b * (nK - 1);
+    const int t = label[b];
+    const int o = q < t ? q : q + 1;
+    for (int i = threadIdx.x; i < ldc; i += kThreads)
+        C[(size_t)m * ldc + i] = i < n ? W[(size_t)t * ldw + i] - W[(size_t)o * ldw + i] : 0.0f;
+    if (threadIdx.x == 0) cst[m] = (double)bias[t] - (double)bias[o];
+}
+
+__global__ void verdict_kernel(const float* __restrict__ margin, int batch, int nq, int32_t* __restrict__ verdict)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    int ok = 1;
+    for (int q = 0; q < nq; ++q)
+        if (!(margin[(size_t)b * nq + q] > 0.0f)) ok = 0;
+    verdict[b] = ok;
+}
+
+template <bool TO_HWC>
+__global__ __launch_bounds__(kThreads) void permute_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                           int batch, int Cc, int H, int W)
+{
+    const int64_t n = (int64_t)Cc * H * W;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n * batch) return;
+    const int64_t b = i / n;
+    const int e = (int)(i - b * n);          // index in (C,H,W) order
+    const int w = e % W, h = (e / W) % H, c = e / (W * H);
+    const int64_t hwc = b * n + ((int64_t)h * W + w) * Cc + c;
+    if (TO_HWC) dst[hwc] = src[i]; else dst[i] = src[hwc];
+}
+
+int pick_rows_per_wave(int R, int groups)
+{
+    // enough blocks to cover 256 CUs a few times over, as many rows per block as that allows
+    int rpw = kMaxRowsPerWave;
+    while (rpw > 1 && ceil_div(R, rpw * kWaves) * groups < 2048) rpw >>= 1;
+    return rpw;
+}
+
+}  // namespace
+
+void launch_relax_params(const float* l, const float* u, float* lambda, float* mu, float* nu,
+                         float* rl, float* ru, int64_t count, hipStream_t s)
+{
+    if (count <= 0) return;
+    hipLaunchKernelGGL(relax_params_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, s,
+                       l, u, lambda, mu, nu, rl, ru, count);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, int R, int n,
+                       const float* lambda, const float* mu, const float* nu, const float* bias,
+                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s)
+{
+    DPC_REQUIRE(C && cst && nsides >= 1 && nsides <= 2 && batch >= 0 && R >= 0 && n >= 1, DPC_EINVAL,
+                "relax_step: bad arguments");
+    DPC_REQUIRE(ldc >= n && ldc % 4 == 0 && ((uintptr_t)C % 16) == 0, DPC_EINVAL,
+                "relax_step: ldc must be >= n and a multiple of 4, C 16-byte aligned");
+    DPC_REQUIRE((lambda != nullptr) == (mu != nullptr) && (mu != nullptr) == (nu != nullptr), DPC_EINVAL,
+                "relax_step: lambda, mu, nu must be given together");
+    if (shared_src)
+        DPC_REQUIRE(ld_src >= ldc && ld_src % 4 == 0 && ((uintptr_t)shared_src % 16) == 0, DPC_EINVAL,
+                    "relax_step: shared source needs ld_src >= ldc, multiple of 4, 16-byte aligned");
+    DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "relax_step: nsides*batch exceeds 65535");
+    if (batch == 0 || R == 0) return;
+    const int rpw = pick_rows_per_wave(R, nsides * batch);
+    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
+    if (shared_src)
+        hipLaunchKernelGGL(relax_step_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n,
+                           lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw);
+    else
+        hipLaunchKernelGGL(relax_step_kernel<false>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n,
+                           lambda, mu, nu, bias, (const float*)nullptr, 0, cst_init, rpw);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_concretise(const float* C, int ldc, const double* cst, int nsides, int batch, int R, int n,
+                       const float* lo, const float* hi, float* out_l, float* out_u,
+                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s)
+{
+    DPC_REQUIRE(nsides >= 1 && nsides <= 2 && batch >= 0 && R >= 0 && n >= 1 && lo && hi && out_l, DPC_EINVAL,
+                "concretise: bad arguments");
+    DPC_REQUIRE(nsides == 1 || out_u, DPC_EINVAL, "concretise: out_u missing");
+    DPC_REQUIRE(ldc >= n && ldc % 4 == 0, DPC_EINVAL, "concretise: ldc must be >= n and a multiple of 4");
+    if (shared_src)
+        DPC_REQUIRE(ld_src >= ldc && ld_src % 4 == 0 && ((uintptr_t)shared_src % 16) == 0 && cst_init, DPC_EINVAL,
+                    "concretise: shared source needs ld_src >= ldc, multiple of 4, 16-byte aligned, cst_init");
+    else
+        DPC_REQUIRE(C && cst && ((uintptr_t)C % 16) == 0, DPC_EINVAL, "concretise: C/cst missing or misaligned");
+    DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "concretise: nsides*batch exceeds 65535");
+    if (batch == 0 || R == 0) return;
+    const int rpw = pick_rows_per_wave(R, nsides * batch);
+    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
+    if (shared_src)
+        hipLaunchKernelGGL(concretise_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n, lo, hi,
+                           out_l, out_u, shared_src, ld_src, cst_init, rpw);
+    else
+        hipLaunchKernelGGL(concretise_kernel<false>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n, lo, hi,
+                           out_l, out_u, (const float*)nullptr, 0, cst_init, rpw);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch,
+                        int nK, int n, float* C, int ldc, double* cst, hipStream_t s)
+{
+    DPC_REQUIRE(nK >= 2 && ldc >= n && ldw >= n, DPC_EINVAL, "margin_rows: bad shape");
+    if (batch == 0) return;
+    hipLaunchKernelGGL(margin_rows_kernel, dim3((unsigned)(batch * (nK - 1))), dim3(kThreads), 0, s,
+                       W, ldw, bias, label, nK, n, C, ldc, cst);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_verdict(const float* margin, int batch, int nq, int32_t* verdict, hipStream_t s)
+{
+    if (batch == 0) return;
+    hipLaunchKernelGGL(verdict_kernel, dim3((unsigned)ceil_div(batch, 64)), dim3(64), 0, s, margin, batch, nq, verdict);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_chw_to_hwc(const float* src, float* dst, int batch, int C, int H, int W, hipStream_t s)
+{
+    const int64_t tot = (int64_t)batch * C * H * W;
+    if (tot == 0) return;
+    hipLaunchKernelGGL(permute_kernel<true>, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s,
+                       src, dst, batch, C, H, W);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_hwc_to_chw(const float* src, float* dst, int batch, int C, int H, int W, hipStream_t s)
+{
+    const int64_t tot = (int64_t)batch * C * H * W;
+    if (tot == 0) return;
+    hipLaunchKernelGGL(permute_kernel<false>, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s,
+                       src, dst, batch, C, H, W);
+    DPC_HIP(hipGetLastError());
+}
+
+}  // namespace dpc

@@ -1,0 +1,202 @@
+"""End-to-end parity of the HIP path (through the C ABI) against the float64 CPU oracle."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle                                            # noqa: E402
+from paper_2507_20055_amd import workloads as wl         # noqa: E402
+from tests.parity_util import compare_with_oracle        # noqa: E402
+
+
+def _binding():
+    from paper_2507_20055_amd import binding
+    return binding
+
+
+def _run_both(net, lo, hi, label, **kw):
+    b = _binding()
+    gnet = b.Network(net)
+    g = gnet.certify(lo, hi, label, **kw)
+    o = oracle.run(net, lo, hi, label=label, max_depth=kw.get("max_backsub_depth", -1))
+    return gnet, g, o
+
+
+@pytest.mark.parametrize("seed,dims,B,eps", [(1, [5, 7, 6, 3], 3, 0.3), (2, [20, 33, 65, 40, 10], 4, 0.1),
+                                             (3, [7, 130, 5], 2, 0.2), (4, [3, 2], 1, 0.5), (5, [64, 257, 129, 10], 5, 0.05)])
+def test_small_fc(seed, dims, B, eps):
+    net = wl.random_small_net(seed, dims)
+    x, lo, hi = wl.random_box(seed + 10, dims[0], B, eps)
+    label = np.arange(B, dtype=np.int32) % dims[-1] if dims[-1] >= 2 else None
+    gnet, g, o = _run_both(net, lo, hi, label)
+    compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
+def test_hand_example_on_gpu():
+    from tests.test_oracle_pins import read_golden, fc_net
+    gd = read_golden("net_2_2_2_2.txt")
+    net = fc_net(2, [(gd["W1"].reshape(2, 2), gd["b1"]), (gd["W2"].reshape(2, 2), gd["b2"]), (gd["W3"].reshape(2, 2), gd["b3"])])
+    b = _binding()
+    gnet = b.Network(net)
+    g = gnet.certify(gd["lo"][None].astype(np.float32), gd["hi"][None].astype(np.float32), gd["label"].astype(np.int32),
+                     keep_symbolic=1)
+    l5, u5 = g.concrete(5)
+    np.testing.assert_allclose(l5[0], gd["l5"], rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(u5[0], gd["u5"], rtol=1e-5, atol=1e-6)
+    v, m = g.verdict()
+    np.testing.assert_allclose(m[0], gd["margin"], rtol=1e-5)
+    assert v[0] == 0
+    cl, kl = g.symbolic(5, 0)
+    cu, ku = g.symbolic(5, 1)
+    np.testing.assert_allclose(cl[0].ravel(), gd["sym_lower_coeff"], rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(ku[0], gd["sym_upper_const"], rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(cu[0].ravel(), gd["sym_upper_coeff"], rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(kl[0], gd["sym_lower_const"], rtol=1e-5, atol=1e-6)
+    gnet.close()
+
+
+@pytest.mark.parametrize("convs,fcs,shape", [([(3, 3, 1, 1), (4, 4, 2, 1)], [6, 3], (2, 6, 6)),
+                                             ([(4, 4, 2, 1), (8, 4, 2, 1)], [10, 4], (3, 12, 12)),
+                                             ([(4, 3, 1, 1), (4, 4, 2, 1), (8, 3, 1, 1), (8, 4, 2, 1)], [16, 16, 5], (3, 8, 8)),
+                                             ([(3, 3, 2, 0)], [4], (1, 7, 9))])
+def test_small_conv(convs, fcs, shape):
+    net = wl.random_small_conv(7, shape, convs, fcs)
+    B = 3
+    x, lo, hi = wl.random_box(8, net.n_in, B, 0.05)
+    label = np.arange(B, dtype=np.int32) % fcs[-1]
+    gnet, g, o = _run_both(net, lo, hi, label)
+    compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
+@pytest.mark.parametrize("depth", [0, 1, 2, 3, 5])
+def test_depth_limited(depth):
+    net = wl.random_small_net(11, [12, 20, 18, 16, 6])
+    x, lo, hi = wl.random_box(12, 12, 3, 0.1)
+    label = np.array([0, 1, 2], np.int32)
+    gnet, g, o = _run_both(net, lo, hi, label, max_backsub_depth=depth)
+    compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
+def test_edge_cases():
+    b = _binding()
+    net = wl.random_small_net(21, [6, 8, 4])
+    gnet = b.Network(net)
+    # empty batch
+    r = gnet.certify(np.zeros((0, 6), np.float32), np.zeros((0, 6), np.float32), np.zeros((0,), np.int32))
+    assert r.concrete(3)[0].shape == (0, 4)
+    # degenerate box (eps = 0): bounds collapse to the forward pass
+    x, _, _ = wl.random_box(3, 6, 2, 0.0)
+    r = gnet.certify(x, x)
+    acts = wl.forward(net, x.astype(np.float64))
+    for k in (1, 3):
+        l, u = r.concrete(k)
+        np.testing.assert_allclose(l, acts[k], rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(u, acts[k], rtol=1e-5, atol=1e-6)
+    # malformed inputs are rejected
+    with pytest.raises(b.DpcError):
+        gnet.certify(x + 1, x)
+    with pytest.raises(b.DpcError):
+        gnet.certify(x, x, np.array([0, 9], np.int32))
+    bad = x.copy(); bad[0, 0] = np.nan
+    with pytest.raises(b.DpcError):
+        gnet.certify(bad, bad)
+    # result reuse: no new allocation, same numbers
+    r1 = gnet.certify(x, x + 0.1, np.array([0, 1], np.int32))
+    l_a = r1.concrete(3)[0].copy()
+    r2 = gnet.certify(x, x + 0.1, np.array([0, 1], np.int32), reuse=r1)
+    assert r2 is r1
+    np.testing.assert_array_equal(r1.concrete(3)[0], l_a)
+    gnet.close()
+
+
+def test_device_inputs_and_stream():
+    import torch
+    b = _binding()
+    net = wl.random_small_net(22, [16, 40, 40, 5])
+    x, lo, hi = wl.random_box(4, 16, 4, 0.1)
+    label = np.array([0, 1, 2, 3], np.int32)
+    gnet = b.Network(net)
+    ref = gnet.certify(lo, hi, label)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        dlo, dhi, dlab = (torch.from_numpy(a).cuda() for a in (lo, hi, label))
+    s.synchronize()
+    got = gnet.certify(dlo, dhi, dlab, stream=s.cuda_stream, profile=1)
+    for k in (1, 3, 5):
+        np.testing.assert_array_equal(ref.concrete(k)[0], got.concrete(k)[0])
+        np.testing.assert_array_equal(ref.concrete(k)[1], got.concrete(k)[1])
+    np.testing.assert_array_equal(ref.verdict()[1], got.verdict()[1])
+    p = got.profile()
+    assert p["contract_launches"] == 3 + 2 and p["total_ms"] > 0 and p["contract_flop"] > 0
+    gnet.close()
+
+
+# ---- the five named configurations -------------------------------------------------------------
+def test_cfg1_full():
+    w = wl.make_workload("cfg1")
+    gnet, g, o = _run_both(w.net, w.lo, w.hi, w.label)
+    flipped, worst = compare_with_oracle(w.net, w.lo, w.hi, g, o, w.label)
+    print("cfg1 worst err/tol", worst)
+    gnet.close()
+
+
+@pytest.mark.parametrize("eps_index", [0, 1, 2])
+def test_cfg2_full_batch_gpu_sampled_oracle(eps_index):
+    """GPU on the full batch of 32 (the launch configuration the benchmark times); oracle on a sample of
+    the inputs (inputs are independent, so the oracle on input b alone is the full-batch value)."""
+    w = wl.make_workload("cfg2", eps_index=eps_index)
+    b = _binding()
+    gnet = b.Network(w.net)
+    g = gnet.certify(w.lo, w.hi, w.label)
+    idx = [0, 13, 31]
+    o = oracle.run(w.net, w.lo[idx], w.hi[idx], label=w.label[idx])
+    sub = _Sub(g, idx)
+    flipped, worst = compare_with_oracle(w.net, w.lo[idx], w.hi[idx], sub, o, w.label[idx], max_flipped_inputs=1, check_samples=500)
+    print("cfg2 eps", w.eps, "worst err/tol", worst, "flipped", flipped)
+    gnet.close()
+
+
+def test_cfg5_full_batch_gpu_sampled_oracle():
+    w = wl.make_workload("cfg5")
+    b = _binding()
+    gnet = b.Network(w.net)
+    g = gnet.certify(w.lo, w.hi, w.label)
+    idx = [0, 63]
+    o = oracle.run(w.net, w.lo[idx], w.hi[idx], label=w.label[idx])
+    flipped, worst = compare_with_oracle(w.net, w.lo[idx], w.hi[idx], _Sub(g, idx), o, w.label[idx], max_flipped_inputs=1,
+                                         check_samples=200)
+    print("cfg5 worst err/tol", worst, "flipped", flipped)
+    gnet.close()
+
+
+def test_cfg3_full_batch_gpu_sampled_oracle():
+    w = wl.make_workload("cfg3")
+    b = _binding()
+    gnet = b.Network(w.net)
+    g = gnet.certify(w.lo, w.hi, w.label)
+    idx = [0, 7, 31]
+    o = oracle.run(w.net, w.lo[idx], w.hi[idx], label=w.label[idx])
+    flipped, worst = compare_with_oracle(w.net, w.lo[idx], w.hi[idx], _Sub(g, idx), o, w.label[idx], max_flipped_inputs=1,
+                                         check_samples=200)
+    print("cfg3 worst err/tol", worst, "flipped", flipped)
+    gnet.close()
+
+
+class _Sub:
+    """View of a GPU result restricted to some inputs of the batch."""
+    def __init__(self, res, idx):
+        self.res, self.idx = res, list(idx)
+
+    def concrete(self, k):
+        l, u = self.res.concrete(k)
+        return l[self.idx], u[self.idx]
+
+    def relaxation(self, k):
+        return tuple(a[self.idx] for a in self.res.relaxation(k))
+
+    def verdict(self):
+        v, m = self.res.verdict()
+        return v[self.idx], m[self.idx]
