@@ -128,7 +128,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-        default_sample = {"cfg1": 1, "cfg2": 8, "cfg3": 8, "cfg4": 1, "cfg5": 2}[args.workload]
+        default_sample = {"cfg1": 1, "cfg2": 32, "cfg3": 32, "cfg4": 2, "cfg5": 16}[args.workload]
         ns = min(B, args.cpu_sample or default_sample)
         tc = time.perf_counter()
         for w in loads:

@@ -184,7 +184,7 @@ dpc_status dpc_op_concretise(const float* C, int32_t ldc, const double* cst, int
                              float* out_l, float* out_u, void* stream);
 
 /* Tuning knob for experiments: key "contract_variant" selects the tile shape of the contraction
- * kernel (0 = default).  Results do not depend on it beyond rounding order. */
+ * kernel (-1 = chosen from the problem shape, the default).  Results do not depend on it beyond rounding order. */
 dpc_status dpc_tuning_set(const char* key, int32_t value);
 
 /* Text of the last error raised on the calling thread ("" if none). */

@@ -8,6 +8,10 @@ import os
 from typing import Optional
 
 import numpy as np
+import torch  # noqa: F401  -- imported BEFORE the library is loaded, on purpose: PyTorch ships its own
+#               libamdhip64.so.7; loading it first makes the dynamic loader resolve this library's
+#               dependency on the HIP runtime to that same copy, so the process holds ONE runtime and
+#               device pointers / streams of torch tensors are valid inside the library.
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdpcert.so")

@@ -126,13 +126,17 @@ struct dpc_result {
 
 namespace {
 
+// Per-kernel-class timing with HIP events on the launch stream.  One event is recorded whenever the
+// class of the next launch differs from the class of the previous one, so a run of back-to-back
+// launches of one class costs two events, not two per launch.
 struct Prof {
     bool on = false;
     hipStream_t s = nullptr;
-    struct Rec { int cls; hipEvent_t a, b; };
-    std::vector<Rec> recs;
+    struct Seg { int cls; hipEvent_t a, b; };
+    std::vector<Seg> segs;
     std::vector<hipEvent_t> pool;
     size_t used = 0;
+    int cur = -1;
     hipEvent_t get()
     {
         if (used == pool.size()) {
@@ -144,15 +148,21 @@ struct Prof {
     }
     void begin(int cls)
     {
-        if (!on) return;
-        Rec r{cls, get(), get()};
-        DPC_HIP(hipEventRecord(r.a, s));
-        recs.push_back(r);
+        if (!on || cls == cur) return;
+        hipEvent_t e = get();
+        DPC_HIP(hipEventRecord(e, s));
+        if (cur >= 0) segs.back().b = e;
+        segs.push_back(Seg{cls, e, nullptr});
+        cur = cls;
     }
-    void end()
+    void end() {}
+    void finish()
     {
-        if (!on) return;
-        DPC_HIP(hipEventRecord(recs.back().b, s));
+        if (!on || cur < 0) return;
+        hipEvent_t e = get();
+        DPC_HIP(hipEventRecord(e, s));
+        segs.back().b = e;
+        cur = -1;
     }
     ~Prof() { for (auto e : pool) (void)hipEventDestroy(e); }
 };
@@ -671,13 +681,14 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             prof.end();
             res->prof.other_launches++;
         }
+        prof.finish();
         if (prof.on) DPC_HIP(hipEventRecord(t1, s));
         DPC_HIP(hipStreamSynchronize(s));
         if (prof.on) {
             float ms = 0.f;
             DPC_HIP(hipEventElapsedTime(&ms, t0, t1));
             res->prof.total_ms = ms;
-            for (auto& r : prof.recs) {
+            for (auto& r : prof.segs) {
                 DPC_HIP(hipEventElapsedTime(&ms, r.a, r.b));
                 (r.cls == P_CONTRACT ? res->prof.contract_ms : r.cls == P_RELAX ? res->prof.relax_ms
                  : r.cls == P_CONC ? res->prof.concretise_ms : res->prof.other_ms) += ms;

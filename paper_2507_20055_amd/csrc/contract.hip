@@ -223,7 +223,7 @@ void launch_variant(const float* A, int64_t M, int K, int lda, const float* W, i
     DPC_HIP(hipGetLastError());
 }
 
-int g_variant = 0;
+int g_variant = -1;      // -1: chosen from the problem shape
 
 }  // namespace
 
@@ -238,11 +238,30 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
     DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0, DPC_EINVAL,
                 "contract: buffers must be 16-byte aligned");
     if (M == 0) return;
-    switch (g_variant) {
+    int variant = g_variant;
+    if (variant < 0) {
+        // Large problems: 128x128 tiles with a short K tile (small LDS footprint -> three workgroups per
+        // CU hide each other's barrier and load latency).  Small problems: 64x64 tiles so that the grid
+        // still covers the 256 CUs.
+        const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
+        variant = tiles128 >= 512 ? 10 : 9;
+    }
+    switch (variant) {
         case 1:  launch_variant<Tile<256, 128, 16, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
         case 2:  launch_variant<Tile<128, 128, 16, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
         case 3:  launch_variant<Tile<256, 128, 16, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
         case 4:  launch_variant<Tile<128, 256, 16, 64, 128>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 10: launch_variant<Tile<128, 128, 8, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 11: launch_variant<Tile<64, 64, 8, 32, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 12: launch_variant<Tile<128, 64, 16, 64, 32>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 13: launch_variant<Tile<64, 128, 8, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 14: launch_variant<Tile<128, 128, 8, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 15: launch_variant<Tile<256, 128, 8, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
         default: launch_variant<Tile<128, 128, 32, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
     }
 }

@@ -22,7 +22,7 @@ def _rows(rng, M, n, ld, zero_frac=0.05):
     return C, full
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [-1] + list(range(16)))
 @pytest.mark.parametrize("M,K,N", [(1, 8, 8), (200, 100, 784), (333, 500, 500), (1000, 10, 100), (4100, 1024, 1024),
                                    (129, 36, 260), (64, 1, 5)])
 def test_contract(M, K, N, variant):
@@ -44,7 +44,7 @@ def test_contract(M, K, N, variant):
         assert np.all(np.abs(got[:, :N] - ref) <= tol), np.abs(got[:, :N] - ref).max()
         assert np.all(got[:, N:] == 0.0)                 # padding columns are written as zeros
     finally:
-        b.dpc_tuning_set("contract_variant", 0)
+        b.dpc_tuning_set("contract_variant", -1)
 
 
 @pytest.mark.parametrize("nsides,B,R,n", [(2, 1, 10, 100), (2, 3, 37, 500), (1, 5, 9, 1024), (2, 2, 130, 784),
