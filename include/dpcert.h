@@ -183,8 +183,24 @@ dpc_status dpc_op_concretise(const float* C, int32_t ldc, const double* cst, int
                              int32_t R, int32_t n, const float* lo, const float* hi,
                              float* out_l, float* out_u, void* stream);
 
+/* Convolution contraction of a traverse iteration: coefficient rows over a convolution layer's
+ * outputs times its Convolution block (Appendix B.3: dense block x convolution block is a
+ * transposed convolution), never forming the expanded matrix.  Channel-last rows:
+ *   in : [M][ih][iw][Co] device, rows ld_in floats apart;  out: [M][oh][ow][Ci] device, ld_out apart
+ *   out[m,y,x,ci] = sum over (ky,kx,co) with y+off-ky = py*stride, x+off-kx = px*stride,
+ *                   0 <= py < ih, 0 <= px < iw, of in[m,py,px,co] * K[co,ci,ky,kx]
+ * K: [Co,Ci,kh,kw] HOST memory (uploaded for the call).  off = the layer's padding when the rows
+ * cover the whole output map, 0 for patch rows.  Columns oh*ow*Ci..ld_out-1 of out are zeroed.
+ * Synchronises the stream before returning. */
+dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int32_t ih, int32_t iw,
+                                 int32_t Co, int32_t Ci, int32_t kh, int32_t kw, int32_t stride, int32_t off,
+                                 const float* K_host, float* out, int32_t ld_out, int32_t oh, int32_t ow,
+                                 void* stream);
+
 /* Tuning knob for experiments: key "contract_variant" selects the tile shape of the contraction
- * kernel (-1 = chosen from the problem shape, the default).  Results do not depend on it beyond rounding order. */
+ * kernel (-1 = chosen from the problem shape, the default); key "conv_algo" = 1 forces the generic
+ * gather kernel for convolution contractions (0 = MFMA / small-channel kernels where they apply).
+ * Results do not depend on either beyond rounding order. */
 dpc_status dpc_tuning_set(const char* key, int32_t value);
 
 /* Text of the last error raised on the calling thread ("" if none). */

@@ -58,3 +58,24 @@ def concretise(C, cst, nsides, batch, R, lo, hi):
         else:
             res.append(k3[side] + np.where(pos, X * hi, X * lo).sum(axis=-1))
     return res[0], (res[1] if nsides == 2 else None)
+
+
+def conv_transpose_rows(rows, ih, iw, K, stride, off, oh, ow):
+    """One traverse iteration through a convolution layer: coefficient rows over the layer's outputs
+    times its expanded weight matrix (Section 3.3: the block of a convolutional layer "represents an
+    expanded convolution kernel"; Appendix B.3: the product reduces to a transposed convolution).
+    Written as the definition: the expanded matrix is built entry by entry and multiplied.
+    rows: [M, ih*iw*Co] channel-last; K: [Co, Ci, kh, kw]; output window of oh x ow positions whose
+    top-left corner is `off` inside the full transposed-convolution extent.  Returns [M, oh*ow*Ci]."""
+    K = np.asarray(K, np.float64)
+    Co, Ci, kh, kw = K.shape
+    E = np.zeros((ih * iw * Co, oh * ow * Ci))
+    for py in range(ih):
+        for px in range(iw):
+            for ky in range(kh):
+                for kx in range(kw):
+                    y, x = py * stride + ky - off, px * stride + kx - off
+                    if 0 <= y < oh and 0 <= x < ow:
+                        r0, c0 = (py * iw + px) * Co, (y * ow + x) * Ci
+                        E[r0:r0 + Co, c0:c0 + Ci] += K[:, :, ky, kx]
+    return np.asarray(rows, np.float64) @ E

@@ -57,6 +57,8 @@ EXPORTS = {
     "dpc_op_contract": [c_vp, c_i64, c_i32, c_i32, c_vp, c_i32, c_i32, c_vp, c_i32, c_vp],
     "dpc_op_relax_step": [c_vp, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, c_vp],
     "dpc_op_concretise": [c_vp, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp],
+    "dpc_op_conv_transpose": [c_vp, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_vp,
+                              c_vp, c_i32, c_i32, c_i32, c_vp],
     "dpc_tuning_set": [ctypes.c_char_p, c_i32],
 }
 for _name, _args in EXPORTS.items():
@@ -239,3 +241,11 @@ def dpc_op_relax_step(C, cst, nsides: int, batch: int, R: int, n: int, lam, mu, 
 def dpc_op_concretise(C, cst, nsides: int, batch: int, R: int, n: int, lo, hi, out_l, out_u, stream: int = 0):
     _check(_lib.dpc_op_concretise(C.data_ptr(), C.stride(0), cst.data_ptr(), nsides, batch, R, n,
                                   lo.data_ptr(), hi.data_ptr(), out_l.data_ptr(), _ptr(out_u), stream or None))
+
+
+def dpc_op_conv_transpose(inp, ih: int, iw: int, Co: int, K_host, stride: int, off: int, out, oh: int, ow: int, stream: int = 0):
+    K_host = np.ascontiguousarray(K_host, dtype=np.float32)
+    Co2, Ci, kh, kw = K_host.shape
+    assert Co2 == Co
+    _check(_lib.dpc_op_conv_transpose(inp.data_ptr(), inp.shape[0], inp.stride(0), ih, iw, Co, Ci, kh, kw, stride, off,
+                                      K_host.ctypes.data, out.data_ptr(), out.stride(0), oh, ow, stream or None))

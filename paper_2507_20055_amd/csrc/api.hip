@@ -855,11 +855,34 @@ dpc_status dpc_op_concretise(const float* C, int32_t ldc, const double* cst, int
     });
 }
 
+dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int32_t ih, int32_t iw, int32_t Co, int32_t Ci,
+                                 int32_t kh, int32_t kw, int32_t stride, int32_t off, const float* K_host,
+                                 float* out, int32_t ld_out, int32_t oh, int32_t ow, void* stream)
+{
+    return guarded([&] {
+        DPC_REQUIRE(in && out && K_host && M >= 0, DPC_EINVAL, "dpc_op_conv_transpose: NULL argument");
+        DPC_REQUIRE(ih >= 1 && iw >= 1 && Co >= 1 && Ci >= 1 && kh >= 1 && kw >= 1 && stride >= 1 && off >= 0 && oh >= 1 && ow >= 1,
+                    DPC_EINVAL, "dpc_op_conv_transpose: bad geometry");
+        DPC_REQUIRE(oh + off <= (ih - 1) * stride + kh && ow + off <= (iw - 1) * stride + kw, DPC_EINVAL,
+                    "dpc_op_conv_transpose: output window exceeds the transposed convolution's extent");
+        DPC_REQUIRE((int64_t)ih * iw * Co <= (1 << 24) && (int64_t)oh * ow * Ci <= (1 << 24), DPC_EINVAL,
+                    "dpc_op_conv_transpose: rows too long");
+        ConvGeom g{Ci, oh, ow, Co, kh, kw, stride, off, ih, iw};
+        ConvWeights w;
+        std::vector<float> zero_bias((size_t)Co, 0.0f);
+        upload_conv_weights(g, K_host, zero_bias.data(), w);
+        hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+        launch_conv_transpose_rows(in, M, ld_in, ih, iw, g, w, out, ld_out, oh, ow, off, st);
+        DPC_HIP(hipStreamSynchronize(st));      // the temporary weights are freed on return
+    });
+}
+
 dpc_status dpc_tuning_set(const char* key, int32_t value)
 {
     return guarded([&] {
         DPC_REQUIRE(key, DPC_EINVAL, "dpc_tuning_set: NULL key");
         if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
+        else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
     });
 }

@@ -69,6 +69,11 @@ void launch_concretise_patch(const float* C, int ldc, const double* cst, int nsi
 double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
                                   const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
 
+// MFMA implicit-GEMM / small-channel kernels for the same operation; false = shape not covered.
+bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
+                                const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
+void set_conv_algo(int v);
+
 // Validation of certify inputs on the device.  Returns 0 = fine, 1 = lo > hi or non-finite, 2 = bad label.
 // `flag` is a device int32 scratch word.  Synchronises the stream.
 int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,

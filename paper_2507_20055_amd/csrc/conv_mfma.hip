@@ -1,0 +1,358 @@
+// Transposed convolution of coefficient rows through a convolution layer (one traverse iteration
+// when the bounds of the layer below are a Convolution block): fp32 MFMA implicit GEMM, and a
+// plain-ALU kernel for layers with very few input channels (the image itself).
+//
+//   out[m, y, x, ci] = sum over taps (ky,kx) and channels co with (y+off-ky) = py*s, (x+off-kx) = px*s,
+//                      0 <= py < ih, 0 <= px < iw, of in[m, py, px, co] * K[co, ci, ky, kx]
+//
+// Gather form: every output coefficient is produced by one accumulator, so the summation order is
+// fixed and no atomics are needed.  With stride s the output positions fall into s*s parity classes
+// (cy, cx) = ((y+off) mod s, (x+off) mod s); a class only meets the taps ky = cy (mod s), kx = cx
+// (mod s), so inside a class the operation is a stride-1 correlation with a sub-sampled kernel.
+//
+// MFMA kernel (v_mfma_f32_32x32x2_f32): GEMM rows = 32 output positions of one class, taken from the
+// flattened (row of the block, position) list so that small patches still fill whole tiles; GEMM
+// columns = output channels ci; reduction = (tap, co).  A workgroup (4 wavefronts) owns up to 256
+// list entries per class; each wavefront owns 2 position tiles x (Ci/32) channel tiles.  The input
+// patches of the workgroup's rows sit in LDS ((H,W,C) order, position stride Co+4 floats to spread
+// banks); a lane fetches the four consecutive channels it feeds with one 16-byte read at an address
+// it computes from (position, tap), or from a zero block when the tap falls outside the patch.  The
+// kernel slice of the current tap ([Co][Ci]) is staged through double-buffered LDS.
+#include "conv.h"
+
+namespace dpc {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kCtThreads = 256;
+constexpr int kCtEntries = 256;          // list entries per class per workgroup (4 waves x 2 tiles x 32)
+
+struct CtArgs {
+    const float* in; long long M; int ld_in; int ih, iw, Co;
+    const float* taps; int Ci, kh, kw, s, off;
+    float* out; int ld_out; int oh, ow;
+    int RB;          // rows per workgroup
+    int pstride;     // LDS floats per input position (Co + 4)
+    int rowstride;   // LDS floats per input row patch (ih*iw*pstride)
+};
+
+template <int NT>
+__global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs a)
+{
+    extern __shared__ float4 lds4[];
+    float* sIn = reinterpret_cast<float*>(lds4);                       // [RB*rowstride] + zero block [pstride]
+    const int in_floats = a.RB * a.rowstride;
+    const int zoff = in_floats;                                        // zero block
+    constexpr int BS = NT * 32 + 8;                                    // floats per kernel-slice row
+    float* sB = sIn + in_floats + a.pstride;                           // [2][Co*BS]
+    int4* sTab = reinterpret_cast<int4*>(sB + 2 * a.Co * BS);          // [256] {e0, py0, px0, outoff}
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
+    const long long m0 = (long long)blockIdx.x * a.RB;
+    const int q0 = blockIdx.y * kCtEntries;
+
+    // ---- stage the input patches of this workgroup's rows ----
+    {
+        const int c4n = a.Co >> 2, npos = a.ih * a.iw;
+        const int total = a.RB * npos * c4n;
+        for (int idx = tid; idx < total; idx += kCtThreads) {
+            const int c4 = idx % c4n, t = idx / c4n;
+            const int pos = t % npos, ml = t / npos;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m0 + ml < a.M) v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + (size_t)pos * a.Co + c4 * 4);
+            *reinterpret_cast<float4*>(sIn + ml * a.rowstride + pos * a.pstride + c4 * 4) = v;
+        }
+        for (int i = tid; i < a.pstride; i += kCtThreads) sIn[zoff + i] = 0.0f;
+        for (int i = tid; i < 2 * a.Co * BS; i += kCtThreads) sB[i] = 0.0f;   // channel padding of the slices stays zero
+        // padding columns of the output rows
+        if (blockIdx.y == 0) {
+            const int elems = a.oh * a.ow * a.Ci, padn = a.ld_out - elems;
+            for (int i = tid; i < a.RB * padn; i += kCtThreads) {
+                const int ml = i / padn, c = i - ml * padn;
+                if (m0 + ml < a.M) a.out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
+            }
+        }
+    }
+    __syncthreads();
+
+    const int slice4 = a.Co * a.Ci / 4;                  // float4 per kernel slice
+    const int ci4n = a.Ci >> 2;
+
+    for (int cy = 0; cy < a.s; ++cy) {
+        // rows y of this class: (y + off) mod s == cy  ->  y = y0 + s*iy
+        const int y0 = ((cy - a.off) % a.s + a.s) % a.s;
+        const int Hc = y0 < a.oh ? (a.oh - y0 + a.s - 1) / a.s : 0;
+        const int base_y = (y0 + a.off - cy) / a.s;
+        const int nky = cy < a.kh ? (a.kh - cy + a.s - 1) / a.s : 0;
+        for (int cx = 0; cx < a.s; ++cx) {
+            const int x0 = ((cx - a.off) % a.s + a.s) % a.s;
+            const int Wc = x0 < a.ow ? (a.ow - x0 + a.s - 1) / a.s : 0;
+            const int base_x = (x0 + a.off - cx) / a.s;
+            const int nkx = cx < a.kw ? (a.kw - cx + a.s - 1) / a.s : 0;
+            const int Pc = Hc * Wc;
+            if (Pc == 0 || q0 >= a.RB * Pc) continue;           // uniform over the workgroup
+
+            // ---- table of this class's list entries ----
+            {
+                const int q = q0 + tid;
+                int4 e = make_int4(0, 0, 0, -1);
+                if (q < a.RB * Pc) {
+                    const int ml = q / Pc, pc = q - ml * Pc;
+                    const int iy = pc / Wc, ix = pc - iy * Wc;
+                    if (m0 + ml < a.M) {
+                        const int y = y0 + a.s * iy, x = x0 + a.s * ix;
+                        e.x = ml * a.rowstride + ((base_y + iy) * a.iw + (base_x + ix)) * a.pstride;
+                        e.y = base_y + iy;
+                        e.z = base_x + ix;
+                        e.w = ml * a.ld_out + (y * a.ow + x) * a.Ci;
+                    }
+                }
+                sTab[tid] = e;
+            }
+            __syncthreads();
+
+            int e0[2], py0[2], px0[2];
+            bool live[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int4 e = sTab[wave * 64 + t * 32 + l32];
+                e0[t] = e.x + 4 * kq; py0[t] = e.y; px0[t] = e.z; live[t] = e.w >= 0;
+            }
+            floatx16 acc[2][NT];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[t][n][v] = 0.0f;
+
+            const int ntaps = nky * nkx;
+            constexpr int SL = 4;                                // float4 per thread per slice, at most (Co*Ci <= 4096)
+            float4 rs[SL];
+            auto load_slice = [&](int ti) {
+                const int jy = ti / nkx, jx = ti - jy * nkx;
+                const float* src = a.taps + (size_t)((cy + a.s * jy) * a.kw + (cx + a.s * jx)) * a.Co * a.Ci;
+#pragma unroll
+                for (int i = 0; i < SL; ++i) {
+                    const int idx = tid + kCtThreads * i;
+                    if (idx < slice4) rs[i] = *reinterpret_cast<const float4*>(src + (size_t)idx * 4);
+                }
+            };
+            auto store_slice = [&](int buf) {
+#pragma unroll
+                for (int i = 0; i < SL; ++i) {
+                    const int idx = tid + kCtThreads * i;
+                    if (idx < slice4) {
+                        const int co = idx / ci4n, c4 = idx - co * ci4n;
+                        *reinterpret_cast<float4*>(sB + buf * a.Co * BS + co * BS + c4 * 4) = rs[i];
+                    }
+                }
+            };
+            if (ntaps > 0) { load_slice(0); store_slice(0); }
+            __syncthreads();
+
+            for (int ti = 0; ti < ntaps; ++ti) {
+                const int buf = ti & 1;
+                if (ti + 1 < ntaps) load_slice(ti + 1);
+                const int jy = ti / nkx, jx = ti - jy * nkx;
+                int addr[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int py = py0[t] - jy, px = px0[t] - jx;
+                    const bool ok = live[t] && py >= 0 && py < a.ih && px >= 0 && px < a.iw;
+                    addr[t] = ok ? e0[t] - (jy * a.iw + jx) * a.pstride : zoff + 4 * kq;
+                }
+                const float* pb = sB + buf * a.Co * BS + l32;
+                for (int g = 0; g < (a.Co >> 3); ++g) {
+                    float4 av[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) av[t] = *reinterpret_cast<const float4*>(sIn + addr[t] + 8 * g);
+                    float b[4][NT];
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int n = 0; n < NT; ++n) b[s][n] = pb[(8 * g + 4 * kq + s) * BS + n * 32];
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const float x = s == 0 ? av[t].x : s == 1 ? av[t].y : s == 2 ? av[t].z : av[t].w;
+#pragma unroll
+                            for (int n = 0; n < NT; ++n)
+                                acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, b[s][n], acc[t][n], 0, 0, 0);
+                        }
+                }
+                if (ti + 1 < ntaps) store_slice(buf ^ 1);
+                __syncthreads();
+            }
+
+            // ---- epilogue: accumulator register 4*i+j of a lane is list entry 8*i + 4*kq + j, channel l32 ----
+            float* obase = a.out + m0 * a.ld_out;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int oo = sTab[wave * 64 + t * 32 + 8 * i + 4 * kq + j].w;
+                        if (oo < 0) continue;
+#pragma unroll
+                        for (int n = 0; n < NT; ++n) {
+                            const int ci = n * 32 + l32;
+                            if (ci < a.Ci) obase[oo + ci] = acc[t][n][4 * i + j];
+                        }
+                    }
+            __syncthreads();          // the table and slice buffers are rebuilt by the next class
+        }
+    }
+}
+
+// Few input channels (CI <= 4, e.g. the image): one thread per (row, output position), channel
+// accumulators in registers, kernel values read with wave-uniform addresses.
+template <int CI>
+__global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(CtArgs a, int yrows_per_block, int lds_rows)
+{
+    extern __shared__ float4 lds4[];
+    float* sIn = reinterpret_cast<float*>(lds4);
+    const int tid = threadIdx.x;
+    const long long m0 = (long long)blockIdx.x * a.RB;
+    // output rows [yb, ye) of this block and the input rows [r_lo, r_hi) they can reach
+    const int yb = blockIdx.y * yrows_per_block, ye = min(a.oh, yb + yrows_per_block);
+    int r_lo = yb + a.off - (a.kh - 1);
+    r_lo = r_lo <= 0 ? 0 : r_lo / a.s;
+    const int r_hi = min(a.ih, (ye - 1 + a.off) / a.s + 1);
+    const int nrows = max(0, r_hi - r_lo);                 // <= lds_rows by construction on the host
+    const int c4n = a.Co >> 2, rowfl = lds_rows * a.iw * a.pstride;   // LDS floats per network row
+    for (int idx = tid; idx < a.RB * nrows * a.iw * c4n; idx += kCtThreads) {
+        const int c4 = idx % c4n, t = idx / c4n;
+        const int pos = t % (nrows * a.iw), ml = t / (nrows * a.iw);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (m0 + ml < a.M)
+            v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + ((size_t)r_lo * a.iw + pos) * a.Co + c4 * 4);
+        *reinterpret_cast<float4*>(sIn + ml * rowfl + pos * a.pstride + c4 * 4) = v;
+    }
+    const int P = a.oh * a.ow, elems = P * CI, padn = a.ld_out - elems;
+    if (blockIdx.y == 0)
+        for (int i = tid; i < a.RB * padn; i += kCtThreads) {
+            const int ml = i / padn, c = i - ml * padn;
+            if (m0 + ml < a.M) a.out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
+        }
+    __syncthreads();
+    const int span = (ye - yb) * a.ow;
+    for (int e = tid; e < a.RB * span; e += kCtThreads) {
+        const int ml = e / span, p = yb * a.ow + (e - ml * span);
+        if (m0 + ml >= a.M) continue;
+        const int y = p / a.ow, x = p - y * a.ow;
+        float acc[CI];
+#pragma unroll
+        for (int c = 0; c < CI; ++c) acc[c] = 0.0f;
+        for (int ky = 0; ky < a.kh; ++ky) {
+            const int ty = y + a.off - ky;
+            const int py = ty / a.s;
+            const bool oky = ty >= 0 && py * a.s == ty && py < a.ih;
+            for (int kx = 0; kx < a.kw; ++kx) {
+                const int tx = x + a.off - kx;
+                const int px = tx / a.s;
+                if (!(oky && tx >= 0 && px * a.s == tx && px < a.iw)) continue;
+                const float4* src = reinterpret_cast<const float4*>(sIn + ml * rowfl + ((py - r_lo) * a.iw + px) * a.pstride);
+                const float* kt = a.taps + (size_t)(ky * a.kw + kx) * a.Co * CI;
+                for (int c4 = 0; c4 < c4n; ++c4) {
+                    const float4 v = src[c4];
+                    const float xs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int c = 0; c < CI; ++c) acc[c] = fmaf(xs[u], kt[(c4 * 4 + u) * CI + c], acc[c]);
+                }
+            }
+        }
+        float* dst = a.out + (m0 + ml) * a.ld_out + (size_t)p * CI;
+#pragma unroll
+        for (int c = 0; c < CI; ++c) dst[c] = acc[c];
+    }
+}
+
+}  // namespace
+
+// Returns false when the shape is outside what these kernels cover (the caller then uses the
+// generic gather kernel).
+bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
+                                const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s)
+{
+    if (g.Co % 8 != 0 || ld_in % 4 != 0 || ((uintptr_t)in % 16) != 0) return false;
+    CtArgs a{};
+    a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
+    a.taps = w.taps; a.Ci = g.Ci; a.kh = g.kh; a.kw = g.kw; a.s = g.stride; a.off = off;
+    a.out = out; a.ld_out = ld_out; a.oh = oh; a.ow = ow;
+    a.pstride = g.Co + 4;
+    a.rowstride = ih * iw * a.pstride;
+    const size_t row_bytes = (size_t)a.rowstride * 4;
+    constexpr size_t kLdsBudget = 150 * 1024;
+
+    if (g.Ci <= 4) {
+        // output rows per workgroup: about 256 positions; input rows those can reach: yr/s + (kh-1)/s + 2
+        const int P = oh * ow;
+        int yr = oh, RB = 1;
+        if (P > 256) yr = std::max(1, 256 / ow);
+        const int lds_rows = std::min(ih, (yr + g.stride - 1) / g.stride + (g.kh - 1) / g.stride + 2);
+        const size_t rb_bytes = (size_t)lds_rows * iw * a.pstride * 4;
+        if (P <= 256) RB = (int)std::max<int64_t>(1, std::min<int64_t>(256 / P, (int64_t)(48 * 1024 / rb_bytes)));
+        if ((size_t)RB * rb_bytes > kLdsBudget) return false;
+        a.RB = RB;
+        dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div(oh, yr));
+        const size_t lds = (size_t)RB * rb_bytes;
+        auto launch = [&](auto kern) {
+            static bool configured = false;
+            if (!configured) {
+                DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)kLdsBudget));
+                configured = true;
+            }
+            hipLaunchKernelGGL(kern, grid, dim3(kCtThreads), lds, s, a, yr, lds_rows);
+        };
+        switch (g.Ci) {
+            case 1: launch(&conv_transpose_smallci_kernel<1>); break;
+            case 2: launch(&conv_transpose_smallci_kernel<2>); break;
+            case 3: launch(&conv_transpose_smallci_kernel<3>); break;
+            default: launch(&conv_transpose_smallci_kernel<4>); break;
+        }
+        DPC_HIP(hipGetLastError());
+        return true;
+    }
+
+    if (g.Ci % 4 != 0 || g.Ci > 64 || g.Co * g.Ci > 4096) return false;   // a kernel slice is staged as at most 4 float4 per thread
+    const int NT = (g.Ci + 31) / 32;
+    // largest class decides how many rows fill the 256 list entries of a workgroup
+    const int Pc_max = (int)(ceil_div(oh, g.stride) * ceil_div(ow, g.stride));
+    const size_t fixed = (size_t)a.pstride * 4 + 2 * (size_t)g.Co * (NT * 32 + 8) * 4 + 256 * 16;
+    int RB = std::max(1, kCtEntries / std::max(Pc_max, 1));
+    // prefer two workgroups per CU when the patches allow it
+    while (RB > 1 && (size_t)RB * row_bytes + fixed > 72 * 1024) --RB;
+    if ((size_t)RB * row_bytes + fixed > kLdsBudget) return false;
+    a.RB = RB;
+    const size_t lds = (size_t)RB * row_bytes + fixed;
+    dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div((int64_t)RB * Pc_max, kCtEntries));
+    if (NT == 1) {
+        static bool configured = false;
+        if (!configured) {
+            DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<1>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget));
+            configured = true;
+        }
+        hipLaunchKernelGGL(conv_transpose_mfma_kernel<1>, grid, dim3(kCtThreads), lds, s, a);
+    } else {
+        static bool configured = false;
+        if (!configured) {
+            DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<2>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget));
+            configured = true;
+        }
+        hipLaunchKernelGGL(conv_transpose_mfma_kernel<2>, grid, dim3(kCtThreads), lds, s, a);
+    }
+    DPC_HIP(hipGetLastError());
+    return true;
+}
+
+}  // namespace dpc

@@ -112,3 +112,55 @@ def test_ops_reject_bad_shapes():
         b.dpc_op_contract(A, 40, A, 32, A)                # K larger than lda
     with pytest.raises(b.DpcError):
         b.dpc_op_contract(A[:, 1:], 8, A, 8, A)           # misaligned / odd leading dimension
+
+
+CONV_CASES = [
+    # ih, iw, Co, Ci, k, stride, off, dense?   (dense rows: whole map, off = pad; patch rows: off = 0)
+    (4, 4, 16, 3, 4, 2, 0, False),      # cfg3 conv2 rows through conv1
+    (8, 8, 32, 16, 4, 2, 1, True),      # cfg3 FC rows through conv2
+    (16, 16, 16, 3, 4, 2, 1, True),     # cfg3 FC rows through conv1
+    (4, 4, 32, 3, 3, 1, 0, False),      # cfg4 conv2 rows through conv1
+    (3, 3, 32, 32, 4, 2, 0, False),     # cfg4 conv3 rows through conv2
+    (8, 8, 32, 3, 3, 1, 0, False),
+    (4, 4, 64, 32, 3, 1, 0, False),     # cfg4 conv4 rows through conv3
+    (6, 6, 32, 32, 4, 2, 0, False),
+    (14, 14, 32, 3, 3, 1, 0, False),
+    (8, 8, 64, 64, 4, 2, 1, True),      # cfg4 FC rows through conv4
+    (16, 16, 64, 32, 3, 1, 1, True),
+    (16, 16, 32, 32, 4, 2, 1, True),
+    (32, 32, 32, 3, 3, 1, 1, True),
+    (5, 7, 8, 12, 3, 2, 0, False),      # odd sizes, stride 2 with a 3x3 kernel (a class without taps)
+    (3, 3, 6, 5, 2, 1, 0, False),       # channels not multiples of 8 / 4: generic kernel
+    (20, 20, 16, 8, 3, 1, 1, True),     # more than 256 positions per class: chunked
+]
+
+
+@pytest.mark.parametrize("algo", [0, 1])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_transpose(case, algo):
+    from paper_2507_20055_amd import binding as b
+    ih, iw, Co, Ci, k, s, off, dense = case
+    if dense:
+        oh = (ih - 1) * s + k - 2 * off
+        ow = (iw - 1) * s + k - 2 * off
+        if s == 2 and k == 4:
+            oh, ow = 2 * ih, 2 * iw
+    else:
+        oh, ow = (ih - 1) * s + k, (iw - 1) * s + k
+    rng = np.random.default_rng(ih * 100 + Co + Ci)
+    for M in (1, 37):
+        n_in, n_out = ih * iw * Co, oh * ow * Ci
+        ld_in, ld_out = (n_in + 3) // 4 * 4, (n_out + 31) // 32 * 32
+        rows, rows_f = _rows(rng, M, n_in, ld_in)
+        K = rng.normal(size=(Co, Ci, k, k)).astype(np.float32)
+        out = torch.full((M, ld_out), float("nan"), device="cuda")
+        b.dpc_tuning_set("conv_algo", algo)
+        try:
+            b.dpc_op_conv_transpose(_dev(rows_f), ih, iw, Co, K, s, off, out, oh, ow)
+        finally:
+            b.dpc_tuning_set("conv_algo", 0)
+        got = out.cpu().numpy()
+        ref = ops.conv_transpose_rows(rows, ih, iw, K, s, off, oh, ow)
+        mag = ops.conv_transpose_rows(np.abs(rows), ih, iw, np.abs(K), s, off, oh, ow)
+        assert np.all(np.abs(got[:, :n_out] - ref) <= 2e-6 * mag + 1e-6), np.abs(got[:, :n_out] - ref).max()
+        assert np.all(got[:, n_out:] == 0.0)

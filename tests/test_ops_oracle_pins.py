@@ -48,3 +48,21 @@ def test_concretise_hand_values():
     l, u = ops.concretise(C, np.array([0.5, 0.5]), 2, 1, 1, np.array([[-1.0, 3.0]]), np.array([[2.0, 5.0]]))
     np.testing.assert_allclose(l, [[0.5 + 1 * -1 - 2 * 5]])
     np.testing.assert_allclose(u, [[0.5 + 1 * 2 - 2 * 3]])
+
+
+def test_conv_transpose_rows_is_the_expanded_matrix():
+    """ops.conv_transpose_rows applied to the identity gives the expanded convolution matrix; the
+    same matrix obtained by pushing unit vectors through an ordinary convolution (independent code,
+    (C,H,W) order) must agree after the channel-last permutation."""
+    import pytest
+    for (Ci, H, W, Co, k, s, p) in [(2, 5, 6, 3, 3, 1, 1), (3, 8, 8, 4, 4, 2, 1), (1, 7, 5, 2, 3, 2, 0)]:
+        rng = np.random.default_rng(Ci + H)
+        K = rng.normal(size=(Co, Ci, k, k)).astype(np.float32)
+        L = wl.Layer("conv", K, np.zeros(Co, np.float32), stride=s, pad=p, in_shape=(Ci, H, W))
+        _, Ho, Wo = L.out_shape
+        n_in, n_out = Ci * H * W, Co * Ho * Wo
+        D = wl.conv_forward(np.eye(n_in), L).T                         # [n_out, n_in], both (C,H,W)
+        E = ops.conv_transpose_rows(np.eye(n_out), Ho, Wo, K, s, p, H, W)   # [n_out, n_in], both (H,W,C)
+        perm_out = np.arange(n_out).reshape(Co, Ho, Wo).transpose(1, 2, 0).ravel()   # hwc position -> chw index
+        perm_in = np.arange(n_in).reshape(Ci, H, W).transpose(1, 2, 0).ravel()
+        np.testing.assert_allclose(E, D[np.ix_(perm_out, perm_in)], rtol=0, atol=1e-12)
