@@ -210,9 +210,14 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 }
 
 // Few input channels (CI <= 4, e.g. the image): one thread per (row, output position), channel
-// accumulators in registers, kernel values read with wave-uniform addresses.
+// accumulators in registers.  Control flow is kept uniform (a tap that falls outside the patch reads
+// a block of zeros instead of being skipped) and the kernel pointer is restrict-qualified, so the
+// compiler keeps the kernel values in scalar registers: the inner loop is one 16-byte LDS read per
+// 4*CI FMAs.
 template <int CI>
-__global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(CtArgs a, int yrows_per_block, int lds_rows)
+__global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(
+    const float* __restrict__ in, const float* __restrict__ taps, float* __restrict__ out, CtArgs a,
+    int yrows_per_block, int lds_rows)
 {
     extern __shared__ float4 lds4[];
     float* sIn = reinterpret_cast<float*>(lds4);
@@ -225,25 +230,28 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(CtAr
     const int r_hi = min(a.ih, (ye - 1 + a.off) / a.s + 1);
     const int nrows = max(0, r_hi - r_lo);                 // <= lds_rows by construction on the host
     const int c4n = a.Co >> 2, rowfl = lds_rows * a.iw * a.pstride;   // LDS floats per network row
+    const int zoff = a.RB * rowfl;                                    // block of zeros [pstride]
     for (int idx = tid; idx < a.RB * nrows * a.iw * c4n; idx += kCtThreads) {
         const int c4 = idx % c4n, t = idx / c4n;
         const int pos = t % (nrows * a.iw), ml = t / (nrows * a.iw);
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (m0 + ml < a.M)
-            v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + ((size_t)r_lo * a.iw + pos) * a.Co + c4 * 4);
+            v = *reinterpret_cast<const float4*>(in + (m0 + ml) * a.ld_in + ((size_t)r_lo * a.iw + pos) * a.Co + c4 * 4);
         *reinterpret_cast<float4*>(sIn + ml * rowfl + pos * a.pstride + c4 * 4) = v;
     }
+    for (int i = tid; i < a.pstride; i += kCtThreads) sIn[zoff + i] = 0.0f;
     const int P = a.oh * a.ow, elems = P * CI, padn = a.ld_out - elems;
     if (blockIdx.y == 0)
         for (int i = tid; i < a.RB * padn; i += kCtThreads) {
             const int ml = i / padn, c = i - ml * padn;
-            if (m0 + ml < a.M) a.out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
+            if (m0 + ml < a.M) out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
         }
     __syncthreads();
-    const int span = (ye - yb) * a.ow;
-    for (int e = tid; e < a.RB * span; e += kCtThreads) {
+    const int span = (ye - yb) * a.ow, total = a.RB * span;
+    for (int base = 0; base < total; base += kCtThreads) {
+        const int e = base + tid;
         const int ml = e / span, p = yb * a.ow + (e - ml * span);
-        if (m0 + ml >= a.M) continue;
+        const bool active = e < total && m0 + ml < a.M;
         const int y = p / a.ow, x = p - y * a.ow;
         float acc[CI];
 #pragma unroll
@@ -251,13 +259,15 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(CtAr
         for (int ky = 0; ky < a.kh; ++ky) {
             const int ty = y + a.off - ky;
             const int py = ty / a.s;
-            const bool oky = ty >= 0 && py * a.s == ty && py < a.ih;
+            const bool oky = active && ty >= 0 && py * a.s == ty && py < a.ih;
             for (int kx = 0; kx < a.kw; ++kx) {
                 const int tx = x + a.off - kx;
                 const int px = tx / a.s;
-                if (!(oky && tx >= 0 && px * a.s == tx && px < a.iw)) continue;
-                const float4* src = reinterpret_cast<const float4*>(sIn + ml * rowfl + ((py - r_lo) * a.iw + px) * a.pstride);
-                const float* kt = a.taps + (size_t)(ky * a.kw + kx) * a.Co * CI;
+                const bool ok = oky && tx >= 0 && px * a.s == tx && px < a.iw;
+                const float4* src = reinterpret_cast<const float4*>(
+                    sIn + (ok ? ml * rowfl + ((py - r_lo) * a.iw + px) * a.pstride : zoff));
+                const float* kt = taps + (size_t)(ky * a.kw + kx) * a.Co * CI;
+#pragma unroll 2
                 for (int c4 = 0; c4 < c4n; ++c4) {
                     const float4 v = src[c4];
                     const float xs[4] = {v.x, v.y, v.z, v.w};
@@ -268,9 +278,11 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(CtAr
                 }
             }
         }
-        float* dst = a.out + (m0 + ml) * a.ld_out + (size_t)p * CI;
+        if (active) {
+            float* dst = out + (m0 + ml) * a.ld_out + (size_t)p * CI;
 #pragma unroll
-        for (int c = 0; c < CI; ++c) dst[c] = acc[c];
+            for (int c = 0; c < CI; ++c) dst[c] = acc[c];
+        }
     }
 }
 
@@ -299,10 +311,10 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         const int lds_rows = std::min(ih, (yr + g.stride - 1) / g.stride + (g.kh - 1) / g.stride + 2);
         const size_t rb_bytes = (size_t)lds_rows * iw * a.pstride * 4;
         if (P <= 256) RB = (int)std::max<int64_t>(1, std::min<int64_t>(256 / P, (int64_t)(48 * 1024 / rb_bytes)));
-        if ((size_t)RB * rb_bytes > kLdsBudget) return false;
+        if ((size_t)RB * rb_bytes + (size_t)a.pstride * 4 > kLdsBudget) return false;
         a.RB = RB;
         dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div(oh, yr));
-        const size_t lds = (size_t)RB * rb_bytes;
+        const size_t lds = (size_t)RB * rb_bytes + (size_t)a.pstride * 4;
         auto launch = [&](auto kern) {
             static bool configured = false;
             if (!configured) {
@@ -310,7 +322,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
                                             (int)kLdsBudget));
                 configured = true;
             }
-            hipLaunchKernelGGL(kern, grid, dim3(kCtThreads), lds, s, a, yr, lds_rows);
+            hipLaunchKernelGGL(kern, grid, dim3(kCtThreads), lds, s, in, w.taps, out, a, yr, lds_rows);
         };
         switch (g.Ci) {
             case 1: launch(&conv_transpose_smallci_kernel<1>); break;
