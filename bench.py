@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=0, help="inputs per eps given to the CPU oracle (0 = default)")
     ap.add_argument("--variant", type=int, default=-1, help="contraction tile variant (tuning)")
     ap.add_argument("--fuse", type=int, default=1)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one plain 256 MiB device-to-device copy first (known size, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -49,6 +51,13 @@ def main():
     torch.cuda.set_device(0)
     if args.variant >= 0:
         binding.dpc_tuning_set("contract_variant", args.variant)
+
+    if args.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, device="cuda", dtype=torch.float32).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     n_eps = len(wl.CONFIGS[args.workload]["eps"])
     loads = [wl.make_workload(args.workload, eps_index=i) for i in range(n_eps)]

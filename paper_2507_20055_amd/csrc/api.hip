@@ -28,6 +28,7 @@ void set_error(const char* fmt, ...)
 }
 
 void set_contract_variant(int v);
+void set_rows_per_wave(int v);
 
 namespace {
 
@@ -98,6 +99,12 @@ struct dpc_network {
     DevBuf<float> buf[2];
     DevBuf<double> cst;
     DevBuf<float> stage;                   // staging for layout permutations / margins
+    // fused-epilogue state: packed per-(side, input, neuron) parameters of every ReLU layer (index 0:
+    // the box), and the slots that collect row-constant partial sums of the fused contractions
+    std::vector<std::unique_ptr<DevBuf<float>>> pk;
+    DevBuf<float> part;
+    int64_t part_stride = 0;
+    static constexpr int kMaxSlots = 96;
 
     int size_of(int idx) const { return idx == 0 ? n0 : layers[idx - 1]->n_out; }
     int ld_of(int idx) const { return (int)round_up(size_of(idx), kLdAlign); }
@@ -259,6 +266,10 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     bool bias_folded = false;
     int depth = 0;
     const int64_t M = (int64_t)nsides * B * R;
+    bool fused_relu = false;
+    int slots = 0;                 // row-constant partial-sum slots written by fused epilogues so far
+    bool concretised = false;      // the last contraction already reduced the rows against the box
+    const bool may_fuse = P.opt->fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
 
     auto relax = [&](const float* la, const float* m, const float* v, const Layer* bias_of) {
         const int n_at = net->size_of(at);
@@ -289,15 +300,36 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             if (L.kind == AFFINE) {
                 DPC_REQUIRE(!f.patch, DPC_EUNSUPPORTED, "patch-form rows cannot cross a fully-connected layer");
                 const int ld_prev = net->ld_of(at - 1);
-                launch_contract(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, P.s);
+                // The step that follows (ReLU step of the layer below, or the concretisation at the input)
+                // runs in the contraction's epilogue when its packed parameters exist.
+                const int below = at - 1;
+                const bool to_input = below == 0 && !keep_sym;
+                const bool to_relu = below > 0 && net->layers[below - 1]->kind == RELU;
+                int used = -1;
+                fused_relu = false;
+                if (may_fuse && (to_input || to_relu) && net->pk[below] && net->pk[below]->p) {
+                    ContractEpilogue e{net->pk[below]->p, ld_prev, R, nsides * B,
+                                       net->part.p + (size_t)slots * net->part_stride, net->part_stride,
+                                       dpc_network::kMaxSlots - slots, to_input ? 0 : 1};
+                    used = launch_contract_fused(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, e, P.s);
+                }
+                if (used >= 0) {
+                    slots += used;
+                    if (to_input) concretised = true;
+                    else { --at; ++depth; fused_relu = true; }       // the ReLU layer below has been replaced too
+                } else {
+                    launch_contract(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, P.s);
+                }
                 res->prof.contract_flop += 2.0 * (double)M * n_at * n_prev;
                 f.ld = ld_prev;
             } else if (f.patch) {
+                fused_relu = false;
                 const Form o = through_conv(f, L.g);
                 res->prof.contract_flop += launch_conv_transpose_rows(cur, M, f.ld, f.pg.ph, f.pg.pw, L.g, L.cw, nxt, o.ld,
                                                                       o.pg.ph, o.pg.pw, 0, P.s);
                 f = o;
             } else {
+                fused_relu = false;
                 const int ld_prev = net->ld_of(at - 1);
                 res->prof.contract_flop += launch_conv_transpose_rows(cur, M, f.ld, L.g.Ho, L.g.Wo, L.g, L.cw, nxt, ld_prev,
                                                                       L.g.H, L.g.W, L.g.pad, P.s);
@@ -306,7 +338,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             P.prof->end();
             res->prof.contract_launches++;
             std::swap(cur, nxt);
-            bias_folded = false;
+            bias_folded = fused_relu;
         }
         --at;
         ++depth;
@@ -326,15 +358,19 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
         res->has_symbolic = true;
     }
     P.prof->begin(P_CONC);
-    if (f.patch)
+    if (concretised) {
+        launch_finalize_bounds(cst, net->part.p, slots, net->part_stride, nsides, B, R, out_l, out_u, P.s);
+    } else if (f.patch) {
         launch_concretise_patch(cur, f.ld, cst, nsides, B, R, f.pg, res->l[at], res->u[at], out_l, out_u,
                                 shared, ld_shared, cst_init, P.s);
-    else
+        res->prof.concretise_bytes += (double)M * f.pg.elems() * 4.0;
+    } else {
         launch_concretise(cur, f.ld, cst, nsides, B, R, n_at, res->l[at], res->u[at], out_l, out_u,
-                          shared, ld_shared, shared ? cst_init : nullptr, P.s);
+                          shared, ld_shared, shared ? cst_init : nullptr, P.s, net->part.p, slots, net->part_stride);
+        res->prof.concretise_bytes += (double)M * n_at * 4.0;
+    }
     P.prof->end();
     res->prof.concretise_launches++;
-    res->prof.concretise_bytes += (double)M * (f.patch ? f.pg.elems() : n_at) * 4.0;
 }
 
 void validate_chain(dpc_network* net)
@@ -622,6 +658,23 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         const size_t need = workspace_floats(net, B, label != nullptr);
         net->buf[0].reserve(need);
         net->buf[1].reserve(need);
+        const bool fuse = opt.fuse && opt.max_backsub_depth < 0;
+        if (fuse) {
+            size_t fuse_rows = 0;          // rows of the passes that can use fused epilogues (dense rows of FC layers)
+            for (int i = 1; i <= nl; ++i)
+                if (net->layers[i - 1]->kind == AFFINE) fuse_rows = std::max(fuse_rows, 2 * (size_t)B * net->size_of(i));
+            if (fuse_rows > 0 && fuse_rows * dpc_network::kMaxSlots * 4 <= ((size_t)1 << 31)) {
+                net->part.reserve(fuse_rows * dpc_network::kMaxSlots);
+                net->part_stride = std::max<int64_t>(net->part_stride, (int64_t)fuse_rows);
+            }
+            if (net->pk.size() != (size_t)nl + 1) net->pk.resize(nl + 1);
+            for (int i = 0; i <= nl; ++i) {
+                const bool want = i == 0 ? !net->in_spatial || true : net->layers[i - 1]->kind == RELU;
+                if (!want) continue;
+                if (!net->pk[i]) net->pk[i].reset(new DevBuf<float>());
+                net->pk[i]->reserve((size_t)2 * B * net->ld_of(i) * 4);
+            }
+        }
         net->cst.reserve(need_rows);
         net->stage.reserve(stage_need);
 
@@ -655,6 +708,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                         bad == 1 ? "dpc_certify: lo > hi or a non-finite bound" : "dpc_certify: label out of range");
         }
 
+        if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
         Pass P{net, res, &opt, s, &prof, B};
         for (int i = 1; i <= nl; ++i) {
             Layer& L = *net->layers[i - 1];
@@ -662,6 +716,9 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 prof.begin(P_OTHER);
                 launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
                                     (int64_t)B * L.n_out, s);
+                if (fuse)
+                    launch_pack_relax(res->lam[i], res->mu[i], res->nu[i], net->layers[i - 2]->dBias.p, B, L.n_out,
+                                      net->ld_of(i), net->pk[i]->p, s);
                 prof.end();
                 res->prof.other_launches++;
                 continue;
@@ -883,6 +940,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         DPC_REQUIRE(key, DPC_EINVAL, "dpc_tuning_set: NULL key");
         if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
+        else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
     });
 }

@@ -52,13 +52,39 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
 // Concretisation of dense rows against per-input bounds; see dpc_op_concretise.
 void launch_concretise(const float* C, int ldc, const double* cst, int nsides, int batch, int R, int n,
                        const float* lo, const float* hi, float* out_l, float* out_u,
-                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s);
+                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s,
+                       const float* part = nullptr, int nslots = 0, int64_t part_stride = 0);
 
-// fp32 MFMA contraction Cout = A * W; see dpc_op_contract.  W must be padded with zeros to
-// [round_up(K,32), round_up(N,128)] so that tile loads need no bounds checks: ldw >= round_up(N,128)
-// and the allocation holds round_up(K,32) rows.
-void launch_contract(const float* A, int64_t M, int K, int lda, const float* Wpad, int N, int ldw,
+// fp32 MFMA contraction Cout = A * W; see dpc_op_contract (tile loads are predicated: no padding of
+// the operands is required beyond leading dimensions that are multiples of 4).
+void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
                      float* Cout, int ldc, hipStream_t s);
+
+// Contraction with the following traversal step fused into its epilogue.  pk: packed per-(group, column)
+// parameters (pm, nm, kp, kn) as float4, [nsb][ldpk]; group g = row / R.  Stored value x*(x>=0?pm:nm)
+// (when store != 0), row-constant partial sums x*(x>=0?kp:kn) written to part[slot][row], one slot per
+// column tile.  Returns the number of slots written, or -1 when the fused path does not cover this call
+// (nothing is launched then).
+struct ContractEpilogue {
+    const float* pk;
+    int ldpk, R, nsb;
+    float* part;
+    int64_t part_stride;
+    int max_slots;
+    int store;
+};
+int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
+                          float* Cout, int ldc, const ContractEpilogue& e, hipStream_t s);
+
+// pk[side][b][c] = (pm, nm, kp, kn) of the sign-split ReLU step through a ReLU layer with relaxation
+// (lambda, mu, nu) followed by the bias fold of the layer below (bias may be NULL); columns n..ld-1 zero.
+void launch_pack_relax(const float* lambda, const float* mu, const float* nu, const float* bias, int batch, int n,
+                       int ld, float* pk, hipStream_t s);
+// pk[side][b][c] = (0, 0, bound taken by C >= 0, bound taken by C < 0) for the concretisation.
+void launch_pack_bounds(const float* lo, const float* hi, int batch, int n, int ld, float* pk, hipStream_t s);
+// out[b, r] = float(cst[m] + sum over slots of part[slot][m]), m = (side*batch + b)*R + r.
+void launch_finalize_bounds(const double* cst, const float* part, int nslots, int64_t part_stride, int nsides, int batch,
+                            int R, float* out_l, float* out_u, hipStream_t s);
 
 // Margin rows of the robustness property: for input b and q-th other class o,
 // row = W[label_b] - W[o], constant = bias[label_b] - bias[o].

@@ -30,9 +30,10 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_ = 1>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int MINW = MINW_;                          // wavefronts per SIMD the register budget must allow
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static constexpr int THREADS = WAVES_M * WAVES_N * 64;
     static constexpr int MT = WM / 32, NT = WN / 32;            // MFMA tiles per wavefront
@@ -47,10 +48,28 @@ struct Tile {
     static_assert(BK % 8 == 0 && WM % 32 == 0 && WN % 32 == 0 && NT <= 4, "tile shape");
 };
 
-template <class T>
-__global__ __launch_bounds__(T::THREADS) void contract_kernel(
+// Fused epilogue (EPI = 1): the step that follows the contraction in the traversal is applied to the
+// accumulators before they leave the registers.  For output element x of row m (group g = m / R, i.e.
+// one side of one input) and column c, with packed parameters P = pk[g][c] = (pm, nm, kp, kn):
+//     stored value  x * (x >= 0 ? pm : nm)           (sign-split ReLU step; skipped when store == 0)
+//     row constant  += x * (x >= 0 ? kp : kn)        (nu and bias terms, or the box bound for the
+//                                                     concretisation at the input layer)
+// Row-constant partial sums are reduced over the tile's columns in a fixed order (butterfly over the
+// 32 lanes of a half-wave, then over the workgroup's wave columns through LDS) and written to
+// part[tile_n][m]; whoever consumes the constants adds the slots in index order, so results do not
+// depend on scheduling.
+struct EpiArgs {
+    const float4* pk;
+    int ldpk, R, nsb;
+    float* part;
+    long long part_stride;
+    int store;
+};
+
+template <class T, int EPI>
+__global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
     const float* __restrict__ A, int64_t M, int K, int lda, const float* __restrict__ W, int N, int ldw,
-    float* __restrict__ Cout, int ldc, int tiles_m, int tiles_n)
+    float* __restrict__ Cout, int ldc, int tiles_m, int tiles_n, EpiArgs ep)
 {
     extern __shared__ float4 lds[];
     float4* sA = lds;                                                        // [2][A_STAGE]
@@ -172,6 +191,113 @@ __global__ __launch_bounds__(T::THREADS) void contract_kernel(
         __syncthreads();
     }
 
+    if constexpr (EPI == 1) {
+        float* sRow = reinterpret_cast<float*>(lds);              // [WAVES_N][BM], the K loop is done with LDS
+        const int wn = wave % T::WAVES_N;
+        const float4 zero4e = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int mt = 0; mt < T::MT; ++mt) {
+            const int64_t rb = m0 + wrow0 + mt * 32;
+            const int64_t rclamp = rb < M ? rb : M - 1;
+            const int g_lo = (int)(rclamp / ep.R);
+            const int64_t boundary = (int64_t)(g_lo + 1) * ep.R;          // first row of the next group
+            const bool split = boundary < rb + 32;                         // wave-uniform; R >= 32: at most one
+            const int g_hi = g_lo + 1 < ep.nsb ? g_lo + 1 : ep.nsb - 1;
+            const int col = n0 + wcol0 + T::NT * l32;
+            float4 pa[T::NT], pb[T::NT];
+#pragma unroll
+            for (int nt = 0; nt < T::NT; ++nt) {
+                const bool ok = col + nt < ep.ldpk;
+                pa[nt] = ok ? ep.pk[(size_t)g_lo * ep.ldpk + col + nt] : zero4e;
+                pb[nt] = (ok && split) ? ep.pk[(size_t)g_hi * ep.ldpk + col + nt] : pa[nt];
+            }
+            float rs[16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t row = rb + 8 * i + 4 * kq + j;
+                    const bool useb = row >= boundary;
+                    float o[T::NT];
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int nt = 0; nt < T::NT; ++nt) {
+                        const float x = acc[mt][nt][4 * i + j];
+                        const float4 P = useb ? pb[nt] : pa[nt];
+                        const bool pos = x >= 0.0f;
+                        o[nt] = x * (pos ? P.x : P.y);
+                        sum += x * (pos ? P.z : P.w);
+                    }
+                    rs[4 * i + j] = sum;
+                    if (ep.store && row < M && col < ldc) {
+                        float* dst = Cout + row * ldc + col;
+                        if constexpr (T::NT == 1) {
+                            dst[0] = o[0];
+                        } else if constexpr (T::NT == 2) {
+                            *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+                        } else if constexpr (T::NT == 4) {
+                            *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+                        } else {
+#pragma unroll
+                            for (int nt = 0; nt < T::NT; ++nt)
+                                if (col + nt < ldc) dst[nt] = o[nt];
+                        }
+                    }
+                }
+            }
+            // Butterfly with halving over the 32 lanes that share these rows: after the steps with lane
+            // bits 0..3 a lane holds the sum over its 16-lane group of register index 8*b0+4*b1+2*b2+b3,
+            // the last step adds the two groups.
+            float v8[8], v4[4], v2[2], v1;
+            {
+                const bool h = l32 & 1;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float send = h ? rs[k] : rs[k + 8];
+                    const float keep = h ? rs[k + 8] : rs[k];
+                    v8[k] = keep + __shfl_xor(send, 1, 64);
+                }
+            }
+            {
+                const bool h = l32 & 2;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float send = h ? v8[k] : v8[k + 4];
+                    const float keep = h ? v8[k + 4] : v8[k];
+                    v4[k] = keep + __shfl_xor(send, 2, 64);
+                }
+            }
+            {
+                const bool h = l32 & 4;
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const float send = h ? v4[k] : v4[k + 2];
+                    const float keep = h ? v4[k + 2] : v4[k];
+                    v2[k] = keep + __shfl_xor(send, 4, 64);
+                }
+            }
+            {
+                const bool h = l32 & 8;
+                const float send = h ? v2[0] : v2[1];
+                const float keep = h ? v2[1] : v2[0];
+                v1 = keep + __shfl_xor(send, 8, 64);
+            }
+            v1 += __shfl_xor(v1, 16, 64);
+            if (l32 < 16) {
+                const int v = 8 * (l32 & 1) + 4 * ((l32 >> 1) & 1) + 2 * ((l32 >> 2) & 1) + ((l32 >> 3) & 1);
+                sRow[wn * T::BM + wrow0 + mt * 32 + 8 * (v >> 2) + 4 * kq + (v & 3)] = v1;
+            }
+        }
+        __syncthreads();
+        for (int r = tid; r < T::BM; r += T::THREADS) {
+            float t = 0.0f;
+#pragma unroll
+            for (int w = 0; w < T::WAVES_N; ++w) t += sRow[w * T::BM + r];
+            if (m0 + r < M) ep.part[(size_t)tn * ep.part_stride + m0 + r] = t;
+        }
+        return;
+    }
+
     // epilogue: accumulator register e = 4*i + j of a lane is row 8*i + 4*(lane/32) + j, column lane%32
     // of its MFMA tile; column tile nt owns interleaved columns NT*l32 + nt.
 #pragma unroll
@@ -203,24 +329,27 @@ __global__ __launch_bounds__(T::THREADS) void contract_kernel(
     }
 }
 
-template <class T>
-void launch_variant(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw, float* Cout,
-                    int ldc, hipStream_t s)
+template <class T, int EPI>
+int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw, float* Cout,
+                   int ldc, const EpiArgs& ep, int max_slots, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&contract_kernel<T>),
+        DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&contract_kernel<T, EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES));
         configured = true;
     }
+    static_assert(EPI == 0 || T::LDS_BYTES >= (size_t)T::WAVES_N * T::BM * 4, "row sums must fit the K-loop LDS");
     const int64_t tiles_m = ceil_div(M, T::BM);
     const int tiles_n = (int)ceil_div(ldc, T::BN);          // padding columns of Cout are written too
     const int64_t tiles = tiles_m * tiles_n;
     DPC_REQUIRE(tiles_m < (1 << 30) && tiles < (int64_t)1 << 31, DPC_EINVAL, "contract: too many tiles");
+    if (EPI == 1 && tiles_n > max_slots) return -1;
     const unsigned grid = (unsigned)round_up(tiles, 8);
-    hipLaunchKernelGGL(contract_kernel<T>, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, A, M, K, lda, W, N, ldw,
-                       Cout, ldc, (int)tiles_m, tiles_n);
+    hipLaunchKernelGGL((contract_kernel<T, EPI>), dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, A, M, K, lda, W, N, ldw,
+                       Cout, ldc, (int)tiles_m, tiles_n, ep);
     DPC_HIP(hipGetLastError());
+    return tiles_n;
 }
 
 int g_variant = -1;      // -1: chosen from the problem shape
@@ -247,23 +376,47 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
         variant = tiles128 >= 512 ? 10 : 9;
     }
     switch (variant) {
-        case 1:  launch_variant<Tile<256, 128, 16, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 2:  launch_variant<Tile<128, 128, 16, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 3:  launch_variant<Tile<256, 128, 16, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 4:  launch_variant<Tile<128, 256, 16, 64, 128>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 10: launch_variant<Tile<128, 128, 8, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 11: launch_variant<Tile<64, 64, 8, 32, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 12: launch_variant<Tile<128, 64, 16, 64, 32>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 13: launch_variant<Tile<64, 128, 8, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 14: launch_variant<Tile<128, 128, 8, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        case 15: launch_variant<Tile<256, 128, 8, 128, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
-        default: launch_variant<Tile<128, 128, 32, 64, 64>>(A, M, K, lda, W, N, ldw, Cout, ldc, s); break;
+        case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 3:  launch_variant<Tile<256, 128, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 4:  launch_variant<Tile<128, 256, 16, 64, 128>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 10: launch_variant<Tile<128, 128, 8, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 16: launch_variant<Tile<128, 128, 8, 64, 64, 4>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 11: launch_variant<Tile<64, 64, 8, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 12: launch_variant<Tile<128, 64, 16, 64, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 13: launch_variant<Tile<64, 128, 8, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 14: launch_variant<Tile<128, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 15: launch_variant<Tile<256, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        default: launch_variant<Tile<128, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
     }
+}
+
+
+int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
+                          float* Cout, int ldc, const ContractEpilogue& e, hipStream_t s)
+{
+    DPC_REQUIRE(A && W && M >= 0 && K >= 1 && N >= 1 && e.pk && e.part, DPC_EINVAL, "contract_fused: bad arguments");
+    DPC_REQUIRE(!e.store || Cout, DPC_EINVAL, "contract_fused: output missing");
+    DPC_REQUIRE(lda >= K && ldw >= N && ldc >= N && lda % 4 == 0 && ldw % 4 == 0 && ldc % 4 == 0, DPC_EINVAL,
+                "contract_fused: leading dimensions must cover the matrix and be multiples of 4");
+    DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0 &&
+                    ((uintptr_t)e.pk % 16) == 0, DPC_EINVAL, "contract_fused: buffers must be 16-byte aligned");
+    DPC_REQUIRE(e.ldpk >= ldc && e.R >= 32 && e.nsb >= 1 && (int64_t)e.nsb * e.R == M && e.part_stride >= M, DPC_EINVAL,
+                "contract_fused: epilogue geometry does not match the rows");
+    if (M == 0) return 0;
+    if (g_variant >= 0 && g_variant != 9 && g_variant != 10) return -1;     // fused epilogue exists for the two default tiles
+    EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store};
+    const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
+    const int variant = g_variant >= 0 ? g_variant : (tiles128 >= 512 ? 10 : 9);
+    if (variant == 10)
+        return launch_variant<Tile<128, 128, 8, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+    return launch_variant<Tile<64, 64, 16, 32, 32>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
 }
 
 }  // namespace dpc

@@ -2,6 +2,8 @@
 // ReLU step (+ bias fold), concretisation, margin rows, verdict.  All HBM-bound: one wavefront
 // streams one coefficient row with 16-byte loads, per-input parameters sit in LDS, the per-row
 // constant is accumulated in fp64 and reduced with wavefront shuffles.
+#include <algorithm>
+
 #include "common.h"
 
 namespace dpc {
@@ -61,15 +63,21 @@ __global__ __launch_bounds__(kThreads) void relax_params_kernel(
 // Sign-split ReLU step + bias fold (replace_lower / replace_upper through a ReLU layer, then the
 // constant part of the affine layer below).  grid = (row tiles, nsides*batch).  LDS per chunk of
 // columns: multiplier for C >= 0, multiplier for C < 0, and the constant picked up per unit of
-// C >= 0 / C < 0 (nu on the side that uses U, plus multiplier * bias).
+// C >= 0 / C < 0 (nu on the side that uses U, plus multiplier * bias).  A wavefront streams two rows
+// at a time so that up to eight 16-byte loads per lane are in flight.
 template <bool SHARED>
 __global__ __launch_bounds__(kThreads) void relax_step_kernel(
     float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
     const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
     const float* __restrict__ bias, const float* __restrict__ src, int ld_src,
-    const float* __restrict__ cst_init, int rows_per_wave)
+    const float* __restrict__ cst_init, int rows_per_wave, int chunk)
 {
-    __shared__ float4 s_pm[kChunk / 4], s_nm[kChunk / 4], s_pk[kChunk / 4], s_nk[kChunk / 4];
+    extern __shared__ float4 s_par[];                  // [4][chunk/4]: pm, nm, pk, nk
+    const int ch4 = chunk >> 2;
+    float4* s_pm = s_par;
+    float4* s_nm = s_par + ch4;
+    float4* s_pk = s_par + 2 * ch4;
+    float4* s_nk = s_par + 3 * ch4;
     const int sb = blockIdx.y;
     const int side = sb / batch, b = sb - side * batch;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -79,8 +87,8 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
 #pragma unroll
     for (int q = 0; q < kMaxRowsPerWave; ++q) acc[q] = 0.0;
 
-    for (int c0 = 0; c0 < ldc; c0 += kChunk) {
-        const int cw = min(kChunk, ldc - c0);          // multiple of 4 (ldc is)
+    for (int c0 = 0; c0 < ldc; c0 += chunk) {
+        const int cw = min(chunk, ldc - c0);           // multiple of 4 (ldc is)
         if (c0 > 0) __syncthreads();
         for (int i = threadIdx.x; i < cw; i += kThreads) {
             const int col = c0 + i;
@@ -104,41 +112,54 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
         const int cw4 = cw >> 2;
         const int nloc = n - c0;
 #pragma unroll
-        for (int q = 0; q < kMaxRowsPerWave; ++q) {
-            const int r = r0 + q;
-            if (q >= rows_per_wave || r >= R) break;
-            const size_t m = (size_t)sb * R + r;
-            const float4* in = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src + c0
-                                                                      : C + m * ldc + c0);
-            float4* out = reinterpret_cast<float4*>(C + m * ldc + c0);
-            double a = 0.0;
+        for (int qp = 0; qp < kMaxRowsPerWave; qp += 2) {
+            if (qp >= rows_per_wave || r0 + qp >= R) break;
+            const bool two = qp + 1 < rows_per_wave && r0 + qp + 1 < R;
+            const float4* in[2];
+            float4* out[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int r = r0 + qp + ((h == 1 && two) ? 1 : 0);
+                const size_t m = (size_t)sb * R + r;
+                in[h] = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src + c0 : C + m * ldc + c0);
+                out[h] = reinterpret_cast<float4*>(C + m * ldc + c0);
+            }
+            double a[2] = {0.0, 0.0};
             for (int base = 0; base < cw4; base += 64 * 4) {
-                float4 v[4];
+                float4 v[2][4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int i4 = base + t * 64 + lane;
-                    if (i4 < cw4) v[t] = SHARED ? in[i4] : nt_load4(in + i4);
+                    if (i4 < cw4) {
+                        v[0][t] = SHARED ? in[0][i4] : nt_load4(in[0] + i4);
+                        if (two) v[1][t] = SHARED ? in[1][i4] : nt_load4(in[1] + i4);
+                    }
                 }
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int i4 = base + t * 64 + lane;
                     if (i4 >= cw4) continue;
                     const float4 pm = s_pm[i4], nm = s_nm[i4], pk = s_pk[i4], nk = s_nk[i4];
-                    const float x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
                     const float pmv[4] = {pm.x, pm.y, pm.z, pm.w}, nmv[4] = {nm.x, nm.y, nm.z, nm.w};
                     const float pkv[4] = {pk.x, pk.y, pk.z, pk.w}, nkv[4] = {nk.x, nk.y, nk.z, nk.w};
-                    float y[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool pos = x[e] >= 0.0f;
-                        const bool live = i4 * 4 + e < nloc;     // padding columns come out as exact zeros
-                        y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
-                        a += live ? (double)x[e] * (double)(pos ? pkv[e] : nkv[e]) : 0.0;
+                    for (int h = 0; h < 2; ++h) {
+                        if (h == 1 && !two) break;
+                        const float x[4] = {v[h][t].x, v[h][t].y, v[h][t].z, v[h][t].w};
+                        float y[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const bool pos = x[e] >= 0.0f;
+                            const bool live = i4 * 4 + e < nloc;     // padding columns come out as exact zeros
+                            y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
+                            a[h] += live ? (double)x[e] * (double)(pos ? pkv[e] : nkv[e]) : 0.0;
+                        }
+                        nt_store4(out[h] + i4, y[0], y[1], y[2], y[3]);
                     }
-                    nt_store4(out + i4, y[0], y[1], y[2], y[3]);
                 }
             }
-            acc[q] += a;
+            acc[qp] += a[0];
+            acc[qp + 1] += a[1];
         }
     }
 #pragma unroll
@@ -153,15 +174,18 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
     }
 }
 
-// Concretisation (simplify_lower / simplify_upper): one wavefront per row, box of input b in LDS.
+// Concretisation (simplify_lower / simplify_upper): one wavefront per two rows, box of input b in LDS.
 template <bool SHARED>
 __global__ __launch_bounds__(kThreads) void concretise_kernel(
     const float* __restrict__ C, int ldc, const double* __restrict__ cst, int batch, int R, int n,
     const float* __restrict__ lo, const float* __restrict__ hi, float* __restrict__ out_l,
     float* __restrict__ out_u, const float* __restrict__ src, int ld_src,
-    const float* __restrict__ cst_init, int rows_per_wave)
+    const float* __restrict__ cst_init, int rows_per_wave, int chunk,
+    const float* __restrict__ part, int nslots, long long part_stride)
 {
-    __shared__ float4 s_p[kChunk / 4], s_n[kChunk / 4];   // bound taken by C >= 0 / C < 0
+    extern __shared__ float4 s_par[];                  // [2][chunk/4]: bound taken by C >= 0 / C < 0
+    float4* s_p = s_par;
+    float4* s_n = s_par + (chunk >> 2);
     const int sb = blockIdx.y;
     const int side = sb / batch, b = sb - side * batch;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -171,8 +195,8 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
 #pragma unroll
     for (int q = 0; q < kMaxRowsPerWave; ++q) acc[q] = 0.0;
 
-    for (int c0 = 0; c0 < ldc; c0 += kChunk) {
-        const int cw = min(kChunk, ldc - c0);
+    for (int c0 = 0; c0 < ldc; c0 += chunk) {
+        const int cw = min(chunk, ldc - c0);
         if (c0 > 0) __syncthreads();
         for (int i = threadIdx.x; i < cw; i += kThreads) {
             const int col = c0 + i;
@@ -189,46 +213,113 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
         const int cw4 = cw >> 2;
         const int nloc = n - c0;
 #pragma unroll
-        for (int q = 0; q < kMaxRowsPerWave; ++q) {
-            const int r = r0 + q;
-            if (q >= rows_per_wave || r >= R) break;
-            const size_t m = (size_t)sb * R + r;
-            const float4* in = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src + c0
-                                                                      : C + m * ldc + c0);
-            double a = 0.0;
+        for (int qp = 0; qp < kMaxRowsPerWave; qp += 2) {
+            if (qp >= rows_per_wave || r0 + qp >= R) break;
+            const bool two = qp + 1 < rows_per_wave && r0 + qp + 1 < R;
+            const float4* in[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int r = r0 + qp + ((h == 1 && two) ? 1 : 0);
+                const size_t m = (size_t)sb * R + r;
+                in[h] = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src + c0 : C + m * ldc + c0);
+            }
+            double a[2] = {0.0, 0.0};
             for (int base = 0; base < cw4; base += 64 * 4) {
-                float4 v[4];
+                float4 v[2][4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int i4 = base + t * 64 + lane;
-                    if (i4 < cw4) v[t] = SHARED ? in[i4] : nt_load4(in + i4);
+                    if (i4 < cw4) {
+                        v[0][t] = SHARED ? in[0][i4] : nt_load4(in[0] + i4);
+                        if (two) v[1][t] = SHARED ? in[1][i4] : nt_load4(in[1] + i4);
+                    }
                 }
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int i4 = base + t * 64 + lane;
                     if (i4 >= cw4) continue;
                     const float4 p = s_p[i4], ng = s_n[i4];
-                    const float x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
                     const float pv[4] = {p.x, p.y, p.z, p.w}, nv[4] = {ng.x, ng.y, ng.z, ng.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (i4 * 4 + e < nloc) a += (double)x[e] * (double)(x[e] >= 0.0f ? pv[e] : nv[e]);
+                    for (int h = 0; h < 2; ++h) {
+                        if (h == 1 && !two) break;
+                        const float x[4] = {v[h][t].x, v[h][t].y, v[h][t].z, v[h][t].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (i4 * 4 + e < nloc) a[h] += (double)x[e] * (double)(x[e] >= 0.0f ? pv[e] : nv[e]);
+                    }
                 }
             }
-            acc[q] += a;
+            acc[qp] += a[0];
+            acc[qp + 1] += a[1];
         }
     }
 #pragma unroll
     for (int q = 0; q < kMaxRowsPerWave; ++q) {
         const int r = r0 + q;
         if (q >= rows_per_wave || r >= R) break;
-        const double t = wave_sum(acc[q]);
+        const size_t m = (size_t)sb * R + r;
+        double extra = 0.0;        // row-constant partial sums left by fused contraction epilogues, slot order fixed
+        for (int t = lane; t < nslots; t += 64) extra += (double)part[(size_t)t * part_stride + m];
+        const double t = wave_sum(acc[q] + extra);
         if (lane == 0) {
-            const size_t m = (size_t)sb * R + r;
             const double v = (cst_init ? (double)cst_init[r] : cst[m]) + t;
             (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)v;
         }
     }
+}
+
+// Packed parameters of the sign-split ReLU step for both sides (see launch_pack_relax).
+__global__ __launch_bounds__(kThreads) void pack_relax_kernel(
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
+    const float* __restrict__ bias, int batch, int n, int ld, float4* __restrict__ pk)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;       // over [2][batch][ld]
+    if (i >= (int64_t)2 * batch * ld) return;
+    const int col = (int)(i % ld);
+    const int sb = (int)(i / ld);
+    const int side = sb / batch, b = sb - side * batch;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col < n) {
+        const float la = lambda[(size_t)b * n + col], m = mu[(size_t)b * n + col], v = nu[(size_t)b * n + col];
+        const float bj = bias ? bias[col] : 0.0f;
+        o.x = side == 0 ? la : m;
+        o.y = side == 0 ? m : la;
+        o.z = (side == 0 ? 0.0f : v) + o.x * bj;
+        o.w = (side == 0 ? v : 0.0f) + o.y * bj;
+    }
+    pk[i] = o;
+}
+
+__global__ __launch_bounds__(kThreads) void pack_bounds_kernel(
+    const float* __restrict__ lo, const float* __restrict__ hi, int batch, int n, int ld, float4* __restrict__ pk)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (int64_t)2 * batch * ld) return;
+    const int col = (int)(i % ld);
+    const int sb = (int)(i / ld);
+    const int side = sb / batch, b = sb - side * batch;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col < n) {
+        const float lv = lo[(size_t)b * n + col], hv = hi[(size_t)b * n + col];
+        o.z = side == 0 ? lv : hv;
+        o.w = side == 0 ? hv : lv;
+    }
+    pk[i] = o;
+}
+
+__global__ __launch_bounds__(kThreads) void finalize_bounds_kernel(
+    const double* __restrict__ cst, const float* __restrict__ part, int nslots, long long part_stride, int batch, int R,
+    long long M, float* __restrict__ out_l, float* __restrict__ out_u)
+{
+    const long long m = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (m >= M) return;
+    double v = cst[m];
+    for (int t = 0; t < nslots; ++t) v += (double)part[(size_t)t * part_stride + m];
+    const long long sb = m / R;
+    const int r = (int)(m - sb * R);
+    const int side = (int)(sb / batch), b = (int)(sb - (long long)side * batch);
+    (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)v;
 }
 
 __global__ __launch_bounds__(kThreads) void margin_rows_kernel(
@@ -268,8 +359,11 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const float* __restri
     if (TO_HWC) dst[hwc] = src[i]; else dst[i] = src[hwc];
 }
 
+int g_rows_per_wave = 0;
+
 int pick_rows_per_wave(int R, int groups)
 {
+    if (g_rows_per_wave > 0) return g_rows_per_wave;
     // enough blocks to cover 256 CUs a few times over, as many rows per block as that allows
     int rpw = kMaxRowsPerWave;
     while (rpw > 1 && ceil_div(R, rpw * kWaves) * groups < 2048) rpw >>= 1;
@@ -277,6 +371,8 @@ int pick_rows_per_wave(int R, int groups)
 }
 
 }  // namespace
+
+void set_rows_per_wave(int v) { g_rows_per_wave = v; }
 
 void launch_relax_params(const float* l, const float* u, float* lambda, float* mu, float* nu,
                          float* rl, float* ru, int64_t count, hipStream_t s)
@@ -303,22 +399,27 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "relax_step: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
     const int rpw = pick_rows_per_wave(R, nsides * batch);
+    const int chunk = std::min(ldc, kChunk);
+    const size_t lds = (size_t)chunk * 16;
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
     if (shared_src)
-        hipLaunchKernelGGL(relax_step_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n,
-                           lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw);
+        hipLaunchKernelGGL(relax_step_kernel<true>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n,
+                           lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw, chunk);
     else
-        hipLaunchKernelGGL(relax_step_kernel<false>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n,
-                           lambda, mu, nu, bias, (const float*)nullptr, 0, cst_init, rpw);
+        hipLaunchKernelGGL(relax_step_kernel<false>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n,
+                           lambda, mu, nu, bias, (const float*)nullptr, 0, cst_init, rpw, chunk);
     DPC_HIP(hipGetLastError());
 }
 
 void launch_concretise(const float* C, int ldc, const double* cst, int nsides, int batch, int R, int n,
                        const float* lo, const float* hi, float* out_l, float* out_u,
-                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s)
+                       const float* shared_src, int ld_src, const float* cst_init, hipStream_t s,
+                       const float* part, int nslots, int64_t part_stride)
 {
     DPC_REQUIRE(nsides >= 1 && nsides <= 2 && batch >= 0 && R >= 0 && n >= 1 && lo && hi && out_l, DPC_EINVAL,
                 "concretise: bad arguments");
+    DPC_REQUIRE(nslots == 0 || (part && part_stride >= (int64_t)nsides * batch * R), DPC_EINVAL,
+                "concretise: bad partial-sum slots");
     DPC_REQUIRE(nsides == 1 || out_u, DPC_EINVAL, "concretise: out_u missing");
     DPC_REQUIRE(ldc >= n && ldc % 4 == 0, DPC_EINVAL, "concretise: ldc must be >= n and a multiple of 4");
     if (shared_src)
@@ -329,13 +430,49 @@ void launch_concretise(const float* C, int ldc, const double* cst, int nsides, i
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "concretise: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
     const int rpw = pick_rows_per_wave(R, nsides * batch);
+    const int chunk = std::min(ldc, kChunk);
+    const size_t lds = (size_t)chunk * 8;
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
     if (shared_src)
-        hipLaunchKernelGGL(concretise_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n, lo, hi,
-                           out_l, out_u, shared_src, ld_src, cst_init, rpw);
+        hipLaunchKernelGGL(concretise_kernel<true>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n, lo, hi,
+                           out_l, out_u, shared_src, ld_src, cst_init, rpw, chunk, part, nslots, (long long)part_stride);
     else
-        hipLaunchKernelGGL(concretise_kernel<false>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, n, lo, hi,
-                           out_l, out_u, (const float*)nullptr, 0, cst_init, rpw);
+        hipLaunchKernelGGL(concretise_kernel<false>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n, lo, hi,
+                           out_l, out_u, (const float*)nullptr, 0, cst_init, rpw, chunk, part, nslots,
+                           (long long)part_stride);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_pack_relax(const float* lambda, const float* mu, const float* nu, const float* bias, int batch, int n,
+                       int ld, float* pk, hipStream_t s)
+{
+    DPC_REQUIRE(lambda && mu && nu && pk && ld >= n && ((uintptr_t)pk % 16) == 0, DPC_EINVAL, "pack_relax: bad arguments");
+    const int64_t tot = (int64_t)2 * batch * ld;
+    if (tot == 0) return;
+    hipLaunchKernelGGL(pack_relax_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, lambda, mu, nu,
+                       bias, batch, n, ld, reinterpret_cast<float4*>(pk));
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_pack_bounds(const float* lo, const float* hi, int batch, int n, int ld, float* pk, hipStream_t s)
+{
+    DPC_REQUIRE(lo && hi && pk && ld >= n && ((uintptr_t)pk % 16) == 0, DPC_EINVAL, "pack_bounds: bad arguments");
+    const int64_t tot = (int64_t)2 * batch * ld;
+    if (tot == 0) return;
+    hipLaunchKernelGGL(pack_bounds_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, lo, hi, batch, n,
+                       ld, reinterpret_cast<float4*>(pk));
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_finalize_bounds(const double* cst, const float* part, int nslots, int64_t part_stride, int nsides, int batch,
+                            int R, float* out_l, float* out_u, hipStream_t s)
+{
+    const int64_t M = (int64_t)nsides * batch * R;
+    DPC_REQUIRE(cst && out_l && (nsides == 1 || out_u) && (nslots == 0 || (part && part_stride >= M)), DPC_EINVAL,
+                "finalize_bounds: bad arguments");
+    if (M == 0) return;
+    hipLaunchKernelGGL(finalize_bounds_kernel, dim3((unsigned)ceil_div(M, kThreads)), dim3(kThreads), 0, s, cst, part, nslots,
+                       (long long)part_stride, batch, R, (long long)M, out_l, out_u);
     DPC_HIP(hipGetLastError());
 }
 

@@ -70,6 +70,25 @@ def test_small_conv(convs, fcs, shape):
     gnet.close()
 
 
+@pytest.mark.parametrize("seed,dims,B", [(31, [40, 64, 96, 33, 10], 3), (32, [100, 500, 500, 300, 40], 2), (33, [16, 32, 7], 5)])
+def test_fused_and_unfused_paths_agree(seed, dims, B):
+    """fuse=1 (ReLU step / concretisation inside the contraction's epilogue) and fuse=0 (every step its own
+    kernel) are two routes through the same arithmetic; both must match the oracle."""
+    net = wl.random_small_net(seed, dims)
+    x, lo, hi = wl.random_box(seed + 1, dims[0], B, 0.05)
+    label = np.arange(B, dtype=np.int32) % dims[-1]
+    b = _binding()
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label)
+    for fuse in (1, 0):
+        g = gnet.certify(lo, hi, label, fuse=fuse)
+        compare_with_oracle(net, lo, hi, g, o, label)
+        p = gnet.certify(lo, hi, label, fuse=fuse, profile=1).profile()
+        if fuse == 0:
+            assert p["relax_launches"] >= p["contract_launches"]
+    gnet.close()
+
+
 @pytest.mark.parametrize("depth", [0, 1, 2, 3, 5])
 def test_depth_limited(depth):
     net = wl.random_small_net(11, [12, 20, 18, 16, 6])
@@ -130,7 +149,7 @@ def test_device_inputs_and_stream():
         np.testing.assert_array_equal(ref.concrete(k)[1], got.concrete(k)[1])
     np.testing.assert_array_equal(ref.verdict()[1], got.verdict()[1])
     p = got.profile()
-    assert p["contract_launches"] == 3 + 2 and p["total_ms"] > 0 and p["contract_flop"] > 0
+    assert p["contract_launches"] == 3 + 2 and p["total_ms"] > 0 and p["contract_flop"] > 0   # 1+2 layer passes, 2 margin
     gnet.close()
 
 
@@ -169,6 +188,19 @@ def test_cfg5_full_batch_gpu_sampled_oracle():
     flipped, worst = compare_with_oracle(w.net, w.lo[idx], w.hi[idx], _Sub(g, idx), o, w.label[idx], max_flipped_inputs=1,
                                          check_samples=200)
     print("cfg5 worst err/tol", worst, "flipped", flipped)
+    gnet.close()
+
+
+def test_cfg4_full_batch_gpu_sampled_oracle():
+    w = wl.make_workload("cfg4")
+    b = _binding()
+    gnet = b.Network(w.net)
+    g = gnet.certify(w.lo, w.hi, w.label)
+    idx = [3, 15]
+    o = oracle.run(w.net, w.lo[idx], w.hi[idx], label=w.label[idx])
+    flipped, worst = compare_with_oracle(w.net, w.lo[idx], w.hi[idx], _Sub(g, idx), o, w.label[idx], max_flipped_inputs=1,
+                                         check_samples=50)
+    print("cfg4 worst err/tol", worst, "flipped", flipped)
     gnet.close()
 
 
