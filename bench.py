@@ -17,6 +17,11 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# L2-miss traffic of the dominant contraction kernel per launch, bytes (fetch + write), from the two
+# rocprofv3 --pmc runs summarised in profiles/pmc_<workload>.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after
+# calibration on a plain 256 MiB copy); mean over the launches of one step.
+TRAFFIC = {"cfg2": 1.373e8, "cfg5": 1.887e9}
+
 DESCR = {
     "cfg1": "cfg1: FC 784-100-100-100-10, B=1, eps=0.01",
     "cfg2": "cfg2: FC 784-6x500-10, B=32, eps in {0.005,0.01,0.02} (96 instances per step)",
@@ -122,7 +127,7 @@ def main():
             "frac": contract_tflops / PEAK_FP32_MFMA_TFLOPS,
             "launches": P["contract_launches"], "avg_launch_ms": P["contract_ms"] / max(P["contract_launches"], 1),
             "flop_per_step": P["contract_flop"] / args.steps,
-            "traffic": None,
+            "traffic": TRAFFIC.get(args.workload),
         },
         "hbm_passes": {
             "relax_step": {"achieved": relax_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": relax_gbs / PEAK_HBM_GBS,
@@ -133,6 +138,46 @@ def main():
         "time_split_ms_per_step": {k: P[k] / args.steps for k in ("contract_ms", "relax_ms", "concretise_ms", "other_ms", "total_ms")},
         "value_without_kernel_events": inputs_per_step * args.steps / dt_plain,
     }
+
+    # The two HBM-bound passes as standalone kernels at this workload's dominant shape (both sides of the widest
+    # hidden layer's rows over the widest layer below), timed with events on the launch stream.
+    sizes = net.sizes
+    hidden = [n for n, k in zip(sizes[1:], net.kinds) if k == "affine"]
+    if len(hidden) >= 2:
+        R, n = max(hidden[:-1]), max(sizes[:-1][:len(sizes) - 2] or [sizes[0]])
+        n = min(n, 4096)
+        ld = (n + 31) // 32 * 32
+        M = 2 * B * R
+        with torch.cuda.stream(stream):
+            C = torch.randn(M, ld, device="cuda")
+            cst = torch.zeros(M, device="cuda", dtype=torch.float64)
+            lam, mu, nu = (torch.rand(B, n, device="cuda") for _ in range(3))
+            bias = torch.randn(n, device="cuda")
+            lo_ = torch.rand(B, n, device="cuda")
+            hi_ = lo_ + 0.1
+            ol, ou = torch.empty(B, R, device="cuda"), torch.empty(B, R, device="cuda")
+
+            def timed(f, reps=20):
+                for _ in range(3):
+                    f()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    f()
+                e1.record(stream)
+                e1.synchronize()
+                return e0.elapsed_time(e1) / reps * 1e-3
+
+            t_relax = timed(lambda: binding.dpc_op_relax_step(C, cst, 2, B, R, n, lam, mu, nu, bias, stream=stream.cuda_stream))
+            t_conc = timed(lambda: binding.dpc_op_concretise(C, cst, 2, B, R, n, lo_, hi_, ol, ou, stream=stream.cuda_stream))
+        out["hbm_passes_standalone"] = {
+            "shape": {"rows": M, "columns": n},
+            "relax_step": {"achieved": M * n * 8 / t_relax / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": M * n * 8 / t_relax / 1e9 / PEAK_HBM_GBS, "us_per_launch": t_relax * 1e6},
+            "concretise": {"achieved": M * n * 4 / t_conc / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": M * n * 4 / t_conc / 1e9 / PEAK_HBM_GBS, "us_per_launch": t_conc * 1e6},
+        }
+        del C, cst
 
     if not args.no_cpu_baseline:
         import oracle

@@ -64,6 +64,7 @@ struct EpiArgs {
     float* part;
     long long part_stride;
     int store;
+    int remap;          // 1: XCD-aware re-linearisation of workgroup ids
 };
 
 template <class T, int EPI>
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
 
     // XCD-aware re-linearisation (gridDim.x is a multiple of 8)
     const int per_xcd = gridDim.x >> 3;
-    const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int v = ep.remap ? (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3) : blockIdx.x;
     if (v >= tiles_m * tiles_n) return;
     const int tm = v / tiles_n, tn = v - tm * tiles_n;
     const int64_t m0 = (int64_t)tm * T::BM;
@@ -353,10 +354,12 @@ int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, in
 }
 
 int g_variant = -1;      // -1: chosen from the problem shape
+int g_remap = 1;
 
 }  // namespace
 
 void set_contract_variant(int v) { g_variant = v; }
+void set_contract_remap(int v) { g_remap = v; }
 
 void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
                      float* Cout, int ldc, hipStream_t s)
@@ -376,24 +379,24 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
         variant = tiles128 >= 512 ? 10 : 9;
     }
     switch (variant) {
-        case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 3:  launch_variant<Tile<256, 128, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 4:  launch_variant<Tile<128, 256, 16, 64, 128>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 10: launch_variant<Tile<128, 128, 8, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 16: launch_variant<Tile<128, 128, 8, 64, 64, 4>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 11: launch_variant<Tile<64, 64, 8, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 12: launch_variant<Tile<128, 64, 16, 64, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 13: launch_variant<Tile<64, 128, 8, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 14: launch_variant<Tile<128, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        case 15: launch_variant<Tile<256, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
-        default: launch_variant<Tile<128, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{}, 0, s); break;
+        case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 3:  launch_variant<Tile<256, 128, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 4:  launch_variant<Tile<128, 256, 16, 64, 128>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 10: launch_variant<Tile<128, 128, 8, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 16: launch_variant<Tile<128, 128, 8, 64, 64, 4>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 11: launch_variant<Tile<64, 64, 8, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 12: launch_variant<Tile<128, 64, 16, 64, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 13: launch_variant<Tile<64, 128, 8, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 14: launch_variant<Tile<128, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 15: launch_variant<Tile<256, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        default: launch_variant<Tile<128, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
     }
 }
 
@@ -411,7 +414,7 @@ int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float
                 "contract_fused: epilogue geometry does not match the rows");
     if (M == 0) return 0;
     if (g_variant >= 0 && g_variant != 9 && g_variant != 10) return -1;     // fused epilogue exists for the two default tiles
-    EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store};
+    EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store, g_remap};
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
     const int variant = g_variant >= 0 ? g_variant : (tiles128 >= 512 ? 10 : 9);
     if (variant == 10)
