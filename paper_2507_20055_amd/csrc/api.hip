@@ -30,6 +30,7 @@ void set_error(const char* fmt, ...)
 void set_contract_variant(int v);
 void set_contract_remap(int v);
 void set_rows_per_wave(int v);
+void set_rows_stream(int v);
 
 namespace {
 
@@ -943,6 +944,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         else if (strcmp(key, "contract_remap") == 0) set_contract_remap(value);
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
         else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
+        else if (strcmp(key, "rows_stream") == 0) set_rows_stream(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
     });
 }

@@ -22,6 +22,8 @@
 // Workgroup -> tile mapping is XCD aware: hardware deals workgroups round-robin to the 8 XCDs, so
 // workgroup ids are re-linearised to give each XCD a contiguous run of tiles, N-tile index fastest;
 // the tiles that re-read one A row panel then share one XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace dpc {
@@ -29,6 +31,17 @@ namespace dpc {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Compile-time loop: indices reach the body as constants, so small per-thread arrays indexed by them stay
+// in registers (a runtime-indexed array would be placed in scratch memory and serialise the prefetch).
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_ = 1>
 struct Tile {
@@ -91,31 +104,27 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
     const int K4 = (K + 3) & ~3, N4 = (N + 3) & ~3;
     const int nk = (K + T::BK - 1) / T::BK;
 
-    // per-thread staging coordinates
-    const float* a_ptr[T::A_LOADS];
-    int a_kc[T::A_LOADS], a_lds[T::A_LOADS];
-#pragma unroll
-    for (int i = 0; i < T::A_LOADS; ++i) {
+    // Per-thread staging slots.  Each slot is a set of scalar variables (not an array): the prefetched
+    // tile must live in registers across the MFMA section, and arrays captured by the helper lambdas were
+    // being placed in scratch memory by the compiler, which serialised every prefetch.
+    struct Slot { const float* ptr; int k; int lds; bool ok; };
+    auto a_slot = [&](int i) __attribute__((always_inline)) {
         const int idx = tid + T::THREADS * i;
         const int row = idx / (T::BK / 4), kc = idx % (T::BK / 4);
         int64_t gr = m0 + row;
         if (gr > M - 1) gr = M - 1;                     // clamp: rows past M are computed, never stored
-        a_ptr[i] = A + gr * lda + kc * 4;
-        a_kc[i] = kc * 4;
-        a_lds[i] = kc * T::A_PLANE + row;
-    }
-    const float* b_ptr[T::B_LOADS];
-    int b_kr[T::B_LOADS], b_lds[T::B_LOADS];
-    bool b_ok[T::B_LOADS];
-#pragma unroll
-    for (int i = 0; i < T::B_LOADS; ++i) {
+        return Slot{A + gr * lda + kc * 4, kc * 4, kc * T::A_PLANE + row, true};
+    };
+    auto b_slot = [&](int i) __attribute__((always_inline)) {
         const int idx = tid + T::THREADS * i;
         const int kr = idx / (T::BN / 4), nc = idx % (T::BN / 4);
-        b_ptr[i] = W + (size_t)kr * ldw + n0 + nc * 4;
-        b_kr[i] = kr;
-        b_ok[i] = n0 + nc * 4 < N4;
-        b_lds[i] = kr * T::B_ROW + nc * 4;
-    }
+        return Slot{W + (size_t)kr * ldw + n0 + nc * 4, kr, kr * T::B_ROW + nc * 4, n0 + nc * 4 < N4};
+    };
+    static_assert(T::A_LOADS <= 4 && T::B_LOADS <= 4, "at most four staging slots per operand");
+    const Slot sa0 = a_slot(0), sa1 = a_slot(T::A_LOADS > 1 ? 1 : 0), sa2 = a_slot(T::A_LOADS > 2 ? 2 : 0),
+               sa3 = a_slot(T::A_LOADS > 3 ? 3 : 0);
+    const Slot sb0 = b_slot(0), sb1 = b_slot(T::B_LOADS > 1 ? 1 : 0), sb2 = b_slot(T::B_LOADS > 2 ? 2 : 0),
+               sb3 = b_slot(T::B_LOADS > 3 ? 3 : 0);
 
     floatx16 acc[T::MT][T::NT];
 #pragma unroll
@@ -125,25 +134,36 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    float4 ra[T::A_LOADS], rb[T::B_LOADS];
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    typedef float vf4 __attribute__((ext_vector_type(4)));
+    vf4 ra0 = {0, 0, 0, 0}, ra1 = ra0, ra2 = ra0, ra3 = ra0, rb0 = ra0, rb1 = ra0, rb2 = ra0, rb3 = ra0;
+    const vf4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    auto load_tile = [&](int kt) {
+#define DPC_LOAD_A(S, R) R = (k0 + S.k < K4) ? *reinterpret_cast<const vf4*>(S.ptr + k0) : zero4
+#define DPC_LOAD_B(S, R) R = (S.ok && k0 + S.k < K) ? *reinterpret_cast<const vf4*>(S.ptr + (size_t)k0 * ldw) : zero4
+    auto load_tile = [&](int kt) __attribute__((always_inline)) {
         const int k0 = kt * T::BK;
-#pragma unroll
-        for (int i = 0; i < T::A_LOADS; ++i)
-            ra[i] = (k0 + a_kc[i] < K4) ? *reinterpret_cast<const float4*>(a_ptr[i] + k0) : zero4;
-#pragma unroll
-        for (int i = 0; i < T::B_LOADS; ++i)
-            rb[i] = (b_ok[i] && k0 + b_kr[i] < K)
-                        ? *reinterpret_cast<const float4*>(b_ptr[i] + (size_t)k0 * ldw) : zero4;
+        DPC_LOAD_A(sa0, ra0);
+        if constexpr (T::A_LOADS > 1) DPC_LOAD_A(sa1, ra1);
+        if constexpr (T::A_LOADS > 2) DPC_LOAD_A(sa2, ra2);
+        if constexpr (T::A_LOADS > 3) DPC_LOAD_A(sa3, ra3);
+        DPC_LOAD_B(sb0, rb0);
+        if constexpr (T::B_LOADS > 1) DPC_LOAD_B(sb1, rb1);
+        if constexpr (T::B_LOADS > 2) DPC_LOAD_B(sb2, rb2);
+        if constexpr (T::B_LOADS > 3) DPC_LOAD_B(sb3, rb3);
     };
-    auto store_tile = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < T::A_LOADS; ++i) sA[stage * T::A_STAGE + a_lds[i]] = ra[i];
-#pragma unroll
-        for (int i = 0; i < T::B_LOADS; ++i)
-            *reinterpret_cast<float4*>(sB + stage * T::B_STAGE + b_lds[i]) = rb[i];
+#undef DPC_LOAD_A
+#undef DPC_LOAD_B
+    auto store_tile = [&](int stage) __attribute__((always_inline)) {
+        vf4* dA = reinterpret_cast<vf4*>(sA + stage * T::A_STAGE);
+        float* dB = sB + stage * T::B_STAGE;
+        dA[sa0.lds] = ra0;
+        if constexpr (T::A_LOADS > 1) dA[sa1.lds] = ra1;
+        if constexpr (T::A_LOADS > 2) dA[sa2.lds] = ra2;
+        if constexpr (T::A_LOADS > 3) dA[sa3.lds] = ra3;
+        *reinterpret_cast<vf4*>(dB + sb0.lds) = rb0;
+        if constexpr (T::B_LOADS > 1) *reinterpret_cast<vf4*>(dB + sb1.lds) = rb1;
+        if constexpr (T::B_LOADS > 2) *reinterpret_cast<vf4*>(dB + sb2.lds) = rb2;
+        if constexpr (T::B_LOADS > 3) *reinterpret_cast<vf4*>(dB + sb3.lds) = rb3;
     };
 
     load_tile(0);
@@ -354,6 +374,18 @@ int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, in
 }
 
 int g_variant = -1;      // -1: chosen from the problem shape
+
+// Tile choice from the problem shape (measured on cfg2- and cfg5-sized contractions):
+//  * fewer than 512 tiles of 128x128: 64x64 tiles, so that the grid still covers the 256 CUs;
+//  * otherwise 128x256 tiles (8 wavefronts of 64x64, K tile 16), unless the last 256-wide column tile
+//    would be at most half used (e.g. 784 columns), where 128x128 tiles waste less.
+int pick_variant(int64_t M, int ldc)
+{
+    const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
+    if (tiles128 < 512) return 9;
+    const int rem = ldc % 256;
+    return (rem != 0 && rem <= 128) ? 17 : 7;
+}
 int g_remap = 1;
 
 }  // namespace
@@ -370,14 +402,7 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
     DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0, DPC_EINVAL,
                 "contract: buffers must be 16-byte aligned");
     if (M == 0) return;
-    int variant = g_variant;
-    if (variant < 0) {
-        // Large problems: 128x128 tiles with a short K tile (small LDS footprint -> three workgroups per
-        // CU hide each other's barrier and load latency).  Small problems: 64x64 tiles so that the grid
-        // still covers the 256 CUs.
-        const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
-        variant = tiles128 >= 512 ? 10 : 9;
-    }
+    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc);
     switch (variant) {
         case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
@@ -413,13 +438,15 @@ int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float
     DPC_REQUIRE(e.ldpk >= ldc && e.R >= 32 && e.nsb >= 1 && (int64_t)e.nsb * e.R == M && e.part_stride >= M, DPC_EINVAL,
                 "contract_fused: epilogue geometry does not match the rows");
     if (M == 0) return 0;
-    if (g_variant >= 0 && g_variant != 9 && g_variant != 10) return -1;     // fused epilogue exists for the two default tiles
+    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc);
     EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store, g_remap};
-    const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
-    const int variant = g_variant >= 0 ? g_variant : (tiles128 >= 512 ? 10 : 9);
-    if (variant == 10)
-        return launch_variant<Tile<128, 128, 8, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
-    return launch_variant<Tile<64, 64, 16, 32, 32>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+    switch (variant) {      // the fused epilogue is instantiated for the tiles the shape heuristic can pick
+        case 17: return launch_variant<Tile<128, 128, 16, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+        case 7:  return launch_variant<Tile<128, 256, 16, 64, 64>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+        case 9:  return launch_variant<Tile<64, 64, 16, 32, 32>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+        case 10: return launch_variant<Tile<128, 128, 8, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+        default: return -1;
+    }
 }
 
 }  // namespace dpc

@@ -269,6 +269,201 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
     }
 }
 
+// Streaming variants for rows of at most 1024 columns (one 16-byte load per lane covers a quarter of
+// the row): a wavefront walks its rows two at a time and issues the loads of the next pair before it
+// computes the current one, and the very first loads are issued before the per-input parameters are
+// staged in LDS, so the HBM stream never waits for the parameter fill or for the reductions.
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
+    float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
+    const float* __restrict__ bias, const float* __restrict__ src, int ld_src,
+    const float* __restrict__ cst_init, int rows_per_wave)
+{
+    extern __shared__ float4 s_par[];                  // [4][ldc/4]: pm, nm, pk, nk
+    const int cw4 = ldc >> 2;
+    float4* s_pm = s_par;
+    float4* s_nm = s_par + cw4;
+    float4* s_pk = s_par + 2 * cw4;
+    float4* s_nk = s_par + 3 * cw4;
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rbeg = blockIdx.x * (rows_per_wave * kWaves) + wave * rows_per_wave;
+    const int rend = min(R, rbeg + rows_per_wave);
+    const int npairs = rend > rbeg ? (rend - rbeg + 1) >> 1 : 0;
+
+    auto row_of = [&](int p, int h) { const int r = rbeg + 2 * p + h; return r < rend ? r : rend - 1; };
+    auto load_pair = [&](int p, float4 (&v)[2][4]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int r = row_of(p, h);
+            const float4* in = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src
+                                                                      : C + ((size_t)sb * R + r) * ldc);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int i4 = t * 64 + lane;
+                if (i4 < cw4) v[h][t] = SHARED ? in[i4] : nt_load4(in + i4);
+            }
+        }
+    };
+    auto compute_pair = [&](int p, float4 (&v)[2][4]) {
+        double a[2] = {0.0, 0.0};
+        const bool two = rbeg + 2 * p + 1 < rend;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int i4 = t * 64 + lane;
+            if (i4 >= cw4) continue;
+            const float4 pm = s_pm[i4], nm = s_nm[i4], pk = s_pk[i4], nk = s_nk[i4];
+            const float pmv[4] = {pm.x, pm.y, pm.z, pm.w}, nmv[4] = {nm.x, nm.y, nm.z, nm.w};
+            const float pkv[4] = {pk.x, pk.y, pk.z, pk.w}, nkv[4] = {nk.x, nk.y, nk.z, nk.w};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (h == 1 && !two) break;
+                const float x[4] = {v[h][t].x, v[h][t].y, v[h][t].z, v[h][t].w};
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool pos = x[e] >= 0.0f;
+                    const bool live = i4 * 4 + e < n;        // padding columns come out as exact zeros
+                    y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
+                    a[h] += live ? (double)x[e] * (double)(pos ? pkv[e] : nkv[e]) : 0.0;
+                }
+                const size_t m = (size_t)sb * R + row_of(p, h);
+                nt_store4(reinterpret_cast<float4*>(C + m * ldc) + i4, y[0], y[1], y[2], y[3]);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h == 1 && !two) break;
+            const double t = wave_sum(a[h]);
+            if (lane == 0) {
+                const int r = row_of(p, h);
+                const size_t m = (size_t)sb * R + r;
+                cst[m] = (cst_init ? (double)cst_init[r] : cst[m]) + t;
+            }
+        }
+    };
+
+    float4 va[2][4], vb[2][4];
+    if (npairs > 0) load_pair(0, va);
+    for (int i = threadIdx.x; i < ldc; i += kThreads) {
+        float pm = 0.f, nm = 0.f, pk = 0.f, nk = 0.f;
+        if (i < n) {
+            const float la = lambda ? lambda[(size_t)b * n + i] : 1.0f;
+            const float m = mu ? mu[(size_t)b * n + i] : 1.0f;
+            const float v = nu ? nu[(size_t)b * n + i] : 0.0f;
+            const float bj = bias ? bias[i] : 0.0f;
+            pm = side == 0 ? la : m;
+            nm = side == 0 ? m : la;
+            pk = (side == 0 ? 0.0f : v) + pm * bj;
+            nk = (side == 0 ? v : 0.0f) + nm * bj;
+        }
+        reinterpret_cast<float*>(s_pm)[i] = pm;
+        reinterpret_cast<float*>(s_nm)[i] = nm;
+        reinterpret_cast<float*>(s_pk)[i] = pk;
+        reinterpret_cast<float*>(s_nk)[i] = nk;
+    }
+    __syncthreads();
+    for (int p = 0; p < npairs; p += 2) {
+        if (p + 1 < npairs) load_pair(p + 1, vb);
+        compute_pair(p, va);
+        if (p + 1 < npairs) {
+            if (p + 2 < npairs) load_pair(p + 2, va);
+            compute_pair(p + 1, vb);
+        }
+    }
+}
+
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
+    const float* __restrict__ C, int ldc, const double* __restrict__ cst, int batch, int R, int n,
+    const float* __restrict__ lo, const float* __restrict__ hi, float* __restrict__ out_l,
+    float* __restrict__ out_u, const float* __restrict__ src, int ld_src,
+    const float* __restrict__ cst_init, int rows_per_wave,
+    const float* __restrict__ part, int nslots, long long part_stride)
+{
+    extern __shared__ float4 s_par[];                  // [2][ldc/4]
+    const int cw4 = ldc >> 2;
+    float4* s_p = s_par;
+    float4* s_n = s_par + cw4;
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rbeg = blockIdx.x * (rows_per_wave * kWaves) + wave * rows_per_wave;
+    const int rend = min(R, rbeg + rows_per_wave);
+    const int npairs = rend > rbeg ? (rend - rbeg + 1) >> 1 : 0;
+
+    auto row_of = [&](int p, int h) { const int r = rbeg + 2 * p + h; return r < rend ? r : rend - 1; };
+    auto load_pair = [&](int p, float4 (&v)[2][4]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int r = row_of(p, h);
+            const float4* in = reinterpret_cast<const float4*>(SHARED ? src + (size_t)r * ld_src
+                                                                      : C + ((size_t)sb * R + r) * ldc);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int i4 = t * 64 + lane;
+                if (i4 < cw4) v[h][t] = SHARED ? in[i4] : nt_load4(in + i4);
+            }
+        }
+    };
+    auto compute_pair = [&](int p, float4 (&v)[2][4]) {
+        double a[2] = {0.0, 0.0};
+        const bool two = rbeg + 2 * p + 1 < rend;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int i4 = t * 64 + lane;
+            if (i4 >= cw4) continue;
+            const float4 pp = s_p[i4], ng = s_n[i4];
+            const float pv[4] = {pp.x, pp.y, pp.z, pp.w}, nv[4] = {ng.x, ng.y, ng.z, ng.w};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (h == 1 && !two) break;
+                const float x[4] = {v[h][t].x, v[h][t].y, v[h][t].z, v[h][t].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (i4 * 4 + e < n) a[h] += (double)x[e] * (double)(x[e] >= 0.0f ? pv[e] : nv[e]);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h == 1 && !two) break;
+            const int r = row_of(p, h);
+            const size_t m = (size_t)sb * R + r;
+            double extra = 0.0;
+            for (int t = lane; t < nslots; t += 64) extra += (double)part[(size_t)t * part_stride + m];
+            const double t = wave_sum(a[h] + extra);
+            if (lane == 0) {
+                const double val = (cst_init ? (double)cst_init[r] : cst[m]) + t;
+                (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)val;
+            }
+        }
+    };
+
+    float4 va[2][4], vb[2][4];
+    if (npairs > 0) load_pair(0, va);
+    for (int i = threadIdx.x; i < ldc; i += kThreads) {
+        float pv = 0.f, qv = 0.f;
+        if (i < n) {
+            const float lv = lo[(size_t)b * n + i], hv = hi[(size_t)b * n + i];
+            pv = side == 0 ? lv : hv;
+            qv = side == 0 ? hv : lv;
+        }
+        reinterpret_cast<float*>(s_p)[i] = pv;
+        reinterpret_cast<float*>(s_n)[i] = qv;
+    }
+    __syncthreads();
+    for (int p = 0; p < npairs; p += 2) {
+        if (p + 1 < npairs) load_pair(p + 1, vb);
+        compute_pair(p, va);
+        if (p + 1 < npairs) {
+            if (p + 2 < npairs) load_pair(p + 2, va);
+            compute_pair(p + 1, vb);
+        }
+    }
+}
+
 // Packed parameters of the sign-split ReLU step for both sides (see launch_pack_relax).
 __global__ __launch_bounds__(kThreads) void pack_relax_kernel(
     const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
@@ -360,11 +555,16 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const float* __restri
 }
 
 int g_rows_per_wave = 0;
+int g_stream = 1;
 
-int pick_rows_per_wave(int R, int groups)
+int pick_rows_per_wave(int R, int groups, bool streaming_rows)
 {
     if (g_rows_per_wave > 0) return g_rows_per_wave;
-    // enough blocks to cover 256 CUs a few times over, as many rows per block as that allows
+    // Rows streamed from HBM: one pair of rows per wavefront (many small workgroups keep more loads in
+    // flight than few long-running ones; measured on cfg2- and cfg5-sized passes).
+    if (streaming_rows) return 2;
+    // Rows re-read from a shared (cache-resident) source: enough blocks to cover 256 CUs a few times over,
+    // as many rows per block as that allows.
     int rpw = kMaxRowsPerWave;
     while (rpw > 1 && ceil_div(R, rpw * kWaves) * groups < 2048) rpw >>= 1;
     return rpw;
@@ -373,6 +573,7 @@ int pick_rows_per_wave(int R, int groups)
 }  // namespace
 
 void set_rows_per_wave(int v) { g_rows_per_wave = v; }
+void set_rows_stream(int v) { g_stream = v; }
 
 void launch_relax_params(const float* l, const float* u, float* lambda, float* mu, float* nu,
                          float* rl, float* ru, int64_t count, hipStream_t s)
@@ -398,10 +599,20 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
                     "relax_step: shared source needs ld_src >= ldc, multiple of 4, 16-byte aligned");
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "relax_step: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
-    const int rpw = pick_rows_per_wave(R, nsides * batch);
+    const int rpw = pick_rows_per_wave(R, nsides * batch, !shared_src && ldc <= 1024 && g_stream);
     const int chunk = std::min(ldc, kChunk);
     const size_t lds = (size_t)chunk * 16;
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
+    if (ldc <= 1024 && g_stream) {
+        if (shared_src)
+            hipLaunchKernelGGL(relax_step_stream_kernel<true>, grid, dim3(kThreads), (size_t)ldc * 16, s, C, ldc, cst, batch,
+                               R, n, lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw);
+        else
+            hipLaunchKernelGGL(relax_step_stream_kernel<false>, grid, dim3(kThreads), (size_t)ldc * 16, s, C, ldc, cst, batch,
+                               R, n, lambda, mu, nu, bias, (const float*)nullptr, 0, cst_init, rpw);
+        DPC_HIP(hipGetLastError());
+        return;
+    }
     if (shared_src)
         hipLaunchKernelGGL(relax_step_kernel<true>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n,
                            lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw, chunk);
@@ -429,10 +640,21 @@ void launch_concretise(const float* C, int ldc, const double* cst, int nsides, i
         DPC_REQUIRE(C && cst && ((uintptr_t)C % 16) == 0, DPC_EINVAL, "concretise: C/cst missing or misaligned");
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "concretise: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
-    const int rpw = pick_rows_per_wave(R, nsides * batch);
+    const int rpw = pick_rows_per_wave(R, nsides * batch, !shared_src && ldc <= 1024 && g_stream);
     const int chunk = std::min(ldc, kChunk);
     const size_t lds = (size_t)chunk * 8;
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
+    if (ldc <= 1024 && g_stream) {
+        if (shared_src)
+            hipLaunchKernelGGL(concretise_stream_kernel<true>, grid, dim3(kThreads), (size_t)ldc * 8, s, C, ldc, cst, batch, R,
+                               n, lo, hi, out_l, out_u, shared_src, ld_src, cst_init, rpw, part, nslots, (long long)part_stride);
+        else
+            hipLaunchKernelGGL(concretise_stream_kernel<false>, grid, dim3(kThreads), (size_t)ldc * 8, s, C, ldc, cst, batch, R,
+                               n, lo, hi, out_l, out_u, (const float*)nullptr, 0, cst_init, rpw, part, nslots,
+                               (long long)part_stride);
+        DPC_HIP(hipGetLastError());
+        return;
+    }
     if (shared_src)
         hipLaunchKernelGGL(concretise_kernel<true>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n, lo, hi,
                            out_l, out_u, shared_src, ld_src, cst_init, rpw, chunk, part, nslots, (long long)part_stride);
