@@ -416,6 +416,9 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
         case 10: launch_variant<Tile<128, 128, 8, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 16: launch_variant<Tile<128, 128, 8, 64, 64, 4>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 18: launch_variant<Tile<64, 64, 64, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 19: launch_variant<Tile<64, 64, 32, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 20: launch_variant<Tile<32, 64, 32, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 11: launch_variant<Tile<64, 64, 8, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 12: launch_variant<Tile<128, 64, 16, 64, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 13: launch_variant<Tile<64, 128, 8, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;

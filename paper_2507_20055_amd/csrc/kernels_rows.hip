@@ -270,9 +270,9 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
 }
 
 // Streaming variants for rows of at most 1024 columns (one 16-byte load per lane covers a quarter of
-// the row): a wavefront walks its rows two at a time and issues the loads of the next pair before it
-// computes the current one, and the very first loads are issued before the per-input parameters are
-// staged in LDS, so the HBM stream never waits for the parameter fill or for the reductions.
+// the row): a wavefront owns one pair of rows and issues all of its loads before the per-input
+// parameters are staged in LDS, so the HBM stream does not wait for the parameter fill; small register
+// footprint, so eight wavefronts per SIMD keep loads in flight.
 template <bool SHARED>
 __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
     float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
         }
     };
 
-    float4 va[2][4], vb[2][4];
+    float4 va[2][4];
     if (npairs > 0) load_pair(0, va);
     for (int i = threadIdx.x; i < ldc; i += kThreads) {
         float pm = 0.f, nm = 0.f, pk = 0.f, nk = 0.f;
@@ -365,13 +365,9 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
         reinterpret_cast<float*>(s_nk)[i] = nk;
     }
     __syncthreads();
-    for (int p = 0; p < npairs; p += 2) {
-        if (p + 1 < npairs) load_pair(p + 1, vb);
+    for (int p = 0; p < npairs; ++p) {       // one pair per wavefront in the launch configuration used; more only if forced
+        if (p > 0) load_pair(p, va);
         compute_pair(p, va);
-        if (p + 1 < npairs) {
-            if (p + 2 < npairs) load_pair(p + 2, va);
-            compute_pair(p + 1, vb);
-        }
     }
 }
 
@@ -441,7 +437,7 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
         }
     };
 
-    float4 va[2][4], vb[2][4];
+    float4 va[2][4];
     if (npairs > 0) load_pair(0, va);
     for (int i = threadIdx.x; i < ldc; i += kThreads) {
         float pv = 0.f, qv = 0.f;
@@ -454,13 +450,9 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
         reinterpret_cast<float*>(s_n)[i] = qv;
     }
     __syncthreads();
-    for (int p = 0; p < npairs; p += 2) {
-        if (p + 1 < npairs) load_pair(p + 1, vb);
+    for (int p = 0; p < npairs; ++p) {       // one pair per wavefront in the launch configuration used; more only if forced
+        if (p > 0) load_pair(p, va);
         compute_pair(p, va);
-        if (p + 1 < npairs) {
-            if (p + 2 < npairs) load_pair(p + 2, va);
-            compute_pair(p + 1, vb);
-        }
     }
 }
 

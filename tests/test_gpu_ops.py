@@ -22,7 +22,7 @@ def _rows(rng, M, n, ld, zero_frac=0.05):
     return C, full
 
 
-@pytest.mark.parametrize("variant", [-1] + list(range(16)))
+@pytest.mark.parametrize("variant", [-1] + list(range(21)))
 @pytest.mark.parametrize("M,K,N", [(1, 8, 8), (200, 100, 784), (333, 500, 500), (1000, 10, 100), (4100, 1024, 1024),
                                    (129, 36, 260), (64, 1, 5)])
 def test_contract(M, K, N, variant):

@@ -89,6 +89,51 @@ def test_fused_and_unfused_paths_agree(seed, dims, B):
     gnet.close()
 
 
+@pytest.mark.parametrize("kind", ["fc", "conv", "single"])
+def test_symbolic_bounds_of_last_layer(kind):
+    """keep_symbolic = 1: the input-level polyhedral bounds of the output neurons against the oracle's, and their
+    extrema over the box against the concrete bounds (conv nets exercise the (H,W,C) -> (C,H,W) read-out)."""
+    if kind == "fc":
+        net = wl.random_small_net(41, [9, 40, 33, 6])
+    elif kind == "conv":
+        net = wl.random_small_conv(42, (2, 6, 5), [(4, 3, 1, 1), (4, 4, 2, 1)], [8, 4])
+    else:
+        net = wl.random_small_net(43, [7, 5])
+    B = 3
+    x, lo, hi = wl.random_box(44, net.n_in, B, 0.1)
+    b = _binding()
+    gnet = b.Network(net)
+    last = len(net.layers)
+    g = gnet.certify(lo, hi, None, keep_symbolic=1)
+    o = oracle.run(net, lo, hi, sym_layer=last)
+    l, u = g.concrete(last)
+    for side, (oc, ok, bound) in enumerate(((o.sym["cl"], o.sym["kl"], l), (o.sym["cu"], o.sym["ku"], u))):
+        c, k = g.symbolic(last, side)
+        scale = np.abs(oc).max() + 1e-30
+        assert np.all(np.abs(c - oc) <= 1e-5 * scale + 1e-4 * np.abs(oc))
+        assert np.all(np.abs(k - ok) <= 1e-5 + 1e-4 * np.abs(ok))
+        pos, neg = np.maximum(c.astype(np.float64), 0), np.minimum(c.astype(np.float64), 0)
+        lo64, hi64 = lo.astype(np.float64)[:, None, :], hi.astype(np.float64)[:, None, :]
+        ext = k + ((pos * lo64 + neg * hi64) if side == 0 else (pos * hi64 + neg * lo64)).sum(-1)
+        np.testing.assert_allclose(ext, bound, rtol=1e-4, atol=1e-4)
+    with pytest.raises(b.DpcError):
+        gnet.certify(lo, hi, None).symbolic(last, 0)          # not kept
+    gnet.close()
+
+
+@pytest.mark.parametrize("R", [1, 31, 32, 33, 64, 100])
+def test_rows_per_group_around_the_fusion_threshold(R):
+    """The fused epilogue needs >= 32 rows per (side, input) group; layers on both sides of that threshold, with
+    tiles straddling group boundaries, must agree with the oracle."""
+    net = wl.random_small_net(50 + R, [24, R, R, 5])
+    B = 5
+    x, lo, hi = wl.random_box(51, 24, B, 0.05)
+    label = np.arange(B, dtype=np.int32) % 5
+    gnet, g, o = _run_both(net, lo, hi, label)
+    compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
 @pytest.mark.parametrize("depth", [0, 1, 2, 3, 5])
 def test_depth_limited(depth):
     net = wl.random_small_net(11, [12, 20, 18, 16, 6])
