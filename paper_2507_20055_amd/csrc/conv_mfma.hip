@@ -16,8 +16,10 @@
 // list entries per class; each wavefront owns 2 position tiles x (Ci/32) channel tiles.  The input
 // patches of the workgroup's rows sit in LDS ((H,W,C) order, position stride Co+4 floats to spread
 // banks); a lane fetches the four consecutive channels it feeds with one 16-byte read at an address
-// it computes from (position, tap), or from a zero block when the tap falls outside the patch.  The
-// kernel slice of the current tap ([Co][Ci]) is staged through double-buffered LDS.
+// it computes from (position, tap), or from a zero block when the tap falls outside the patch.  When the
+// patches of all channels would leave room for only one workgroup per CU, the reduction runs over channel
+// chunks and LDS holds one chunk at a time.  Kernel values are read from global memory (L2-resident) one
+// (tap, 8-channel group) ahead into registers, so the (tap, group) loop has no barrier.
 #include "conv.h"
 
 namespace dpc {
@@ -34,7 +36,8 @@ struct CtArgs {
     const float* taps; int Ci, kh, kw, s, off;
     float* out; int ld_out; int oh, ow;
     int RB;          // rows per workgroup
-    int pstride;     // LDS floats per input position (Co + 4)
+    int CC;          // channels of the reduction staged in LDS at a time (divides Co, multiple of 8)
+    int pstride;     // LDS floats per input position (CC + 4)
     int rowstride;   // LDS floats per input row patch (ih*iw*pstride)
 };
 
@@ -45,40 +48,44 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     float* sIn = reinterpret_cast<float*>(lds4);                       // [RB*rowstride] + zero block [pstride]
     const int in_floats = a.RB * a.rowstride;
     const int zoff = in_floats;                                        // zero block
-    constexpr int BS = NT * 32 + 8;                                    // floats per kernel-slice row
-    float* sB = sIn + in_floats + a.pstride;                           // [2][Co*BS]
-    int4* sTab = reinterpret_cast<int4*>(sB + 2 * a.Co * BS);          // [256] {e0, py0, px0, outoff}
+    int4* sTab = reinterpret_cast<int4*>(sIn + in_floats + a.pstride); // [256] {e0, py0, px0, outoff}
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
     const long long m0 = (long long)blockIdx.x * a.RB;
     const int q0 = blockIdx.y * kCtEntries;
+    const int npos = a.ih * a.iw;
+    const int nchunks = a.Co / a.CC;                                   // channel chunks of the reduction
+    const int cc4n = a.CC >> 2;
 
-    // ---- stage the input patches of this workgroup's rows ----
-    {
-        const int c4n = a.Co >> 2, npos = a.ih * a.iw;
-        const int total = a.RB * npos * c4n;
+    // stage channels [c0, c0 + CC) of the input patches of this workgroup's rows
+    auto stage_input = [&](int c0) __attribute__((always_inline)) {
+        const int total = a.RB * npos * cc4n;
         for (int idx = tid; idx < total; idx += kCtThreads) {
-            const int c4 = idx % c4n, t = idx / c4n;
+            const int c4 = idx % cc4n, t = idx / cc4n;
             const int pos = t % npos, ml = t / npos;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m0 + ml < a.M) v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + (size_t)pos * a.Co + c4 * 4);
+            if (m0 + ml < a.M)
+                v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + (size_t)pos * a.Co + c0 + c4 * 4);
             *reinterpret_cast<float4*>(sIn + ml * a.rowstride + pos * a.pstride + c4 * 4) = v;
         }
-        for (int i = tid; i < a.pstride; i += kCtThreads) sIn[zoff + i] = 0.0f;
-        for (int i = tid; i < 2 * a.Co * BS; i += kCtThreads) sB[i] = 0.0f;   // channel padding of the slices stays zero
-        // padding columns of the output rows
-        if (blockIdx.y == 0) {
-            const int elems = a.oh * a.ow * a.Ci, padn = a.ld_out - elems;
-            for (int i = tid; i < a.RB * padn; i += kCtThreads) {
-                const int ml = i / padn, c = i - ml * padn;
-                if (m0 + ml < a.M) a.out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
-            }
+    };
+
+    for (int i = tid; i < a.pstride; i += kCtThreads) sIn[zoff + i] = 0.0f;
+    if (blockIdx.y == 0) {           // padding columns of the output rows
+        const int elems = a.oh * a.ow * a.Ci, padn = a.ld_out - elems;
+        for (int i = tid; i < a.RB * padn; i += kCtThreads) {
+            const int ml = i / padn, c = i - ml * padn;
+            if (m0 + ml < a.M) a.out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
         }
     }
+    if (nchunks == 1) stage_input(0);
     __syncthreads();
 
-    const int slice4 = a.Co * a.Ci / 4;                  // float4 per kernel slice
-    const int ci4n = a.Ci >> 2;
+    // kernel values straight from global memory (the whole kernel is a few hundred KB and is read by every
+    // workgroup, so it lives in L2): lane (kq, l32) needs K[tap][co = 8g+4kq+s][ci = 32n + l32], s = 0..3
+    bool ci_ok[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) ci_ok[n] = n * 32 + l32 < a.Ci;
 
     for (int cy = 0; cy < a.s; ++cy) {
         // rows y of this class: (y + off) mod s == cy  ->  y = y0 + s*iy
@@ -129,51 +136,43 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                     for (int v = 0; v < 16; ++v) acc[t][n][v] = 0.0f;
 
             const int ntaps = nky * nkx;
-            constexpr int SL = 4;                                // float4 per thread per slice, at most (Co*Ci <= 4096)
-            float4 rs[SL];
-            auto load_slice = [&](int ti) {
-                const int jy = ti / nkx, jx = ti - jy * nkx;
-                const float* src = a.taps + (size_t)((cy + a.s * jy) * a.kw + (cx + a.s * jx)) * a.Co * a.Ci;
-#pragma unroll
-                for (int i = 0; i < SL; ++i) {
-                    const int idx = tid + kCtThreads * i;
-                    if (idx < slice4) rs[i] = *reinterpret_cast<const float4*>(src + (size_t)idx * 4);
+            const int ngr = a.CC >> 3;                            // groups of 8 channels per chunk
+            for (int cc = 0; cc < nchunks; ++cc) {
+                if (nchunks > 1) {
+                    __syncthreads();                              // everyone is done with the previous chunk
+                    stage_input(cc * a.CC);
+                    __syncthreads();
                 }
-            };
-            auto store_slice = [&](int buf) {
-#pragma unroll
-                for (int i = 0; i < SL; ++i) {
-                    const int idx = tid + kCtThreads * i;
-                    if (idx < slice4) {
-                        const int co = idx / ci4n, c4 = idx - co * ci4n;
-                        *reinterpret_cast<float4*>(sB + buf * a.Co * BS + co * BS + c4 * 4) = rs[i];
-                    }
-                }
-            };
-            if (ntaps > 0) { load_slice(0); store_slice(0); }
-            __syncthreads();
-
-            for (int ti = 0; ti < ntaps; ++ti) {
-                const int buf = ti & 1;
-                if (ti + 1 < ntaps) load_slice(ti + 1);
-                const int jy = ti / nkx, jx = ti - jy * nkx;
-                int addr[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int py = py0[t] - jy, px = px0[t] - jx;
-                    const bool ok = live[t] && py >= 0 && py < a.ih && px >= 0 && px < a.iw;
-                    addr[t] = ok ? e0[t] - (jy * a.iw + jx) * a.pstride : zoff + 4 * kq;
-                }
-                const float* pb = sB + buf * a.Co * BS + l32;
-                for (int g = 0; g < (a.Co >> 3); ++g) {
-                    float4 av[2];
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) av[t] = *reinterpret_cast<const float4*>(sIn + addr[t] + 8 * g);
-                    float b[4][NT];
+                const int nit = ntaps * ngr;                      // flattened (tap, group) iterations
+                auto kptr = [&](int it) __attribute__((always_inline)) {
+                    const int ti = it / ngr, g = it - ti * ngr;
+                    const int jy = ti / nkx, jx = ti - jy * nkx;
+                    const int tap = (cy + a.s * jy) * a.kw + (cx + a.s * jx);
+                    return a.taps + ((size_t)tap * a.Co + cc * a.CC + 8 * g + 4 * kq) * a.Ci + l32;
+                };
+                float bcur[4][NT], bnxt[4][NT];
+                auto load_b = [&](int it, float (&bb)[4][NT]) __attribute__((always_inline)) {
+                    const float* p = kptr(it);
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
-                        for (int n = 0; n < NT; ++n) b[s][n] = pb[(8 * g + 4 * kq + s) * BS + n * 32];
+                        for (int n = 0; n < NT; ++n) bb[s][n] = ci_ok[n] ? p[(size_t)s * a.Ci + n * 32] : 0.0f;
+                };
+                int addr[2] = {zoff + 4 * kq, zoff + 4 * kq};
+                auto step = [&](int it, float (&bb)[4][NT]) __attribute__((always_inline)) {
+                    const int ti = it / ngr, g = it - ti * ngr;
+                    if (g == 0) {
+                        const int jy = ti / nkx, jx = ti - jy * nkx;
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const int py = py0[t] - jy, px = px0[t] - jx;
+                            const bool ok = live[t] && py >= 0 && py < a.ih && px >= 0 && px < a.iw;
+                            addr[t] = ok ? e0[t] - (jy * a.iw + jx) * a.pstride : zoff + 4 * kq;
+                        }
+                    }
+                    float4 av[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) av[t] = *reinterpret_cast<const float4*>(sIn + addr[t] + 8 * g);
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -181,11 +180,18 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                             const float x = s == 0 ? av[t].x : s == 1 ? av[t].y : s == 2 ? av[t].z : av[t].w;
 #pragma unroll
                             for (int n = 0; n < NT; ++n)
-                                acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, b[s][n], acc[t][n], 0, 0, 0);
+                                acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, bb[s][n], acc[t][n], 0, 0, 0);
                         }
+                };
+                if (nit > 0) load_b(0, bcur);
+                for (int it = 0; it < nit; it += 2) {
+                    if (it + 1 < nit) load_b(it + 1, bnxt);
+                    step(it, bcur);
+                    if (it + 1 < nit) {
+                        if (it + 2 < nit) load_b(it + 2, bcur);
+                        step(it + 1, bnxt);
+                    }
                 }
-                if (ti + 1 < ntaps) store_slice(buf ^ 1);
-                __syncthreads();
             }
 
             // ---- epilogue: accumulator register 4*i+j of a lane is list entry 8*i + 4*kq + j, channel l32 ----
@@ -199,12 +205,10 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                         const int oo = sTab[wave * 64 + t * 32 + 8 * i + 4 * kq + j].w;
                         if (oo < 0) continue;
 #pragma unroll
-                        for (int n = 0; n < NT; ++n) {
-                            const int ci = n * 32 + l32;
-                            if (ci < a.Ci) obase[oo + ci] = acc[t][n][4 * i + j];
-                        }
+                        for (int n = 0; n < NT; ++n)
+                            if (ci_ok[n]) obase[oo + n * 32 + l32] = acc[t][n][4 * i + j];
                     }
-            __syncthreads();          // the table and slice buffers are rebuilt by the next class
+            __syncthreads();          // the table is rebuilt by the next class
         }
     }
 }
@@ -334,17 +338,24 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         return true;
     }
 
-    if (g.Ci % 4 != 0 || g.Ci > 64 || g.Co * g.Ci > 4096) return false;   // a kernel slice is staged as at most 4 float4 per thread
+    if (g.Ci > 64) return false;
     const int NT = (g.Ci + 31) / 32;
     // largest class decides how many rows fill the 256 list entries of a workgroup
     const int Pc_max = (int)(ceil_div(oh, g.stride) * ceil_div(ow, g.stride));
-    const size_t fixed = (size_t)a.pstride * 4 + 2 * (size_t)g.Co * (NT * 32 + 8) * 4 + 256 * 16;
     int RB = std::max(1, kCtEntries / std::max(Pc_max, 1));
-    // prefer two workgroups per CU when the patches allow it
-    while (RB > 1 && (size_t)RB * row_bytes + fixed > 72 * 1024) --RB;
-    if ((size_t)RB * row_bytes + fixed > kLdsBudget) return false;
+    // channel chunk: all channels if two workgroups then fit a CU, otherwise the largest divisor of Co that does
+    int CC = g.Co;
+    auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 16; };
+    while (CC > 8 && lds_for(RB, CC) > 72 * 1024 && (CC / 2) % 8 == 0) CC /= 2;
+    while (RB > 1 && lds_for(RB, CC) > 72 * 1024) --RB;
+    if (lds_for(RB, CC) > kLdsBudget) return false;
+    a.CC = CC;
+    a.pstride = CC + 4;
+    a.rowstride = ih * iw * a.pstride;
+    const size_t row_bytes2 = (size_t)a.rowstride * 4;
+    const size_t fixed = (size_t)a.pstride * 4 + 256 * 16;
     a.RB = RB;
-    const size_t lds = (size_t)RB * row_bytes + fixed;
+    const size_t lds = (size_t)RB * row_bytes2 + fixed;
     dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div((int64_t)RB * Pc_max, kCtEntries));
     if (NT == 1) {
         static bool configured = false;
