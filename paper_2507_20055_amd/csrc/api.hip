@@ -28,6 +28,7 @@ void set_error(const char* fmt, ...)
 }
 
 void set_contract_variant(int v);
+static int g_merge_final = 1;     // 1: output-layer bounds and margins share one traversal
 void set_contract_remap(int v);
 void set_rows_per_wave(int v);
 void set_rows_stream(int v);
@@ -233,7 +234,7 @@ size_t workspace_floats(const dpc_network* net, int B, bool with_margin)
         }
     }
     if (with_margin) {
-        const size_t rows = (size_t)B * (net->layers[nl - 1]->n_out - 1);
+        const size_t rows = 2 * (size_t)B * (2 * (size_t)net->layers[nl - 1]->n_out - 1);
         for (int j = 0; j < nl; ++j) need = std::max(need, rows * net->ld_of(j));
     }
     return need;
@@ -251,7 +252,8 @@ struct Pass {
     int B;
 };
 
-void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym)
+void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym,
+              double useful = 1.0)       // fraction of the rows whose bounds are used (flop accounting only)
 {
     dpc_network* net = P.net;
     dpc_result* res = P.res;
@@ -322,7 +324,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 } else {
                     launch_contract(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, P.s);
                 }
-                res->prof.contract_flop += 2.0 * (double)M * n_at * n_prev;
+                res->prof.contract_flop += useful * 2.0 * (double)M * n_at * n_prev;
                 f.ld = ld_prev;
             } else if (f.patch) {
                 fused_relu = false;
@@ -333,7 +335,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             } else {
                 fused_relu = false;
                 const int ld_prev = net->ld_of(at - 1);
-                res->prof.contract_flop += launch_conv_transpose_rows(cur, M, f.ld, L.g.Ho, L.g.Wo, L.g, L.cw, nxt, ld_prev,
+                res->prof.contract_flop += useful * launch_conv_transpose_rows(cur, M, f.ld, L.g.Ho, L.g.Wo, L.g, L.cw, nxt, ld_prev,
                                                                       L.g.H, L.g.W, L.g.pad, P.s);
                 f.ld = ld_prev;
             }
@@ -654,7 +656,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
 
         // ---- workspace ----
         size_t need_rows = 1;
-        const size_t stage_need = 2 * (size_t)B * n0 + 16;   // box staging + one flag word
+        const size_t stage_need = std::max(2 * (size_t)B * n0, 2 * (size_t)B * (2 * (size_t)nK - 1)) + 16;   // box staging / merged last pass + one flag word
         for (int i = 1; i <= nl; ++i)
             if (net->layers[i - 1]->kind != RELU) need_rows = std::max(need_rows, 2 * (size_t)B * net->size_of(i));
         const size_t need = workspace_floats(net, B, label != nullptr);
@@ -711,6 +713,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         }
 
         if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
+        const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
         Pass P{net, res, &opt, s, &prof, B};
         for (int i = 1; i <= nl; ++i) {
             Layer& L = *net->layers[i - 1];
@@ -725,9 +728,26 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 res->prof.other_launches++;
                 continue;
             }
+            if (merge_final && i == nl) continue;       // bounded together with the margins below
             run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
         }
-        if (label) {
+        if (merge_final) {
+            // Output-layer rows and margin rows walk the same layers: one pass of 2*nK-1 rows per (side, input)
+            // instead of two passes (the margins' upper-side rows are computed and dropped).
+            const int Rm = 2 * nK - 1;
+            float* tl = net->stage.p;
+            float* tu = net->stage.p + (size_t)B * Rm;
+            prof.begin(P_OTHER);
+            launch_final_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
+                              net->ld_of(nl - 1), net->cst.p, s);
+            prof.end();
+            res->prof.other_launches++;
+            run_pass(P, nl - 1, 2, Rm, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rm));
+            prof.begin(P_OTHER);
+            launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s);
+            prof.end();
+            res->prof.other_launches++;
+        } else if (label) {
             const int nq = nK - 1;
             prof.begin(P_OTHER);
             launch_margin_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
@@ -943,6 +963,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
         else if (strcmp(key, "contract_remap") == 0) set_contract_remap(value);
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
+        else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
         else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
         else if (strcmp(key, "rows_stream") == 0) set_rows_stream(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);

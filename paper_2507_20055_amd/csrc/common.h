@@ -91,6 +91,13 @@ void launch_finalize_bounds(const double* cst, const float* part, int nslots, in
 void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch,
                         int nK, int n, float* C, int ldc, double* cst, hipStream_t s);
 
+// Output-layer rows and margin rows stacked in one pass (R = 2*nK - 1 rows per (side, input)); and the
+// kernel that splits that pass's bounds into l,u of the output layer, margins and verdicts.
+void launch_final_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch, int nK, int n,
+                       float* C, int ldc, double* cst, hipStream_t s);
+void launch_split_final(const float* tl, const float* tu, int batch, int nK, float* l, float* u, float* margin,
+                        int32_t* verdict, hipStream_t s);
+
 // verdict[b] = all margins of input b > 0.
 void launch_verdict(const float* margin, int batch, int nq, int32_t* verdict, hipStream_t s);
 

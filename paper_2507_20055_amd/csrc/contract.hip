@@ -103,6 +103,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
 
     const int K4 = (K + 3) & ~3, N4 = (N + 3) & ~3;
     const int nk = (K + T::BK - 1) / T::BK;
+    const bool wave_active = n0 + wcol0 < N4;
 
     // Per-thread staging slots.  Each slot is a set of scalar variables (not an array): the prefetched
     // tile must live in registers across the MFMA section, and arrays captured by the helper lambdas were
@@ -176,6 +177,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
 
         const float4* pa = sA + stage * T::A_STAGE + wrow0 + l32;
         const float* pb = sB + stage * T::B_STAGE + wcol0 + T::NT * l32;
+        if (wave_active)                 // a wavefront whose columns all lie past N only helps staging
 #pragma unroll
         for (int g = 0; g < T::BK / 8; ++g) {
             float4 a[T::MT];

@@ -522,6 +522,51 @@ __global__ __launch_bounds__(kThreads) void margin_rows_kernel(
     if (threadIdx.x == 0) cst[m] = (double)bias[t] - (double)bias[o];
 }
 
+// Rows of the last pass when output-layer bounds and margins share one traversal: for group (side, b),
+// rows 0..nK-1 are the output neurons' own expressions (weight rows, bias), rows nK..2nK-2 the margin
+// expressions logit[label_b] - logit[o] for the nK-1 other classes o in ascending order.
+__global__ __launch_bounds__(kThreads) void final_rows_kernel(
+    const float* __restrict__ W, int ldw, const float* __restrict__ bias, const int32_t* __restrict__ label, int batch,
+    int nK, int n, float* __restrict__ C, int ldc, double* __restrict__ cst)
+{
+    const int Rm = 2 * nK - 1;
+    const int m = blockIdx.x;                 // (side*batch + b)*Rm + r
+    const int r = m % Rm, b = (m / Rm) % batch;
+    int t = r, o = -1;
+    if (r >= nK) {
+        const int q = r - nK;
+        t = label[b];
+        o = q < t ? q : q + 1;
+    }
+    for (int i = threadIdx.x; i < ldc; i += kThreads) {
+        float v = 0.0f;
+        if (i < n) v = o < 0 ? W[(size_t)t * ldw + i] : W[(size_t)t * ldw + i] - W[(size_t)o * ldw + i];
+        C[(size_t)m * ldc + i] = v;
+    }
+    if (threadIdx.x == 0) cst[m] = o < 0 ? (double)bias[t] : (double)bias[t] - (double)bias[o];
+}
+
+// Splits the merged last pass: l,u of the output layer, margins (lower side only) and verdicts.
+__global__ void split_final_kernel(const float* __restrict__ tl, const float* __restrict__ tu, int batch, int nK,
+                                   float* __restrict__ l, float* __restrict__ u, float* __restrict__ margin,
+                                   int32_t* __restrict__ verdict)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    const int Rm = 2 * nK - 1;
+    for (int r = 0; r < nK; ++r) {
+        l[(size_t)b * nK + r] = tl[(size_t)b * Rm + r];
+        u[(size_t)b * nK + r] = tu[(size_t)b * Rm + r];
+    }
+    int ok = 1;
+    for (int q = 0; q < nK - 1; ++q) {
+        const float mg = tl[(size_t)b * Rm + nK + q];
+        margin[(size_t)b * (nK - 1) + q] = mg;
+        if (!(mg > 0.0f)) ok = 0;
+    }
+    verdict[b] = ok;
+}
+
 __global__ void verdict_kernel(const float* __restrict__ margin, int batch, int nq, int32_t* __restrict__ verdict)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -697,6 +742,25 @@ void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_
     if (batch == 0) return;
     hipLaunchKernelGGL(margin_rows_kernel, dim3((unsigned)(batch * (nK - 1))), dim3(kThreads), 0, s,
                        W, ldw, bias, label, nK, n, C, ldc, cst);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_final_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch, int nK, int n,
+                       float* C, int ldc, double* cst, hipStream_t s)
+{
+    DPC_REQUIRE(nK >= 2 && ldc >= n && ldw >= n, DPC_EINVAL, "final_rows: bad shape");
+    if (batch == 0) return;
+    hipLaunchKernelGGL(final_rows_kernel, dim3((unsigned)(2 * batch * (2 * nK - 1))), dim3(kThreads), 0, s, W, ldw, bias,
+                       label, batch, nK, n, C, ldc, cst);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_split_final(const float* tl, const float* tu, int batch, int nK, float* l, float* u, float* margin,
+                        int32_t* verdict, hipStream_t s)
+{
+    if (batch == 0) return;
+    hipLaunchKernelGGL(split_final_kernel, dim3((unsigned)ceil_div(batch, 64)), dim3(64), 0, s, tl, tu, batch, nK, l, u,
+                       margin, verdict);
     DPC_HIP(hipGetLastError());
 }
 

@@ -89,6 +89,24 @@ def test_fused_and_unfused_paths_agree(seed, dims, B):
     gnet.close()
 
 
+def test_merged_and_separate_final_pass_agree():
+    """Output-layer bounds and margins share one traversal by default; the two-pass route must give the same."""
+    b = _binding()
+    net = wl.random_small_net(61, [20, 48, 40, 7])
+    x, lo, hi = wl.random_box(62, 20, 4, 0.08)
+    label = np.array([0, 3, 6, 2], np.int32)
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label)
+    for merge in (1, 0):
+        b.dpc_tuning_set("merge_final", merge)
+        try:
+            g = gnet.certify(lo, hi, label)
+            compare_with_oracle(net, lo, hi, g, o, label)
+        finally:
+            b.dpc_tuning_set("merge_final", 1)
+    gnet.close()
+
+
 @pytest.mark.parametrize("kind", ["fc", "conv", "single"])
 def test_symbolic_bounds_of_last_layer(kind):
     """keep_symbolic = 1: the input-level polyhedral bounds of the output neurons against the oracle's, and their
@@ -194,7 +212,7 @@ def test_device_inputs_and_stream():
         np.testing.assert_array_equal(ref.concrete(k)[1], got.concrete(k)[1])
     np.testing.assert_array_equal(ref.verdict()[1], got.verdict()[1])
     p = got.profile()
-    assert p["contract_launches"] == 3 + 2 and p["total_ms"] > 0 and p["contract_flop"] > 0   # 1+2 layer passes, 2 margin
+    assert p["contract_launches"] == 1 + 2 and p["total_ms"] > 0 and p["contract_flop"] > 0   # layer 3: 1; output + margins (one pass): 2
     gnet.close()
 
 
