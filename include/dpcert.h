@@ -96,11 +96,13 @@ typedef struct {
                                    contraction runs in that contraction's epilogue where supported;
                                    0: every step is its own kernel */
     int32_t profile;            /* 1: time every kernel class with HIP events (see dpc_result_profile) */
-    int32_t reserved;
+    int32_t use_graph;          /* 1 (default): when a result object is reused on a non-null stream, the call's kernel
+                                   sequence is captured into a HIP graph once and replayed (launch-bound small networks);
+                                   0: always launch kernel by kernel */
     void*   stream;             /* hipStream_t all work is enqueued on (NULL = the null stream) */
 } dpc_options;
 
-/* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, null stream). */
+/* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, graph replay on, null stream). */
 dpc_status dpc_options_default(dpc_options* opt);
 
 /* Runs the certifier on `batch` boxes.

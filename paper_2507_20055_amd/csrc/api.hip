@@ -29,6 +29,7 @@ void set_error(const char* fmt, ...)
 
 void set_contract_variant(int v);
 static int g_merge_final = 1;     // 1: output-layer bounds and margins share one traversal
+static uint64_t g_tuning_epoch = 1;  // bumped by every dpc_tuning_set: captured launch sequences are keyed on it
 void set_contract_remap(int v);
 void set_rows_per_wave(int v);
 void set_rows_stream(int v);
@@ -52,12 +53,13 @@ template <class T>
 struct DevBuf {
     T* p = nullptr;
     size_t count = 0;
-    void reserve(size_t n)
+    bool reserve(size_t n)             // true when the buffer was (re)allocated: old addresses are dead
     {
-        if (n <= count) return;
+        if (n <= count) return false;
         release();
         DPC_HIP(hipMalloc(reinterpret_cast<void**>(&p), n * sizeof(T)));
         count = n;
+        return true;
     }
     void release()
     {
@@ -107,6 +109,7 @@ struct dpc_network {
     std::vector<std::unique_ptr<DevBuf<float>>> pk;
     DevBuf<float> part;
     int64_t part_stride = 0;
+    uint64_t ws_epoch = 1;                 // bumped whenever a workspace buffer moves (captured graphs hold addresses)
     static constexpr int kMaxSlots = 96;
 
     int size_of(int idx) const { return idx == 0 ? n0 : layers[idx - 1]->n_out; }
@@ -132,6 +135,19 @@ struct dpc_result {
     DevBuf<float> sym_coeff;                 // [2][B*nK][ld0]
     DevBuf<double> sym_cst;                  // [2][B*nK]
     dpc_profile prof{};
+    // the kernel sequence of a certify call on this result, captured once and replayed on reuse
+    hipGraphExec_t gexec = nullptr;
+    struct GraphKey {
+        int depth = 0, fuse = 0, has_label = 0;
+        uint64_t tuning_epoch = 0, ws_epoch = 0;
+        bool operator==(const GraphKey& o) const
+        {
+            return depth == o.depth && fuse == o.fuse && has_label == o.has_label && tuning_epoch == o.tuning_epoch &&
+                   ws_epoch == o.ws_epoch;
+        }
+    } gkey;
+    dpc_profile gprof{};                   // launch and flop counters of the captured sequence
+    ~dpc_result() { if (gexec) (void)hipGraphExecDestroy(gexec); }
 };
 
 namespace {
@@ -580,6 +596,7 @@ dpc_status dpc_options_default(dpc_options* opt)
         opt->keep_symbolic = 0;
         opt->fuse = 1;
         opt->profile = 0;
+        opt->use_graph = 1;
         opt->stream = nullptr;
     });
 }
@@ -660,15 +677,15 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         for (int i = 1; i <= nl; ++i)
             if (net->layers[i - 1]->kind != RELU) need_rows = std::max(need_rows, 2 * (size_t)B * net->size_of(i));
         const size_t need = workspace_floats(net, B, label != nullptr);
-        net->buf[0].reserve(need);
-        net->buf[1].reserve(need);
+        bool moved = net->buf[0].reserve(need);
+        moved |= net->buf[1].reserve(need);
         const bool fuse = opt.fuse && opt.max_backsub_depth < 0;
         if (fuse) {
             size_t fuse_rows = 0;          // rows of the passes that can use fused epilogues (dense rows of FC layers)
             for (int i = 1; i <= nl; ++i)
                 if (net->layers[i - 1]->kind == AFFINE) fuse_rows = std::max(fuse_rows, 2 * (size_t)B * net->size_of(i));
             if (fuse_rows > 0 && fuse_rows * dpc_network::kMaxSlots * 4 <= ((size_t)1 << 31)) {
-                net->part.reserve(fuse_rows * dpc_network::kMaxSlots);
+                moved |= net->part.reserve(fuse_rows * dpc_network::kMaxSlots);
                 net->part_stride = std::max<int64_t>(net->part_stride, (int64_t)fuse_rows);
             }
             if (net->pk.size() != (size_t)nl + 1) net->pk.resize(nl + 1);
@@ -676,11 +693,12 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 const bool want = i == 0 ? !net->in_spatial || true : net->layers[i - 1]->kind == RELU;
                 if (!want) continue;
                 if (!net->pk[i]) net->pk[i].reset(new DevBuf<float>());
-                net->pk[i]->reserve((size_t)2 * B * net->ld_of(i) * 4);
+                moved |= net->pk[i]->reserve((size_t)2 * B * net->ld_of(i) * 4);
             }
         }
-        net->cst.reserve(need_rows);
-        net->stage.reserve(stage_need);
+        moved |= net->cst.reserve(need_rows);
+        moved |= net->stage.reserve(stage_need);
+        if (moved) ++net->ws_epoch;
 
         if (B == 0) {
             if (fresh) { *result = fresh.release(); net->live_results++; }
@@ -712,53 +730,85 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                         bad == 1 ? "dpc_certify: lo > hi or a non-finite bound" : "dpc_certify: label out of range");
         }
 
-        if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
+        // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
+        // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
+        const bool graphable = opt.use_graph && s != nullptr && !prof.on && !opt.keep_symbolic && !fresh;
+        const dpc_result::GraphKey gkey{opt.max_backsub_depth, opt.fuse != 0, label != nullptr, g_tuning_epoch, net->ws_epoch};
         const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
-        Pass P{net, res, &opt, s, &prof, B};
-        for (int i = 1; i <= nl; ++i) {
-            Layer& L = *net->layers[i - 1];
-            if (L.kind == RELU) {
+        auto enqueue_all = [&]() {
+            if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
+            Pass P{net, res, &opt, s, &prof, B};
+            for (int i = 1; i <= nl; ++i) {
+                Layer& L = *net->layers[i - 1];
+                if (L.kind == RELU) {
+                    prof.begin(P_OTHER);
+                    launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
+                                        (int64_t)B * L.n_out, s);
+                    if (fuse)
+                        launch_pack_relax(res->lam[i], res->mu[i], res->nu[i], net->layers[i - 2]->dBias.p, B, L.n_out,
+                                          net->ld_of(i), net->pk[i]->p, s);
+                    prof.end();
+                    res->prof.other_launches++;
+                    continue;
+                }
+                if (merge_final && i == nl) continue;       // bounded together with the margins below
+                run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
+            }
+            if (merge_final) {
+                // Output-layer rows and margin rows walk the same layers: one pass of 2*nK-1 rows per (side, input)
+                // instead of two passes (the margins' upper-side rows are computed and dropped).
+                const int Rm = 2 * nK - 1;
+                float* tl = net->stage.p;
+                float* tu = net->stage.p + (size_t)B * Rm;
                 prof.begin(P_OTHER);
-                launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
-                                    (int64_t)B * L.n_out, s);
-                if (fuse)
-                    launch_pack_relax(res->lam[i], res->mu[i], res->nu[i], net->layers[i - 2]->dBias.p, B, L.n_out,
-                                      net->ld_of(i), net->pk[i]->p, s);
+                launch_final_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
+                                  net->ld_of(nl - 1), net->cst.p, s);
                 prof.end();
                 res->prof.other_launches++;
-                continue;
+                run_pass(P, nl - 1, 2, Rm, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rm));
+                prof.begin(P_OTHER);
+                launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s);
+                prof.end();
+                res->prof.other_launches++;
+            } else if (label) {
+                const int nq = nK - 1;
+                prof.begin(P_OTHER);
+                launch_margin_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
+                                   net->ld_of(nl - 1), net->cst.p, s);
+                prof.end();
+                res->prof.other_launches++;
+                run_pass(P, nl - 1, 1, nq, nullptr, res->margin.p, nullptr, false);
+                prof.begin(P_OTHER);
+                launch_verdict(res->margin.p, B, nq, res->verdict.p, s);
+                prof.end();
+                res->prof.other_launches++;
             }
-            if (merge_final && i == nl) continue;       // bounded together with the margins below
-            run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
-        }
-        if (merge_final) {
-            // Output-layer rows and margin rows walk the same layers: one pass of 2*nK-1 rows per (side, input)
-            // instead of two passes (the margins' upper-side rows are computed and dropped).
-            const int Rm = 2 * nK - 1;
-            float* tl = net->stage.p;
-            float* tu = net->stage.p + (size_t)B * Rm;
-            prof.begin(P_OTHER);
-            launch_final_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
-                              net->ld_of(nl - 1), net->cst.p, s);
-            prof.end();
-            res->prof.other_launches++;
-            run_pass(P, nl - 1, 2, Rm, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rm));
-            prof.begin(P_OTHER);
-            launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s);
-            prof.end();
-            res->prof.other_launches++;
-        } else if (label) {
-            const int nq = nK - 1;
-            prof.begin(P_OTHER);
-            launch_margin_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
-                               net->ld_of(nl - 1), net->cst.p, s);
-            prof.end();
-            res->prof.other_launches++;
-            run_pass(P, nl - 1, 1, nq, nullptr, res->margin.p, nullptr, false);
-            prof.begin(P_OTHER);
-            launch_verdict(res->margin.p, B, nq, res->verdict.p, s);
-            prof.end();
-            res->prof.other_launches++;
+        };
+        if (graphable && res->gexec && res->gkey == gkey) {
+            res->prof = res->gprof;
+            DPC_HIP(hipGraphLaunch(res->gexec, s));
+        } else if (graphable) {
+            if (res->gexec) { (void)hipGraphExecDestroy(res->gexec); res->gexec = nullptr; }
+            DPC_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+            hipGraph_t graph = nullptr;
+            try {
+                enqueue_all();
+            } catch (...) {
+                (void)hipStreamEndCapture(s, &graph);
+                if (graph) (void)hipGraphDestroy(graph);
+                throw;
+            }
+            DPC_HIP(hipStreamEndCapture(s, &graph));
+            hipGraphExec_t exec = nullptr;
+            const hipError_t ie = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            DPC_REQUIRE(ie == hipSuccess, DPC_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(ie));
+            res->gexec = exec;
+            res->gkey = gkey;
+            res->gprof = res->prof;
+            DPC_HIP(hipGraphLaunch(res->gexec, s));
+        } else {
+            enqueue_all();
         }
         prof.finish();
         if (prof.on) DPC_HIP(hipEventRecord(t1, s));
@@ -960,6 +1010,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
 {
     return guarded([&] {
         DPC_REQUIRE(key, DPC_EINVAL, "dpc_tuning_set: NULL key");
+        ++g_tuning_epoch;
         if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
         else if (strcmp(key, "contract_remap") == 0) set_contract_remap(value);
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);

@@ -216,6 +216,41 @@ def test_device_inputs_and_stream():
     gnet.close()
 
 
+@pytest.mark.parametrize("kind", ["fc", "conv"])
+def test_graph_replay_matches_eager(kind):
+    """A reused result on a caller's stream replays the kernel sequence as one HIP graph.  Every replay
+    (different boxes each time, eager library work and synchronisation between the replays, a batch change
+    on the same network in the middle) must equal the eager launch sequence bit for bit."""
+    import torch
+    b = _binding()
+    if kind == "fc":
+        net, B = wl.random_small_net(31, [24, 70, 70, 70, 6]), 5
+    else:
+        net, B = wl.random_small_conv(32, (3, 8, 8), [(4, 3, 1, 1), (8, 4, 2, 1)], [16, 5]), 3
+    n0 = net.n_in
+    gnet = b.Network(net)
+    s = torch.cuda.Stream()
+    res = None
+    last = len(net.layers)
+    for it in range(6):
+        x, lo, hi = wl.random_box(100 + it, n0, B, 0.02 * (1 + it % 3))
+        label = np.argmax(wl.forward(net, x.astype(np.float64))[-1], axis=1).astype(np.int32)
+        eager = gnet.certify(lo, hi, label, use_graph=0)
+        res = gnet.certify(lo, hi, label, stream=s.cuda_stream, reuse=res)     # it = 0 eager, 1 captures, 2.. replay
+        for k in range(1, last + 1):
+            np.testing.assert_array_equal(eager.concrete(k)[0], res.concrete(k)[0])
+            np.testing.assert_array_equal(eager.concrete(k)[1], res.concrete(k)[1])
+        np.testing.assert_array_equal(eager.verdict()[1], res.verdict()[1])
+        np.testing.assert_array_equal(eager.verdict()[0], res.verdict()[0])
+        assert res.profile()["contract_launches"] == eager.profile()["contract_launches"]
+        if it == 3:
+            # a larger batch on the same network moves the shared workspace: the captured graph must not be replayed
+            xb, lob, hib = wl.random_box(7, n0, 4 * B, 0.01)
+            gnet.certify(lob, hib)
+        torch.cuda.synchronize()
+    gnet.close()
+
+
 # ---- the five named configurations -------------------------------------------------------------
 def test_cfg1_full():
     w = wl.make_workload("cfg1")
