@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="inputs per eps given to the CPU oracle (0 = default)")
     ap.add_argument("--variant", type=int, default=-1, help="contraction tile variant (tuning)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE", help="dpc_tuning_set(KEY, VALUE) before the run")
     ap.add_argument("--fuse", type=int, default=1)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 256 MiB device-to-device copy first (known size, to scale rocprofv3 byte counters)")
@@ -56,6 +57,9 @@ def main():
     torch.cuda.set_device(0)
     if args.variant >= 0:
         binding.dpc_tuning_set("contract_variant", args.variant)
+    for kv in args.tune:
+        key, _, val = kv.partition("=")
+        binding.dpc_tuning_set(key, int(val))
 
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, device="cuda", dtype=torch.float32).normal_()

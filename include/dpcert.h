@@ -201,8 +201,12 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
 
 /* Tuning knob for experiments: key "contract_variant" selects the tile shape of the contraction
  * kernel (-1 = chosen from the problem shape, the default); key "conv_algo" = 1 forces the generic
- * gather kernel for convolution contractions (0 = MFMA / small-channel kernels where they apply).
- * Results do not depend on either beyond rounding order. */
+ * gather kernel for convolution contractions (0 = MFMA / small-channel kernels where they apply);
+ * key "chain" chooses when the traversal of a fully-connected layer's rows runs as one kernel with the
+ * coefficient rows resident in LDS (-1 = by problem shape, the default; 0 = never; 1 = whenever the
+ * layer widths fit); "merge_final" = 0 bounds the output layer and the margins in two traversals instead
+ * of one; "contract_remap", "rows_per_wave", "rows_stream" select launch shapes of the contraction and
+ * row kernels.  Results do not depend on any of them beyond rounding order. */
 dpc_status dpc_tuning_set(const char* key, int32_t value);
 
 /* Text of the last error raised on the calling thread ("" if none). */

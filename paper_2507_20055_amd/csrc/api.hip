@@ -291,6 +291,37 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     bool concretised = false;      // the last contraction already reduced the rows against the box
     const bool may_fuse = P.opt->fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
 
+    // Fully-connected layers all the way down: the whole traversal in one kernel, rows resident in LDS.
+    if (may_fuse && own && own->kind == AFFINE && !f.patch && nsides == 2 && at >= 1 && net->layers[at - 1]->kind == RELU &&
+        net->pk[at] && net->pk[at]->p) {
+        ChainStepDesc steps[16];
+        int ns = 0;
+        bool ok = true;
+        double flop = 0.0;
+        for (int j = at - 1; ok; j -= 2) {          // j: 1-based index of the affine layer the step crosses
+            if (j < 1 || ns >= 16) { ok = false; break; }
+            const Layer& L = *net->layers[j - 1];
+            const int below = j - 1;
+            if (L.kind != AFFINE || !net->pk[below] || !net->pk[below]->p) { ok = false; break; }
+            if (below > 0 && net->layers[below - 1]->kind != RELU) { ok = false; break; }
+            steps[ns++] = ChainStepDesc{L.dW.p, net->pk[below]->p, L.n_out, L.ldw, net->ld_of(below), below > 0 ? 1 : 0};
+            flop += 2.0 * (double)M * L.n_out * L.n_in;
+            if (below == 0) break;
+        }
+        if (ok) {
+            ChainDesc d{own->dW.p, own->dBias.p, net->pk[at]->p, own->ldw, net->ld_of(at), net->ld_of(at), R, B, ns, steps,
+                        out_l, out_u};
+            P.prof->begin(P_CONTRACT);
+            const bool done = launch_chain(d, P.s);
+            P.prof->end();
+            if (done) {
+                res->prof.contract_flop += useful * flop;
+                res->prof.contract_launches++;
+                return;
+            }
+        }
+    }
+
     auto relax = [&](const float* la, const float* m, const float* v, const Layer* bias_of) {
         const int n_at = net->size_of(at);
         P.prof->begin(P_RELAX);
@@ -546,7 +577,7 @@ dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
             const bool prev_spatial = net->spatial((int)i, &pc, &ph, &pw);
             if (L.kind == AFFINE) {
                 L.ldw = (int)round_up(L.n_in, kLdAlign);
-                std::vector<float> w((size_t)L.n_out * L.ldw, 0.0f);
+                std::vector<float> w((size_t)round_up(L.n_out, 8) * L.ldw, 0.0f);   // rows padded to whole K groups of 8 (zeros)
                 for (int r = 0; r < L.n_out; ++r)
                     for (int c = 0; c < L.n_in; ++c) {
                         int dst = c;                    // column c is a (C,H,W) index when the input is spatial
@@ -1015,6 +1046,8 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         else if (strcmp(key, "contract_remap") == 0) set_contract_remap(value);
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
         else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
+        else if (strcmp(key, "chain") == 0) set_chain_mode(value);
+        else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);
         else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
         else if (strcmp(key, "rows_stream") == 0) set_rows_stream(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);

@@ -76,6 +76,32 @@ struct ContractEpilogue {
 int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
                           float* Cout, int ldc, const ContractEpilogue& e, hipStream_t s);
 
+// Whole traversal of the rows of one fully-connected layer with the coefficient rows resident in LDS
+// (fill from the layer's own weight rows through the ReLU step below, then one contraction + traversal step
+// per affine layer, the last one concretising against the box).  Parameters are the packed ones of
+// launch_pack_relax / launch_pack_bounds, groups = 2 * B in (side, input) order.  W of every step must have
+// its rows padded with zeros to a multiple of 8.  Returns false, launching nothing, when the shape is not
+// covered (panels wider than 1024 columns, too few workgroups to fill the device, ...).
+struct ChainStepDesc {
+    const float* W;        // [round_up(K, 8)][ldw]
+    const float* pk;       // [2 * B][ldpk] float4
+    int K, ldw, ldpk, store;
+};
+struct ChainDesc {
+    const float* W0;       // [R][ldw0]: the bounded layer's own rows
+    const float* bias0;    // [R]
+    const float* pk0;      // [2 * B][ldpk0] float4: ReLU layer directly below
+    int ldw0, ldpk0, width0;
+    int R, B;
+    int nsteps;
+    const ChainStepDesc* steps;
+    float* out_l;          // [B][R]
+    float* out_u;
+};
+bool launch_chain(const ChainDesc& d, hipStream_t s);
+void set_chain_mode(int v);          // -1: by shape, 0: never, 1: whenever covered
+void set_chain_rows(int v);          // 32 or 64: row block for panels up to 512 columns
+
 // pk[side][b][c] = (pm, nm, kp, kn) of the sign-split ReLU step through a ReLU layer with relaxation
 // (lambda, mu, nu) followed by the bias fold of the layer below (bias may be NULL); columns n..ld-1 zero.
 void launch_pack_relax(const float* lambda, const float* mu, const float* nu, const float* bias, int batch, int n,

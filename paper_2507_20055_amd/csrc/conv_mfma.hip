@@ -304,7 +304,6 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     a.out = out; a.ld_out = ld_out; a.oh = oh; a.ow = ow;
     a.pstride = g.Co + 4;
     a.rowstride = ih * iw * a.pstride;
-    const size_t row_bytes = (size_t)a.rowstride * 4;
     constexpr size_t kLdsBudget = 150 * 1024;
 
     if (g.Ci <= 4) {

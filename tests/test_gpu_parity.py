@@ -216,6 +216,41 @@ def test_device_inputs_and_stream():
     gnet.close()
 
 
+@pytest.mark.parametrize("seed,dims,B", [(71, [24, 70, 70, 70, 6], 5),            # rows per group not a multiple of the row block
+                                         (72, [50, 100, 257, 129, 10], 3),        # widths off every alignment
+                                         (73, [1000, 64, 96, 4], 2),              # input wider than one chunk of the last step
+                                         (74, [40, 600, 520, 5], 2),              # panels wider than 512: 32-row variant
+                                         (75, [1100, 530, 40, 33, 3], 1),         # 32-row variant, two chunks at the input
+                                         (76, [16, 32, 40, 7], 4)])               # a single step
+@pytest.mark.parametrize("rows", [32, 64])
+def test_resident_traversal_kernel(seed, dims, B, rows):
+    """Traversal of a fully-connected layer's rows as one kernel (coefficients resident in LDS), forced on for
+    shapes the default heuristic would leave to the per-layer kernels; against the oracle, and it must really
+    have run (fewer contraction launches than the per-layer route)."""
+    b = _binding()
+    net = wl.random_small_net(seed, dims)
+    x, lo, hi = wl.random_box(seed + 1, dims[0], B, 0.05)
+    label = np.arange(B, dtype=np.int32) % dims[-1]
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label)
+    launches = {}
+    try:
+        b.dpc_tuning_set("chain_rows", rows)          # row block of the variant for panels up to 512 columns
+        for mode in (1, 0):
+            b.dpc_tuning_set("chain", mode)
+            g = gnet.certify(lo, hi, label, profile=1)
+            compare_with_oracle(net, lo, hi, g, o, label)
+            p = g.profile()
+            launches[mode] = (p["contract_launches"], p["relax_launches"])
+    finally:
+        b.dpc_tuning_set("chain", -1)
+        b.dpc_tuning_set("chain_rows", 64)
+    n_affine = len(dims) - 1
+    assert launches[0][0] - launches[1][0] == sum(i - 2 for i in range(2, n_affine)), launches
+    assert launches[0][1] - launches[1][1] == n_affine - 2, launches       # no separate first ReLU step either
+    gnet.close()
+
+
 @pytest.mark.parametrize("kind", ["fc", "conv"])
 def test_graph_replay_matches_eager(kind):
     """A reused result on a caller's stream replays the kernel sequence as one HIP graph.  Every replay
