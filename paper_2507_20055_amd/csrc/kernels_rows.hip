@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
                             const bool pos = x[e] >= 0.0f;
                             const bool live = i4 * 4 + e < nloc;     // padding columns come out as exact zeros
                             y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
-                            a[h] += live ? (double)x[e] * (double)(pos ? pkv[e] : nkv[e]) : 0.0;
+                            a[h] = live ? fmaf(x[e], pos ? pkv[e] : nkv[e], a[h]) : a[h];
                         }
                         nt_store4(out[h] + i4, y[0], y[1], y[2], y[3]);
                     }
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
         }
     };
     auto compute_pair = [&](int p, float4 (&v)[2][4]) {
-        double a[2] = {0.0, 0.0};
+        float a[2] = {0.0f, 0.0f};     // a lane adds at most 16 products in fp32; lanes are combined in fp64
         const bool two = rbeg + 2 * p + 1 < rend;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
                     const bool pos = x[e] >= 0.0f;
                     const bool live = i4 * 4 + e < n;        // padding columns come out as exact zeros
                     y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
-                    a[h] += live ? (double)x[e] * (double)(pos ? pkv[e] : nkv[e]) : 0.0;
+                    a[h] = live ? fmaf(x[e], pos ? pkv[e] : nkv[e], a[h]) : a[h];
                 }
                 const size_t m = (size_t)sb * R + row_of(p, h);
                 nt_store4(reinterpret_cast<float4*>(C + m * ldc) + i4, y[0], y[1], y[2], y[3]);
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             if (h == 1 && !two) break;
-            const double t = wave_sum(a[h]);
+            const double t = wave_sum((double)a[h]);
             if (lane == 0) {
                 const int r = row_of(p, h);
                 const size_t m = (size_t)sb * R + r;
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
         }
     };
     auto compute_pair = [&](int p, float4 (&v)[2][4]) {
-        double a[2] = {0.0, 0.0};
+        float a[2] = {0.0f, 0.0f};     // a lane adds at most 16 products in fp32; lanes are combined in fp64
         const bool two = rbeg + 2 * p + 1 < rend;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
                 const float x[4] = {v[h][t].x, v[h][t].y, v[h][t].z, v[h][t].w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (i4 * 4 + e < n) a[h] += (double)x[e] * (double)(x[e] >= 0.0f ? pv[e] : nv[e]);
+                    if (i4 * 4 + e < n) a[h] = fmaf(x[e], x[e] >= 0.0f ? pv[e] : nv[e], a[h]);
             }
         }
 #pragma unroll
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
             const size_t m = (size_t)sb * R + r;
             double extra = 0.0;
             for (int t = lane; t < nslots; t += 64) extra += (double)part[(size_t)t * part_stride + m];
-            const double t = wave_sum(a[h] + extra);
+            const double t = wave_sum((double)a[h] + extra);
             if (lane == 0) {
                 const double val = (cst_init ? (double)cst_init[r] : cst[m]) + t;
                 (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)val;
