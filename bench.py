@@ -17,10 +17,10 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# L2-miss traffic of the dominant contraction kernel per launch, bytes (fetch + write), from the two
-# rocprofv3 --pmc runs summarised in profiles/pmc_<workload>.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after
-# calibration on a plain 256 MiB copy); mean over the launches of one step.
-TRAFFIC = {"cfg2": 1.373e8, "cfg5": 1.887e9}
+# L2-miss traffic of the dominant MFMA kernel per launch, bytes (fetch + write), from the two rocprofv3 --pmc
+# runs summarised in profiles/pmc_<workload>.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after calibration on a
+# plain 256 MiB copy); mean over the launches of one step.  Only valid for the default tuning.
+TRAFFIC = {"cfg2": 7.351e7, "cfg5": 2.561e9}
 
 DESCR = {
     "cfg1": "cfg1: FC 784-100-100-100-10, B=1, eps=0.01",
@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="inputs per eps given to the CPU oracle (0 = default)")
     ap.add_argument("--variant", type=int, default=-1, help="contraction tile variant (tuning)")
+    ap.add_argument("--host-inputs", action="store_true", help="pass host arrays (adds the PCIe upload of the boxes to every step)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE", help="dpc_tuning_set(KEY, VALUE) before the run")
     ap.add_argument("--fuse", type=int, default=1)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -75,6 +76,8 @@ def main():
     with torch.cuda.stream(stream):
         dev = [(torch.from_numpy(w.lo).cuda(), torch.from_numpy(w.hi).cuda(), torch.from_numpy(w.label).cuda()) for w in loads]
     stream.synchronize()
+    if args.host_inputs:
+        dev = [(w.lo, w.hi, w.label) for w in loads]
     B = loads[0].lo.shape[0]
     results = [None] * n_eps
 
@@ -108,7 +111,14 @@ def main():
     min_abs_margin = float(min(float(np.abs(r.verdict()[1]).min()) for r in results))
 
     P = prof_tot
-    contract_tflops = P["contract_flop"] / (P["contract_ms"] * 1e-3) / 1e12 if P["contract_ms"] > 0 else 0.0
+    # dominant MFMA kernel: the LDS-resident traversal kernel where it runs, else the per-layer contraction
+    dom = "chain" if P["chain_ms"] > P["contract_ms"] else "contract"
+    dom_name = {"chain": "chain_kernel (whole traversal of a layer's rows: fp32 MFMA C*W per layer crossed, rows resident in LDS)",
+                "contract": "contract / conv-transpose kernels (fp32 MFMA C*W of one traversal step)"}[dom]
+    dom_ms, dom_flop, dom_launches = P[dom + "_ms"], P[dom + "_flop"], P[dom + "_launches"]
+    dom_tflops = dom_flop / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    mfma_ms = P["chain_ms"] + P["contract_ms"]
+    mfma_tflops = (P["chain_flop"] + P["contract_flop"]) / (mfma_ms * 1e-3) / 1e12 if mfma_ms > 0 else 0.0
     relax_gbs = P["relax_bytes"] / (P["relax_ms"] * 1e-3) / 1e9 if P["relax_ms"] > 0 else 0.0
     conc_gbs = P["concretise_bytes"] / (P["concretise_ms"] * 1e-3) / 1e9 if P["concretise_ms"] > 0 else 0.0
 
@@ -126,22 +136,28 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": DESCR[args.workload], "inputs_per_step": inputs_per_step,
-                   "verified": verified, "min_abs_margin": min_abs_margin, "fuse": args.fuse},
+                   "verified": verified, "min_abs_margin": min_abs_margin, "fuse": args.fuse,
+                   "inputs": "host" if args.host_inputs else "resident in HBM"},
         "roofline": {
-            "kernel": "contract (fp32 MFMA C*W of back-substitution)",
-            "bound": "mfma", "achieved": contract_tflops, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-            "frac": contract_tflops / PEAK_FP32_MFMA_TFLOPS,
-            "launches": P["contract_launches"], "avg_launch_ms": P["contract_ms"] / max(P["contract_launches"], 1),
-            "flop_per_step": P["contract_flop"] / args.steps,
-            "traffic": TRAFFIC.get(args.workload),
+            "kernel": dom_name,
+            "bound": "mfma", "achieved": dom_tflops, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": dom_tflops / PEAK_FP32_MFMA_TFLOPS,
+            "launches": dom_launches, "avg_launch_ms": dom_ms / max(dom_launches, 1),
+            "flop_per_launch": dom_flop / max(dom_launches, 1),
+            "traffic": TRAFFIC.get(args.workload) if not args.tune and args.variant < 0 and args.fuse == 1 else None,
+            "all_mfma_kernels": {"achieved": mfma_tflops, "frac": mfma_tflops / PEAK_FP32_MFMA_TFLOPS,
+                                 "flop_per_step": (P["chain_flop"] + P["contract_flop"]) / args.steps,
+                                 "ms_per_step": mfma_ms / args.steps},
         },
-        "hbm_passes": {
+        # the row passes left outside the MFMA kernels' epilogues in this run (on the fully-connected workloads
+        # only the few margin / output rows: launch-bound; the kernels themselves are measured below)
+        "hbm_passes_in_run": {
             "relax_step": {"achieved": relax_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": relax_gbs / PEAK_HBM_GBS,
                            "launches": P["relax_launches"], "ms_per_step": P["relax_ms"] / args.steps},
             "concretise": {"achieved": conc_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": conc_gbs / PEAK_HBM_GBS,
                            "launches": P["concretise_launches"], "ms_per_step": P["concretise_ms"] / args.steps},
         },
-        "time_split_ms_per_step": {k: P[k] / args.steps for k in ("contract_ms", "relax_ms", "concretise_ms", "other_ms", "total_ms")},
+        "time_split_ms_per_step": {k: P[k] / args.steps for k in ("chain_ms", "contract_ms", "relax_ms", "concretise_ms", "other_ms", "total_ms")},
         "value_with_kernel_events": inputs_per_step * args.steps / dt_events,
     }
 

@@ -146,6 +146,11 @@ typedef struct {
     double  contract_flop;       /* 2*M*K*N per contraction (conv: compressed-core count) */
     double  relax_bytes;         /* 8 B per coefficient (first step of a pass: 4 B) */
     double  concretise_bytes;    /* 4 B per coefficient */
+    /* whole traversals run as one LDS-resident kernel (not included in the contract_* fields) */
+    double  chain_ms;
+    double  chain_flop;          /* sum of 2*M*K*N over the layers each launch crosses */
+    int32_t chain_launches;
+    int32_t reserved;
 } dpc_profile;
 dpc_status dpc_result_profile(const dpc_result* res, dpc_profile* out);
 

@@ -36,7 +36,9 @@ class dpc_profile(ctypes.Structure):
                 ("contract_ms", ctypes.c_double), ("relax_ms", ctypes.c_double),
                 ("concretise_ms", ctypes.c_double), ("other_ms", ctypes.c_double), ("total_ms", ctypes.c_double),
                 ("contract_flop", ctypes.c_double), ("relax_bytes", ctypes.c_double),
-                ("concretise_bytes", ctypes.c_double)]
+                ("concretise_bytes", ctypes.c_double),
+                ("chain_ms", ctypes.c_double), ("chain_flop", ctypes.c_double),
+                ("chain_launches", c_i32), ("reserved", c_i32)]
 
 
 EXPORTS = {

@@ -192,7 +192,7 @@ struct Prof {
     }
     ~Prof() { for (auto e : pool) (void)hipEventDestroy(e); }
 };
-enum { P_CONTRACT = 0, P_RELAX = 1, P_CONC = 2, P_OTHER = 3 };
+enum { P_CONTRACT = 0, P_RELAX = 1, P_CONC = 2, P_OTHER = 3, P_CHAIN = 4 };
 
 // Shape of the coefficient rows during a traversal: dense over a whole layer, or patch form
 // (rows of a convolution layer: a small window of the current layer, see conv.h).
@@ -311,12 +311,12 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
         if (ok) {
             ChainDesc d{own->dW.p, own->dBias.p, net->pk[at]->p, own->ldw, net->ld_of(at), net->ld_of(at), R, B, ns, steps,
                         out_l, out_u};
-            P.prof->begin(P_CONTRACT);
+            P.prof->begin(P_CHAIN);
             const bool done = launch_chain(d, P.s);
             P.prof->end();
             if (done) {
-                res->prof.contract_flop += useful * flop;
-                res->prof.contract_launches++;
+                res->prof.chain_flop += useful * flop;
+                res->prof.chain_launches++;
                 return;
             }
         }
@@ -851,7 +851,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             for (auto& r : prof.segs) {
                 DPC_HIP(hipEventElapsedTime(&ms, r.a, r.b));
                 (r.cls == P_CONTRACT ? res->prof.contract_ms : r.cls == P_RELAX ? res->prof.relax_ms
-                 : r.cls == P_CONC ? res->prof.concretise_ms : res->prof.other_ms) += ms;
+                 : r.cls == P_CONC ? res->prof.concretise_ms : r.cls == P_CHAIN ? res->prof.chain_ms : res->prof.other_ms) += ms;
             }
         }
         if (fresh) { *result = fresh.release(); net->live_results++; }

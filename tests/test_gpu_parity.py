@@ -241,7 +241,8 @@ def test_resident_traversal_kernel(seed, dims, B, rows):
             g = gnet.certify(lo, hi, label, profile=1)
             compare_with_oracle(net, lo, hi, g, o, label)
             p = g.profile()
-            launches[mode] = (p["contract_launches"], p["relax_launches"])
+            launches[mode] = (p["contract_launches"] + p["chain_launches"], p["relax_launches"])
+            assert p["chain_launches"] == (len(dims) - 3 if mode else 0)         # one per hidden layer after the first
     finally:
         b.dpc_tuning_set("chain", -1)
         b.dpc_tuning_set("chain_rows", 64)
