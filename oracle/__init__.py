@@ -54,6 +54,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.dpo_run.restype = ctypes.c_int
+        _lib.dpo_run_reuse.restype = ctypes.c_int
         assert _lib.dpo_layer_struct_size() == ctypes.sizeof(_Layer)
     return _lib
 
@@ -71,8 +72,13 @@ class OracleResult:
 
 
 def run(net, lo, hi, label=None, sym_layer: int = -1, max_depth: int = -1,
-        threads: Optional[int] = None) -> OracleResult:
+        threads: Optional[int] = None, certifier: str = "deeppoly") -> OracleResult:
+    """certifier: "deeppoly" (Appendix C, DeepPoly; max_depth >= 0 gives DeepPoly_p) or "reusecert" (Appendix C,
+    ReuseCert: l, u of affine layers are the concretised stored bounds, ReLU-layer l, u stay 0, sym_layer may
+    name any affine layer)."""
     lib = _load()
+    assert certifier in ("deeppoly", "reusecert")
+    assert certifier == "deeppoly" or max_depth < 0
     if threads is not None:
         os.environ["OMP_NUM_THREADS"] = str(threads)
     lo = np.ascontiguousarray(lo, dtype=np.float32)
@@ -152,11 +158,16 @@ def run(net, lo, hi, label=None, sym_layer: int = -1, max_depth: int = -1,
         sp = [res.sym[k].ctypes.data for k in ("cl", "kl", "cu", "ku")]
 
     vp = ctypes.c_void_p
-    rc = lib.dpo_run(ctypes.c_int(nl), arr, ctypes.c_int(B), vp(lo.ctypes.data), vp(hi.ctypes.data), vp(lab_p),
-                     ptrs(l), ptrs(u), ptrs(lam), ptrs(mu), ptrs(nu), vp(mar_p), vp(ver_p),
-                     ctypes.c_int(sym_layer), vp(sp[0]), vp(sp[1]), vp(sp[2]), vp(sp[3]),
-                     ctypes.c_int(max_depth))
+    if certifier == "reusecert":
+        rc = lib.dpo_run_reuse(ctypes.c_int(nl), arr, ctypes.c_int(B), vp(lo.ctypes.data), vp(hi.ctypes.data), vp(lab_p),
+                               ptrs(l), ptrs(u), ptrs(lam), ptrs(mu), ptrs(nu), vp(mar_p), vp(ver_p),
+                               ctypes.c_int(sym_layer), vp(sp[0]), vp(sp[1]), vp(sp[2]), vp(sp[3]))
+    else:
+        rc = lib.dpo_run(ctypes.c_int(nl), arr, ctypes.c_int(B), vp(lo.ctypes.data), vp(hi.ctypes.data), vp(lab_p),
+                         ptrs(l), ptrs(u), ptrs(lam), ptrs(mu), ptrs(nu), vp(mar_p), vp(ver_p),
+                         ctypes.c_int(sym_layer), vp(sp[0]), vp(sp[1]), vp(sp[2]), vp(sp[3]),
+                         ctypes.c_int(max_depth))
     if rc != 0:
-        raise ValueError(f"dpo_run rejected its input (code {rc})")
+        raise ValueError(f"the oracle rejected its input (code {rc})")
     del keep
     return res

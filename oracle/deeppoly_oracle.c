@@ -319,4 +319,167 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
     return 0;
 }
 
+/*
+ * ReuseCert (Appendix C, "ReuseCert"; Section 6.1): DeepPoly that keeps, for every affine layer, the
+ * polyhedral bounds already back-substituted to the input layer and reuses them, so that every later
+ * traversal is a single replacement step.
+ *   - first affine layer (curr[layer] == 1): L = U = prev.dot(w) + b, which is over the input layer; l, u by
+ *     simplify_* against the box;
+ *   - ReLU layer over an affine neuron p: (l, u) = (p[L].map(simplify_lower), p[U].map(simplify_upper)), the
+ *     concretisation of p's stored input-level bounds; L = relu_n(l, u, p) = (l + u >= 0) ? p[L] : 0 and
+ *     U = compute_upper(l, u, p) = l >= 0 ? p[U] : u <= 0 ? 0 : u/(u-l) * p[U] - u*l/(u-l): both are again
+ *     input-level expressions.  The transformer leaves the ReLU neuron's own l, u at 0;
+ *   - any later affine layer: backsubs_*_L/U = traverse with stop_traverse(n) = (n[layer] <= 1): the terms on
+ *     the ReLU layer below are replaced by c >= 0 ? c*L : c*U (mirrored for the upper side), which lands on
+ *     the input layer at once, where the traversal stops.  Middle layers store the result as L, U (their l, u
+ *     stay 0 in the specification); the last layer also maps simplify_* over it to get l, u;
+ *   - property check as for DeepPoly: logit[label] - logit[o] is lower-bounded with backsubs_lower.
+ * Outputs: l[k], u[k] of an affine layer k are the concretisations of its stored L, U (the values the next
+ * ReLU transformer uses; for the first and last layer these are the specification's l, u); entries of ReLU
+ * layers are left at 0 as in the specification.  sym_layer exports the stored L, U of one affine layer.
+ * Supported topology: affine (or convolution) and ReLU layers strictly alternating, affine first and last.
+ * Returns 0 on success, 8 when the topology is not covered.
+ */
+int dpo_run_reuse(int nlayers, const dpo_layer* layers, int B,
+                  const float* lo, const float* hi, const int* label,
+                  double** l, double** u, double** lam, double** mu, double** nu,
+                  double* margin, int* verdict,
+                  int sym_layer, double* sym_cl, double* sym_kl, double* sym_cu, double* sym_ku)
+{
+    if (nlayers < 1 || B < 0) return 1;
+    int nmax = 1;
+    for (int i = 0; i < nlayers; ++i) {
+        const int want_relu = (i % 2 == 1);
+        if ((layers[i].kind == DPO_RELU) != want_relu) return 8;
+        if (i > 0 && layers[i].n_in != layers[i - 1].n_out) return 3;
+        if (layers[i].kind == DPO_RELU && layers[i].n_in != layers[i].n_out) return 3;
+        if (layers[i].n_out > nmax) nmax = layers[i].n_out;
+    }
+    if (layers[nlayers - 1].kind == DPO_RELU) return 8;
+    if (label && layers[nlayers - 1].kind != DPO_AFFINE) return 4;
+    const int n0 = layers[0].n_in;
+    const size_t w = (size_t)n0 + 1;                   /* coefficients over the inputs, then the constant */
+    for (size_t i = 0; i < (size_t)B * n0; ++i) {
+        if (!(lo[i] <= hi[i])) return 5;
+        l[0][i] = (double)lo[i];
+        u[0][i] = (double)hi[i];
+    }
+    if (label)
+        for (int bi = 0; bi < B; ++bi)
+            if (label[bi] < 0 || label[bi] >= layers[nlayers - 1].n_out) return 7;
+
+    /* stored input-level bounds of the current affine layer (EL, EU), and the ReLU layer's L, U built
+     * from them (RL, RU): [n, n0 + 1] each */
+    double* EL = (double*)malloc(sizeof(double) * nmax * w);
+    double* EU = (double*)malloc(sizeof(double) * nmax * w);
+    double* RL = (double*)malloc(sizeof(double) * nmax * w);
+    double* RU = (double*)malloc(sizeof(double) * nmax * w);
+    if (!EL || !EU || !RL || !RU) { free(EL); free(EU); free(RL); free(RU); return 6; }
+
+    int rc = 0;
+    for (int bi = 0; bi < B && rc == 0; ++bi) {
+        const double* bl = l[0] + (size_t)bi * n0;
+        const double* bu = u[0] + (size_t)bi * n0;
+        for (int k = 1; k <= nlayers; ++k) {
+            const dpo_layer* L = &layers[k - 1];
+            const int n = L->n_out;
+            if (L->kind == DPO_RELU) {
+                /* (l, u) of the predecessor were written when its stored bounds were concretised */
+                for (int i = 0; i < n; ++i) {
+                    const size_t o = (size_t)bi * n + i;
+                    const double pl = l[k - 1][o], pu = u[k - 1][o];
+                    l[k][o] = 0.0;
+                    u[k][o] = 0.0;
+                    lam[k][o] = (pl + pu >= 0.0) ? 1.0 : 0.0;
+                    if (pl >= 0.0)      { mu[k][o] = 1.0; nu[k][o] = 0.0; }
+                    else if (pu <= 0.0) { mu[k][o] = 0.0; nu[k][o] = 0.0; }
+                    else { mu[k][o] = pu / (pu - pl); nu[k][o] = -(pu * pl) / (pu - pl); }
+                    for (size_t c = 0; c < w; ++c) {
+                        RL[i * w + c] = lam[k][o] * EL[i * w + c];
+                        RU[i * w + c] = mu[k][o] * EU[i * w + c];
+                    }
+                    RU[i * w + n0] += nu[k][o];
+                }
+                continue;
+            }
+            /* affine / convolution layer: new stored bounds, one row per neuron */
+            double* NL = (k == 1) ? EL : (double*)malloc(sizeof(double) * (size_t)n * w);
+            double* NU = (k == 1) ? EU : (double*)malloc(sizeof(double) * (size_t)n * w);
+            if (!NL || !NU) { rc = 6; if (k != 1) { free(NL); free(NU); } break; }
+            const int nrows = n + ((k == nlayers && label) ? L->n_out - 1 : 0);   /* margin rows ride along */
+            #pragma omp parallel
+            {
+                double* coef = (double*)malloc(sizeof(double) * (size_t)L->n_in);
+                double* el = (double*)malloc(sizeof(double) * w);
+                #pragma omp for schedule(dynamic, 4)
+                for (int r = 0; r < nrows; ++r) {
+                    if (!coef || !el) continue;
+                    double c0;
+                    if (r < n) {
+                        c0 = neuron_expr(L, r, coef);
+                    } else {
+                        const int q = r - n, t = label[bi], o = q < t ? q : q + 1;
+                        for (int p = 0; p < L->n_in; ++p)
+                            coef[p] = (double)L->W[(size_t)t * L->n_in + p] - (double)L->W[(size_t)o * L->n_in + p];
+                        c0 = (double)L->b[t] - (double)L->b[o];
+                    }
+                    for (int side = 0; side < 2; ++side) {
+                        if (r >= n && side == DPO_UPPER) break;
+                        double* dst = r < n ? (side == DPO_LOWER ? NL : NU) + (size_t)r * w : el;
+                        if (k == 1) {
+                            for (int p = 0; p < n0; ++p) dst[p] = coef[p];
+                            dst[n0] = c0;
+                        } else {
+                            for (size_t c = 0; c < w; ++c) dst[c] = 0.0;
+                            dst[n0] = c0;
+                            for (int j = 0; j < L->n_in; ++j) {
+                                const double cj = coef[j];
+                                if (cj == 0.0) continue;
+                                const int use_L = (side == DPO_LOWER) ? (cj >= 0.0) : !(cj >= 0.0);
+                                const double* src = (use_L ? RL : RU) + (size_t)j * w;
+                                for (size_t c = 0; c < w; ++c) dst[c] += cj * src[c];
+                            }
+                        }
+                        /* map(simplify_*) over the input-level expression */
+                        double acc = dst[n0];
+                        for (int p = 0; p < n0; ++p) {
+                            const double cp = dst[p];
+                            if (side == DPO_LOWER) acc += (cp >= 0.0) ? cp * bl[p] : cp * bu[p];
+                            else                   acc += (cp >= 0.0) ? cp * bu[p] : cp * bl[p];
+                        }
+                        if (r < n) (side == DPO_LOWER ? l[k] : u[k])[(size_t)bi * n + r] = acc;
+                        else margin[(size_t)bi * (L->n_out - 1) + (r - n)] = acc;
+                    }
+                }
+                free(coef);
+                free(el);
+            }
+            if (sym_layer == k) {
+                for (int r = 0; r < n; ++r) {
+                    const size_t o = (size_t)bi * n + r;
+                    memcpy(sym_cl + o * n0, NL + (size_t)r * w, sizeof(double) * n0);
+                    memcpy(sym_cu + o * n0, NU + (size_t)r * w, sizeof(double) * n0);
+                    sym_kl[o] = NL[(size_t)r * w + n0];
+                    sym_ku[o] = NU[(size_t)r * w + n0];
+                }
+            }
+            if (k != 1) {
+                memcpy(EL, NL, sizeof(double) * (size_t)n * w);
+                memcpy(EU, NU, sizeof(double) * (size_t)n * w);
+                free(NL);
+                free(NU);
+            }
+        }
+        if (rc == 0 && label) {
+            const int nq = layers[nlayers - 1].n_out - 1;
+            int ok = 1;
+            for (int q = 0; q < nq; ++q)
+                if (!(margin[(size_t)bi * nq + q] > 0.0)) ok = 0;
+            verdict[bi] = ok;
+        }
+    }
+    free(EL); free(EU); free(RL); free(RU);
+    return rc;
+}
+
 int dpo_layer_struct_size(void) { return (int)sizeof(dpo_layer); }

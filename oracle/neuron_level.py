@@ -67,9 +67,16 @@ def _affine_rows(layer, n_prev_layer_index):
     return rows
 
 
-def certify(net, lo, hi, label=None, max_iters: int = -1):
+def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deeppoly"):
     """lo, hi: sequences of length n0 (one input).  Returns (shapes, margins, verdict)
-    where shapes[layer][pos] is a Shape."""
+    where shapes[layer][pos] is a Shape.
+
+    certifier: "deeppoly"; "skippoly" (Appendix C, SkipPoly: the ReLU transformer writes L, U over the neurons two
+    layers back by scaling the predecessor's own L, U); "reusecert" (Appendix C, ReuseCert: stop_traverse(n) =
+    n[layer] <= 1, middle affine layers store the traversed expressions as L, U and leave l, u at 0, the ReLU
+    transformer concretises the predecessor's stored L, U itself; each Shape of an affine layer additionally
+    carries cl, cu = that concretisation)."""
+    assert certifier in ("deeppoly", "skippoly", "reusecert")
     shapes: List[List[Shape]] = [[Shape(float(a), float(b)) for a, b in zip(lo, hi)]]
 
     def map_(e: PolyExp, f) -> PolyExp:
@@ -100,26 +107,40 @@ def certify(net, lo, hi, label=None, max_iters: int = -1):
     # backward traversal visits the deepest layer first; with a bounded iteration
     # count the traversal stops early and simplify_* uses the stored l, u reached
     priority2 = lambda n: n[0]
-    stop_traverse = lambda n: False
+    stop_traverse = (lambda n: n[0] <= 1) if certifier == "reusecert" else (lambda n: False)
     backsubs_lower = lambda e: map_(traverse(e, priority2, stop_traverse, replace_lower), simplify_lower).const
     backsubs_upper = lambda e: map_(traverse(e, priority2, stop_traverse, replace_upper), simplify_upper).const
 
+    nl = len(net.layers)
     for k, layer in enumerate(net.layers, start=1):
         prev = shapes[k - 1]
         cur = []
         if layer.kind == "relu":
             for i, p in enumerate(prev):
                 n = PolyExp(0.0, {(k - 1, i): 1.0})
-                l = p.l if p.l >= 0.0 else 0.0
-                u = p.u if p.u >= 0.0 else 0.0
-                L = n if p.l + p.u >= 0.0 else PolyExp(0.0)
-                if p.l >= 0.0:
-                    U = n
-                elif p.u <= 0.0:
+                if certifier == "reusecert":
+                    # Relu -> (0, 0, relu_n(prev[L].map(simplify_lower), prev[U].map(simplify_upper), prev), compute_upper(...))
+                    pl = map_(p.L, simplify_lower).const
+                    pu = map_(p.U, simplify_upper).const
+                    p.cl, p.cu = pl, pu
+                    l, u, below_L, below_U = 0.0, 0.0, p.L, p.U
+                else:
+                    pl, pu = p.l, p.u
+                    l = pl if pl >= 0.0 else 0.0
+                    u = pu if pu >= 0.0 else 0.0
+                    below_L, below_U = (p.L, p.U) if certifier == "skippoly" else (n, n)
+                L = below_L if pl + pu >= 0.0 else PolyExp(0.0)
+                if pl >= 0.0:
+                    U = below_U
+                elif pu <= 0.0:
                     U = PolyExp(0.0)
                 else:
-                    U = n.scale(p.u / (p.u - p.l)).add(PolyExp(-(p.u * p.l) / (p.u - p.l)))
+                    U = below_U.scale(pu / (pu - pl)).add(PolyExp(-(pu * pl) / (pu - pl)))
                 cur.append(Shape(l, u, L, U))
+        elif certifier == "reusecert" and not (k == 1 or k == nl):
+            for e in _affine_rows(layer, k - 1):
+                cur.append(Shape(0.0, 0.0, traverse(e, priority2, stop_traverse, replace_lower),
+                                 traverse(e, priority2, stop_traverse, replace_upper)))
         else:
             for e in _affine_rows(layer, k - 1):
                 cur.append(Shape(backsubs_lower(e), backsubs_upper(e), e, e))
