@@ -99,8 +99,15 @@ typedef struct {
     int32_t use_graph;          /* 1 (default): when a result object is reused on a non-null stream, the call's kernel
                                    sequence is captured into a HIP graph once and replayed (launch-bound small networks);
                                    0: always launch kernel by kernel */
+    int32_t certifier;          /* DPC_DEEPPOLY (0, default) or DPC_REUSECERT (1): every affine layer keeps its bounds
+                                   already back-substituted to the input and later layers reuse them, one replacement
+                                   step per layer (Appendix C, ReuseCert; Section 6.1).  Fully-connected networks with
+                                   affine and ReLU layers alternating only; needs max_backsub_depth = -1 and
+                                   keep_symbolic = 0.  dpc_result_concrete then returns, for an affine layer, the
+                                   concretisation of its stored bounds (the values the next ReLU transformer uses) */
     void*   stream;             /* hipStream_t all work is enqueued on (NULL = the null stream) */
 } dpc_options;
+enum { DPC_DEEPPOLY = 0, DPC_REUSECERT = 1 };
 
 /* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, graph replay on, null stream). */
 dpc_status dpc_options_default(dpc_options* opt);

@@ -85,6 +85,9 @@ struct Layer {
     int ldw = 0;
     DevBuf<float> dBias;                   // [n_out] per neuron
     ConvWeights cw;                        // CONV only
+    // ReuseCert: [W+ | W- | b] and [W- | W+ | b], [n_out, ld_split] each, built on first use
+    DevBuf<float> dSplit[2];
+    int ld_split = 0;
 };
 
 }  // namespace
@@ -109,6 +112,7 @@ struct dpc_network {
     std::vector<std::unique_ptr<DevBuf<float>>> pk;
     DevBuf<float> part;
     int64_t part_stride = 0;
+    DevBuf<float> rc_rows;                 // ReuseCert: split output/margin rows of the last step, per input
     uint64_t ws_epoch = 1;                 // bumped whenever a workspace buffer moves (captured graphs hold addresses)
     static constexpr int kMaxSlots = 96;
 
@@ -628,6 +632,7 @@ dpc_status dpc_options_default(dpc_options* opt)
         opt->fuse = 1;
         opt->profile = 0;
         opt->use_graph = 1;
+        opt->certifier = DPC_DEEPPOLY;
         opt->stream = nullptr;
     });
 }
@@ -653,6 +658,17 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     "dpc_certify: keep_symbolic needs a full traversal");
         const int nl = (int)net->layers.size();
         const Layer& last = *net->layers[nl - 1];
+        DPC_REQUIRE(opt.certifier == DPC_DEEPPOLY || opt.certifier == DPC_REUSECERT, DPC_EINVAL, "dpc_certify: unknown certifier %d",
+                    opt.certifier);
+        const bool reuse_cert = opt.certifier == DPC_REUSECERT;
+        if (reuse_cert) {
+            DPC_REQUIRE(opt.max_backsub_depth == -1 && opt.keep_symbolic == 0, DPC_EINVAL,
+                        "dpc_certify: ReuseCert needs max_backsub_depth = -1 and keep_symbolic = 0");
+            DPC_REQUIRE(nl % 2 == 1, DPC_EUNSUPPORTED, "dpc_certify: ReuseCert needs affine and ReLU layers alternating");
+            for (int i = 0; i < nl; ++i)
+                DPC_REQUIRE(net->layers[i]->kind == (i % 2 ? RELU : AFFINE), DPC_EUNSUPPORTED,
+                            "dpc_certify: ReuseCert covers fully-connected networks with affine and ReLU layers alternating");
+        }
         if (label) DPC_REQUIRE(last.kind == AFFINE && last.n_out >= 2, DPC_EUNSUPPORTED,
                                "dpc_certify: a label needs a fully-connected last layer with >= 2 outputs");
         DeviceGuard guard(net->device);
@@ -707,7 +723,17 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         const size_t stage_need = std::max(2 * (size_t)B * n0, 2 * (size_t)B * (2 * (size_t)nK - 1)) + 16;   // box staging / merged last pass + one flag word
         for (int i = 1; i <= nl; ++i)
             if (net->layers[i - 1]->kind != RELU) need_rows = std::max(need_rows, 2 * (size_t)B * net->size_of(i));
-        const size_t need = workspace_floats(net, B, label != nullptr);
+        need_rows = std::max(need_rows, 2 * (size_t)B * (2 * (size_t)nK - 1));   // output + margin rows of the last pass
+        size_t need = workspace_floats(net, B, label != nullptr);
+        const int ldE = (int)round_up(n0 + 1, kLdAlign);          // ReuseCert: input-level expression rows
+        if (reuse_cert) {
+            size_t nmax = 1;
+            for (int i = 1; i <= nl; i += 2) nmax = std::max<size_t>(nmax, net->size_of(i));
+            const size_t Rm = 2 * (size_t)nK - 1;
+            need = std::max(need, 2 * (size_t)B * std::max(nmax, Rm) * ldE);
+            need = std::max(need, (size_t)B * (2 * nmax + 1) * ldE);
+            if (label) need = std::max(need, 2 * (size_t)B * Rm * ((size_t)net->ld_of(nl - 1) + ldE));   // last step: rows + results
+        }
         bool moved = net->buf[0].reserve(need);
         moved |= net->buf[1].reserve(need);
         const bool fuse = opt.fuse && opt.max_backsub_depth < 0;
@@ -726,6 +752,19 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 if (!net->pk[i]) net->pk[i].reset(new DevBuf<float>());
                 moved |= net->pk[i]->reserve((size_t)2 * B * net->ld_of(i) * 4);
             }
+        }
+        if (reuse_cert) {
+            // split weights of every affine layer but the first (once), and room for the split rows of the last step
+            for (int i = 3; i <= nl; i += 2) {
+                Layer& L = *net->layers[i - 1];
+                if (L.dSplit[0].p) continue;
+                L.ld_split = (int)round_up(2 * L.n_in + 1, kLdAlign);
+                for (int side = 0; side < 2; ++side) {
+                    L.dSplit[side].reserve((size_t)L.n_out * L.ld_split);
+                    launch_reuse_split(L.dW.p, L.ldw, L.dBias.p, nullptr, L.n_out, L.n_in, L.dSplit[side].p, L.ld_split, 0, side, s);
+                }
+            }
+            if (nl >= 3) moved |= net->rc_rows.reserve(2 * (size_t)B * (2 * (size_t)nK - 1) * net->layers[nl - 1]->ld_split);
         }
         moved |= net->cst.reserve(need_rows);
         moved |= net->stage.reserve(stage_need);
@@ -764,9 +803,87 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
         // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
         const bool graphable = opt.use_graph && s != nullptr && !prof.on && !opt.keep_symbolic && !fresh;
-        const dpc_result::GraphKey gkey{opt.max_backsub_depth, opt.fuse != 0, label != nullptr, g_tuning_epoch, net->ws_epoch};
+        const dpc_result::GraphKey gkey{opt.max_backsub_depth, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws_epoch};
         const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
+        auto enqueue_reusecert = [&]() {
+            Pass P{net, res, &opt, s, &prof, B};
+            float* E = net->buf[0].p;            // stored bounds of the current affine layer: [side][b][n][ldE]
+            float* Rr = net->buf[1].p;           // [b][2n + 1][ldE]: the ReLU layer's input-level bounds + unit row
+            double* cst = net->cst.p;
+            // constants travel in column n0 of the rows; the concretisation kernel takes them as fp64 per row
+            auto concretise_rows = [&](const float* rows, int R, float* out_l, float* out_u) {
+                const int64_t M = 2 * (int64_t)B * R;
+                prof.begin(P_CONC);
+                launch_reuse_const(rows, ldE, n0, M, cst, s);
+                launch_concretise(rows, ldE, cst, 2, B, R, n0, res->l[0], res->u[0], out_l, out_u, nullptr, 0, nullptr, s);
+                prof.end();
+                res->prof.concretise_launches++;
+                res->prof.concretise_bytes += (double)M * n0 * 4.0;
+            };
+            {   // first layer: L = U = W x + b is already over the input
+                Layer& L1 = *net->layers[0];
+                run_pass(P, 0, 2, L1.n_out, &L1, res->l[1], res->u[1], false);
+            }
+            for (int i = 2; i <= nl; ++i) {
+                Layer& L = *net->layers[i - 1];
+                if (L.kind == RELU) {
+                    const Layer& A = *net->layers[i - 2];
+                    prof.begin(P_OTHER);
+                    launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
+                                        (int64_t)B * L.n_out, s);
+                    prof.end();
+                    res->prof.other_launches++;
+                    prof.begin(P_RELAX);
+                    launch_reuse_scale(i == 2 ? nullptr : E, A.dW.p, A.ldw, A.dBias.p, res->lam[i], res->mu[i], res->nu[i], B, L.n_out,
+                                       n0, ldE, Rr, s);
+                    prof.end();
+                    res->prof.relax_launches++;
+                    res->prof.relax_bytes += (double)B * (2.0 * L.n_out + 1) * ldE * (i == 2 ? 4.0 : 8.0);
+                    continue;
+                }
+                const int K = 2 * L.n_in + 1;
+                const bool is_last = i == nl;
+                if (!is_last || !label) {
+                    // stored bounds of the layer: [W+ | W- | b] Rr[b] (lower), [W- | W+ | b] Rr[b] (upper)
+                    prof.begin(P_CONTRACT);
+                    for (int side = 0; side < 2; ++side)
+                        launch_contract_batched(L.dSplit[side].p, 0, L.n_out, K, L.ld_split, Rr, (int64_t)K * ldE, n0 + 1, ldE,
+                                                E + (size_t)side * B * L.n_out * ldE, (int64_t)L.n_out * ldE, ldE, B, s);
+                    prof.end();
+                    res->prof.contract_launches += 2;
+                    res->prof.contract_flop += 2.0 * 2.0 * B * (double)L.n_out * K * (n0 + 1);
+                    concretise_rows(E, L.n_out, res->l[i], res->u[i]);
+                } else {
+                    // last layer with a property: output rows and margin rows (label-dependent, so per input) in one step
+                    const int Rm = 2 * nK - 1;
+                    const int64_t rows = 2 * (int64_t)B * Rm;
+                    float* Fr = net->buf[0].p;                                   // rows over the last hidden layer
+                    float* T = net->buf[0].p + (size_t)rows * net->ld_of(nl - 1); // their input-level expressions
+                    prof.begin(P_OTHER);
+                    launch_final_rows(L.dW.p, L.ldw, L.dBias.p, res->label.p, B, nK, L.n_in, Fr, net->ld_of(nl - 1), cst, s);
+                    launch_reuse_split(Fr, net->ld_of(nl - 1), nullptr, cst, rows, L.n_in, net->rc_rows.p, L.ld_split, (int64_t)B * Rm, 0, s);
+                    prof.end();
+                    res->prof.other_launches += 2;
+                    prof.begin(P_CONTRACT);
+                    for (int side = 0; side < 2; ++side)
+                        launch_contract_batched(net->rc_rows.p + (size_t)side * B * Rm * L.ld_split, (int64_t)Rm * L.ld_split, Rm, K,
+                                                L.ld_split, Rr, (int64_t)K * ldE, n0 + 1, ldE,
+                                                T + (size_t)side * B * Rm * ldE, (int64_t)Rm * ldE, ldE, B, s);
+                    prof.end();
+                    res->prof.contract_launches += 2;
+                    res->prof.contract_flop += 2.0 * 2.0 * B * (double)Rm * K * (n0 + 1);
+                    float* tl = net->stage.p;
+                    float* tu = net->stage.p + (size_t)B * Rm;
+                    concretise_rows(T, Rm, tl, tu);
+                    prof.begin(P_OTHER);
+                    launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s);
+                    prof.end();
+                    res->prof.other_launches++;
+                }
+            }
+        };
         auto enqueue_all = [&]() {
+            if (reuse_cert && nl >= 3) { enqueue_reusecert(); return; }
             if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
             Pass P{net, res, &opt, s, &prof, B};
             for (int i = 1; i <= nl; ++i) {

@@ -60,6 +60,11 @@ void launch_concretise(const float* C, int ldc, const double* cst, int nsides, i
 void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
                      float* Cout, int ldc, hipStream_t s);
 
+// `batches` contractions of equal shape in one launch: problem z reads A + z*strideA, W + z*strideW and writes
+// Cout + z*strideC (strides in floats; 0 shares the operand between the problems).
+void launch_contract_batched(const float* A, int64_t strideA, int64_t M, int K, int lda, const float* W, int64_t strideW, int N,
+                             int ldw, float* Cout, int64_t strideC, int ldc, int batches, hipStream_t s);
+
 // Contraction with the following traversal step fused into its epilogue.  pk: packed per-(group, column)
 // parameters (pm, nm, kp, kn) as float4, [nsb][ldpk]; group g = row / R.  Stored value x*(x>=0?pm:nm)
 // (when store != 0), row-constant partial sums x*(x>=0?kp:kn) written to part[slot][row], one slot per
@@ -101,6 +106,18 @@ struct ChainDesc {
 bool launch_chain(const ChainDesc& d, hipStream_t s);
 void set_chain_mode(int v);          // -1: by shape, 0: never, 1: whenever covered
 void set_chain_rows(int v);          // 32 or 64: row block for panels up to 512 columns
+
+// ---- ReuseCert helpers (Appendix C, ReuseCert): see reuse.hip for the layout -------------------
+// Rr[b] = [lambda * L ; mu * U + nu ; unit row] from the stored bounds E[side][b][n][ldE] of the layer below the ReLU
+// layer, or (E == NULL) from the first layer's shared rows (W1 [n][ldw], bias [n]).
+void launch_reuse_scale(const float* E, const float* W1, int ldw, const float* bias, const float* lambda, const float* mu,
+                        const float* nu, int batch, int n, int n0, int ldE, float* Rr, hipStream_t s);
+// dst[m] = [c+ | c- | constant] (side 0) or [c- | c+ | constant] (side 1) of row m of src ([rows][ld_src], n columns);
+// constant = bias_d[m] if given, else bias_f[m]; side = m / rows_per_side (rows_per_side > 0) or side0.
+void launch_reuse_split(const float* src, int ld_src, const float* bias_f, const double* bias_d, int64_t rows, int n,
+                        float* dst, int ld_dst, int64_t rows_per_side, int side0, hipStream_t s);
+// cst[m] = C[m][col]
+void launch_reuse_const(const float* C, int ldc, int col, int64_t rows, double* cst, hipStream_t s);
 
 // pk[side][b][c] = (pm, nm, kp, kn) of the sign-split ReLU step through a ReLU layer with relaxation
 // (lambda, mu, nu) followed by the bias fold of the layer below (bias may be NULL); columns n..ld-1 zero.

@@ -78,6 +78,8 @@ struct EpiArgs {
     long long part_stride;
     int store;
     int remap;          // 1: XCD-aware re-linearisation of workgroup ids
+    // batched launches (gridDim.y problems of equal shape): element offsets per batch index of A, W and Cout
+    long long strideA = 0, strideW = 0, strideC = 0;
 };
 
 template <class T, int EPI>
@@ -88,6 +90,11 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
     extern __shared__ float4 lds[];
     float4* sA = lds;                                                        // [2][A_STAGE]
     float* sB = reinterpret_cast<float*>(lds + 2 * T::A_STAGE);              // [2][B_STAGE]
+    if (gridDim.y > 1) {
+        A += (long long)blockIdx.y * ep.strideA;
+        W += (long long)blockIdx.y * ep.strideW;
+        Cout += (long long)blockIdx.y * ep.strideC;
+    }
 
     // XCD-aware re-linearisation (gridDim.x is a multiple of 8)
     const int per_xcd = gridDim.x >> 3;
@@ -354,7 +361,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void contract_kernel(
 
 template <class T, int EPI>
 int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw, float* Cout,
-                   int ldc, const EpiArgs& ep, int max_slots, hipStream_t s)
+                   int ldc, const EpiArgs& ep, int max_slots, hipStream_t s, int batches = 1)
 {
     static bool configured = false;
     if (!configured) {
@@ -369,8 +376,8 @@ int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, in
     DPC_REQUIRE(tiles_m < (1 << 30) && tiles < (int64_t)1 << 31, DPC_EINVAL, "contract: too many tiles");
     if (EPI == 1 && tiles_n > max_slots) return -1;
     const unsigned grid = (unsigned)round_up(tiles, 8);
-    hipLaunchKernelGGL((contract_kernel<T, EPI>), dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, A, M, K, lda, W, N, ldw,
-                       Cout, ldc, (int)tiles_m, tiles_n, ep);
+    hipLaunchKernelGGL((contract_kernel<T, EPI>), dim3(grid, (unsigned)batches), dim3(T::THREADS), T::LDS_BYTES, s, A, M, K,
+                       lda, W, N, ldw, Cout, ldc, (int)tiles_m, tiles_n, ep);
     DPC_HIP(hipGetLastError());
     return tiles_n;
 }
@@ -430,6 +437,27 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
     }
 }
 
+
+void launch_contract_batched(const float* A, int64_t strideA, int64_t M, int K, int lda, const float* W, int64_t strideW, int N,
+                             int ldw, float* Cout, int64_t strideC, int ldc, int batches, hipStream_t s)
+{
+    DPC_REQUIRE(A && W && Cout && M >= 0 && K >= 1 && N >= 1 && batches >= 0 && batches <= 65535, DPC_EINVAL,
+                "contract_batched: bad arguments");
+    DPC_REQUIRE(lda >= K && ldw >= N && ldc >= N && lda % 4 == 0 && ldw % 4 == 0 && ldc % 4 == 0 && strideA % 4 == 0 &&
+                    strideW % 4 == 0 && strideC % 4 == 0, DPC_EINVAL,
+                "contract_batched: leading dimensions and batch strides must cover the matrix and be multiples of 4");
+    DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0, DPC_EINVAL,
+                "contract_batched: buffers must be 16-byte aligned");
+    if (M == 0 || batches == 0) return;
+    EpiArgs ep{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap, (long long)strideA, (long long)strideW, (long long)strideC};
+    // tile choice as for one problem of batches * M rows
+    const int variant = g_variant >= 0 ? g_variant : pick_variant(M * batches, ldc);
+    switch (variant) {
+        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
+        case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
+        default: launch_variant<Tile<64, 64, 16, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
+    }
+}
 
 int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
                           float* Cout, int ldc, const ContractEpilogue& e, hipStream_t s)

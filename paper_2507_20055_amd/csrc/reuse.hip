@@ -1,0 +1,137 @@
+// ReuseCert (Appendix C, "ReuseCert"; Section 6.1): every affine layer keeps its polyhedral bounds already
+// back-substituted to the input layer, so a later layer's traversal is ONE replacement step
+//     lower_k = W+ * Lr + W- * Ur + b,   upper_k = W+ * Ur + W- * Lr + b,
+// where Lr, Ur are the ReLU layer's bounds over the input: Lr_j = lambda_j * L_j, Ur_j = mu_j * U_j + nu_j.
+//
+// Layout: an input-level expression is a row of ldE = round_up(n0 + 1, 32) floats, coefficients over the n0
+// inputs followed by the constant in column n0.  Stored bounds of layer k: E[side][b][r] (side 0 = L, 1 = U).
+// The replacement step is a contraction  [W+ | W- | b] (shared, [n_k, 2 n_{k-1} + 1])  x  Rr[b]
+// ([2 n_{k-1} + 1, ldE] per input: rows Lr, then Ur, then the unit row that carries the bias), batched over
+// the inputs; the helpers here build those two operands.
+#include "common.h"
+
+namespace dpc {
+
+namespace {
+
+constexpr int kThreads = 256;
+typedef float vf4 __attribute__((ext_vector_type(4)));
+
+// Rr[b][j]       = lambda[b][j] * L_j            (j < n)
+// Rr[b][n + j]   = mu[b][j] * U_j + nu[b][j] e_n0
+// Rr[b][2n]      = e_n0
+// SHARED: L_j = U_j = (W1[j], bias[j]) for every input (first layer); otherwise rows of E.
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void reuse_scale_kernel(
+    const float* __restrict__ E, const float* __restrict__ W1, int ldw, const float* __restrict__ bias,
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
+    int batch, int n, int n0, int ldE, float* __restrict__ Rr)
+{
+    const int b = blockIdx.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j = blockIdx.x * (kThreads / 64) + wave;
+    if (j > 2 * n) return;
+    float* dst = Rr + ((size_t)b * (2 * n + 1) + j) * ldE;
+    if (j == 2 * n) {
+        for (int c = lane * 4; c < ldE; c += 256) {
+            vf4 o = {0.f, 0.f, 0.f, 0.f};
+            if (n0 >= c && n0 < c + 4) o[n0 - c] = 1.0f;
+            *reinterpret_cast<vf4*>(dst + c) = o;
+        }
+        return;
+    }
+    const int side = j >= n, jj = side ? j - n : j;
+    const float scale = side ? mu[(size_t)b * n + jj] : lambda[(size_t)b * n + jj];
+    const float add = side ? nu[(size_t)b * n + jj] : 0.0f;
+    const float* src = SHARED ? W1 + (size_t)jj * ldw : E + (((size_t)side * batch + b) * n + jj) * ldE;
+    const float cst = SHARED ? bias[jj] : 0.0f;
+    for (int c = lane * 4; c < ldE; c += 256) {
+        vf4 x = {0.f, 0.f, 0.f, 0.f};
+        if (SHARED) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) x[t] = c + t < n0 ? src[c + t] : (c + t == n0 ? cst : 0.0f);
+        } else {
+            x = *reinterpret_cast<const vf4*>(src + c);
+        }
+        vf4 o;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = scale * x[t] + (c + t == n0 ? add : 0.0f);
+        *reinterpret_cast<vf4*>(dst + c) = o;
+    }
+}
+
+// dst[m] = [ c+ | c- | constant ] (lower side) or [ c- | c+ | constant ] (upper side) of row m of src, c+ = max(c, 0),
+// c- = min(c, 0); columns 2n+1 .. ld_dst-1 zero.  side = m / rows_per_side when rows_per_side > 0, else `side0`.
+__global__ __launch_bounds__(kThreads) void reuse_split_kernel(
+    const float* __restrict__ src, int ld_src, const float* __restrict__ bias_f, const double* __restrict__ bias_d,
+    long long rows, int n, float* __restrict__ dst, int ld_dst, long long rows_per_side, int side0)
+{
+    const long long m = (long long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (m >= rows) return;
+    const int side = rows_per_side > 0 ? (int)(m / rows_per_side) : side0;
+    const float* in = src + m * ld_src;
+    float* out = dst + m * ld_dst;
+    const float cst = bias_d ? (float)bias_d[m] : bias_f[m];
+    for (int c = lane; c < ld_dst; c += 64) {
+        float v = 0.0f;
+        if (c < 2 * n) {
+            const float w = in[c < n ? c : c - n];
+            const bool first = c < n;                           // first half multiplies Lr, second half Ur
+            const bool take_pos = (side == 0) == first;         // lower: c+ on Lr, c- on Ur; upper: mirrored
+            v = take_pos ? fmaxf(w, 0.0f) : fminf(w, 0.0f);
+        } else if (c == 2 * n) {
+            v = cst;
+        }
+        out[c] = v;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void reuse_const_kernel(const float* __restrict__ C, int ldc, int col, long long rows,
+                                                              double* __restrict__ cst)
+{
+    const long long m = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (m < rows) cst[m] = (double)C[m * ldc + col];
+}
+
+}  // namespace
+
+void launch_reuse_scale(const float* E, const float* W1, int ldw, const float* bias, const float* lambda, const float* mu,
+                        const float* nu, int batch, int n, int n0, int ldE, float* Rr, hipStream_t s)
+{
+    DPC_REQUIRE(lambda && mu && nu && Rr && (E || (W1 && bias)) && n >= 1 && n0 >= 1 && ldE > n0 && ldE % 4 == 0 &&
+                    batch >= 0 && batch <= 65535, DPC_EINVAL, "reuse_scale: bad arguments");
+    DPC_REQUIRE(E || ldw >= n0, DPC_EINVAL, "reuse_scale: weight rows too short");
+    DPC_REQUIRE(((uintptr_t)Rr % 16) == 0 && (!E || ((uintptr_t)E % 16) == 0), DPC_EINVAL, "reuse_scale: buffers must be 16-byte aligned");
+    if (batch == 0) return;
+    dim3 grid((unsigned)ceil_div(2 * n + 1, kThreads / 64), (unsigned)batch);
+    if (E)
+        hipLaunchKernelGGL(reuse_scale_kernel<false>, grid, dim3(kThreads), 0, s, E, (const float*)nullptr, 0, (const float*)nullptr,
+                           lambda, mu, nu, batch, n, n0, ldE, Rr);
+    else
+        hipLaunchKernelGGL(reuse_scale_kernel<true>, grid, dim3(kThreads), 0, s, (const float*)nullptr, W1, ldw, bias, lambda, mu,
+                           nu, batch, n, n0, ldE, Rr);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_reuse_split(const float* src, int ld_src, const float* bias_f, const double* bias_d, int64_t rows, int n,
+                        float* dst, int ld_dst, int64_t rows_per_side, int side0, hipStream_t s)
+{
+    DPC_REQUIRE(src && dst && (bias_f || bias_d) && rows >= 0 && n >= 1 && ld_src >= n && ld_dst >= 2 * n + 1, DPC_EINVAL,
+                "reuse_split: bad arguments");
+    if (rows == 0) return;
+    hipLaunchKernelGGL(reuse_split_kernel, dim3((unsigned)ceil_div(rows, kThreads / 64)), dim3(kThreads), 0, s, src, ld_src, bias_f,
+                       bias_d, (long long)rows, n, dst, ld_dst, (long long)rows_per_side, side0);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_reuse_const(const float* C, int ldc, int col, int64_t rows, double* cst, hipStream_t s)
+{
+    DPC_REQUIRE(C && cst && col >= 0 && col < ldc && rows >= 0, DPC_EINVAL, "reuse_const: bad arguments");
+    if (rows == 0) return;
+    hipLaunchKernelGGL(reuse_const_kernel, dim3((unsigned)ceil_div(rows, kThreads)), dim3(kThreads), 0, s, C, ldc, col,
+                       (long long)rows, cst);
+    DPC_HIP(hipGetLastError());
+}
+
+}  // namespace dpc

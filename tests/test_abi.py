@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_sizes_match_header_layout():
-    assert ctypes.sizeof(binding.dpc_options) == 32
+    assert ctypes.sizeof(binding.dpc_options) == 40
     opt = binding.dpc_options()
     assert binding._lib.dpc_options_default(ctypes.byref(opt)) == 0
     assert opt.struct_size == ctypes.sizeof(binding.dpc_options)

@@ -252,6 +252,73 @@ def test_resident_traversal_kernel(seed, dims, B, rows):
     gnet.close()
 
 
+@pytest.mark.parametrize("seed,dims,B,eps", [(81, [5, 7, 6, 3], 3, 0.3), (82, [20, 33, 65, 40, 10], 4, 0.1), (83, [7, 130, 5], 2, 0.2),
+                                             (84, [64, 257, 129, 70, 10], 5, 0.05), (85, [31, 40, 40, 40, 40, 2], 2, 0.1),
+                                             (86, [1030, 48, 36, 4], 2, 0.02)])
+def test_reusecert(seed, dims, B, eps):
+    """ReuseCert (stored input-level bounds, one replacement step per layer) against the oracle's ReuseCert:
+    concretised stored bounds of every affine layer, relaxations, margins, verdicts; with and without a property."""
+    net = wl.random_small_net(seed, dims)
+    x, lo, hi = wl.random_box(seed + 10, dims[0], B, eps)
+    label = np.arange(B, dtype=np.int32) % dims[-1]
+    b = _binding()
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
+    g = gnet.certify(lo, hi, label, certifier="reusecert")
+    compare_with_oracle(net, lo, hi, g, o, label, relu_bounds=False)
+    g2 = gnet.certify(lo, hi, None, certifier="reusecert")          # bounds only: the last layer is an ordinary step
+    compare_with_oracle(net, lo, hi, g2, o, None, relu_bounds=False)
+    # the certifier is a different one: on networks with at least three affine layers its output bounds differ from
+    # DeepPoly's somewhere (they coincide up to two affine layers)
+    d = gnet.certify(lo, hi, label)
+    last = len(net.layers)
+    same = np.allclose(d.concrete(last)[0], g.concrete(last)[0], rtol=1e-6, atol=1e-7)
+    assert same == (len(dims) <= 3)
+    gnet.close()
+
+
+def test_reusecert_hand_example_and_errors():
+    from tests.test_oracle_pins import read_golden, fc_net
+    gd = read_golden("net_2_2_2_2.txt")
+    e = read_golden("reusecert_2_2_2_2.txt")
+    net = fc_net(2, [(gd["W1"].reshape(2, 2), gd["b1"]), (gd["W2"].reshape(2, 2), gd["b2"]), (gd["W3"].reshape(2, 2), gd["b3"])])
+    b = _binding()
+    gnet = b.Network(net)
+    g = gnet.certify(gd["lo"][None].astype(np.float32), gd["hi"][None].astype(np.float32), gd["label"].astype(np.int32),
+                     certifier="reusecert")
+    np.testing.assert_allclose(g.concrete(3)[0][0], e["l3"], rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(g.concrete(3)[1][0], e["u3"], rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(g.concrete(5)[0][0], e["l5"], rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(g.concrete(5)[1][0], e["u5"], rtol=1e-6, atol=1e-6)
+    v, m = g.verdict()
+    np.testing.assert_allclose(m[0], e["margin"], rtol=1e-6)
+    assert v[0] == 0
+    with pytest.raises(b.DpcError):
+        gnet.certify(gd["lo"][None].astype(np.float32), gd["hi"][None].astype(np.float32), None, certifier="reusecert",
+                     max_backsub_depth=2)
+    gnet.close()
+    conv = wl.random_small_conv(7, (2, 6, 6), [(3, 3, 1, 1)], [6, 3])
+    cnet = b.Network(conv)
+    x, lo, hi = wl.random_box(8, conv.n_in, 1, 0.05)
+    with pytest.raises(b.DpcError):
+        cnet.certify(lo, hi, None, certifier="reusecert")            # convolution layers are not covered
+    cnet.close()
+
+
+@pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5])])
+def test_reusecert_full_batch_gpu_sampled_oracle(cfg, idx):
+    """ReuseCert at the benchmark's launch configuration (full batch); the oracle on a sample of the inputs."""
+    w = wl.make_workload(cfg)
+    b = _binding()
+    gnet = b.Network(w.net)
+    g = gnet.certify(w.lo, w.hi, w.label, certifier="reusecert")
+    o = oracle.run(w.net, w.lo[idx], w.hi[idx], label=w.label[idx], certifier="reusecert")
+    flipped, worst = compare_with_oracle(w.net, w.lo[idx], w.hi[idx], _Sub(g, idx), o, w.label[idx], max_flipped_inputs=1,
+                                         check_samples=300, relu_bounds=False)
+    print(cfg, "reusecert worst err/tol", worst)
+    gnet.close()
+
+
 @pytest.mark.parametrize("kind", ["fc", "conv"])
 def test_graph_replay_matches_eager(kind):
     """A reused result on a caller's stream replays the kernel sequence as one HIP graph.  Every replay
