@@ -73,6 +73,7 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
 bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
                                 const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
 void set_conv_algo(int v);
+int conv_algo();
 
 // Validation of certify inputs on the device.  Returns 0 = fine, 1 = lo > hi or non-finite, 2 = bad label.
 // `flag` is a device int32 scratch word.  Synchronises the stream.

@@ -290,6 +290,159 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(
     }
 }
 
+
+// Few input channels through the MFMA units: with CI <= 4 output channels per position a direct implicit GEMM
+// would use 3 of the 32 columns of a tile.  Instead the per-position product with ALL taps is formed first,
+//     P[(row, py, px)][(ky, kx), ci] = sum_co in[row, py, px, co] * K[co, ci, ky, kx]
+// -- a GEMM with kh*kw*CI columns (27 of 32 for a 3x3 kernel on an RGB image, 48 of 64 for 4x4) -- into LDS, and
+// every output coefficient then gathers its (at most kh*kw/s^2) terms from P in a fixed order.  The kernel matrix
+// is read once per workgroup and kept in registers in the B-operand layout; input coefficients go from global
+// memory straight into the A operand (a lane owns one list entry and reads its channels 16 bytes at a time;
+// within each group of 8 channels the lower half-wave takes 0..3, the upper half 4..7), two tiles of 32 entries
+// per wavefront in flight.  A workgroup walks `panels` consecutive panels (RB rows x one strip of output rows
+// each) so that the kernel-matrix fetch and the launch cost are spread over more work.
+constexpr int kPThreads = 256;         // workgroup of the product-then-gather kernel below
+
+template <int NT, int S, int CO8>
+__global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
+    const float* __restrict__ in, const float* __restrict__ taps, float* __restrict__ out, CtArgs a,
+    int yrows_per_block, int lds_rows, int panels)
+{
+    constexpr int CO = CO8 * 8, NC = 32 * NT, PS = NC + 3, NW = kPThreads / 64;
+    extern __shared__ float4 lds4[];
+    float* sP = reinterpret_cast<float*>(lds4);        // [entries rounded up to 32][PS]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
+    const int CI = a.Ci;
+    const int yb = blockIdx.y * yrows_per_block, ye = min(a.oh, yb + yrows_per_block);
+    int r_lo = yb + a.off - (a.kh - 1);
+    r_lo = r_lo <= 0 ? 0 : (r_lo + S - 1) / S;                         // first input row any of these outputs reads
+    const int r_hi = min(a.ih, (ye - 1 + a.off) / S + 1);
+    const int nrows = max(0, r_hi - r_lo);                             // <= lds_rows by construction on the host
+    const int ncols = a.kh * a.kw * CI;
+    const int npos = nrows * a.iw, E = a.RB * npos, ntiles = (E + 31) >> 5;
+    const int Pout = a.oh * a.ow, elems = Pout * CI, padn = a.ld_out - elems;
+    const int span = (ye - yb) * a.ow, total = a.RB * span;
+    typedef float vf4 __attribute__((ext_vector_type(4)));
+    const unsigned long long magic_span = (1ull << 32) / (unsigned)max(span, 1) + 1;   // e / span for e * span < 2^32
+    const unsigned long long magic_ow = (1ull << 32) / (unsigned)max(a.ow, 1) + 1;
+    const int zoff = ((a.RB * lds_rows * a.iw + 31) & ~31) * PS;                         // four zeros behind the panel
+    if (tid < 4) sP[zoff + tid] = 0.0f;
+
+    // kernel matrix in the B-operand layout: step (g, s4) of the reduction multiplies channel 8g + 4kq + s4
+    float bk[NT][CO8 * 4];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int col = n * 32 + l32;
+        const int tap = col / CI, ci = col - tap * CI;
+#pragma unroll
+        for (int k = 0; k < CO8 * 4; ++k) {
+            const int co = 8 * (k >> 2) + 4 * kq + (k & 3);
+            bk[n][k] = col < ncols ? taps[((size_t)tap * CO + co) * CI + ci] : 0.0f;
+        }
+    }
+
+    // The input tiles of a wavefront are fetched one step ahead, across panel boundaries too, so that the loads of
+    // the next step are in flight during the MFMAs of this one and during the gather phase.
+    const int ipp = (ntiles + 2 * NW - 1) / (2 * NW);                  // steps (tile pairs) per wavefront per panel
+    auto fetch = [&](int pi, int it, vf4 (&r)[2][CO8]) __attribute__((always_inline)) {
+        const long long m0 = ((long long)blockIdx.x * panels + pi) * a.RB;
+        const int t0 = wave * 2 + it * 2 * NW;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int e = (t0 + u) * 32 + l32;
+            const int ml = e / max(npos, 1), pos = e - ml * npos;
+            const bool ok = pi < panels && t0 + u < ntiles && e < E && m0 + ml < a.M;
+            const float* p = in + (m0 + (ok ? ml : 0)) * a.ld_in + ((size_t)r_lo * a.iw + (ok ? pos : 0)) * CO + 4 * kq;
+#pragma unroll
+            for (int g = 0; g < CO8; ++g) {
+                r[u][g] = vf4{0.f, 0.f, 0.f, 0.f};
+                if (ok) r[u][g] = *reinterpret_cast<const vf4*>(p + 8 * g);
+            }
+        }
+    };
+    vf4 nxt[2][CO8];
+    fetch(0, 0, nxt);
+
+    for (int pi = 0; pi < panels; ++pi) {
+        const long long m0 = ((long long)blockIdx.x * panels + pi) * a.RB;
+        if (m0 >= a.M) break;                                          // uniform over the workgroup
+        if (blockIdx.y == 0)
+            for (int i = tid; i < a.RB * padn; i += kPThreads) {
+                const int ml = i / padn, c = i - ml * padn;
+                if (m0 + ml < a.M) out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
+            }
+        for (int it = 0; it < ipp; ++it) {
+            const int t0 = wave * 2 + it * 2 * NW;
+            vf4 av[2][CO8];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int g = 0; g < CO8; ++g) av[u][g] = nxt[u][g];
+            if (it + 1 < ipp) fetch(pi, it + 1, nxt);
+            else fetch(pi + 1, 0, nxt);
+            if (t0 >= ntiles) continue;
+            floatx16 acc[2][NT];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[u][n][r] = 0.0f;
+#pragma unroll
+            for (int g = 0; g < CO8; ++g)
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                    for (int n = 0; n < NT; ++n)
+#pragma unroll
+                        for (int u = 0; u < 2; ++u)
+                            acc[u][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][g][s4], bk[n][4 * g + s4], acc[u][n], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                if (t0 + u >= ntiles) break;
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        sP[((t0 + u) * 32 + 8 * (r >> 2) + 4 * kq + (r & 3)) * PS + n * 32 + l32] = acc[u][n][r];
+            }
+        }
+        __syncthreads();
+
+        // Gather: one thread per output position, all taps in uniform control flow (a tap that falls outside the
+        // patch reads a block of zeros); quotients by the run-time extents through multiply-high.
+        for (int e = tid; e < total; e += kPThreads) {
+            const int ml = (int)(((unsigned long long)e * magic_span) >> 32);
+            const int q = e - ml * span;
+            const int yy = (int)(((unsigned long long)q * magic_ow) >> 32);
+            const int x = q - yy * a.ow, y = yb + yy;
+            const int rbase = ml * npos - r_lo * a.iw;
+            float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+            for (int ky = 0; ky < a.kh; ++ky) {
+                const int ty = y + a.off - ky;
+                const int py = ty / S;
+                const bool oky = ty >= 0 && py * S == ty && py < a.ih;
+                const int rowoff = rbase + py * a.iw;
+                for (int kx = 0; kx < a.kw; ++kx) {
+                    const int tx = x + a.off - kx;
+                    const int px = tx / S;
+                    const bool ok = oky && tx >= 0 && px * S == tx && px < a.iw;
+                    const float* src = sP + (ok ? (rowoff + px) * PS + (ky * a.kw + kx) * CI : zoff);
+                    o0 += src[0]; o1 += src[1]; o2 += src[2]; o3 += src[3];      // columns past CI are never stored
+                }
+            }
+            if (m0 + ml < a.M) {
+                float* dst = out + (m0 + ml) * a.ld_out + (size_t)(y * a.ow + x) * CI;
+                dst[0] = o0;
+                if (CI > 1) dst[1] = o1;
+                if (CI > 2) dst[2] = o2;
+                if (CI > 3) dst[3] = o3;
+            }
+        }
+        __syncthreads();                   // the panel is overwritten by the next one
+    }
+}
+
 }  // namespace
 
 // Returns false when the shape is outside what these kernels cover (the caller then uses the
@@ -305,6 +458,57 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     a.pstride = g.Co + 4;
     a.rowstride = ih * iw * a.pstride;
     constexpr size_t kLdsBudget = 150 * 1024;
+
+    if (g.Ci <= 4 && conv_algo() != 2 && (g.stride == 1 || g.stride == 2) &&
+        (g.Co == 8 || g.Co == 16 || g.Co == 32 || g.Co == 64) && g.kh * g.kw * g.Ci <= 64) {
+        // MFMA route: P = input x all taps into LDS, then gather.  Workgroups take whole rows when the P panel of a
+        // row fits (several rows if it is small), else strips of output rows.
+        const int NT = (g.kh * g.kw * g.Ci + 31) / 32;
+        const int PS = 32 * NT + 3;
+        const size_t sB_bytes = 16;        // the block of zeros behind the panel
+        // panel of at most 48 KB: three workgroups per compute unit, so that one's gather phase overlaps another's MFMAs
+        // and loads (measured best among 24 .. 72 KB)
+        const int64_t emax = (int64_t)((48 * 1024 - sB_bytes) / ((size_t)PS * 4)) / 32 * 32;     // list entries a panel can hold
+        auto rows_reached = [&](int yb, int ye) {
+            int r_lo = yb + off - (g.kh - 1);
+            r_lo = r_lo <= 0 ? 0 : (r_lo + g.stride - 1) / g.stride;
+            const int r_hi = std::min(ih, (ye - 1 + off) / g.stride + 1);
+            return std::max(0, r_hi - r_lo);
+        };
+        int yr = oh, RB = 1, lds_rows = ih;
+        if ((int64_t)ih * iw <= emax) {
+            RB = (int)std::max<int64_t>(1, std::min<int64_t>(emax / ((int64_t)ih * iw), 64));
+        } else {
+            for (yr = oh; yr >= 1; --yr) {
+                lds_rows = 0;
+                for (int yb = 0; yb < oh; yb += yr) lds_rows = std::max(lds_rows, rows_reached(yb, std::min(oh, yb + yr)));
+                if ((int64_t)lds_rows * iw <= emax) break;
+            }
+        }
+        if (yr >= 1 && (int64_t)RB * lds_rows * iw <= emax) {
+            a.RB = RB;
+            const size_t lds = sB_bytes + (size_t)round_up((int64_t)RB * lds_rows * iw, 32) * PS * 4;
+            // panels per workgroup: as many as keep about eight workgroups per compute unit in the grid
+            const int64_t units = ceil_div(M, RB) * ceil_div(oh, yr);
+            const int panels = (int)std::max<int64_t>(1, std::min<int64_t>(16, units / 2048));
+            dim3 grid((unsigned)ceil_div(ceil_div(M, RB), panels), (unsigned)ceil_div(oh, yr));
+            auto launch = [&](auto kern) {
+                hipLaunchKernelGGL(kern, grid, dim3(kPThreads), lds, s, in, w.taps, out, a, yr, lds_rows, panels);
+            };
+#define DPC_P_CASE(NTV, SV, C8) if (NT == NTV && g.stride == SV && g.Co == 8 * C8) { \
+        static bool configured = false; \
+        if (!configured) { DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_transpose_p_kernel<NTV, SV, C8>), \
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024)); configured = true; } \
+        launch(&conv_transpose_p_kernel<NTV, SV, C8>); }
+            DPC_P_CASE(1, 1, 1) DPC_P_CASE(1, 1, 2) DPC_P_CASE(1, 1, 4) DPC_P_CASE(1, 1, 8)
+            DPC_P_CASE(2, 1, 1) DPC_P_CASE(2, 1, 2) DPC_P_CASE(2, 1, 4) DPC_P_CASE(2, 1, 8)
+            DPC_P_CASE(1, 2, 1) DPC_P_CASE(1, 2, 2) DPC_P_CASE(1, 2, 4) DPC_P_CASE(1, 2, 8)
+            DPC_P_CASE(2, 2, 1) DPC_P_CASE(2, 2, 2) DPC_P_CASE(2, 2, 4) DPC_P_CASE(2, 2, 8)
+#undef DPC_P_CASE
+            DPC_HIP(hipGetLastError());
+            return true;
+        }
+    }
 
     if (g.Ci <= 4) {
         // output rows per workgroup: about 256 positions; input rows those can reach: yr/s + (kh-1)/s + 2

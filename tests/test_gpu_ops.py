@@ -132,10 +132,15 @@ CONV_CASES = [
     (5, 7, 8, 12, 3, 2, 0, False),      # odd sizes, stride 2 with a 3x3 kernel (a class without taps)
     (3, 3, 6, 5, 2, 1, 0, False),       # channels not multiples of 8 / 4: generic kernel
     (20, 20, 16, 8, 3, 1, 1, True),     # more than 256 positions per class: chunked
+    (6, 6, 8, 1, 3, 1, 1, True),        # few input channels: 1, 2 and 4 of them, 8 and 64 output channels
+    (10, 9, 16, 2, 3, 2, 0, False),
+    (7, 5, 64, 4, 4, 2, 0, False),
+    (40, 24, 16, 3, 4, 2, 1, True),     # strips of output rows, stride 2
+    (33, 31, 32, 4, 3, 1, 1, True),     # strips, ragged widths, 36 of 64 product columns
 ]
 
 
-@pytest.mark.parametrize("algo", [0, 1])
+@pytest.mark.parametrize("algo", [0, 1, 2])
 @pytest.mark.parametrize("case", CONV_CASES)
 def test_conv_transpose(case, algo):
     from paper_2507_20055_amd import binding as b
@@ -148,7 +153,7 @@ def test_conv_transpose(case, algo):
     else:
         oh, ow = (ih - 1) * s + k, (iw - 1) * s + k
     rng = np.random.default_rng(ih * 100 + Co + Ci)
-    for M in (1, 37):
+    for M in (1, 37, 300) + ((1500,) if (ih, Ci, algo) == (32, 3, 0) else ()):     # 1500: several panels per workgroup
         n_in, n_out = ih * iw * Co, oh * ow * Ci
         ld_in, ld_out = (n_in + 3) // 4 * 4, (n_out + 31) // 32 * 32
         rows, rows_f = _rows(rng, M, n_in, ld_in)
