@@ -84,8 +84,14 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     // kernel values straight from global memory (the whole kernel is a few hundred KB and is read by every
     // workgroup, so it lives in L2): lane (kq, l32) needs K[tap][co = 8g+4kq+s][ci = 32n + l32], s = 0..3
     bool ci_ok[NT];
+    int kvoff[NT];                                    // byte offset of this lane's kernel column (clamped into range)
 #pragma unroll
-    for (int n = 0; n < NT; ++n) ci_ok[n] = n * 32 + l32 < a.Ci;
+    for (int n = 0; n < NT; ++n) {
+        ci_ok[n] = n * 32 + l32 < a.Ci;
+        kvoff[n] = (4 * kq * a.Ci + min(n * 32 + l32, a.Ci - 1)) * 4;
+    }
+    const __amdgpu_buffer_rsrc_t kres =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.taps), 0, a.kh * a.kw * a.Co * a.Ci * 4, 0x00020000);
 
     for (int cy = 0; cy < a.s; ++cy) {
         // rows y of this class: (y + off) mod s == cy  ->  y = y0 + s*iy
@@ -144,19 +150,26 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                     __syncthreads();
                 }
                 const int nit = ntaps * ngr;                      // flattened (tap, group) iterations
-                auto kptr = [&](int it) __attribute__((always_inline)) {
+                // Kernel values through a buffer resource (one lane offset, scalar offsets for the rest), fetched three
+                // (tap, group) steps ahead into rotating register sets.  Plain predicated pointer loads ended up in
+                // separate basic blocks with a full wait behind them, which exposed the L2 latency at every step.
+                auto koff = [&](int it) __attribute__((always_inline)) {
                     const int ti = it / ngr, g = it - ti * ngr;
                     const int jy = ti / nkx, jx = ti - jy * nkx;
                     const int tap = (cy + a.s * jy) * a.kw + (cx + a.s * jx);
-                    return a.taps + ((size_t)tap * a.Co + cc * a.CC + 8 * g + 4 * kq) * a.Ci + l32;
+                    return (tap * a.Co + cc * a.CC + 8 * g) * a.Ci * 4;           // bytes, wave-uniform
                 };
-                float bcur[4][NT], bnxt[4][NT];
                 auto load_b = [&](int it, float (&bb)[4][NT]) __attribute__((always_inline)) {
-                    const float* p = kptr(it);
+                    const int so = koff(it);
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
-                        for (int n = 0; n < NT; ++n) bb[s][n] = ci_ok[n] ? p[(size_t)s * a.Ci + n * 32] : 0.0f;
+                        for (int n = 0; n < NT; ++n) {
+                            // columns past Ci read a clamped (valid) column: they only feed accumulator columns that
+                            // are never stored, and touching the value here would force a wait right behind the load
+                            bb[s][n] = __builtin_bit_cast(
+                                float, __builtin_amdgcn_raw_buffer_load_b32(kres, kvoff[n], so + s * a.Ci * 4, 0));
+                        }
                 };
                 int addr[2] = {zoff + 4 * kq, zoff + 4 * kq};
                 auto step = [&](int it, float (&bb)[4][NT]) __attribute__((always_inline)) {
@@ -183,13 +196,24 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                                 acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, bb[s][n], acc[t][n], 0, 0, 0);
                         }
                 };
-                if (nit > 0) load_b(0, bcur);
-                for (int it = 0; it < nit; it += 2) {
-                    if (it + 1 < nit) load_b(it + 1, bnxt);
-                    step(it, bcur);
+                float b0[4][NT], b1[4][NT], b2[4][NT], b3[4][NT];
+                if (nit > 0) load_b(0, b0);
+                if (nit > 1) load_b(1, b1);
+                if (nit > 2) load_b(2, b2);
+                for (int it = 0; it < nit; it += 4) {
+                    if (it + 3 < nit) load_b(it + 3, b3);
+                    step(it, b0);
                     if (it + 1 < nit) {
-                        if (it + 2 < nit) load_b(it + 2, bcur);
-                        step(it + 1, bnxt);
+                        if (it + 4 < nit) load_b(it + 4, b0);
+                        step(it + 1, b1);
+                    }
+                    if (it + 2 < nit) {
+                        if (it + 5 < nit) load_b(it + 5, b1);
+                        step(it + 2, b2);
+                    }
+                    if (it + 3 < nit) {
+                        if (it + 6 < nit) load_b(it + 6, b2);
+                        step(it + 3, b3);
                     }
                 }
             }
