@@ -8,6 +8,9 @@
 #include <algorithm>
 #include <cmath>
 #include <memory>
+#include <mutex>
+#include <set>
+#include <utility>
 #include <vector>
 
 #include "common.h"
@@ -16,6 +19,18 @@
 namespace dpc {
 
 static thread_local std::string g_error;
+
+void ensure_dynamic_lds(const void* kernel, int bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<const void*, int>> done;
+    int dev = 0;
+    DPC_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({kernel, dev})) return;
+    DPC_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    done.insert({kernel, dev});
+}
 
 void set_error(const char* fmt, ...)
 {
@@ -254,7 +269,7 @@ size_t workspace_floats(const dpc_network* net, int B, bool with_margin)
         }
     }
     if (with_margin) {
-        const size_t rows = 2 * (size_t)B * (2 * (size_t)net->layers[nl - 1]->n_out - 1);
+        const size_t rows = 2 * (size_t)B * std::max<size_t>(2 * (size_t)net->layers[nl - 1]->n_out - 1, 32);
         for (int j = 0; j < nl; ++j) need = std::max(need, rows * net->ld_of(j));
     }
     return need;
@@ -720,10 +735,13 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
 
         // ---- workspace ----
         size_t need_rows = 1;
-        const size_t stage_need = std::max(2 * (size_t)B * n0, 2 * (size_t)B * (2 * (size_t)nK - 1)) + 16;   // box staging / merged last pass + one flag word
+        // rows per (side, input) group of the merged output + margin pass: padded up to the smallest group the fused
+        // contraction epilogue takes, so that this pass can use it too
+        const size_t RsMax = std::max<size_t>(2 * (size_t)nK - 1, 32);
+        const size_t stage_need = std::max(2 * (size_t)B * n0, 2 * (size_t)B * RsMax) + 16;   // box staging / merged last pass + one flag word
         for (int i = 1; i <= nl; ++i)
             if (net->layers[i - 1]->kind != RELU) need_rows = std::max(need_rows, 2 * (size_t)B * net->size_of(i));
-        need_rows = std::max(need_rows, 2 * (size_t)B * (2 * (size_t)nK - 1));   // output + margin rows of the last pass
+        need_rows = std::max(need_rows, 2 * (size_t)B * RsMax);   // output + margin rows of the last pass
         size_t need = workspace_floats(net, B, label != nullptr);
         const int ldE = (int)round_up(n0 + 1, kLdAlign);          // ReuseCert: input-level expression rows
         if (reuse_cert) {
@@ -741,6 +759,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             size_t fuse_rows = 0;          // rows of the passes that can use fused epilogues (dense rows of FC layers)
             for (int i = 1; i <= nl; ++i)
                 if (net->layers[i - 1]->kind == AFFINE) fuse_rows = std::max(fuse_rows, 2 * (size_t)B * net->size_of(i));
+            if (label && last.kind == AFFINE) fuse_rows = std::max(fuse_rows, 2 * (size_t)B * RsMax);
             if (fuse_rows > 0 && fuse_rows * dpc_network::kMaxSlots * 4 <= ((size_t)1 << 31)) {
                 moved |= net->part.reserve(fuse_rows * dpc_network::kMaxSlots);
                 net->part_stride = std::max<int64_t>(net->part_stride, (int64_t)fuse_rows);
@@ -906,16 +925,18 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 // Output-layer rows and margin rows walk the same layers: one pass of 2*nK-1 rows per (side, input)
                 // instead of two passes (the margins' upper-side rows are computed and dropped).
                 const int Rm = 2 * nK - 1;
+                // groups padded with zero rows to the fused epilogue's minimum when that route is open
+                const int Rs = (fuse && !opt.keep_symbolic && Rm < 32) ? 32 : Rm;
                 float* tl = net->stage.p;
-                float* tu = net->stage.p + (size_t)B * Rm;
+                float* tu = net->stage.p + (size_t)B * Rs;
                 prof.begin(P_OTHER);
                 launch_final_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
-                                  net->ld_of(nl - 1), net->cst.p, s);
+                                  net->ld_of(nl - 1), net->cst.p, s, Rs);
                 prof.end();
                 res->prof.other_launches++;
-                run_pass(P, nl - 1, 2, Rm, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rm));
+                run_pass(P, nl - 1, 2, Rs, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rs));
                 prof.begin(P_OTHER);
-                launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s);
+                launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s, Rs);
                 prof.end();
                 res->prof.other_launches++;
             } else if (label) {

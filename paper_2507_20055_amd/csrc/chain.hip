@@ -347,12 +347,7 @@ template <int BM, int KMAX, int WAVES, int MBS, int NBS, int MBF, int NBF>
 void launch_chain_variant(const ChainArgs& a, int groups, hipStream_t s)
 {
     constexpr size_t lds = chain_lds_bytes<BM, KMAX, WAVES>();
-    static bool configured = false;
-    if (!configured) {
-        DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_kernel<BM, KMAX, WAVES, MBS, NBS, MBF, NBF>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = true;
-    }
+    ensure_dynamic_lds(reinterpret_cast<const void*>(&chain_kernel<BM, KMAX, WAVES, MBS, NBS, MBF, NBF>), (int)lds);
     hipLaunchKernelGGL((chain_kernel<BM, KMAX, WAVES, MBS, NBS, MBF, NBF>), dim3((unsigned)(groups * a.bpg)), dim3(WAVES * 64), lds,
                        s, a);
     DPC_HIP(hipGetLastError());

@@ -28,6 +28,10 @@ struct Fail { dpc_status code; };          // thrown internally, caught at every
         if (!(cond)) { dpc::set_error(__VA_ARGS__); throw dpc::Fail{code}; }               \
     } while (0)
 
+// Raises a kernel's dynamic-LDS limit.  The attribute belongs to the (kernel, device) pair, so it is applied once
+// for every device the kernel is launched on (thread-safe).
+void ensure_dynamic_lds(const void* kernel, int bytes);
+
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 static inline int64_t ceil_div(int64_t x, int64_t m) { return (x + m - 1) / m; }
 
@@ -134,12 +138,13 @@ void launch_finalize_bounds(const double* cst, const float* part, int nslots, in
 void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch,
                         int nK, int n, float* C, int ldc, double* cst, hipStream_t s);
 
-// Output-layer rows and margin rows stacked in one pass (R = 2*nK - 1 rows per (side, input)); and the
-// kernel that splits that pass's bounds into l,u of the output layer, margins and verdicts.
+// Output-layer rows and margin rows stacked in one pass (2*nK - 1 rows per (side, input), held in groups of
+// Rs >= 2*nK - 1 rows whose tail is zero; Rs = 0 means no padding); and the kernel that splits that pass's bounds
+// ([batch][Rs] per side) into l,u of the output layer, margins and verdicts.
 void launch_final_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch, int nK, int n,
-                       float* C, int ldc, double* cst, hipStream_t s);
+                       float* C, int ldc, double* cst, hipStream_t s, int Rs = 0);
 void launch_split_final(const float* tl, const float* tu, int batch, int nK, float* l, float* u, float* margin,
-                        int32_t* verdict, hipStream_t s);
+                        int32_t* verdict, hipStream_t s, int Rs = 0);
 
 // verdict[b] = all margins of input b > 0.
 void launch_verdict(const float* margin, int batch, int nq, int32_t* verdict, hipStream_t s);

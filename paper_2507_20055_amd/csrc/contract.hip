@@ -363,12 +363,7 @@ template <class T, int EPI>
 int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw, float* Cout,
                    int ldc, const EpiArgs& ep, int max_slots, hipStream_t s, int batches = 1)
 {
-    static bool configured = false;
-    if (!configured) {
-        DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&contract_kernel<T, EPI>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES));
-        configured = true;
-    }
+    ensure_dynamic_lds(reinterpret_cast<const void*>(&contract_kernel<T, EPI>), (int)T::LDS_BYTES);
     static_assert(EPI == 0 || T::LDS_BYTES >= (size_t)T::WAVES_N * T::BM * 4, "row sums must fit the K-loop LDS");
     const int64_t tiles_m = ceil_div(M, T::BM);
     const int tiles_n = (int)ceil_div(ldc, T::BN);          // padding columns of Cout are written too

@@ -520,9 +520,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
                 hipLaunchKernelGGL(kern, grid, dim3(kPThreads), lds, s, in, w.taps, out, a, yr, lds_rows, panels);
             };
 #define DPC_P_CASE(NTV, SV, C8) if (NT == NTV && g.stride == SV && g.Co == 8 * C8) { \
-        static bool configured = false; \
-        if (!configured) { DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_transpose_p_kernel<NTV, SV, C8>), \
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024)); configured = true; } \
+        ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_p_kernel<NTV, SV, C8>), 64 * 1024); \
         launch(&conv_transpose_p_kernel<NTV, SV, C8>); }
             DPC_P_CASE(1, 1, 1) DPC_P_CASE(1, 1, 2) DPC_P_CASE(1, 1, 4) DPC_P_CASE(1, 1, 8)
             DPC_P_CASE(2, 1, 1) DPC_P_CASE(2, 1, 2) DPC_P_CASE(2, 1, 4) DPC_P_CASE(2, 1, 8)
@@ -547,12 +545,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div(oh, yr));
         const size_t lds = (size_t)RB * rb_bytes + (size_t)a.pstride * 4;
         auto launch = [&](auto kern) {
-            static bool configured = false;
-            if (!configured) {
-                DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)kLdsBudget));
-                configured = true;
-            }
+            ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kLdsBudget);
             hipLaunchKernelGGL(kern, grid, dim3(kCtThreads), lds, s, in, w.taps, out, a, yr, lds_rows);
         };
         switch (g.Ci) {
@@ -585,20 +578,10 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     const size_t lds = (size_t)RB * row_bytes2 + fixed;
     dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div((int64_t)RB * Pc_max, kCtEntries));
     if (NT == 1) {
-        static bool configured = false;
-        if (!configured) {
-            DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<1>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget));
-            configured = true;
-        }
+        ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<1>), (int)kLdsBudget);
         hipLaunchKernelGGL(conv_transpose_mfma_kernel<1>, grid, dim3(kCtThreads), lds, s, a);
     } else {
-        static bool configured = false;
-        if (!configured) {
-            DPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<2>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget));
-            configured = true;
-        }
+        ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<2>), (int)kLdsBudget);
         hipLaunchKernelGGL(conv_transpose_mfma_kernel<2>, grid, dim3(kCtThreads), lds, s, a);
     }
     DPC_HIP(hipGetLastError());

@@ -524,43 +524,44 @@ __global__ __launch_bounds__(kThreads) void margin_rows_kernel(
 
 // Rows of the last pass when output-layer bounds and margins share one traversal: for group (side, b),
 // rows 0..nK-1 are the output neurons' own expressions (weight rows, bias), rows nK..2nK-2 the margin
-// expressions logit[label_b] - logit[o] for the nK-1 other classes o in ascending order.
+// expressions logit[label_b] - logit[o] for the nK-1 other classes o in ascending order.  A group holds Rs >= 2nK-1
+// rows; rows past 2nK-2 are zero (padding that lets the pass use kernels with a minimum group size).
 __global__ __launch_bounds__(kThreads) void final_rows_kernel(
     const float* __restrict__ W, int ldw, const float* __restrict__ bias, const int32_t* __restrict__ label, int batch,
-    int nK, int n, float* __restrict__ C, int ldc, double* __restrict__ cst)
+    int nK, int n, float* __restrict__ C, int ldc, double* __restrict__ cst, int Rs)
 {
     const int Rm = 2 * nK - 1;
-    const int m = blockIdx.x;                 // (side*batch + b)*Rm + r
-    const int r = m % Rm, b = (m / Rm) % batch;
-    int t = r, o = -1;
-    if (r >= nK) {
+    const int m = blockIdx.x;                 // (side*batch + b)*Rs + r
+    const int r = m % Rs, b = (m / Rs) % batch;
+    const bool pad = r >= Rm;
+    int t = pad ? 0 : r, o = -1;
+    if (!pad && r >= nK) {
         const int q = r - nK;
         t = label[b];
         o = q < t ? q : q + 1;
     }
     for (int i = threadIdx.x; i < ldc; i += kThreads) {
         float v = 0.0f;
-        if (i < n) v = o < 0 ? W[(size_t)t * ldw + i] : W[(size_t)t * ldw + i] - W[(size_t)o * ldw + i];
+        if (i < n && !pad) v = o < 0 ? W[(size_t)t * ldw + i] : W[(size_t)t * ldw + i] - W[(size_t)o * ldw + i];
         C[(size_t)m * ldc + i] = v;
     }
-    if (threadIdx.x == 0) cst[m] = o < 0 ? (double)bias[t] : (double)bias[t] - (double)bias[o];
+    if (threadIdx.x == 0) cst[m] = pad ? 0.0 : o < 0 ? (double)bias[t] : (double)bias[t] - (double)bias[o];
 }
 
 // Splits the merged last pass: l,u of the output layer, margins (lower side only) and verdicts.
 __global__ void split_final_kernel(const float* __restrict__ tl, const float* __restrict__ tu, int batch, int nK,
                                    float* __restrict__ l, float* __restrict__ u, float* __restrict__ margin,
-                                   int32_t* __restrict__ verdict)
+                                   int32_t* __restrict__ verdict, int Rs)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= batch) return;
-    const int Rm = 2 * nK - 1;
     for (int r = 0; r < nK; ++r) {
-        l[(size_t)b * nK + r] = tl[(size_t)b * Rm + r];
-        u[(size_t)b * nK + r] = tu[(size_t)b * Rm + r];
+        l[(size_t)b * nK + r] = tl[(size_t)b * Rs + r];
+        u[(size_t)b * nK + r] = tu[(size_t)b * Rs + r];
     }
     int ok = 1;
     for (int q = 0; q < nK - 1; ++q) {
-        const float mg = tl[(size_t)b * Rm + nK + q];
+        const float mg = tl[(size_t)b * Rs + nK + q];
         margin[(size_t)b * (nK - 1) + q] = mg;
         if (!(mg > 0.0f)) ok = 0;
     }
@@ -746,21 +747,23 @@ void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_
 }
 
 void launch_final_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch, int nK, int n,
-                       float* C, int ldc, double* cst, hipStream_t s)
+                       float* C, int ldc, double* cst, hipStream_t s, int Rs)
 {
-    DPC_REQUIRE(nK >= 2 && ldc >= n && ldw >= n, DPC_EINVAL, "final_rows: bad shape");
+    if (Rs <= 0) Rs = 2 * nK - 1;
+    DPC_REQUIRE(nK >= 2 && ldc >= n && ldw >= n && Rs >= 2 * nK - 1, DPC_EINVAL, "final_rows: bad shape");
     if (batch == 0) return;
-    hipLaunchKernelGGL(final_rows_kernel, dim3((unsigned)(2 * batch * (2 * nK - 1))), dim3(kThreads), 0, s, W, ldw, bias,
-                       label, batch, nK, n, C, ldc, cst);
+    hipLaunchKernelGGL(final_rows_kernel, dim3((unsigned)(2 * batch * Rs)), dim3(kThreads), 0, s, W, ldw, bias,
+                       label, batch, nK, n, C, ldc, cst, Rs);
     DPC_HIP(hipGetLastError());
 }
 
 void launch_split_final(const float* tl, const float* tu, int batch, int nK, float* l, float* u, float* margin,
-                        int32_t* verdict, hipStream_t s)
+                        int32_t* verdict, hipStream_t s, int Rs)
 {
     if (batch == 0) return;
+    if (Rs <= 0) Rs = 2 * nK - 1;
     hipLaunchKernelGGL(split_final_kernel, dim3((unsigned)ceil_div(batch, 64)), dim3(64), 0, s, tl, tu, batch, nK, l, u,
-                       margin, verdict);
+                       margin, verdict, Rs);
     DPC_HIP(hipGetLastError());
 }
 
