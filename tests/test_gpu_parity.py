@@ -59,7 +59,10 @@ def test_hand_example_on_gpu():
 @pytest.mark.parametrize("convs,fcs,shape", [([(3, 3, 1, 1), (4, 4, 2, 1)], [6, 3], (2, 6, 6)),
                                              ([(4, 4, 2, 1), (8, 4, 2, 1)], [10, 4], (3, 12, 12)),
                                              ([(4, 3, 1, 1), (4, 4, 2, 1), (8, 3, 1, 1), (8, 4, 2, 1)], [16, 16, 5], (3, 8, 8)),
-                                             ([(3, 3, 2, 0)], [4], (1, 7, 9))])
+                                             ([(3, 3, 2, 0)], [4], (1, 7, 9)),
+                                             # channel counts the MFMA convolution kernels take
+                                             ([(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4], (3, 10, 10)),
+                                             ([(16, 4, 2, 1), (40, 3, 1, 0), (8, 3, 2, 1)], [9, 3], (2, 13, 11))])
 def test_small_conv(convs, fcs, shape):
     net = wl.random_small_conv(7, shape, convs, fcs)
     B = 3
@@ -67,6 +70,8 @@ def test_small_conv(convs, fcs, shape):
     label = np.arange(B, dtype=np.int32) % fcs[-1]
     gnet, g, o = _run_both(net, lo, hi, label)
     compare_with_oracle(net, lo, hi, g, o, label)
+    g0 = gnet.certify(lo, hi, label, fuse=0)             # every step its own kernel: same bounds
+    compare_with_oracle(net, lo, hi, g0, o, label)
     gnet.close()
 
 
