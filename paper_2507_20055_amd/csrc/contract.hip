@@ -445,8 +445,9 @@ void launch_contract_batched(const float* A, int64_t strideA, int64_t M, int K, 
                 "contract_batched: buffers must be 16-byte aligned");
     if (M == 0 || batches == 0) return;
     EpiArgs ep{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap, (long long)strideA, (long long)strideW, (long long)strideC};
-    // tile choice as for one problem of batches * M rows
-    const int variant = g_variant >= 0 ? g_variant : pick_variant(M * batches, ldc);
+    // tile choice as for one problem of batches * M rows; problems of at most 512 rows tile better with 64x64
+    // (measured on the 500-row steps of ReuseCert)
+    const int variant = g_variant >= 0 ? g_variant : M <= 512 ? 9 : pick_variant(M * batches, ldc);
     switch (variant) {
         case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
         case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
