@@ -36,6 +36,21 @@ def test_struct_sizes_match_header_layout():
     assert binding._lib.dpc_options_default(ctypes.byref(opt)) == 0
     assert opt.struct_size == ctypes.sizeof(binding.dpc_options)
     assert opt.max_backsub_depth == -1 and opt.fuse == 1 and opt.keep_symbolic == 0
+    assert opt.certifier == binding.CERTIFIERS["deeppoly"] == 0 and opt.use_graph == 1
+    # dpc_profile: 5 int32 (+4 padding), 8 doubles, then chain_ms, chain_flop, chain_launches, reserved
+    assert ctypes.sizeof(binding.dpc_profile) == 24 + 8 * 8 + 16 + 8
+    header = open(os.path.join(ROOT, "include", "dpcert.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\} dpc_profile;", header, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = [n.strip() for decl in body.split(";") for n in re.sub(r"^\s*(int32_t|double)\s+", "", decl.strip()).split(",") if n.strip()]
+    assert names == [f for f, _ in binding.dpc_profile._fields_]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in (r.stderr + r.stdout)
 
 
 def _new():
