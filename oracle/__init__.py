@@ -72,13 +72,14 @@ class OracleResult:
 
 
 def run(net, lo, hi, label=None, sym_layer: int = -1, max_depth: int = -1,
-        threads: Optional[int] = None, certifier: str = "deeppoly") -> OracleResult:
-    """certifier: "deeppoly" (Appendix C, DeepPoly; max_depth >= 0 gives DeepPoly_p) or "reusecert" (Appendix C,
+        threads: Optional[int] = None, certifier: str = "deeppoly", max_depth_last: Optional[int] = None) -> OracleResult:
+    """certifier: "deeppoly" (Appendix C, DeepPoly; max_depth >= 0 gives DeepPoly_p; max_depth_last, if given, is the
+    limit of the last layer and the property rows: max_depth = 0, max_depth_last = -1 is CROWN-IBP) or "reusecert" (Appendix C,
     ReuseCert: l, u of affine layers are the concretised stored bounds, ReLU-layer l, u stay 0, sym_layer may
     name any affine layer)."""
     lib = _load()
     assert certifier in ("deeppoly", "reusecert")
-    assert certifier == "deeppoly" or max_depth < 0
+    assert certifier == "deeppoly" or (max_depth < 0 and max_depth_last is None)
     if threads is not None:
         os.environ["OMP_NUM_THREADS"] = str(threads)
     lo = np.ascontiguousarray(lo, dtype=np.float32)
@@ -166,7 +167,7 @@ def run(net, lo, hi, label=None, sym_layer: int = -1, max_depth: int = -1,
         rc = lib.dpo_run(ctypes.c_int(nl), arr, ctypes.c_int(B), vp(lo.ctypes.data), vp(hi.ctypes.data), vp(lab_p),
                          ptrs(l), ptrs(u), ptrs(lam), ptrs(mu), ptrs(nu), vp(mar_p), vp(ver_p),
                          ctypes.c_int(sym_layer), vp(sp[0]), vp(sp[1]), vp(sp[2]), vp(sp[3]),
-                         ctypes.c_int(max_depth))
+                         ctypes.c_int(max_depth), ctypes.c_int(-2 if max_depth_last is None else max_depth_last))
     if rc != 0:
         raise ValueError(f"the oracle rejected its input (code {rc})")
     del keep

@@ -34,7 +34,11 @@
  *     such bound is > 0.
  *   - max_depth >= 0 gives the DeepPoly_p variant of Section 6.2: at most p
  *     traverse iterations, then simplify_* against the stored l, u of the layer
- *     reached.  max_depth < 0: full traversal.
+ *     reached.  max_depth < 0: full traversal.  max_depth_last (-2: same as
+ *     max_depth) is the limit used for the last layer and the property rows:
+ *     max_depth = 0 with max_depth_last = -1 is CROWN-IBP (Appendix C: every
+ *     affine layer maps simplify_* over its own expression -- interval bounds --
+ *     except the last one, which back-substitutes fully).
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC (see oracle/__init__.py).
  */
@@ -211,10 +215,11 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
             double** l, double** u, double** lam, double** mu, double** nu,
             double* margin, int* verdict,
             int sym_layer, double* sym_cl, double* sym_kl, double* sym_cu, double* sym_ku,
-            int max_depth)
+            int max_depth, int max_depth_last)
 {
     if (nlayers < 1 || B < 0) return 1;
     if (layers[0].kind == DPO_RELU) return 2;
+    if (max_depth_last == -2) max_depth_last = max_depth;
     int nmax = layers[0].n_in;
     for (int i = 0; i < nlayers; ++i) {
         if (i > 0 && layers[i].n_in != layers[i - 1].n_out) return 3;
@@ -251,6 +256,7 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
             continue;
         }
         const int want_sym = (sym_layer == k);
+        const int depth_k = (k == nlayers) ? max_depth_last : max_depth;
         int fail = 0;
         #pragma omp parallel
         {
@@ -266,10 +272,10 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
                     if (!buf_a || !buf_b) continue;
                     const size_t o = (size_t)bi * n + r;
                     double c0 = neuron_expr(L, r, buf_a);
-                    l[k][o] = backsubs(&st, bi, k - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth,
+                    l[k][o] = backsubs(&st, bi, k - 1, DPO_LOWER, c0, buf_a, buf_b, depth_k,
                                        want_sym ? sym_cl + o * n0 : NULL, want_sym ? sym_kl + o : NULL);
                     c0 = neuron_expr(L, r, buf_a);
-                    u[k][o] = backsubs(&st, bi, k - 1, DPO_UPPER, c0, buf_a, buf_b, max_depth,
+                    u[k][o] = backsubs(&st, bi, k - 1, DPO_UPPER, c0, buf_a, buf_b, depth_k,
                                        want_sym ? sym_cu + o * n0 : NULL, want_sym ? sym_ku + o : NULL);
                 }
             free(buf_a);
@@ -303,7 +309,7 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
                         buf_a[p] = (double)L->W[(size_t)t * nP + p] - (double)L->W[(size_t)o * nP + p];
                     const double c0 = (double)L->b[t] - (double)L->b[o];
                     margin[(size_t)bi * (nK - 1) + q] =
-                        backsubs(&st, bi, nlayers - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth, NULL, NULL);
+                        backsubs(&st, bi, nlayers - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth_last, NULL, NULL);
                 }
             free(buf_a);
             free(buf_b);

@@ -67,7 +67,7 @@ def _affine_rows(layer, n_prev_layer_index):
     return rows
 
 
-def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deeppoly"):
+def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deeppoly", max_iters_last=None):
     """lo, hi: sequences of length n0 (one input).  Returns (shapes, margins, verdict)
     where shapes[layer][pos] is a Shape.
 
@@ -75,7 +75,8 @@ def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deep
     layers back by scaling the predecessor's own L, U); "reusecert" (Appendix C, ReuseCert: stop_traverse(n) =
     n[layer] <= 1, middle affine layers store the traversed expressions as L, U and leave l, u at 0, the ReLU
     transformer concretises the predecessor's stored L, U itself; each Shape of an affine layer additionally
-    carries cl, cu = that concretisation)."""
+    carries cl, cu = that concretisation).  max_iters_last: iteration limit of the last layer's traversals and the
+    property rows (default: max_iters); max_iters = 0 with max_iters_last = -1 is CROWN-IBP (Appendix C)."""
     assert certifier in ("deeppoly", "skippoly", "reusecert")
     shapes: List[List[Shape]] = [[Shape(float(a), float(b)) for a, b in zip(lo, hi)]]
 
@@ -85,11 +86,13 @@ def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deep
             out = out.add(f(n, c))
         return out
 
+    limit = [max_iters]
+
     def traverse(e: PolyExp, priority, stop, f) -> PolyExp:
         iters = 0
         while True:
             active = [n for n in e.terms if not stop(n) and n[0] > 0]   # input neurons have no L/U
-            if not active or (max_iters >= 0 and iters >= max_iters):
+            if not active or (limit[0] >= 0 and iters >= limit[0]):
                 return e
             best = max(priority(n) for n in active)
             chosen = {n for n in active if priority(n) == best}
@@ -115,6 +118,8 @@ def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deep
     for k, layer in enumerate(net.layers, start=1):
         prev = shapes[k - 1]
         cur = []
+        if k == nl and max_iters_last is not None:
+            limit[0] = max_iters_last
         if layer.kind == "relu":
             for i, p in enumerate(prev):
                 n = PolyExp(0.0, {(k - 1, i): 1.0})

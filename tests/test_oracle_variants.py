@@ -167,3 +167,58 @@ def test_skippoly_computes_deeppoly_bounds(seed, dims):
     # and the ReLU neurons' polyhedral bounds really skip a layer
     assert all(n[0] == 0 for s in sh[2] for n in list(s.L.terms) + list(s.U.terms))
     assert all(n[0] == 2 for s in sh[4] for n in list(s.L.terms) + list(s.U.terms))
+
+
+# ---------------------------------------------------------------- CROWN-IBP (Appendix C): interval bounds, last layer back-substituted
+def test_crownibp_hand_example():
+    g, net = _hand_net()
+    e = read_golden("crownibp_2_2_2_2.txt")
+    lo, hi, lab = g["lo"][None], g["hi"][None], g["label"].astype(np.int32)
+    tol = dict(rtol=0, atol=1e-12)
+    r = oracle.run(net, lo, hi, label=lab, max_depth=0, max_depth_last=-1)
+    for k, key in ((3, "3"), (5, "5")):
+        np.testing.assert_allclose(r.l[k][0], e["l" + key], **tol)
+        np.testing.assert_allclose(r.u[k][0], e["u" + key], **tol)
+    np.testing.assert_allclose(r.lam[4][0], e["lam2"], **tol)
+    np.testing.assert_allclose(r.mu[4][0], e["mu2"], **tol)
+    np.testing.assert_allclose(r.nu[4][0], e["nu2"], **tol)
+    np.testing.assert_allclose(r.margin[0], e["margin"], **tol)
+    assert r.verdict[0] == 0
+    sh, m, v = neuron_level.certify(net, lo[0], hi[0], label=int(lab[0]), max_iters=0, max_iters_last=-1)
+    np.testing.assert_allclose([s.l for s in sh[5]], e["l5"], **tol)
+    np.testing.assert_allclose([s.u for s in sh[5]], e["u5"], **tol)
+    np.testing.assert_allclose(m, e["margin"], **tol)
+
+
+@pytest.mark.parametrize("seed,dims", [(41, [4, 6, 5, 3]), (42, [3, 5, 5, 5, 4])])
+def test_crownibp_structure(seed, dims):
+    net = wl.random_small_net(seed, dims)
+    x, lo, hi = wl.random_box(seed + 2, dims[0], 2, 0.4)
+    lab = np.array([0, 1], np.int32)
+    last = len(net.layers)
+    r = oracle.run(net, lo, hi, label=lab, max_depth=0, max_depth_last=-1)
+    ibp = oracle.run(net, lo, hi, max_depth=0)
+    full = oracle.run(net, lo, hi, label=lab)
+    # hidden layers: plain interval propagation; the last layer is something else (back-substituted bounds need not
+    # be tighter than interval bounds, so only the difference is asserted)
+    for k in range(1, last):
+        np.testing.assert_array_equal(r.l[k], ibp.l[k])
+        np.testing.assert_array_equal(r.u[k], ibp.u[k])
+    assert not np.allclose(r.l[last], ibp.l[last]) and not np.allclose(r.l[last], full.l[last])
+    # brute force: the neuron-level transcription with the same limits
+    for bi in range(2):
+        sh, m, v = neuron_level.certify(net, lo[bi], hi[bi], label=int(lab[bi]), max_iters=0, max_iters_last=-1)
+        np.testing.assert_allclose([s.l for s in sh[last]], r.l[last][bi], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose([s.u for s in sh[last]], r.u[last][bi], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(m, r.margin[bi], rtol=1e-10, atol=1e-12)
+        # sound
+        pts = _samples(lo[bi].astype(np.float64), hi[bi].astype(np.float64), 4000, seed)
+        acts = wl.forward(net, pts)
+        for k in range(1, last + 1):
+            assert np.all(acts[k] >= r.l[k][bi] - 1e-9) and np.all(acts[k] <= r.u[k][bi] + 1e-9)
+    # one hidden layer: its bounds are interval bounds under DeepPoly too, so the two certifiers coincide
+    net2 = wl.random_small_net(seed, dims[:2] + dims[-1:])
+    a = oracle.run(net2, lo, hi, label=lab % dims[-1])
+    b = oracle.run(net2, lo, hi, label=lab % dims[-1], max_depth=0, max_depth_last=-1)
+    np.testing.assert_allclose(b.l[3], a.l[3], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(b.margin, a.margin, rtol=1e-12, atol=1e-12)
