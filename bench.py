@@ -44,6 +44,8 @@ def main():
                     help="reusecert: the NEXT-row certifier (fully-connected workloads only); default deeppoly is the headline")
     ap.add_argument("--max-depth", type=int, default=-1,
                     help="p >= 0: DeepPoly_p (at most p traverse iterations, then concretise against stored bounds); 0 = IBP")
+    ap.add_argument("--final-depth", type=int, default=-2,
+                    help="traversal limit of the last layer and margins (-2: same as --max-depth); --max-depth 0 --final-depth -1 = CROWN-IBP")
     ap.add_argument("--host-inputs", action="store_true", help="pass host arrays (adds the PCIe upload of the boxes to every step)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE", help="dpc_tuning_set(KEY, VALUE) before the run")
     ap.add_argument("--fuse", type=int, default=1)
@@ -88,7 +90,8 @@ def main():
     def step(profile):
         for i, (lo, hi, lab) in enumerate(dev):
             results[i] = net.certify(lo, hi, lab, stream=stream.cuda_stream, profile=profile, fuse=args.fuse, reuse=results[i],
-                                     certifier=args.certifier, max_backsub_depth=args.max_depth)
+                                     certifier=args.certifier, max_backsub_depth=args.max_depth,
+                                     final_backsub_depth=args.final_depth)
 
     for _ in range(args.warmup):
         step(0)
@@ -142,14 +145,14 @@ def main():
         "data": "synthetic",
         "config": {"workload": DESCR[args.workload], "inputs_per_step": inputs_per_step,
                    "verified": verified, "min_abs_margin": min_abs_margin, "fuse": args.fuse,
-                   "inputs": "host" if args.host_inputs else "resident in HBM", "certifier": args.certifier, "max_backsub_depth": args.max_depth},
+                   "inputs": "host" if args.host_inputs else "resident in HBM", "certifier": args.certifier, "max_backsub_depth": args.max_depth, "final_backsub_depth": args.final_depth},
         "roofline": {
             "kernel": dom_name,
             "bound": "mfma", "achieved": dom_tflops, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
             "frac": dom_tflops / PEAK_FP32_MFMA_TFLOPS,
             "launches": dom_launches, "avg_launch_ms": dom_ms / max(dom_launches, 1),
             "flop_per_launch": dom_flop / max(dom_launches, 1),
-            "traffic": TRAFFIC.get(args.workload) if not args.tune and args.variant < 0 and args.fuse == 1 and args.certifier == "deeppoly" and args.max_depth < 0 else None,
+            "traffic": TRAFFIC.get(args.workload) if not args.tune and args.variant < 0 and args.fuse == 1 and args.certifier == "deeppoly" and args.max_depth < 0 and args.final_depth in (-2, -1) else None,
             "all_mfma_kernels": {"achieved": mfma_tflops, "frac": mfma_tflops / PEAK_FP32_MFMA_TFLOPS,
                                  "flop_per_step": (P["chain_flop"] + P["contract_flop"]) / args.steps,
                                  "ms_per_step": mfma_ms / args.steps},
@@ -214,7 +217,7 @@ def main():
         tc = time.perf_counter()
         for w in loads:
             oracle.run(w.net, w.lo[:ns], w.hi[:ns], label=w.label[:ns], threads=cores, certifier=args.certifier,
-                       max_depth=args.max_depth)
+                       max_depth=args.max_depth, max_depth_last=None if args.final_depth == -2 else args.final_depth)
         tcpu = time.perf_counter() - tc
         out["cpu_baseline"] = {"value": ns * n_eps / tcpu, "unit": "inputs/s", "cores": cores, "kind": "oracle",
                                "sample": f"first {ns} of {B} inputs of each of the {n_eps} eps settings, float64 oracle, {tcpu:.1f} s"}

@@ -105,8 +105,13 @@ typedef struct {
                                    affine and ReLU layers alternating only; needs max_backsub_depth = -1 and
                                    keep_symbolic = 0.  dpc_result_concrete then returns, for an affine layer, the
                                    concretisation of its stored bounds (the values the next ReLU transformer uses) */
+    int32_t final_backsub_depth; /* traversal limit of the LAST layer and of the property (margin) rows: DPC_SAME_DEPTH
+                                   (-2, default) = max_backsub_depth; -1 = to the input; p >= 0 as above.
+                                   max_backsub_depth = 0 with final_backsub_depth = -1 is CROWN-IBP (Appendix C): interval
+                                   bounds for every hidden layer, full back-substitution for the output constraints */
     void*   stream;             /* hipStream_t all work is enqueued on (NULL = the null stream) */
 } dpc_options;
+enum { DPC_SAME_DEPTH = -2 };
 enum { DPC_DEEPPOLY = 0, DPC_REUSECERT = 1 };
 
 /* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, graph replay on, null stream). */

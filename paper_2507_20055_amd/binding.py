@@ -27,7 +27,7 @@ c_i32, c_i64, c_vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
 
 class dpc_options(ctypes.Structure):
     _fields_ = [("struct_size", c_i32), ("max_backsub_depth", c_i32), ("keep_symbolic", c_i32),
-                ("fuse", c_i32), ("profile", c_i32), ("use_graph", c_i32), ("certifier", c_i32), ("stream", c_vp)]
+                ("fuse", c_i32), ("profile", c_i32), ("use_graph", c_i32), ("certifier", c_i32), ("final_backsub_depth", c_i32), ("stream", c_vp)]
 
 
 CERTIFIERS = {"deeppoly": 0, "reusecert": 1}
@@ -153,7 +153,8 @@ class Network:
 
     def certify(self, lo, hi, label=None, *, max_backsub_depth: int = -1, keep_symbolic: int = 0,
                 fuse: int = 1, profile: int = 0, use_graph: int = 1, stream: int = 0,
-                reuse: Optional["Result"] = None, certifier: str = "deeppoly") -> "Result":
+                reuse: Optional["Result"] = None, certifier: str = "deeppoly",
+                final_backsub_depth: int = -2) -> "Result":
         lo, hi = _f32(lo), _f32(hi)
         batch = int(lo.shape[0])
         assert tuple(lo.shape) == (batch, self.sizes[0]) and tuple(hi.shape) == tuple(lo.shape)
@@ -164,6 +165,7 @@ class Network:
         opt.max_backsub_depth, opt.keep_symbolic, opt.fuse, opt.profile = max_backsub_depth, keep_symbolic, fuse, profile
         opt.use_graph = use_graph
         opt.certifier = CERTIFIERS[certifier]
+        opt.final_backsub_depth = final_backsub_depth
         opt.stream = stream or None
         h = c_vp(reuse._h.value) if reuse is not None else c_vp()
         _check(_lib.dpc_certify(self._h, batch, _ptr(lo), _ptr(hi), _ptr(label), ctypes.byref(opt), ctypes.byref(h)))

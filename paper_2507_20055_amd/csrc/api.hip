@@ -285,6 +285,7 @@ struct Pass {
     hipStream_t s;
     Prof* prof;
     int B;
+    int maxd;             // traversal limit of this pass (-1: to the input)
 };
 
 void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym,
@@ -293,7 +294,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     dpc_network* net = P.net;
     dpc_result* res = P.res;
     const int B = P.B;
-    const int maxd = P.opt->max_backsub_depth;
+    const int maxd = P.maxd;
     float* cur = net->buf[0].p;
     float* nxt = net->buf[1].p;
     double* cst = net->cst.p;
@@ -648,6 +649,7 @@ dpc_status dpc_options_default(dpc_options* opt)
         opt->profile = 0;
         opt->use_graph = 1;
         opt->certifier = DPC_DEEPPOLY;
+        opt->final_backsub_depth = DPC_SAME_DEPTH;
         opt->stream = nullptr;
     });
 }
@@ -668,8 +670,10 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         }
         DPC_REQUIRE(batch >= 0 && batch <= 16384, DPC_EINVAL, "dpc_certify: batch %d out of range [0, 16384]", batch);
         DPC_REQUIRE(opt.max_backsub_depth >= -1, DPC_EINVAL, "dpc_certify: max_backsub_depth must be >= -1");
+        DPC_REQUIRE(opt.final_backsub_depth >= DPC_SAME_DEPTH, DPC_EINVAL, "dpc_certify: final_backsub_depth must be >= -2");
+        if (opt.final_backsub_depth == DPC_SAME_DEPTH) opt.final_backsub_depth = opt.max_backsub_depth;
         DPC_REQUIRE(opt.keep_symbolic == 0 || opt.keep_symbolic == 1, DPC_EINVAL, "dpc_certify: keep_symbolic must be 0 or 1");
-        DPC_REQUIRE(opt.keep_symbolic == 0 || opt.max_backsub_depth == -1, DPC_EINVAL,
+        DPC_REQUIRE(opt.keep_symbolic == 0 || opt.final_backsub_depth == -1, DPC_EINVAL,
                     "dpc_certify: keep_symbolic needs a full traversal");
         const int nl = (int)net->layers.size();
         const Layer& last = *net->layers[nl - 1];
@@ -677,7 +681,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     opt.certifier);
         const bool reuse_cert = opt.certifier == DPC_REUSECERT;
         if (reuse_cert) {
-            DPC_REQUIRE(opt.max_backsub_depth == -1 && opt.keep_symbolic == 0, DPC_EINVAL,
+            DPC_REQUIRE(opt.max_backsub_depth == -1 && opt.final_backsub_depth == -1 && opt.keep_symbolic == 0, DPC_EINVAL,
                         "dpc_certify: ReuseCert needs max_backsub_depth = -1 and keep_symbolic = 0");
             DPC_REQUIRE(nl % 2 == 1, DPC_EUNSUPPORTED, "dpc_certify: ReuseCert needs affine and ReLU layers alternating");
             for (int i = 0; i < nl; ++i)
@@ -754,7 +758,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         }
         bool moved = net->buf[0].reserve(need);
         moved |= net->buf[1].reserve(need);
-        const bool fuse = opt.fuse && opt.max_backsub_depth < 0;
+        const bool fuse = opt.fuse && (opt.max_backsub_depth < 0 || opt.final_backsub_depth < 0);
         if (fuse) {
             size_t fuse_rows = 0;          // rows of the passes that can use fused epilogues (dense rows of FC layers)
             for (int i = 1; i <= nl; ++i)
@@ -822,10 +826,10 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
         // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
         const bool graphable = opt.use_graph && s != nullptr && !prof.on && !opt.keep_symbolic && !fresh;
-        const dpc_result::GraphKey gkey{opt.max_backsub_depth, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws_epoch};
+        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws_epoch};
         const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
         auto enqueue_reusecert = [&]() {
-            Pass P{net, res, &opt, s, &prof, B};
+            Pass P{net, res, &opt, s, &prof, B, -1};
             float* E = net->buf[0].p;            // stored bounds of the current affine layer: [side][b][n][ldE]
             float* Rr = net->buf[1].p;           // [b][2n + 1][ldE]: the ReLU layer's input-level bounds + unit row
             double* cst = net->cst.p;
@@ -904,7 +908,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         auto enqueue_all = [&]() {
             if (reuse_cert && nl >= 3) { enqueue_reusecert(); return; }
             if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
-            Pass P{net, res, &opt, s, &prof, B};
+            Pass P{net, res, &opt, s, &prof, B, opt.max_backsub_depth};
             for (int i = 1; i <= nl; ++i) {
                 Layer& L = *net->layers[i - 1];
                 if (L.kind == RELU) {
@@ -919,8 +923,10 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     continue;
                 }
                 if (merge_final && i == nl) continue;       // bounded together with the margins below
+                P.maxd = i == nl ? opt.final_backsub_depth : opt.max_backsub_depth;
                 run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
             }
+            P.maxd = opt.final_backsub_depth;
             if (merge_final) {
                 // Output-layer rows and margin rows walk the same layers: one pass of 2*nK-1 rows per (side, input)
                 // instead of two passes (the margins' upper-side rows are computed and dropped).

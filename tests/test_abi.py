@@ -36,7 +36,7 @@ def test_struct_sizes_match_header_layout():
     assert binding._lib.dpc_options_default(ctypes.byref(opt)) == 0
     assert opt.struct_size == ctypes.sizeof(binding.dpc_options)
     assert opt.max_backsub_depth == -1 and opt.fuse == 1 and opt.keep_symbolic == 0
-    assert opt.certifier == binding.CERTIFIERS["deeppoly"] == 0 and opt.use_graph == 1
+    assert opt.certifier == binding.CERTIFIERS["deeppoly"] == 0 and opt.use_graph == 1 and opt.final_backsub_depth == -2
     # dpc_profile: 5 int32 (+4 padding), 8 doubles, then chain_ms, chain_flop, chain_launches, reserved
     assert ctypes.sizeof(binding.dpc_profile) == 24 + 8 * 8 + 16 + 8
     header = open(os.path.join(ROOT, "include", "dpcert.h")).read()

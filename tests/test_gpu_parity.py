@@ -324,6 +324,39 @@ def test_reusecert_full_batch_gpu_sampled_oracle(cfg, idx):
     gnet.close()
 
 
+@pytest.mark.parametrize("depth,final", [(0, -1), (1, -1), (2, 0), (0, 3)])
+def test_separate_limit_for_the_last_layer(depth, final):
+    """max_backsub_depth for the hidden layers, final_backsub_depth for the output layer and the margins;
+    (0, -1) is CROWN-IBP."""
+    net = wl.random_small_net(91, [14, 40, 36, 33, 6])
+    x, lo, hi = wl.random_box(92, 14, 4, 0.1)
+    label = np.array([0, 1, 2, 5], np.int32)
+    b = _binding()
+    gnet = b.Network(net)
+    g = gnet.certify(lo, hi, label, max_backsub_depth=depth, final_backsub_depth=final)
+    o = oracle.run(net, lo, hi, label=label, max_depth=depth, max_depth_last=final)
+    compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
+def test_crownibp_hand_example_on_gpu():
+    from tests.test_oracle_pins import read_golden, fc_net
+    gd = read_golden("net_2_2_2_2.txt")
+    e = read_golden("crownibp_2_2_2_2.txt")
+    net = fc_net(2, [(gd["W1"].reshape(2, 2), gd["b1"]), (gd["W2"].reshape(2, 2), gd["b2"]), (gd["W3"].reshape(2, 2), gd["b3"])])
+    b = _binding()
+    gnet = b.Network(net)
+    g = gnet.certify(gd["lo"][None].astype(np.float32), gd["hi"][None].astype(np.float32), gd["label"].astype(np.int32),
+                     max_backsub_depth=0, final_backsub_depth=-1)
+    for k, key in ((3, "3"), (5, "5")):
+        np.testing.assert_allclose(g.concrete(k)[0][0], e["l" + key], rtol=1e-6, atol=1e-6)
+        np.testing.assert_allclose(g.concrete(k)[1][0], e["u" + key], rtol=1e-6, atol=1e-6)
+    v, m = g.verdict()
+    np.testing.assert_allclose(m[0], e["margin"], rtol=1e-6)
+    assert v[0] == 0
+    gnet.close()
+
+
 @pytest.mark.parametrize("kind", ["fc", "conv"])
 def test_graph_replay_matches_eager(kind):
     """A reused result on a caller's stream replays the kernel sequence as one HIP graph.  Every replay
