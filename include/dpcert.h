@@ -221,7 +221,9 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
  * gather kernel for convolution contractions (0 = MFMA / small-channel kernels where they apply);
  * key "chain" chooses when the traversal of a fully-connected layer's rows runs as one kernel with the
  * coefficient rows resident in LDS (-1 = by problem shape, the default; 0 = never; 1 = whenever the
- * layer widths fit); "merge_final" = 0 bounds the output layer and the margins in two traversals instead
+ * layer widths fit) and "chain_rows" its row block for panels up to 512 columns (64, the default, or 32 with two
+ * workgroups per compute unit); "conv_algo" = 2 sends few-input-channel layers to the plain-ALU kernel;
+ * "merge_final" = 0 bounds the output layer and the margins in two traversals instead
  * of one; "contract_remap", "rows_per_wave", "rows_stream" select launch shapes of the contraction and
  * row kernels.  Results do not depend on any of them beyond rounding order. */
 dpc_status dpc_tuning_set(const char* key, int32_t value);
