@@ -125,6 +125,7 @@ struct dpc_network {
     // fused-epilogue state: packed per-(side, input, neuron) parameters of every ReLU layer (index 0:
     // the box), and the slots that collect row-constant partial sums of the fused contractions
     std::vector<std::unique_ptr<DevBuf<float>>> pk;
+    DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
     DevBuf<float> part;
     int64_t part_stride = 0;
     DevBuf<float> rc_rows;                 // ReuseCert: split output/margin rows of the last step, per input
@@ -359,6 +360,21 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
 
     while (at > 0 && (maxd < 0 || depth < maxd)) {
         const Layer& L = *net->layers[at - 1];
+        if (L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.opt->fuse && maxd < 0 && !keep_sym && net->pk2.p &&
+            net->layers[0]->kind == CONV && (shared != nullptr || bias_folded || depth > 0)) {
+            // patch rows over the first ReLU layer: ReLU step, first layer and concretisation in one kernel
+            const Layer& first = *net->layers[0];
+            PatchTail pt{shared ? shared : cur, shared ? ld_shared : f.ld, shared ? 1 : 0, cst, cst_init, R, B, &f.pg, &first.g,
+                         net->pk2.p, net->ld_of(2), first.cw.bias_c, first.cw.taps, res->l[0], res->u[0], out_l, out_u};
+            P.prof->begin(P_CONTRACT);
+            const bool done = launch_patch_tail(pt, P.s);
+            P.prof->end();
+            if (done) {
+                res->prof.contract_flop += useful * 2.0 * (double)M * f.pg.ph * f.pg.pw * first.g.Co * first.g.Ci * first.g.kh * first.g.kw;
+                res->prof.contract_launches++;
+                return;
+            }
+        }
         if (L.kind == RELU) {
             const Layer& below = *net->layers[at - 2];
             const bool fold = (maxd < 0 || depth + 2 <= maxd);
@@ -768,6 +784,8 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 moved |= net->part.reserve(fuse_rows * dpc_network::kMaxSlots);
                 net->part_stride = std::max<int64_t>(net->part_stride, (int64_t)fuse_rows);
             }
+            if (nl >= 3 && net->layers[0]->kind == CONV && net->layers[0]->g.Ci <= 4 && net->layers[1]->kind == RELU)
+                moved |= net->pk2.reserve((size_t)B * net->ld_of(2) * 2);
             if (net->pk.size() != (size_t)nl + 1) net->pk.resize(nl + 1);
             for (int i = 0; i <= nl; ++i) {
                 const bool want = i == 0 ? !net->in_spatial || true : net->layers[i - 1]->kind == RELU;
@@ -918,6 +936,8 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     if (fuse)
                         launch_pack_relax(res->lam[i], res->mu[i], res->nu[i], net->layers[i - 2]->dBias.p, B, L.n_out,
                                           net->ld_of(i), net->pk[i]->p, s);
+                    if (fuse && i == 2 && net->pk2.p)
+                        launch_pack_relax2(res->lam[i], res->mu[i], res->nu[i], B, L.n_out, net->ld_of(i), net->pk2.p, s);
                     prof.end();
                     res->prof.other_launches++;
                     continue;

@@ -127,6 +127,9 @@ void launch_reuse_const(const float* C, int ldc, int col, int64_t rows, double* 
 // (lambda, mu, nu) followed by the bias fold of the layer below (bias may be NULL); columns n..ld-1 zero.
 void launch_pack_relax(const float* lambda, const float* mu, const float* nu, const float* bias, int batch, int n,
                        int ld, float* pk, hipStream_t s);
+// pk2[b][c] = (mu, nu with lambda in its sign bit: negative = 1), float2; columns n..ld-1 zero.
+void launch_pack_relax2(const float* lambda, const float* mu, const float* nu, int batch, int n, int ld, float* pk2,
+                        hipStream_t s);
 // pk[side][b][c] = (0, 0, bound taken by C >= 0, bound taken by C < 0) for the concretisation.
 void launch_pack_bounds(const float* lo, const float* hi, int batch, int n, int ld, float* pk, hipStream_t s);
 // out[b, r] = float(cst[m] + sum over slots of part[slot][m]), m = (side*batch + b)*R + r.

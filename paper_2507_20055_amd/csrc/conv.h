@@ -72,6 +72,23 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
 // MFMA implicit-GEMM / small-channel kernels for the same operation; false = shape not covered.
 bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
                                 const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
+// Tail of a traversal of patch-form rows in one kernel: the ReLU step of the network's first ReLU layer, the
+// transposed convolution through the first layer (at most 4 input channels) and the concretisation against the box
+// (see conv_tail.hip).  `form` describes the rows over the ReLU layer, `conv` the first layer.  Rows are
+// [side][input][R]; in: [2*batch*R][ld_in], or with shared != 0 the bounded layer's own cores [form->rows_C][ld_in]
+// with constants cst_init_c.  pk2: compact ReLU parameters (launch_pack_relax2).  Returns false, launching nothing,
+// when the shape is not covered.
+struct PatchTail {
+    const float* in; int ld_in; int shared;
+    const double* cst; const float* cst_init_c;
+    int R, batch;
+    const PatchGeom* form; const ConvGeom* conv;
+    const float* pk2; int ldpk; const float* bias_c; const float* taps;
+    const float* lo; const float* hi;
+    float* out_l; float* out_u;
+};
+bool launch_patch_tail(const PatchTail& d, hipStream_t s);
+
 void set_conv_algo(int v);
 int conv_algo();
 

@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
     const int ncols = a.kh * a.kw * CI;
     const int npos = nrows * a.iw, E = a.RB * npos, ntiles = (E + 31) >> 5;
     const int Pout = a.oh * a.ow, elems = Pout * CI, padn = a.ld_out - elems;
-    const int span = (ye - yb) * a.ow, total = a.RB * span;
+    const int span = (ye - yb) * a.ow, total = a.RB * span, nky = (a.kh + S - 1) / S, nkx = (a.kw + S - 1) / S;
     typedef float vf4 __attribute__((ext_vector_type(4)));
     const unsigned long long magic_span = (1ull << 32) / (unsigned)max(span, 1) + 1;   // e / span for e * span < 2^32
     const unsigned long long magic_ow = (1ull << 32) / (unsigned)max(a.ow, 1) + 1;
@@ -442,15 +442,15 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
             const int x = q - yy * a.ow, y = yb + yy;
             const int rbase = ml * npos - r_lo * a.iw;
             float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
-            for (int ky = 0; ky < a.kh; ++ky) {
-                const int ty = y + a.off - ky;
-                const int py = ty / S;
-                const bool oky = ty >= 0 && py * S == ty && py < a.ih;
+            // taps that can reach this output: ky = (y + off) mod S + S * jy, read at input row (y + off) / S - jy
+            const int ybase = (y + a.off) / S, ry = y + a.off - ybase * S, xbase = (x + a.off) / S, rx = x + a.off - xbase * S;
+            for (int jy = 0; jy < nky; ++jy) {
+                const int ky = ry + S * jy, py = ybase - jy;
+                const bool oky = ky < a.kh && py >= 0 && py < a.ih;
                 const int rowoff = rbase + py * a.iw;
-                for (int kx = 0; kx < a.kw; ++kx) {
-                    const int tx = x + a.off - kx;
-                    const int px = tx / S;
-                    const bool ok = oky && tx >= 0 && px * S == tx && px < a.iw;
+                for (int jx = 0; jx < nkx; ++jx) {
+                    const int kx = rx + S * jx, px = xbase - jx;
+                    const bool ok = oky && kx < a.kw && px >= 0 && px < a.iw;
                     const float* src = sP + (ok ? (rowoff + px) * PS + (ky * a.kw + kx) * CI : zoff);
                     o0 += src[0]; o1 += src[1]; o2 += src[2]; o3 += src[3];      // columns past CI are never stored
                 }

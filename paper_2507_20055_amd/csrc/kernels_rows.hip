@@ -478,6 +478,24 @@ __global__ __launch_bounds__(kThreads) void pack_relax_kernel(
     pk[i] = o;
 }
 
+// Compact parameters of a ReLU layer for kernels that apply the sign split themselves: (mu, nu) per (input, neuron)
+// with lambda (0 or 1) carried in the sign bit of nu (nu itself is never negative); columns n..ld-1 zero.
+__global__ __launch_bounds__(kThreads) void pack_relax2_kernel(
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu, int batch, int n, int ld,
+    float2* __restrict__ pk2)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;       // over [batch][ld]
+    if (i >= (int64_t)batch * ld) return;
+    const int col = (int)(i % ld), b = (int)(i / ld);
+    float2 o = make_float2(0.f, 0.f);
+    if (col < n) {
+        const float v = fabsf(nu[(size_t)b * n + col]);
+        o.x = mu[(size_t)b * n + col];
+        o.y = lambda[(size_t)b * n + col] != 0.0f ? -v : v;
+    }
+    pk2[i] = o;
+}
+
 __global__ __launch_bounds__(kThreads) void pack_bounds_kernel(
     const float* __restrict__ lo, const float* __restrict__ hi, int batch, int n, int ld, float4* __restrict__ pk)
 {
@@ -711,6 +729,17 @@ void launch_pack_relax(const float* lambda, const float* mu, const float* nu, co
     if (tot == 0) return;
     hipLaunchKernelGGL(pack_relax_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, lambda, mu, nu,
                        bias, batch, n, ld, reinterpret_cast<float4*>(pk));
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_pack_relax2(const float* lambda, const float* mu, const float* nu, int batch, int n, int ld, float* pk2,
+                        hipStream_t s)
+{
+    DPC_REQUIRE(lambda && mu && nu && pk2 && ld >= n && ((uintptr_t)pk2 % 16) == 0, DPC_EINVAL, "pack_relax2: bad arguments");
+    const int64_t tot = (int64_t)batch * ld;
+    if (tot == 0) return;
+    hipLaunchKernelGGL(pack_relax2_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, lambda, mu, nu, batch,
+                       n, ld, reinterpret_cast<float2*>(pk2));
     DPC_HIP(hipGetLastError());
 }
 

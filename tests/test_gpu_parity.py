@@ -62,7 +62,11 @@ def test_hand_example_on_gpu():
                                              ([(3, 3, 2, 0)], [4], (1, 7, 9)),
                                              # channel counts the MFMA convolution kernels take
                                              ([(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4], (3, 10, 10)),
-                                             ([(16, 4, 2, 1), (40, 3, 1, 0), (8, 3, 2, 1)], [9, 3], (2, 13, 11))])
+                                             ([(16, 4, 2, 1), (40, 3, 1, 0), (8, 3, 2, 1)], [9, 3], (2, 13, 11)),
+                                             # one kernel for ReLU step + first layer + concretisation: 32 and 8 channels,
+                                             # 4 and 1 input channels, both strides
+                                             ([(32, 3, 1, 1), (16, 4, 2, 0)], [8, 3], (4, 9, 9)),
+                                             ([(8, 4, 2, 1), (8, 3, 1, 1), (16, 3, 1, 1)], [5, 3], (1, 10, 10))])
 def test_small_conv(convs, fcs, shape):
     net = wl.random_small_conv(7, shape, convs, fcs)
     B = 3
