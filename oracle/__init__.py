@@ -11,9 +11,10 @@ semantics of Sections 2.2 and 3.2); this file only marshals numpy arrays.
 used as a brute-force cross-check on tiny networks.
 
 Networks are duck-typed: an object with ``n_in`` and ``layers``; each layer has
-``kind`` in {"affine", "conv", "relu"}, ``W``, ``b`` and, for conv, ``stride``,
+``kind`` in {"affine", "conv", "relu", "add"}, ``W``, ``b`` and, for conv, ``stride``,
 ``pad``, ``in_shape`` = (Ci, H, W).  Neurons of a conv layer are flattened
-(channel, row, column).
+(channel, row, column).  An "add" layer (residual networks) outputs the layer below plus
+the output of layer index ``skip`` (0 = the input, i = the i-th layer).
 """
 from __future__ import annotations
 
@@ -45,7 +46,7 @@ class _Layer(ctypes.Structure):
                 ("W", ctypes.c_void_p), ("b", ctypes.c_void_p),
                 ("Ci", ctypes.c_int), ("H", ctypes.c_int), ("Wd", ctypes.c_int), ("Co", ctypes.c_int),
                 ("kh", ctypes.c_int), ("kw", ctypes.c_int), ("stride", ctypes.c_int), ("pad", ctypes.c_int),
-                ("Ho", ctypes.c_int), ("Wo", ctypes.c_int)]
+                ("Ho", ctypes.c_int), ("Wo", ctypes.c_int), ("skip", ctypes.c_int)]
 
 
 def _load():
@@ -116,6 +117,10 @@ def run(net, lo, hi, label=None, sym_layer: int = -1, max_depth: int = -1,
             a.stride, a.pad, a.Ho, a.Wo = L.stride, L.pad, Ho, Wo
         elif L.kind == "relu":
             a.kind, a.n_out = 2, n_prev
+        elif L.kind == "add":
+            assert certifier == "deeppoly", "ReuseCert is specified for chain networks only"
+            assert 0 <= L.skip <= i and sizes[L.skip] == n_prev
+            a.kind, a.n_out, a.skip = 3, n_prev, L.skip
         else:
             raise ValueError(L.kind)
         n_prev = a.n_out

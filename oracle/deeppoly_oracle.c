@@ -39,6 +39,14 @@
  *     max_depth = 0 with max_depth_last = -1 is CROWN-IBP (Appendix C: every
  *     affine layer maps simplify_* over its own expression -- interval bounds --
  *     except the last one, which back-substitutes fully).
+ *   - Add layer (residual / skip networks; Section 5.2 on expressions that span several blocks; the
+ *     specification language names two predecessors prev0, prev1 but the paper prints no Add
+ *     transformer -- reading): neuron i of an Add layer is eta_i of the layer directly below plus eta_i of
+ *     an earlier layer `skip`; its transformer is the Affine one with unit weights over the two
+ *     predecessors: L = U = prev0 + prev1, l = backsubs_lower(L), u = backsubs_upper(U).  An expression
+ *     may then hold terms of several layers at once; traverse with priority = layer index replaces, in
+ *     every iteration, all terms of the deepest layer that holds any (Section 4.2), and simplify_* maps
+ *     over whatever terms are left, each against its own layer's l, u.
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC (see oracle/__init__.py).
  */
@@ -46,7 +54,7 @@
 #include <string.h>
 #include <math.h>
 
-enum { DPO_AFFINE = 0, DPO_CONV = 1, DPO_RELU = 2 };
+enum { DPO_AFFINE = 0, DPO_CONV = 1, DPO_RELU = 2, DPO_ADD = 3 };
 enum { DPO_LOWER = 0, DPO_UPPER = 1 };
 
 typedef struct {
@@ -55,6 +63,7 @@ typedef struct {
     const float* W;          /* affine: [n_out, n_in]; conv: [Co, Ci, kh, kw] */
     const float* b;          /* [n_out] or [Co] */
     int Ci, H, Wd, Co, kh, kw, stride, pad, Ho, Wo;   /* conv only */
+    int skip;                /* Add only: layer index (0 = input) of the second operand */
 } dpo_layer;
 
 /* Per-network, per-batch state: l,u of every layer, relaxation of ReLU layers.
@@ -198,6 +207,98 @@ static double neuron_expr(const dpo_layer* L, int r, double* coeff)
     return (double)L->b[co];
 }
 
+/* ---- networks with Add layers: an expression may hold terms of several layers at once ---- */
+typedef struct {
+    double** c;        /* [nlayers+1]: coefficient vector per layer index */
+    int* present;      /* [nlayers+1]: the layer holds terms of the expression */
+    double* tmp;       /* one replacement step's result */
+} dpo_multi;
+
+static void multi_free(const dpo_state* st, dpo_multi* e)
+{
+    if (!e) return;
+    if (e->c) for (int i = 0; i <= st->nlayers; ++i) free(e->c[i]);
+    free(e->c); free(e->present); free(e->tmp); free(e);
+}
+
+static dpo_multi* multi_new(const dpo_state* st, int nmax)
+{
+    dpo_multi* e = (dpo_multi*)calloc(1, sizeof(dpo_multi));
+    if (!e) return NULL;
+    e->c = (double**)calloc((size_t)st->nlayers + 1, sizeof(double*));
+    e->present = (int*)calloc((size_t)st->nlayers + 1, sizeof(int));
+    e->tmp = (double*)malloc(sizeof(double) * (size_t)nmax);
+    int ok = e->c && e->present && e->tmp;
+    for (int i = 0; ok && i <= st->nlayers; ++i) {
+        e->c[i] = (double*)calloc((size_t)layer_size(st, i), sizeof(double));
+        if (!e->c[i]) ok = 0;
+    }
+    if (!ok) { multi_free(st, e); return NULL; }
+    return e;
+}
+
+static void multi_clear(const dpo_state* st, dpo_multi* e)
+{
+    for (int i = 0; i <= st->nlayers; ++i) {
+        if (e->present[i]) memset(e->c[i], 0, sizeof(double) * (size_t)layer_size(st, i));
+        e->present[i] = 0;
+    }
+}
+
+/* e += the expression of neuron r of layer k written over its predecessor(s); returns its constant */
+static double multi_neuron_expr(const dpo_state* st, dpo_multi* e, int k, int r)
+{
+    const dpo_layer* L = &st->layers[k - 1];
+    if (L->kind == DPO_ADD) {
+        e->c[k - 1][r] += 1.0; e->present[k - 1] = 1;
+        e->c[L->skip][r] += 1.0; e->present[L->skip] = 1;
+        return 0.0;
+    }
+    const double c0 = neuron_expr(L, r, e->tmp);
+    for (int p = 0; p < L->n_in; ++p) e->c[k - 1][p] += e->tmp[p];
+    e->present[k - 1] = 1;
+    return c0;
+}
+
+/* backsubs_lower / backsubs_upper for an expression with terms on several layers. */
+static double backsubs_multi(const dpo_state* st, int bi, int side, double c0, dpo_multi* e, int max_depth,
+                             double* sym_c, double* sym_c0)
+{
+    int depth = 0;
+    for (;;) {
+        int at = st->nlayers;
+        while (at > 0 && !e->present[at]) --at;              /* deepest layer that holds terms */
+        if (at == 0 || (max_depth >= 0 && depth >= max_depth)) break;
+        const dpo_layer* L = &st->layers[at - 1];
+        if (L->kind == DPO_ADD) {
+            /* L_i = U_i = eta_i(layer at-1) + eta_i(layer skip) */
+            for (int i = 0; i < L->n_out; ++i) {
+                e->c[at - 1][i] += e->c[at][i];
+                e->c[L->skip][i] += e->c[at][i];
+            }
+            e->present[at - 1] = 1;
+            e->present[L->skip] = 1;
+        } else {
+            replace_layer(st, bi, at, side, e->c[at], &c0, e->tmp);
+            for (int p = 0; p < L->n_in; ++p) e->c[at - 1][p] += e->tmp[p];
+            e->present[at - 1] = 1;
+        }
+        memset(e->c[at], 0, sizeof(double) * (size_t)L->n_out);
+        e->present[at] = 0;
+        ++depth;
+    }
+    int only_input = 1;
+    for (int i = 1; i <= st->nlayers; ++i) if (e->present[i]) only_input = 0;
+    if (sym_c && only_input) {
+        memcpy(sym_c, e->c[0], sizeof(double) * (size_t)layer_size(st, 0));
+        *sym_c0 = c0;
+    }
+    double acc = c0;
+    for (int i = 0; i <= st->nlayers; ++i)
+        if (e->present[i]) acc = simplify(st, bi, i, side, acc, e->c[i]);
+    return acc;
+}
+
 /*
  * Run DeepPoly over the whole network.
  *   l,u,lam,mu,nu : arrays of nlayers+1 pointers (index 0 = input layer); l[i],u[i]
@@ -221,9 +322,17 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
     if (layers[0].kind == DPO_RELU) return 2;
     if (max_depth_last == -2) max_depth_last = max_depth;
     int nmax = layers[0].n_in;
+    int has_add = 0;
     for (int i = 0; i < nlayers; ++i) {
         if (i > 0 && layers[i].n_in != layers[i - 1].n_out) return 3;
         if (layers[i].kind == DPO_RELU && layers[i].n_in != layers[i].n_out) return 3;
+        if (layers[i].kind == DPO_ADD) {
+            /* second operand: an earlier layer (index < i in 0-based layer numbering = layer index <= i) of equal size */
+            if (i == 0 || layers[i].n_in != layers[i].n_out || layers[i].skip < 0 || layers[i].skip > i) return 3;
+            const int ns = layers[i].skip == 0 ? layers[0].n_in : layers[layers[i].skip - 1].n_out;
+            if (ns != layers[i].n_out) return 3;
+            has_add = 1;
+        }
         if (layers[i].n_out > nmax) nmax = layers[i].n_out;
     }
     if (label && layers[nlayers - 1].kind != DPO_AFFINE) return 4;
@@ -262,15 +371,27 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
         {
             double* buf_a = (double*)malloc(sizeof(double) * (size_t)nmax);
             double* buf_b = (double*)malloc(sizeof(double) * (size_t)nmax);
-            if (!buf_a || !buf_b) {
+            dpo_multi* e = has_add ? multi_new(&st, nmax) : NULL;
+            if (!buf_a || !buf_b || (has_add && !e)) {
                 #pragma omp atomic write
                 fail = 1;
             }
             #pragma omp for collapse(2) schedule(dynamic, 8)
             for (int bi = 0; bi < B; ++bi)
                 for (int r = 0; r < n; ++r) {
-                    if (!buf_a || !buf_b) continue;
+                    if (!buf_a || !buf_b || (has_add && !e)) continue;
                     const size_t o = (size_t)bi * n + r;
+                    if (has_add) {
+                        for (int side = DPO_LOWER; side <= DPO_UPPER; ++side) {
+                            multi_clear(&st, e);
+                            const double k0 = multi_neuron_expr(&st, e, k, r);
+                            const double v = backsubs_multi(&st, bi, side, k0, e, depth_k,
+                                                            want_sym ? (side == DPO_LOWER ? sym_cl : sym_cu) + o * n0 : NULL,
+                                                            want_sym ? (side == DPO_LOWER ? sym_kl : sym_ku) + o : NULL);
+                            if (side == DPO_LOWER) l[k][o] = v; else u[k][o] = v;
+                        }
+                        continue;
+                    }
                     double c0 = neuron_expr(L, r, buf_a);
                     l[k][o] = backsubs(&st, bi, k - 1, DPO_LOWER, c0, buf_a, buf_b, depth_k,
                                        want_sym ? sym_cl + o * n0 : NULL, want_sym ? sym_kl + o : NULL);
@@ -280,6 +401,7 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
                 }
             free(buf_a);
             free(buf_b);
+            multi_free(&st, e);
         }
         if (fail) return 6;
     }
@@ -298,21 +420,34 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
                 #pragma omp atomic write
                 fail = 1;
             }
+            dpo_multi* e = has_add ? multi_new(&st, nmax) : NULL;
+            if (has_add && !e) {
+                #pragma omp atomic write
+                fail = 1;
+            }
             #pragma omp for collapse(2) schedule(dynamic, 1)
             for (int bi = 0; bi < B; ++bi)
                 for (int q = 0; q < nK - 1; ++q) {
-                    if (!buf_a || !buf_b) continue;
+                    if (!buf_a || !buf_b || (has_add && !e)) continue;
                     const int t = label[bi];
                     const int o = q < t ? q : q + 1;
                     /* logit[t] - logit[o] as a polyhedral expression over the last hidden layer */
                     for (int p = 0; p < nP; ++p)
                         buf_a[p] = (double)L->W[(size_t)t * nP + p] - (double)L->W[(size_t)o * nP + p];
                     const double c0 = (double)L->b[t] - (double)L->b[o];
+                    if (has_add) {
+                        multi_clear(&st, e);
+                        memcpy(e->c[nlayers - 1], buf_a, sizeof(double) * (size_t)nP);
+                        e->present[nlayers - 1] = 1;
+                        margin[(size_t)bi * (nK - 1) + q] = backsubs_multi(&st, bi, DPO_LOWER, c0, e, max_depth_last, NULL, NULL);
+                        continue;
+                    }
                     margin[(size_t)bi * (nK - 1) + q] =
                         backsubs(&st, bi, nlayers - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth_last, NULL, NULL);
                 }
             free(buf_a);
             free(buf_b);
+            multi_free(&st, e);
         }
         if (fail) return 6;
         for (int bi = 0; bi < B; ++bi) {

@@ -40,9 +40,15 @@ class Shape:
         self.l, self.u, self.L, self.U = l, u, L, U
 
 
-def _affine_rows(layer, n_prev_layer_index):
-    """prev.dot(curr[weight]) + curr[bias] for every neuron of an affine/conv layer."""
+def _affine_rows(layer, n_prev_layer_index, n_prev=None):
+    """prev.dot(curr[weight]) + curr[bias] for every neuron of an affine/conv layer; for an Add layer (reading: the
+    Affine transformer with unit weights over its two predecessors) prev0 + prev1."""
     rows = []
+    if layer.kind == "add":
+        for i in range(n_prev):
+            e = PolyExp(0.0, {(n_prev_layer_index, i): 1.0})
+            rows.append(e.add(PolyExp(0.0, {(layer.skip, i): 1.0})))
+        return rows
     if layer.kind == "affine":
         for r in range(layer.W.shape[0]):
             rows.append(PolyExp(float(layer.b[r]),
@@ -143,11 +149,12 @@ def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deep
                     U = below_U.scale(pu / (pu - pl)).add(PolyExp(-(pu * pl) / (pu - pl)))
                 cur.append(Shape(l, u, L, U))
         elif certifier == "reusecert" and not (k == 1 or k == nl):
+            assert layer.kind != "add"
             for e in _affine_rows(layer, k - 1):
                 cur.append(Shape(0.0, 0.0, traverse(e, priority2, stop_traverse, replace_lower),
                                  traverse(e, priority2, stop_traverse, replace_upper)))
         else:
-            for e in _affine_rows(layer, k - 1):
+            for e in _affine_rows(layer, k - 1, len(prev)):
                 cur.append(Shape(backsubs_lower(e), backsubs_upper(e), e, e))
         shapes.append(cur)
 

@@ -32,12 +32,13 @@ import numpy as np
 
 @dataclass
 class Layer:
-    kind: str                                  # "affine" | "conv" | "relu"
+    kind: str                                  # "affine" | "conv" | "relu" | "add"
     W: Optional[np.ndarray] = None             # affine: [out, in]; conv: [Co, Ci, kh, kw]
     b: Optional[np.ndarray] = None             # [out] or [Co]
     stride: int = 1
     pad: int = 0
     in_shape: Optional[Tuple[int, int, int]] = None   # conv only: (Ci, H, W)
+    skip: int = -1                             # add only: layer index (0 = input) whose output is added to the layer below
 
     @property
     def out_shape(self) -> Tuple[int, int, int]:
@@ -63,7 +64,7 @@ class Network:
             elif L.kind == "conv":
                 c, h, w = L.out_shape
                 out.append(c * h * w)
-            else:
+            else:                                  # relu, add: same size as the layer below
                 out.append(out[-1])
         return out
 
@@ -107,6 +108,8 @@ def forward(net: Network, x: np.ndarray, upto: Optional[int] = None) -> List[np.
             h = h @ L.W.astype(x.dtype).T + L.b.astype(x.dtype)
         elif L.kind == "conv":
             h = conv_forward(h, L)
+        elif L.kind == "add":
+            h = h + acts[L.skip]
         else:
             h = np.maximum(h, 0)
         acts.append(h)
@@ -151,6 +154,30 @@ def make_conv(rng, in_shape, convs, fcs) -> Network:
         if i != len(fcs) - 1:
             net.layers.append(Layer("relu"))
         n = f
+    return net
+
+
+def make_res_fc(rng, n_in: int, width: int, blocks: int, n_out: int, std_scale: float = 1.0, bias_std: float = 0.01) -> Network:
+    """Fully-connected residual network: affine(n_in -> width), ReLU, then `blocks` times
+    [affine, ReLU, affine, add(block input), ReLU] at constant width, then affine(width -> n_out).
+    W ~ N(0, std_scale^2 / fan_in), bias ~ N(0, bias_std^2), drawn in network order (weight, then bias)."""
+    net = Network(n_in=n_in)
+
+    def affine(n_to, n_from):
+        W = rng.normal(0.0, std_scale / np.sqrt(n_from), size=(n_to, n_from))
+        b = rng.normal(0.0, bias_std, size=(n_to,))
+        net.layers.append(Layer("affine", _f32(W), _f32(b)))
+
+    affine(width, n_in)
+    net.layers.append(Layer("relu"))
+    for _ in range(blocks):
+        src = len(net.layers)                  # layer index of the block's input (output of the ReLU just added)
+        affine(width, width)
+        net.layers.append(Layer("relu"))
+        affine(width, width)
+        net.layers.append(Layer("add", skip=src))
+        net.layers.append(Layer("relu"))
+    affine(n_out, width)
     return net
 
 
@@ -218,6 +245,11 @@ def random_small_conv(seed: int, in_shape, convs, fcs, bias_std: float = 0.1) ->
         if L.b is not None:
             L.b = _f32(rng.normal(0.0, bias_std, size=L.b.shape))
     return net
+
+
+def random_small_res(seed: int, n_in: int, width: int, blocks: int, n_out: int, bias_std: float = 0.3) -> Network:
+    """Small residual FC net with O(1) weights for unit tests."""
+    return make_res_fc(np.random.default_rng(seed), n_in, width, blocks, n_out, 1.0, bias_std)
 
 
 def random_box(seed: int, n: int, batch: int, eps: float, lo_clip=None, hi_clip=None):
