@@ -75,6 +75,19 @@ dpc_status dpc_network_add_conv2d(dpc_network* net, int32_t Ci, int32_t H, int32
 /* ReLU over the previous layer (element-wise). */
 dpc_status dpc_network_add_relu(dpc_network* net);
 
+/* Add layer of a residual network: neuron i = neuron i of the previous layer + neuron i of layer
+ * `from_layer` (0 = the network input, k = the k-th layer added; it must lie below the previous
+ * layer and have the same size and, for convolutional layers, the same shape).  The paper's
+ * specification language names two predecessors (prev0, prev1) but prints no Add transformer; the
+ * library reads it as the Affine transformer with unit weights over both: L = U = prev0 + prev1,
+ * l, u by back-substitution.  A polyhedral expression that crosses the layer then has terms on two
+ * layers at once: two blocks of one coefficient tensor (Section 5.1), which are summed when the
+ * traversal brings them onto the same layer (Section 5.2, overlapping blocks are merged); the
+ * deepest layer is always replaced first (Section 4.2).  The previous layer must be fully-connected
+ * or a convolution (DPC_EUNSUPPORTED otherwise); networks with Add layers take full DeepPoly
+ * traversals only (no depth limit, no ReuseCert: dpc_certify returns DPC_EUNSUPPORTED). */
+dpc_status dpc_network_add_skip(dpc_network* net, int32_t from_layer);
+
 /* Validate the chain, upload weights to HIP device `device` in the layouts the
  * kernels use.  After this call no layer can be added.  Synchronous. */
 dpc_status dpc_network_finalize(dpc_network* net, int32_t device);

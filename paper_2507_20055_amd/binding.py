@@ -49,6 +49,7 @@ EXPORTS = {
     "dpc_network_add_affine": [c_vp, c_i32, c_i32, c_vp, c_vp],
     "dpc_network_add_conv2d": [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp],
     "dpc_network_add_relu": [c_vp],
+    "dpc_network_add_skip": [c_vp, c_i32],
     "dpc_network_finalize": [c_vp, c_i32],
     "dpc_network_destroy": [c_vp],
     "dpc_options_default": [ctypes.POINTER(dpc_options)],
@@ -140,6 +141,9 @@ class Network:
                     self.sizes.append(Co * Ho * Wo)
                 elif L.kind == "relu":
                     _check(_lib.dpc_network_add_relu(self._h))
+                    self.sizes.append(self.sizes[-1])
+                elif L.kind == "add":
+                    _check(_lib.dpc_network_add_skip(self._h, int(L.skip)))
                     self.sizes.append(self.sizes[-1])
                 else:
                     raise ValueError(L.kind)

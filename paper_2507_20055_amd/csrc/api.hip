@@ -51,7 +51,7 @@ void set_rows_stream(int v);
 
 namespace {
 
-enum Kind { AFFINE = 0, CONV = 1, RELU = 2 };
+enum Kind { AFFINE = 0, CONV = 1, RELU = 2, ADD = 3 };
 
 struct DeviceGuard {
     int prev = -1;
@@ -92,6 +92,7 @@ struct Layer {
     int kind = AFFINE;
     int n_in = 0, n_out = 0;
     ConvGeom g{};                          // CONV only
+    int skip = -1;                         // ADD only: layer index (0 = input) of the second operand
     bool spatial_out = false;              // neurons of this layer carry a (C,H,W) shape (stored H,W,C)
     int C = 0, H = 0, W = 0;               // that shape
     std::vector<float> hW, hb;             // host copies in the caller's layout
@@ -126,6 +127,8 @@ struct dpc_network {
     // the box), and the slots that collect row-constant partial sums of the fused contractions
     std::vector<std::unique_ptr<DevBuf<float>>> pk;
     DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
+    std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
+    int skip_depth = 0;                    // how many skip connections span one layer at most
     DevBuf<float> part;
     int64_t part_stride = 0;
     DevBuf<float> rc_rows;                 // ReuseCert: split output/margin rows of the last step, per input
@@ -257,15 +260,17 @@ size_t workspace_floats(const dpc_network* net, int B, bool with_margin)
     size_t need = 1;
     const int nl = (int)net->layers.size();
     for (int i = 1; i <= nl; ++i) {
-        const Layer& own = *net->layers[i - 1];
-        if (own.kind == RELU) continue;
+        if (net->layers[i - 1]->kind == RELU) continue;
+        // an Add layer is bounded through the rows of the layer below it (plus a unit block on the skip operand)
+        const int top = net->layers[i - 1]->kind == ADD ? i - 1 : i;
+        const Layer& own = *net->layers[top - 1];
         const size_t rows = 2 * (size_t)B * own.n_out;
-        Form f = start_form(net, i - 1, &own);
+        Form f = start_form(net, top - 1, &own);
         need = std::max(need, rows * f.ld);
-        for (int at = i - 1; at > 0; --at) {
+        for (int at = top - 1; at > 0; --at) {
             const Layer& L = *net->layers[at - 1];
             if (L.kind == CONV && f.patch) f = through_conv(f, L.g);
-            else if (L.kind != RELU) f.ld = net->ld_of(at - 1);
+            else if (L.kind == AFFINE || L.kind == CONV) f.ld = net->ld_of(at - 1);
             need = std::max(need, rows * f.ld);
         }
     }
@@ -289,8 +294,23 @@ struct Pass {
     int maxd;             // traversal limit of this pass (-1: to the input)
 };
 
+// A block of the expression that waits on a skip connection until the traversal reaches the layer it is over
+// (residual networks: the expression then has terms on two layers at once).
+struct Waiting {
+    int target;            // layer index the block is over
+    int kind;              // 0: rows of its own (src = a skip buffer), 1: the bounded layer's shared rows / cores, 2: unit block
+    const float* src;
+    int ld;
+    int slot;              // skip buffer held (kind 0), else -1
+    bool patch;
+    int ph, pw, S, P;      // patch geometry of the block when it was set aside
+};
+
+// diag_target >= 0: the expressions are those of an Add layer's neurons, i.e. the rows of `own` (the layer below the Add
+// layer) plus coefficient 1 on the same neuron of layer diag_target.
 void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym,
-              double useful = 1.0)       // fraction of the rows whose bounds are used (flop accounting only)
+              double useful = 1.0,       // fraction of the rows whose bounds are used (flop accounting only)
+              int diag_target = -1)
 {
     dpc_network* net = P.net;
     dpc_result* res = P.res;
@@ -312,8 +332,18 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     bool concretised = false;      // the last contraction already reduced the rows against the box
     const bool may_fuse = P.opt->fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
 
+    std::vector<Waiting> waiting;
+    std::vector<int> free_slots;
+    for (int k = (int)net->skipbuf.size() - 1; k >= 0; --k) free_slots.push_back(k);
+    if (diag_target >= 0) waiting.push_back(Waiting{diag_target, 2, nullptr, 0, -1, f.patch, 1, 1, 1, 0});
+    auto blocked = [&](int idx) {
+        for (const Waiting& w : waiting)
+            if (w.target == idx) return true;
+        return false;
+    };
+
     // Fully-connected layers all the way down: the whole traversal in one kernel, rows resident in LDS.
-    if (may_fuse && own && own->kind == AFFINE && !f.patch && nsides == 2 && at >= 1 && net->layers[at - 1]->kind == RELU &&
+    if (waiting.empty() && may_fuse && own && own->kind == AFFINE && !f.patch && nsides == 2 && at >= 1 && net->layers[at - 1]->kind == RELU &&
         net->pk[at] && net->pk[at]->p) {
         ChainStepDesc steps[16];
         int ns = 0;
@@ -358,9 +388,53 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
         shared = nullptr;
     };
 
+    // blocks that waited for layer idx are added to the rows (which must be per-input rows by then)
+    auto merge_at = [&](int idx) {
+        for (size_t k = 0; k < waiting.size();) {
+            if (waiting[k].target != idx) { ++k; continue; }
+            const Waiting w = waiting[k];
+            if (shared) relax(nullptr, nullptr, nullptr, nullptr);
+            P.prof->begin(P_RELAX);
+            if (f.patch) {
+                DPC_REQUIRE(w.patch && w.S == f.pg.S && f.pg.P >= w.P, DPC_EUNSUPPORTED,
+                            "a skip connection across layers that change the stride is not supported");
+                launch_merge_block(cur, f.ld, M, R, f.pg.rows_C, f.pg.ph, f.pg.pw, f.pg.C, w.kind, w.src, w.ld, w.ph, w.pw,
+                                   f.pg.P - w.P, P.s);
+            } else {
+                DPC_REQUIRE(!w.patch, DPC_EUNSUPPORTED, "patch-form block waiting for dense rows");
+                launch_merge_block(cur, f.ld, M, R, R, 1, 1, net->size_of(idx), w.kind, w.src, w.ld, 1, 1, 0, P.s);
+            }
+            P.prof->end();
+            res->prof.relax_launches++;
+            if (w.slot >= 0) free_slots.push_back(w.slot);
+            waiting.erase(waiting.begin() + k);
+        }
+    };
+
     while (at > 0 && (maxd < 0 || depth < maxd)) {
+        merge_at(at);
         const Layer& L = *net->layers[at - 1];
-        if (L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.opt->fuse && maxd < 0 && !keep_sym && net->pk2.p &&
+        if (L.kind == ADD) {
+            // neurons of this layer = layer below + layer L.skip: the rows go on through the layer below, a copy waits
+            Waiting w{L.skip, 0, nullptr, 0, -1, f.patch, f.pg.ph, f.pg.pw, f.pg.S, f.pg.P};
+            if (shared) {
+                w.kind = 1; w.src = shared; w.ld = ld_shared;
+            } else {
+                DPC_REQUIRE(!free_slots.empty(), DPC_EUNSUPPORTED, "skip connections nested deeper than the workspace allows");
+                w.slot = free_slots.back();
+                free_slots.pop_back();
+                float* dst = net->skipbuf[w.slot]->p;
+                DPC_HIP(hipMemcpyAsync(dst, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
+                w.src = dst; w.ld = f.ld;
+            }
+            waiting.push_back(w);
+            bias_folded = false;
+            fused_relu = false;
+            --at;
+            ++depth;
+            continue;
+        }
+        if (waiting.empty() && L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.opt->fuse && maxd < 0 && !keep_sym && net->pk2.p &&
             net->layers[0]->kind == CONV && (shared != nullptr || bias_folded || depth > 0)) {
             // patch rows over the first ReLU layer: ReLU step, first layer and concretisation in one kernel
             const Layer& first = *net->layers[0];
@@ -377,7 +451,8 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
         }
         if (L.kind == RELU) {
             const Layer& below = *net->layers[at - 2];
-            const bool fold = (maxd < 0 || depth + 2 <= maxd);
+            // the bias of the layer below is folded in the same pass unless a block still has to join the rows there
+            const bool fold = (maxd < 0 || depth + 2 <= maxd) && !blocked(at - 1);
             relax(res->lam[at], res->mu[at], res->nu[at], fold ? &below : nullptr);
             bias_folded = fold;
         } else {
@@ -390,8 +465,8 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 // The step that follows (ReLU step of the layer below, or the concretisation at the input)
                 // runs in the contraction's epilogue when its packed parameters exist.
                 const int below = at - 1;
-                const bool to_input = below == 0 && !keep_sym;
-                const bool to_relu = below > 0 && net->layers[below - 1]->kind == RELU;
+                const bool to_input = below == 0 && !keep_sym && !blocked(0);
+                const bool to_relu = below > 0 && net->layers[below - 1]->kind == RELU && !blocked(below) && !blocked(below - 1);
                 int used = -1;
                 fused_relu = false;
                 if (may_fuse && (to_input || to_relu) && net->pk[below] && net->pk[below]->p) {
@@ -431,6 +506,8 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
         ++depth;
     }
 
+    merge_at(at);
+    DPC_REQUIRE(waiting.empty(), DPC_EUNSUPPORTED, "depth-limited traversals that end inside a residual block are not supported");
     const int n_at = net->size_of(at);
     if (keep_sym) {
         DPC_REQUIRE(at == 0 && !f.patch, DPC_EUNSUPPORTED, "symbolic bounds are kept for dense rows at the input only");
@@ -595,6 +672,35 @@ dpc_status dpc_network_add_relu(dpc_network* net)
     });
 }
 
+dpc_status dpc_network_add_skip(dpc_network* net, int32_t from_layer)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net, DPC_EINVAL, "dpc_network_add_skip: NULL network");
+        DPC_REQUIRE(!net->finalized, DPC_ESTATE, "network already finalized");
+        const int count = (int)net->layers.size();
+        DPC_REQUIRE(count >= 1, DPC_EUNSUPPORTED, "dpc_network_add_skip: an Add layer cannot be the first layer");
+        const Layer& below = *net->layers.back();
+        DPC_REQUIRE(below.kind == AFFINE || below.kind == CONV, DPC_EUNSUPPORTED,
+                    "dpc_network_add_skip: the layer below an Add layer must be fully-connected or a convolution");
+        DPC_REQUIRE(from_layer >= 0 && from_layer <= count - 1, DPC_EINVAL,
+                    "dpc_network_add_skip: from_layer %d out of range [0, %d]", from_layer, count - 1);
+        int sc = 0, sh = 0, sw = 0;
+        const bool sp = net->spatial(from_layer, &sc, &sh, &sw);
+        DPC_REQUIRE(net->size_of(from_layer) == below.n_out, DPC_EINVAL,
+                    "dpc_network_add_skip: layer %d has %d neurons, the layer below the Add layer %d", from_layer,
+                    net->size_of(from_layer), below.n_out);
+        DPC_REQUIRE(sp == below.spatial_out && (!sp || (sc == below.C && sh == below.H && sw == below.W)), DPC_EINVAL,
+                    "dpc_network_add_skip: the two operands differ in shape");
+        auto L = std::make_unique<Layer>();
+        L->kind = ADD;
+        L->skip = from_layer;
+        L->n_in = L->n_out = below.n_out;
+        L->spatial_out = below.spatial_out;
+        L->C = below.C; L->H = below.H; L->W = below.W;
+        net->layers.push_back(std::move(L));
+    });
+}
+
 dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
 {
     return guarded([&] {
@@ -609,6 +715,16 @@ dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
         for (size_t i = 0; i < net->layers.size(); ++i) {
             Layer& L = *net->layers[i];
             if (L.kind == RELU) continue;
+            if (L.kind == ADD) {
+                // no weights; zero biases so that the ReLU step above it can fold "the bias of the layer below" as usual
+                L.dBias.reserve(L.n_out);
+                DPC_HIP(hipMemset(L.dBias.p, 0, (size_t)L.n_out * sizeof(float)));
+                if (L.spatial_out) {
+                    DPC_HIP(hipMalloc(reinterpret_cast<void**>(&L.cw.bias_c), (size_t)L.C * sizeof(float)));
+                    DPC_HIP(hipMemset(L.cw.bias_c, 0, (size_t)L.C * sizeof(float)));
+                }
+                continue;
+            }
             int pc, ph, pw;
             const bool prev_spatial = net->spatial((int)i, &pc, &ph, &pw);
             if (L.kind == AFFINE) {
@@ -634,6 +750,14 @@ dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
                 L.dBias.reserve(L.n_out);
                 DPC_HIP(hipMemcpy(L.dBias.p, bias.data(), bias.size() * sizeof(float), hipMemcpyHostToDevice));
             }
+        }
+        // how many skip connections span one layer at most = how many blocks of rows can wait at once
+        net->skip_depth = 0;
+        for (size_t p = 0; p <= net->layers.size(); ++p) {
+            int open = 0;
+            for (size_t j = 0; j < net->layers.size(); ++j)
+                if (net->layers[j]->kind == ADD && (size_t)net->layers[j]->skip <= p && p <= j) ++open;
+            net->skip_depth = std::max(net->skip_depth, open);
         }
         net->finalized = true;
     });
@@ -704,6 +828,9 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 DPC_REQUIRE(net->layers[i]->kind == (i % 2 ? RELU : AFFINE), DPC_EUNSUPPORTED,
                             "dpc_certify: ReuseCert covers fully-connected networks with affine and ReLU layers alternating");
         }
+        if (net->skip_depth > 0)
+            DPC_REQUIRE(!reuse_cert && opt.max_backsub_depth == -1 && opt.final_backsub_depth == -1, DPC_EUNSUPPORTED,
+                        "dpc_certify: networks with Add layers take full DeepPoly traversals only");
         if (label) DPC_REQUIRE(last.kind == AFFINE && last.n_out >= 2, DPC_EUNSUPPORTED,
                                "dpc_certify: a label needs a fully-connected last layer with >= 2 outputs");
         DeviceGuard guard(net->device);
@@ -774,6 +901,11 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         }
         bool moved = net->buf[0].reserve(need);
         moved |= net->buf[1].reserve(need);
+        if ((int)net->skipbuf.size() < net->skip_depth) net->skipbuf.resize(net->skip_depth);
+        for (auto& sb : net->skipbuf) {
+            if (!sb) sb.reset(new DevBuf<float>());
+            moved |= sb->reserve(need);
+        }
         const bool fuse = opt.fuse && (opt.max_backsub_depth < 0 || opt.final_backsub_depth < 0);
         if (fuse) {
             size_t fuse_rows = 0;          // rows of the passes that can use fused epilogues (dense rows of FC layers)
@@ -944,6 +1076,12 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 }
                 if (merge_final && i == nl) continue;       // bounded together with the margins below
                 P.maxd = i == nl ? opt.final_backsub_depth : opt.max_backsub_depth;
+                if (L.kind == ADD) {
+                    // expressions of its neurons: the rows of the layer below + a unit block on the skip operand
+                    Layer& below = *net->layers[i - 2];
+                    run_pass(P, i - 2, 2, L.n_out, &below, res->l[i], res->u[i], opt.keep_symbolic && i == nl, 1.0, L.skip);
+                    continue;
+                }
                 run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
             }
             P.maxd = opt.final_backsub_depth;

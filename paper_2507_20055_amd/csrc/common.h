@@ -127,6 +127,11 @@ void launch_reuse_const(const float* C, int ldc, int col, int64_t rows, double* 
 // (lambda, mu, nu) followed by the bias fold of the layer below (bias may be NULL); columns n..ld-1 zero.
 void launch_pack_relax(const float* lambda, const float* mu, const float* nu, const float* bias, int batch, int n,
                        int ld, float* pk, hipStream_t s);
+// dst rows += a block of the same expression that waited on a skip connection (residual networks); rows are
+// [M][ph2*pw2*C] patches (dense rows: ph2 = pw2 = 1, C = n), the block is ph1 x pw1 x C at offset (d, d).
+// kind 0: src[m][..]; kind 1: src[r % rows_C][..] (r = m % R); kind 2: += 1 on channel r % rows_C of position (d, d).
+void launch_merge_block(float* dst, int ld_dst, int64_t M, int R, int rows_C, int ph2, int pw2, int C, int kind,
+                        const float* src, int ld_src, int ph1, int pw1, int d, hipStream_t s);
 // pk2[b][c] = (mu, nu with lambda in its sign bit: negative = 1), float2; columns n..ld-1 zero.
 void launch_pack_relax2(const float* lambda, const float* mu, const float* nu, int batch, int n, int ld, float* pk2,
                         hipStream_t s);

@@ -478,6 +478,37 @@ __global__ __launch_bounds__(kThreads) void pack_relax_kernel(
     pk[i] = o;
 }
 
+// Sum of two blocks of one expression that have reached the same layer (residual networks: the rows that went
+// through a block's branch and the rows that waited on its skip connection).  The waiting block covers a
+// sub-window of the rows' patch (or all of a dense row: one position with n "channels"):
+//   kind 0: a block of its own per row, src[m][ph1*pw1*C];  kind 1: one block per output channel of the bounded
+//   layer, shared by all inputs and positions, src[r % rows_C][...];  kind 2: coefficient 1 on the row's own neuron.
+struct MergeArgs {
+    float* dst; int ld_dst;
+    const float* src; int ld_src;
+    int R, rows_C;
+    int ph1, pw1, pw2, C, d;      // waiting block ph1 x pw1 x C sits at offset (d, d) inside rows of width pw2
+    int kind;
+};
+
+__global__ __launch_bounds__(kThreads) void merge_block_kernel(MergeArgs a)
+{
+    const size_t m = blockIdx.x;
+    const int r = (int)(m % (size_t)a.R);
+    float* dst = a.dst + m * a.ld_dst;
+    if (a.kind == 2) {
+        if (threadIdx.x == 0) dst[(size_t)(a.d * a.pw2 + a.d) * a.C + r % a.rows_C] += 1.0f;
+        return;
+    }
+    const float* src = a.src + (a.kind == 1 ? (size_t)(r % a.rows_C) : m) * a.ld_src;
+    const int n1 = a.ph1 * a.pw1 * a.C;
+    for (int e = threadIdx.x; e < n1; e += kThreads) {
+        const int pos = e / a.C, c = e - pos * a.C;
+        const int py = pos / a.pw1, px = pos - py * a.pw1;
+        dst[(size_t)((py + a.d) * a.pw2 + px + a.d) * a.C + c] += src[e];
+    }
+}
+
 // Compact parameters of a ReLU layer for kernels that apply the sign split themselves: (mu, nu) per (input, neuron)
 // with lambda (0 or 1) carried in the sign bit of nu (nu itself is never negative); columns n..ld-1 zero.
 __global__ __launch_bounds__(kThreads) void pack_relax2_kernel(
@@ -729,6 +760,22 @@ void launch_pack_relax(const float* lambda, const float* mu, const float* nu, co
     if (tot == 0) return;
     hipLaunchKernelGGL(pack_relax_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, lambda, mu, nu,
                        bias, batch, n, ld, reinterpret_cast<float4*>(pk));
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_merge_block(float* dst, int ld_dst, int64_t M, int R, int rows_C, int ph2, int pw2, int C, int kind,
+                        const float* src, int ld_src, int ph1, int pw1, int d, hipStream_t s)
+{
+    DPC_REQUIRE(dst && M >= 0 && R >= 1 && rows_C >= 1 && C >= 1 && kind >= 0 && kind <= 2 && d >= 0, DPC_EINVAL,
+                "merge_block: bad arguments");
+    DPC_REQUIRE(ph1 >= 1 && pw1 >= 1 && ph1 + d <= ph2 && pw1 + d <= pw2 && (int64_t)ph2 * pw2 * C <= ld_dst, DPC_EINVAL,
+                "merge_block: the waiting block does not fit the rows");
+    DPC_REQUIRE(kind == 2 ? (ph1 == 1 && pw1 == 1 && rows_C <= C) : (src && (int64_t)ph1 * pw1 * C <= ld_src), DPC_EINVAL,
+                "merge_block: bad source block");
+    DPC_REQUIRE(M <= 0x7fffffff, DPC_EINVAL, "merge_block: too many rows");
+    if (M == 0) return;
+    MergeArgs a{dst, ld_dst, src, ld_src, R, rows_C, ph1, pw1, pw2, C, d, kind};
+    hipLaunchKernelGGL(merge_block_kernel, dim3((unsigned)M), dim3(kThreads), 0, s, a);
     DPC_HIP(hipGetLastError());
 }
 

@@ -181,6 +181,47 @@ def make_res_fc(rng, n_in: int, width: int, blocks: int, n_out: int, std_scale: 
     return net
 
 
+def make_res_conv(rng, in_shape, width: int, blocks: int, k: int, tail, fcs) -> Network:
+    """Convolutional residual network: conv(Ci -> width, k x k, stride 1, same padding), ReLU, `blocks` times
+    [conv, ReLU, conv, add(block input), ReLU] at constant shape, then the convolutions in `tail`
+    ((Co, k, stride, pad), each followed by ReLU) and the fully-connected layers `fcs`.  He-normal, k odd."""
+    assert k % 2 == 1
+    Ci, H, W = in_shape
+    net = Network(n_in=Ci * H * W)
+    shape = in_shape
+
+    def conv(Co, kk, s, p):
+        nonlocal shape
+        fan_in = shape[0] * kk * kk
+        Wt = rng.normal(0.0, np.sqrt(2.0 / fan_in), size=(Co, shape[0], kk, kk))
+        b = rng.normal(0.0, 0.01, size=(Co,))
+        L = Layer("conv", _f32(Wt), _f32(b), stride=s, pad=p, in_shape=shape)
+        net.layers.append(L)
+        shape = L.out_shape
+
+    conv(width, k, 1, k // 2)
+    net.layers.append(Layer("relu"))
+    for _ in range(blocks):
+        src = len(net.layers)
+        conv(width, k, 1, k // 2)
+        net.layers.append(Layer("relu"))
+        conv(width, k, 1, k // 2)
+        net.layers.append(Layer("add", skip=src))
+        net.layers.append(Layer("relu"))
+    for (Co, kk, s, p) in tail:
+        conv(Co, kk, s, p)
+        net.layers.append(Layer("relu"))
+    n = shape[0] * shape[1] * shape[2]
+    for i, f in enumerate(fcs):
+        Wt = rng.normal(0.0, np.sqrt(2.0 / n), size=(f, n))
+        b = rng.normal(0.0, 0.01, size=(f,))
+        net.layers.append(Layer("affine", _f32(Wt), _f32(b)))
+        if i != len(fcs) - 1:
+            net.layers.append(Layer("relu"))
+        n = f
+    return net
+
+
 def make_inputs(net: Network, seed: int, batch: int, eps: float):
     rng = np.random.default_rng(seed + 1000)
     x = _f32(rng.uniform(0.0, 1.0, size=(batch, net.n_in)))
@@ -250,6 +291,15 @@ def random_small_conv(seed: int, in_shape, convs, fcs, bias_std: float = 0.1) ->
 def random_small_res(seed: int, n_in: int, width: int, blocks: int, n_out: int, bias_std: float = 0.3) -> Network:
     """Small residual FC net with O(1) weights for unit tests."""
     return make_res_fc(np.random.default_rng(seed), n_in, width, blocks, n_out, 1.0, bias_std)
+
+
+def random_small_res_conv(seed: int, in_shape, width: int, blocks: int, k: int, tail, fcs, bias_std: float = 0.1) -> Network:
+    rng = np.random.default_rng(seed)
+    net = make_res_conv(rng, in_shape, width, blocks, k, tail, fcs)
+    for L in net.layers:
+        if L.b is not None:
+            L.b = _f32(rng.normal(0.0, bias_std, size=L.b.shape))
+    return net
 
 
 def random_box(seed: int, n: int, batch: int, eps: float, lo_clip=None, hi_clip=None):

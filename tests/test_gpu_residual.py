@@ -1,0 +1,103 @@
+"""Parity of the HIP path on residual networks (Add layers: expressions with blocks on two layers at once)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle                                            # noqa: E402
+from paper_2507_20055_amd import workloads as wl         # noqa: E402
+from paper_2507_20055_amd.workloads import Layer, Network  # noqa: E402
+from tests.parity_util import compare_with_oracle        # noqa: E402
+
+
+def _binding():
+    from paper_2507_20055_amd import binding
+    return binding
+
+
+def _check(net, lo, hi, label, fuses=(1, 0)):
+    b = _binding()
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label)
+    for fuse in fuses:
+        g = gnet.certify(lo, hi, label, fuse=fuse)
+        compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
+@pytest.mark.parametrize("seed,n_in,width,blocks,n_out,B", [(1, 6, 8, 1, 3, 2), (2, 20, 40, 2, 5, 3), (3, 33, 70, 3, 10, 4),
+                                                           (4, 64, 130, 2, 10, 5)])
+def test_small_residual_fc(seed, n_in, width, blocks, n_out, B):
+    net = wl.random_small_res(seed, n_in, width, blocks, n_out)
+    x, lo, hi = wl.random_box(seed + 10, n_in, B, 0.05)
+    label = np.arange(B, dtype=np.int32) % n_out
+    _check(net, lo, hi, label)
+
+
+def _mk(rng, n_to, n_from):
+    return Layer("affine", (rng.normal(size=(n_to, n_from)) / np.sqrt(n_from)).astype(np.float32),
+                 (rng.normal(size=n_to) * 0.3).astype(np.float32))
+
+
+def _variants():
+    rng = np.random.default_rng(7)
+    n = 36
+    yield "skip from the input", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=0), Layer("relu"),
+                                             _mk(rng, 4, n)])
+    yield "skip from an affine layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("relu"), _mk(rng, n, n),
+                                                   Layer("add", skip=3), Layer("relu"), _mk(rng, 4, n)])
+    yield "nested skips", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("relu"), _mk(rng, n, n),
+                                      Layer("add", skip=4), _mk(rng, n, n), Layer("add", skip=2), Layer("relu"), _mk(rng, 5, n)])
+    yield "two skips onto one layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=2),
+                                                  _mk(rng, n, n), Layer("add", skip=2), Layer("relu"), _mk(rng, 3, n)])
+    yield "affine directly above the Add layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=2),
+                                                             _mk(rng, 6, n)])
+    yield "Add as the last layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=1)])
+
+
+@pytest.mark.parametrize("name,net", list(_variants()))
+def test_skip_topologies(name, net):
+    x, lo, hi = wl.random_box(8, net.n_in, 3, 0.04)
+    n_out = net.sizes()[-1]
+    label = (np.arange(3, dtype=np.int32) % n_out) if net.layers[-1].kind == "affine" else None
+    _check(net, lo, hi, label)
+
+
+@pytest.mark.parametrize("shape,width,blocks,k,tail,fcs", [((2, 6, 6), 4, 1, 3, [], [5, 3]),
+                                                          ((3, 8, 8), 8, 2, 3, [(8, 4, 2, 1)], [10, 4]),
+                                                          ((1, 9, 7), 16, 1, 3, [(8, 3, 2, 0)], [6, 3]),
+                                                          ((3, 10, 10), 8, 1, 5, [(16, 4, 2, 1)], [7, 4])])
+def test_small_residual_conv(shape, width, blocks, k, tail, fcs):
+    net = wl.random_small_res_conv(9, shape, width, blocks, k, tail, fcs)
+    B = 3
+    x, lo, hi = wl.random_box(10, net.n_in, B, 0.03)
+    label = np.arange(B, dtype=np.int32) % fcs[-1]
+    _check(net, lo, hi, label)
+
+
+def test_depth_limits_and_reusecert_are_refused_on_residual_networks():
+    b = _binding()
+    net = wl.random_small_res(5, 6, 8, 1, 3)
+    x, lo, hi = wl.random_box(6, 6, 2, 0.05)
+    gnet = b.Network(net)
+    for kw in (dict(max_backsub_depth=2), dict(certifier="reusecert"), dict(final_backsub_depth=0)):
+        with pytest.raises(b.DpcError) as e:
+            gnet.certify(lo, hi, None, **kw)
+        assert e.value.code == 2
+    gnet.close()
+
+
+def test_graph_replay_on_a_residual_network():
+    import torch
+    b = _binding()
+    net = wl.random_small_res(12, 20, 40, 2, 5)
+    gnet = b.Network(net)
+    stream = torch.cuda.Stream()
+    prev = None
+    for rep in range(4):
+        x, lo, hi = wl.random_box(20 + rep, 20, 3, 0.05)
+        label = np.arange(3, dtype=np.int32) % 5
+        o = oracle.run(net, lo, hi, label=label)
+        prev = gnet.certify(lo, hi, label, stream=stream.cuda_stream, reuse=prev)
+        compare_with_oracle(net, lo, hi, prev, o, label)
+    gnet.close()
