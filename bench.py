@@ -28,6 +28,8 @@ DESCR = {
     "cfg3": "cfg3: conv16 4x4s2 - conv32 4x4s2 - FC100 - FC10 on 3x32x32, B=32, eps=2/255",
     "cfg4": "cfg4: conv32 3x3 - conv32 4x4s2 - conv64 3x3 - conv64 4x4s2 - FC512 - FC512 - FC10 on 3x32x32, B=16, eps=1/255",
     "cfg5": "cfg5: FC 1024-9x1024-10, B=64, eps=0.005",
+    "res_fc": "res_fc: residual FC 784-512-3x[512,512,+skip]-10, B=32, eps=0.001",
+    "res_conv": "res_conv: residual conv16 3x3 - 2x[conv16 3x3, conv16 3x3, +skip] - conv32 4x4s2 - FC100 - FC10 on 1x28x28, B=16, eps=0.003",
 }
 
 
@@ -212,7 +214,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-        default_sample = {"cfg1": 1, "cfg2": 32, "cfg3": 32, "cfg4": 2, "cfg5": 16}[args.workload]
+        default_sample = {"cfg1": 1, "cfg2": 32, "cfg3": 32, "cfg4": 2, "cfg5": 16, "res_fc": 16, "res_conv": 2}[args.workload]
         ns = min(B, args.cpu_sample or default_sample)
         tc = time.perf_counter()
         for w in loads:

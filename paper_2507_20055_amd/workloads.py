@@ -241,6 +241,9 @@ def _cfg4(rng): return make_conv(rng, (3, 32, 32),
                                  [(32, 3, 1, 1), (32, 4, 2, 1), (64, 3, 1, 1), (64, 4, 2, 1)],
                                  [512, 512, 10])
 def _cfg5(rng): return make_fc(rng, [1024] + [1024] * 9 + [10])
+# residual stand-ins (the paper's "Skip" MNIST network is named in Table 5 without its layers)
+def _res_fc(rng): return make_res_fc(rng, 784, 512, 3, 10)
+def _res_conv(rng): return make_res_conv(rng, (1, 28, 28), 16, 2, 3, [(32, 4, 2, 1)], [100, 10])
 
 
 CONFIGS = {
@@ -249,6 +252,8 @@ CONFIGS = {
     "cfg3": dict(build=_cfg3, seed=1, batch=32, eps=[2.0 / 255.0]),
     "cfg4": dict(build=_cfg4, seed=2, batch=16, eps=[1.0 / 255.0]),
     "cfg5": dict(build=_cfg5, seed=3, batch=64, eps=[0.005]),
+    "res_fc": dict(build=_res_fc, seed=4, batch=32, eps=[0.001]),
+    "res_conv": dict(build=_res_conv, seed=5, batch=16, eps=[0.003]),
 }
 
 

@@ -101,3 +101,31 @@ def test_graph_replay_on_a_residual_network():
         prev = gnet.certify(lo, hi, label, stream=stream.cuda_stream, reuse=prev)
         compare_with_oracle(net, lo, hi, prev, o, label)
     gnet.close()
+
+
+@pytest.mark.parametrize("name,sample", [("res_fc", 4), ("res_conv", 1)])
+def test_residual_workloads_full_batch_gpu_sampled_oracle(name, sample):
+    """The bench configuration at its full batch on the GPU; the oracle bounds a prefix of the inputs (the library
+    treats inputs independently, so the prefix's results must not depend on the batch)."""
+    b = _binding()
+    w = wl.make_workload(name)
+    gnet = b.Network(w.net)
+    g = gnet.certify(w.lo, w.hi, w.label)
+    o = oracle.run(w.net, w.lo[:sample], w.hi[:sample], label=w.label[:sample])
+
+    class Prefix:
+        def concrete(self, k):
+            l, u = g.concrete(k)
+            return l[:sample], u[:sample]
+
+        def relaxation(self, k):
+            return tuple(a[:sample] for a in g.relaxation(k))
+
+        def verdict(self):
+            v, m = g.verdict()
+            return v[:sample], m[:sample]
+
+    compare_with_oracle(w.net, w.lo[:sample], w.hi[:sample], Prefix(), o, w.label[:sample], max_flipped_inputs=1)
+    gl, gu = g.concrete(len(w.net.layers))
+    assert (gl <= gu).all()
+    gnet.close()
