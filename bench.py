@@ -143,7 +143,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": {"0": "f32", "2": "bf16x3 (operands split into two bf16 terms, fp32 accumulation)",
+                  "3": "bf16x6 (operands split into three bf16 terms, fp32 accumulation)"}[dict(kv.partition("=")[::2] for kv in args.tune).get("contract_split", "0")],
         "data": "synthetic",
         "config": {"workload": DESCR[args.workload], "inputs_per_step": inputs_per_step,
                    "verified": verified, "min_abs_margin": min_abs_margin, "fuse": args.fuse,

@@ -238,7 +238,13 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
  * workgroups per compute unit); "conv_algo" = 2 sends few-input-channel layers to the plain-ALU kernel;
  * "merge_final" = 0 bounds the output layer and the margins in two traversals instead
  * of one; "contract_remap", "rows_per_wave", "rows_stream" select launch shapes of the contraction and
- * row kernels.  Results do not depend on any of them beyond rounding order. */
+ * row kernels.  Results do not depend on any of them beyond rounding order.
+ * Split-precision experiment (the exception to that sentence): "contract_split" = 2 or 3 (default 0) runs
+ * the contractions through fully-connected layers on the bf16 matrix units with both operands written as
+ * sums of 2 or 3 bf16 terms and the 3 or 6 largest partial products accumulated in fp32 ("bf16x3": about
+ * 16 significand bits per product, "bf16x6": about 24); layers whose size is not a multiple of 4 and all
+ * convolutions stay on the fp32 kernels; the resident traversal kernel is not used.  "contract_split_wide"
+ * (-1 by shape, 0, 1) selects its 128 x 256 tile. */
 dpc_status dpc_tuning_set(const char* key, int32_t value);
 
 /* Text of the last error raised on the calling thread ("" if none). */

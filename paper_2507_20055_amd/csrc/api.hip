@@ -104,6 +104,9 @@ struct Layer {
     // ReuseCert: [W+ | W- | b] and [W- | W+ | b], [n_out, ld_split] each, built on first use
     DevBuf<float> dSplit[2];
     int ld_split = 0;
+    // split-precision experiment: bf16 terms of the transposed weights, built when the tuning key is set
+    DevBuf<uint16_t> dWt;
+    int wt_terms = 0;
 };
 
 }  // namespace
@@ -330,6 +333,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     bool fused_relu = false;
     int slots = 0;                 // row-constant partial-sum slots written by fused epilogues so far
     bool concretised = false;      // the last contraction already reduced the rows against the box
+    const int split = contract_split_terms();       // > 0: contractions on the bf16 MFMA units, every step its own kernel
     const bool may_fuse = P.opt->fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
 
     std::vector<Waiting> waiting;
@@ -343,7 +347,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     };
 
     // Fully-connected layers all the way down: the whole traversal in one kernel, rows resident in LDS.
-    if (waiting.empty() && may_fuse && own && own->kind == AFFINE && !f.patch && nsides == 2 && at >= 1 && net->layers[at - 1]->kind == RELU &&
+    if (split == 0 && waiting.empty() && may_fuse && own && own->kind == AFFINE && !f.patch && nsides == 2 && at >= 1 && net->layers[at - 1]->kind == RELU &&
         net->pk[at] && net->pk[at]->p) {
         ChainStepDesc steps[16];
         int ns = 0;
@@ -473,12 +477,16 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                     ContractEpilogue e{net->pk[below]->p, ld_prev, R, nsides * B,
                                        net->part.p + (size_t)slots * net->part_stride, net->part_stride,
                                        dpc_network::kMaxSlots - slots, to_input ? 0 : 1};
-                    used = launch_contract_fused(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, e, P.s);
+                    used = (split > 0 && L.wt_terms == split && L.dWt.p)
+                               ? launch_contract_split_fused(cur, M, n_at, f.ld, L.dWt.p, split, n_prev, nxt, ld_prev, e, P.s)
+                               : launch_contract_fused(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, e, P.s);
                 }
                 if (used >= 0) {
                     slots += used;
                     if (to_input) concretised = true;
                     else { --at; ++depth; fused_relu = true; }       // the ReLU layer below has been replaced too
+                } else if (split > 0 && L.wt_terms == split && L.dWt.p) {
+                    launch_contract_split(cur, M, n_at, f.ld, L.dWt.p, split, n_prev, nxt, ld_prev, P.s);
                 } else {
                     launch_contract(cur, M, n_at, f.ld, L.dW.p, n_prev, L.ldw, nxt, ld_prev, P.s);
                 }
@@ -939,6 +947,17 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             }
             if (nl >= 3) moved |= net->rc_rows.reserve(2 * (size_t)B * (2 * (size_t)nK - 1) * net->layers[nl - 1]->ld_split);
         }
+        if (const int terms = contract_split_terms()) {
+            for (int i = 1; i <= nl; ++i) {
+                Layer& L = *net->layers[i - 1];
+                if (L.kind != AFFINE || L.n_out % 4 != 0 || L.wt_terms == terms) continue;
+                int ldk, npad;
+                L.dWt.release();
+                L.dWt.reserve(split_weights_elems(L.n_out, L.n_in, terms, &ldk, &npad));
+                launch_split_weights(L.dW.p, L.n_out, L.n_in, L.ldw, terms, L.dWt.p, s);
+                L.wt_terms = terms;
+            }
+        }
         moved |= net->cst.reserve(need_rows);
         moved |= net->stage.reserve(stage_need);
         if (moved) ++net->ws_epoch;
@@ -1350,6 +1369,12 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
         else if (strcmp(key, "chain") == 0) set_chain_mode(value);
         else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);
+        else if (strcmp(key, "contract_split_wide") == 0) {
+            set_contract_split_wide(value);
+        } else if (strcmp(key, "contract_split") == 0) {
+            DPC_REQUIRE(value == 0 || value == 2 || value == 3, DPC_EINVAL, "dpc_tuning_set: contract_split takes 0, 2 or 3");
+            set_contract_split(value);
+        }
         else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
         else if (strcmp(key, "rows_stream") == 0) set_rows_stream(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);

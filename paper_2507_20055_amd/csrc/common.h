@@ -127,6 +127,17 @@ void launch_reuse_const(const float* C, int ldc, int col, int64_t rows, double* 
 // (lambda, mu, nu) followed by the bias fold of the layer below (bias may be NULL); columns n..ld-1 zero.
 void launch_pack_relax(const float* lambda, const float* mu, const float* nu, const float* bias, int batch, int n,
                        int ld, float* pk, hipStream_t s);
+// Split-precision contraction (experiment; see contract_split.hip).  terms = 2 ("bf16x3") or 3 ("bf16x6").
+// Wt: [terms][round_up(N,128)][round_up(K,32)] bf16, built by launch_split_weights from W [K][ldw] fp32.
+size_t split_weights_elems(int K, int N, int terms, int* ldk, int* npad);
+void launch_split_weights(const float* W, int K, int N, int ldw, int terms, void* Wt, hipStream_t s);
+void launch_contract_split(const float* A, int64_t M, int K, int lda, const void* Wt, int terms, int N, float* C, int ldc,
+                           hipStream_t s);
+int launch_contract_split_fused(const float* A, int64_t M, int K, int lda, const void* Wt, int terms, int N, float* C, int ldc,
+                                const ContractEpilogue& e, hipStream_t s);
+void set_contract_split(int v);
+void set_contract_split_wide(int v);
+int contract_split_terms();
 // dst rows += a block of the same expression that waited on a skip connection (residual networks); rows are
 // [M][ph2*pw2*C] patches (dense rows: ph2 = pw2 = 1, C = n), the block is ph1 x pw1 x C at offset (d, d).
 // kind 0: src[m][..]; kind 1: src[r % rows_C][..] (r = m % R); kind 2: += 1 on channel r % rows_C of position (d, d).

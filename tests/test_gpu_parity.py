@@ -475,3 +475,44 @@ class _Sub:
     def verdict(self):
         v, m = self.res.verdict()
         return v[self.idx], m[self.idx]
+
+
+@pytest.mark.parametrize("terms", [2, 3])
+@pytest.mark.parametrize("seed,dims,B", [(71, [40, 64, 96, 36, 10], 3), (72, [100, 500, 500, 300, 40], 2), (73, [16, 32, 40, 7], 5),
+                                         (74, [33, 130, 257, 64, 5], 4), (75, [784, 260, 132, 10], 33)])
+def test_split_precision_contraction(terms, seed, dims, B):
+    """Opt-in experiment: contractions on the bf16 MFMA units with operands split into 2 (bf16x3) or 3 (bf16x6) bf16
+    terms, fp32 accumulation.  Same tolerance as the fp32 path; layers whose size is not a multiple of 4 stay on the
+    fp32 kernel.  Both the fused-epilogue and the every-step-its-own-kernel routes."""
+    net = wl.random_small_net(seed, dims)
+    x, lo, hi = wl.random_box(seed + 1, dims[0], B, 0.03)
+    label = np.arange(B, dtype=np.int32) % dims[-1]
+    b = _binding()
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label)
+    b.dpc_tuning_set("contract_split", terms)
+    try:
+        for fuse in (1, 0):
+            g = gnet.certify(lo, hi, label, fuse=fuse)
+            compare_with_oracle(net, lo, hi, g, o, label)
+        for wide in (0, 1):
+            b.dpc_tuning_set("contract_split_wide", wide)
+            compare_with_oracle(net, lo, hi, gnet.certify(lo, hi, label), o, label)
+    finally:
+        b.dpc_tuning_set("contract_split_wide", -1)
+        b.dpc_tuning_set("contract_split", 0)
+    gnet.close()
+
+
+def test_split_precision_on_the_headline_workload_sample():
+    b = _binding()
+    w = wl.make_workload("cfg2", batch=6)
+    o = oracle.run(w.net, w.lo, w.hi, label=w.label)
+    gnet = b.Network(w.net)
+    try:
+        for terms in (2, 3):
+            b.dpc_tuning_set("contract_split", terms)
+            compare_with_oracle(w.net, w.lo, w.hi, gnet.certify(w.lo, w.hi, w.label), o, w.label)
+    finally:
+        b.dpc_tuning_set("contract_split", 0)
+    gnet.close()
