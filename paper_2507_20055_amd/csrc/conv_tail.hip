@@ -94,6 +94,13 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
         const int co0 = r0 % a.rows_C, wo = (r0 / a.rows_C) % a.rows_W, ho = r0 / (a.rows_C * a.rows_W);
         const int oy = ho * a.pS - a.pP, ox = wo * a.pS - a.pP;        // patch origin on the ReLU layer's grid
         const int t0 = (wave + it * NW) * T;
+        // both operands through buffer loads whose resources start at the panel's first row (the bounded layer's cores
+        // for shared rows) and at the input's parameter block: 32-bit lane offsets, no branches, no zero fill
+        const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(SHARED ? a.in + (size_t)co0 * a.ld_in : a.in + m0 * a.ld_in), 0, live ? a.RB * a.ld_in * 4 : 0, 0x00020000);
+        const __amdgpu_buffer_rsrc_t qres = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float2*>(a.pk2 + (size_t)b * a.ldpk), 0, live ? a.ldpk * 8 : 0, 0x00020000);
+        constexpr int kOutside = (int)0x80000000;
 #pragma unroll
         for (int u = 0; u < T; ++u) {
             const int e = (t0 + u) * 32 + l32;
@@ -101,19 +108,14 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
             const int py = (int)(((unsigned long long)pos * magic_iw) >> 32), px = pos - py * a.iw;
             const int gy = oy + py, gx = ox + px;
             const bool ok = live && t0 + u < ntiles && e < E && m0 + ml < a.M && gy >= 0 && gy < a.gh && gx >= 0 && gx < a.gw;
-            const float* p = SHARED ? a.in + (size_t)(co0 + (ok ? ml : 0)) * a.ld_in + (size_t)(ok ? pos : 0) * CO + 4 * kq
-                                    : a.in + (m0 + (ok ? ml : 0)) * a.ld_in + (size_t)(ok ? pos : 0) * CO + 4 * kq;
-            const float2* q = a.pk2 + (size_t)b * a.ldpk + (size_t)(ok ? gy * a.gw + gx : 0) * CO + 4 * kq;
+            // a lane outside the panel, the rows or the grid gets an offset outside the resources and reads zeros
+            const int xo = ok ? (ml * a.ld_in + pos * CO + 4 * kq) * 4 : kOutside;
+            const int qo = ok ? ((gy * a.gw + gx) * CO + 4 * kq) * 8 : kOutside;
 #pragma unroll
             for (int g = 0; g < CO8; ++g) {
-                X[u][g] = vf4{0.f, 0.f, 0.f, 0.f};
-                PK[u][g][0] = make_float4(0.f, 0.f, 0.f, 0.f);
-                PK[u][g][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (ok) {
-                    X[u][g] = *reinterpret_cast<const vf4*>(p + 8 * g);
-                    PK[u][g][0] = *reinterpret_cast<const float4*>(q + 8 * g);
-                    PK[u][g][1] = *reinterpret_cast<const float4*>(q + 8 * g + 2);
-                }
+                X[u][g] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo + 32 * g, 0, 0));
+                PK[u][g][0] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(qres, qo + 64 * g, 0, 0));
+                PK[u][g][1] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(qres, qo + 64 * g + 16, 0, 0));
             }
         }
     };
@@ -270,6 +272,7 @@ bool launch_patch_tail(const PatchTail& d, hipStream_t s)
     for (int rb = 1; rb <= 64 && pg.rows_C % rb == 0; rb *= 2)
         if (bytes(rb) <= 48 * 1024) RB = rb;
     if (RB == 0) return false;
+    if ((int64_t)RB * d.ld_in * 4 >= ((int64_t)1 << 31) || (int64_t)d.ldpk * 8 >= ((int64_t)1 << 31)) return false;     // 32-bit buffer offsets
     const int64_t M = (int64_t)2 * d.batch * d.R;
     TailArgs a{};
     a.in = d.in; a.ld_in = d.ld_in; a.cst = d.cst; a.cst_init_c = d.cst_init_c;
