@@ -15,6 +15,7 @@
 // rows of a panel belong to one (side, input) group and one spatial position of that layer: they share the patch
 // origin, i.e. the same window of ReLU parameters and of the box.
 #include <algorithm>
+#include <type_traits>
 
 #include "conv.h"
 
@@ -85,14 +86,30 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
     const int ipp = (ntiles + T * NW - 1) / (T * NW);                  // steps per wavefront per panel
     const unsigned long long magic_npos = (1ull << 32) / (unsigned)max(npos, 1) + 1;     // e / npos for e * npos < 2^32
     const unsigned long long magic_iw = (1ull << 32) / (unsigned)max(a.iw, 1) + 1;
-    auto fetch = [&](int pi, int it, vf4 (&X)[T][CO8], float4 (&PK)[T][CO8][2]) __attribute__((always_inline)) {
-        const long long mraw = ((long long)blockIdx.x * a.panels + pi) * a.RB;
-        const bool live = pi < a.panels && mraw < a.M;
-        const long long m0 = live ? mraw : 0;
-        const int grp = (int)(m0 / a.R), r0 = (int)(m0 - (long long)grp * a.R);
+    // Position of a panel: consecutive panels are RB rows apart, so the decomposition of the first row is carried from
+    // panel to panel with a few scalar compares instead of being divided out again (RB divides rows_C, rows_C divides R).
+    struct Pos { long long m0; int grp, r0, co0, wo, ho; };
+    auto first_pos = [&](long long m0) __attribute__((always_inline)) {
+        Pos p;
+        p.m0 = m0;
+        p.grp = (int)(m0 / a.R);
+        p.r0 = (int)(m0 - (long long)p.grp * a.R);
+        p.co0 = p.r0 % a.rows_C;
+        p.wo = (p.r0 / a.rows_C) % a.rows_W;
+        p.ho = p.r0 / (a.rows_C * a.rows_W);
+        return p;
+    };
+    auto advance = [&](Pos p) __attribute__((always_inline)) {
+        p.m0 += a.RB; p.r0 += a.RB; p.co0 += a.RB;
+        if (p.co0 >= a.rows_C) { p.co0 = 0; if (++p.wo >= a.rows_W) { p.wo = 0; ++p.ho; } }
+        if (p.r0 >= a.R) { p.r0 = 0; p.co0 = 0; p.wo = 0; p.ho = 0; ++p.grp; }
+        return p;
+    };
+    auto fetch = [&](const Pos& pp, bool live, int it, vf4 (&X)[T][CO8], float4 (&PK)[T][CO8][2]) __attribute__((always_inline)) {
+        const long long m0 = live ? pp.m0 : 0;
+        const int grp = live ? pp.grp : 0, co0 = live ? pp.co0 : 0;
         const int b = grp - (grp >= a.batch ? a.batch : 0);
-        const int co0 = r0 % a.rows_C, wo = (r0 / a.rows_C) % a.rows_W, ho = r0 / (a.rows_C * a.rows_W);
-        const int oy = ho * a.pS - a.pP, ox = wo * a.pS - a.pP;        // patch origin on the ReLU layer's grid
+        const int oy = pp.ho * a.pS - a.pP, ox = pp.wo * a.pS - a.pP;  // patch origin on the ReLU layer's grid
         const int t0 = (wave + it * NW) * T;
         // both operands through buffer loads whose resources start at the panel's first row (the bounded layer's cores
         // for shared rows) and at the input's parameter block: 32-bit lane offsets, no branches, no zero fill
@@ -121,45 +138,54 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
     };
     vf4 X[T][CO8];
     float4 PK[T][CO8][2];
-    fetch(0, 0, X, PK);
+    Pos cur = first_pos((long long)blockIdx.x * a.panels * a.RB);
+    bool cur_live = a.panels > 0 && cur.m0 < a.M;
+    fetch(cur, cur_live, 0, X, PK);
 
     for (int pi = 0; pi < a.panels; ++pi) {
-        const long long m0 = ((long long)blockIdx.x * a.panels + pi) * a.RB;
-        if (m0 >= a.M) break;                                          // uniform over the workgroup; nothing in flight
-        const int grp = (int)(m0 / a.R), r0 = (int)(m0 - (long long)grp * a.R);
-        const int side = grp >= a.batch, b = grp - side * a.batch;
-        const int co0 = r0 % a.rows_C, wo = (r0 / a.rows_C) % a.rows_W, ho = r0 / (a.rows_C * a.rows_W);
-        const int qy = ho * a.qS - a.qP, qx = wo * a.qS - a.qP;        // output patch origin on the image
+        if (!cur_live) break;                                          // uniform over the workgroup; nothing in flight
+        const Pos nxt = advance(cur);
+        const bool nxt_live = pi + 1 < a.panels && nxt.m0 < a.M;
+        const long long m0 = cur.m0;
+        const int r0 = cur.r0, co0 = cur.co0;
+        const int side = cur.grp >= a.batch, b = cur.grp - side * a.batch;
+        const int qy = cur.ho * a.qS - a.qP, qx = cur.wo * a.qS - a.qP;   // output patch origin on the image
 
         // ---- ReLU step on the fetched tiles, product with all taps, panel to LDS ----
         for (int it = 0; it < ipp; ++it) {
             const int t0 = (wave + it * NW) * T;
             vf4 av[T][CO8];
             float ks[T];
+            // ReLU step, per element x with (mu, nu | lambda) and the bias of its channel: the part of x on which this
+            // side takes the upper relaxation is p (x >= 0 on the upper side, x < 0 on the lower side), the rest n:
+            //   y = p * mu + lambda * n,   constant += p * (mu * bias + nu) + lambda * n * bias
+            auto relu_step = [&](auto upper_side) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < T; ++u) {
-                ks[u] = 0.0f;
+                for (int u = 0; u < T; ++u) {
+                    ks[u] = 0.0f;
 #pragma unroll
-                for (int g = 0; g < CO8; ++g) {
-                    const vf4 x = X[u][g];
-                    const float4 p01 = PK[u][g][0], p23 = PK[u][g][1];
-                    const float mu[4] = {p01.x, p01.z, p23.x, p23.z}, nl[4] = {p01.y, p01.w, p23.y, p23.w};
-                    vf4 y;
+                    for (int g = 0; g < CO8; ++g) {
+                        const vf4 x = X[u][g];
+                        const float4 p01 = PK[u][g][0], p23 = PK[u][g][1];
+                        const float mu[4] = {p01.x, p01.z, p23.x, p23.z}, nl[4] = {p01.y, p01.w, p23.y, p23.w};
+                        vf4 y;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const float lam = __float_as_uint(nl[k]) >> 31 ? 1.0f : 0.0f;
-                        const float nu = fabsf(nl[k]);
-                        const bool upper = (x[k] >= 0.0f) == (side == 1);
-                        const float mult = upper ? mu[k] : lam;
-                        const float kk = upper ? fmaf(mu[k], bias[g][k], nu) : lam * bias[g][k];
-                        y[k] = x[k] * mult;
-                        ks[u] = fmaf(x[k], kk, ks[u]);
+                        for (int k = 0; k < 4; ++k) {
+                            const float p = decltype(upper_side)::value ? fmaxf(x[k], 0.0f) : fminf(x[k], 0.0f);
+                            const float n = decltype(upper_side)::value ? fminf(x[k], 0.0f) : fmaxf(x[k], 0.0f);
+                            // lambda (0 or 1) is the sign bit of the second parameter: n where it is set, else 0
+                            const float ln = __uint_as_float(__float_as_uint(n) & (unsigned)((int)__float_as_uint(nl[k]) >> 31));
+                            y[k] = fmaf(p, mu[k], ln);
+                            ks[u] = fmaf(ln, bias[g][k], fmaf(p, fmaf(mu[k], bias[g][k], fabsf(nl[k])), ks[u]));
+                        }
+                        av[u][g] = y;
                     }
-                    av[u][g] = y;
                 }
-            }
-            if (it + 1 < ipp) fetch(pi, it + 1, X, PK);
-            else fetch(pi + 1, 0, X, PK);
+            };
+            if (side) relu_step(std::true_type{});
+            else relu_step(std::false_type{});
+            if (it + 1 < ipp) fetch(cur, true, it + 1, X, PK);
+            else fetch(nxt, nxt_live, 0, X, PK);
             if (t0 >= ntiles) continue;
             floatx16 acc[T][NT];
 #pragma unroll
@@ -245,6 +271,8 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
             }
         }
         __syncthreads();                   // the panel and the sums are overwritten by the next panel
+        cur = nxt;
+        cur_live = nxt_live;
     }
 }
 
