@@ -56,13 +56,15 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const int npos = a.ih * a.iw;
     const int nchunks = a.Co / a.CC;                                   // channel chunks of the reduction
     const int cc4n = a.CC >> 2;
+    const unsigned long long magic_cc4n = (1ull << 32) / (unsigned)cc4n + 1, magic_npos = (1ull << 32) / (unsigned)npos + 1;
 
     // stage channels [c0, c0 + CC) of the input patches of this workgroup's rows
     auto stage_input = [&](int c0) __attribute__((always_inline)) {
         const int total = a.RB * npos * cc4n;
         for (int idx = tid; idx < total; idx += kCtThreads) {
-            const int c4 = idx % cc4n, t = idx / cc4n;
-            const int pos = t % npos, ml = t / npos;
+            // quotients by the run-time extents through multiply-high (exact: idx * divisor < 2^32)
+            const int t = (int)(((unsigned long long)idx * magic_cc4n) >> 32), c4 = idx - t * cc4n;
+            const int ml = (int)(((unsigned long long)t * magic_npos) >> 32), pos = t - ml * npos;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (m0 + ml < a.M)
                 v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + (size_t)pos * a.Co + c0 + c4 * 4);
@@ -153,14 +155,15 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                 // Kernel values through a buffer resource (one lane offset, scalar offsets for the rest), fetched three
                 // (tap, group) steps ahead into rotating register sets.  Plain predicated pointer loads ended up in
                 // separate basic blocks with a full wait behind them, which exposed the L2 latency at every step.
-                auto koff = [&](int it) __attribute__((always_inline)) {
-                    const int ti = it / ngr, g = it - ti * ngr;
-                    const int jy = ti / nkx, jx = ti - jy * nkx;
-                    const int tap = (cy + a.s * jy) * a.kw + (cx + a.s * jx);
-                    return (tap * a.Co + cc * a.CC + 8 * g) * a.Ci * 4;           // bytes, wave-uniform
+                // The loads and the steps each walk the (tap, group) sequence in order, so both keep running counters:
+                // dividing the flattened index out again cost two scalar divisions per load and per step, ~120 scalar
+                // instructions in front of every 8 (16) MFMAs.
+                auto tap_off = [&](int jy, int jx) __attribute__((always_inline)) {
+                    return (((cy + a.s * jy) * a.kw + (cx + a.s * jx)) * a.Co + cc * a.CC) * a.Ci * 4;   // bytes, wave-uniform
                 };
-                auto load_b = [&](int it, float (&bb)[4][NT]) __attribute__((always_inline)) {
-                    const int so = koff(it);
+                int lg = 0, ljx = 0, ljy = 0, lbase = tap_off(0, 0);      // (group, tap) of the next load
+                auto load_b = [&](float (&bb)[4][NT]) __attribute__((always_inline)) {
+                    const int so = lbase + lg * 8 * a.Ci * 4;
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -170,12 +173,18 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                             bb[s][n] = __builtin_bit_cast(
                                 float, __builtin_amdgcn_raw_buffer_load_b32(kres, kvoff[n], so + s * a.Ci * 4, 0));
                         }
+                    if (++lg == ngr) {
+                        lg = 0;
+                        if (++ljx == nkx) { ljx = 0; ++ljy; }
+                        lbase = tap_off(ljy, ljx);
+                    }
                 };
                 int addr[2] = {zoff + 4 * kq, zoff + 4 * kq};
-                auto step = [&](int it, float (&bb)[4][NT]) __attribute__((always_inline)) {
-                    const int ti = it / ngr, g = it - ti * ngr;
+                int sg = 0, sjx = 0, sjy = 0;                              // (group, tap) of the next step
+                auto step = [&](float (&bb)[4][NT]) __attribute__((always_inline)) {
+                    const int g = sg;
                     if (g == 0) {
-                        const int jy = ti / nkx, jx = ti - jy * nkx;
+                        const int jy = sjy, jx = sjx;
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
                             const int py = py0[t] - jy, px = px0[t] - jx;
@@ -195,25 +204,29 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                             for (int n = 0; n < NT; ++n)
                                 acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, bb[s][n], acc[t][n], 0, 0, 0);
                         }
+                    if (++sg == ngr) {
+                        sg = 0;
+                        if (++sjx == nkx) { sjx = 0; ++sjy; }
+                    }
                 };
                 float b0[4][NT], b1[4][NT], b2[4][NT], b3[4][NT];
-                if (nit > 0) load_b(0, b0);
-                if (nit > 1) load_b(1, b1);
-                if (nit > 2) load_b(2, b2);
+                if (nit > 0) load_b(b0);
+                if (nit > 1) load_b(b1);
+                if (nit > 2) load_b(b2);
                 for (int it = 0; it < nit; it += 4) {
-                    if (it + 3 < nit) load_b(it + 3, b3);
-                    step(it, b0);
+                    if (it + 3 < nit) load_b(b3);
+                    step(b0);
                     if (it + 1 < nit) {
-                        if (it + 4 < nit) load_b(it + 4, b0);
-                        step(it + 1, b1);
+                        if (it + 4 < nit) load_b(b0);
+                        step(b1);
                     }
                     if (it + 2 < nit) {
-                        if (it + 5 < nit) load_b(it + 5, b1);
-                        step(it + 2, b2);
+                        if (it + 5 < nit) load_b(b1);
+                        step(b2);
                     }
                     if (it + 3 < nit) {
-                        if (it + 6 < nit) load_b(it + 6, b2);
-                        step(it + 3, b3);
+                        if (it + 6 < nit) load_b(b2);
+                        step(b3);
                     }
                 }
             }
