@@ -129,3 +129,39 @@ def test_residual_workloads_full_batch_gpu_sampled_oracle(name, sample):
     gl, gu = g.concrete(len(w.net.layers))
     assert (gl <= gu).all()
     gnet.close()
+
+
+@pytest.mark.parametrize("conv", [False, True])
+def test_symbolic_bounds_of_the_output_layer_on_a_residual_network(conv):
+    """keep_symbolic = 1: the input-level expressions of the last layer against the oracle's export."""
+    b = _binding()
+    if conv:
+        net = wl.random_small_res_conv(15, (2, 6, 6), 4, 1, 3, [], [5, 3])
+    else:
+        net = wl.random_small_res(15, 12, 20, 2, 4)
+    B = 2
+    x, lo, hi = wl.random_box(16, net.n_in, B, 0.04)
+    nl = len(net.layers)
+    o = oracle.run(net, lo, hi, sym_layer=nl)
+    gnet = b.Network(net)
+    g = gnet.certify(lo, hi, None, keep_symbolic=1)
+    for side, (ck, kk) in enumerate((("cl", "kl"), ("cu", "ku"))):
+        c, k = g.symbolic(nl, side)
+        scale = np.abs(o.sym[ck]).max()
+        assert np.abs(c - o.sym[ck]).max() <= 1e-4 * scale + 1e-6
+        np.testing.assert_allclose(k, o.sym[kk], rtol=1e-4, atol=1e-5)
+    compare_with_oracle(net, lo, hi, g, o, None)
+    gnet.close()
+
+
+def test_empty_and_single_input_batches_on_a_residual_network():
+    b = _binding()
+    net = wl.random_small_res(17, 10, 16, 1, 3)
+    gnet = b.Network(net)
+    g0 = gnet.certify(np.zeros((0, 10), np.float32), np.zeros((0, 10), np.float32), np.zeros((0,), np.int32))
+    assert g0.concrete(len(net.layers))[0].shape == (0, 3)
+    x, lo, hi = wl.random_box(18, 10, 1, 0.05)
+    label = np.array([1], np.int32)
+    o = oracle.run(net, lo, hi, label=label)
+    compare_with_oracle(net, lo, hi, gnet.certify(lo, hi, label), o, label)
+    gnet.close()
