@@ -84,8 +84,9 @@ dpc_status dpc_network_add_relu(dpc_network* net);
  * layers at once: two blocks of one coefficient tensor (Section 5.1), which are summed when the
  * traversal brings them onto the same layer (Section 5.2, overlapping blocks are merged); the
  * deepest layer is always replaced first (Section 4.2).  The previous layer must be fully-connected
- * or a convolution (DPC_EUNSUPPORTED otherwise); networks with Add layers take full DeepPoly
- * traversals only (no depth limit, no ReuseCert: dpc_certify returns DPC_EUNSUPPORTED). */
+ * or a convolution (DPC_EUNSUPPORTED otherwise).  A depth-limited traversal that stops while a
+ * block still waits on a skip connection concretises the expression over both layers it holds.
+ * ReuseCert is specified for chain networks: dpc_certify returns DPC_EUNSUPPORTED. */
 dpc_status dpc_network_add_skip(dpc_network* net, int32_t from_layer);
 
 /* Validate the chain, upload weights to HIP device `device` in the layouts the

@@ -313,7 +313,7 @@ struct Waiting {
 // layer) plus coefficient 1 on the same neuron of layer diag_target.
 void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym,
               double useful = 1.0,       // fraction of the rows whose bounds are used (flop accounting only)
-              int diag_target = -1)
+              int diag_target = -1, int depth0 = 0)    // depth0: traverse iterations the starting rows already stand for
 {
     dpc_network* net = P.net;
     dpc_result* res = P.res;
@@ -328,7 +328,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     const int ld_shared = own ? (f.patch ? own->cw.ld_core : own->ldw) : 0;
     const float* cst_init = own ? (f.patch ? own->cw.bias_c : own->dBias.p) : nullptr;
     bool bias_folded = false;
-    int depth = 0;
+    int depth = depth0;
     const int64_t M = (int64_t)nsides * B * R;
     bool fused_relu = false;
     int slots = 0;                 // row-constant partial-sum slots written by fused epilogues so far
@@ -515,7 +515,54 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     }
 
     merge_at(at);
-    DPC_REQUIRE(waiting.empty(), DPC_EUNSUPPORTED, "depth-limited traversals that end inside a residual block are not supported");
+    if (!waiting.empty()) {
+        // the depth limit was reached while blocks still wait on skip connections: simplify_* maps over the terms of
+        // every layer the expression holds, so each waiting block is concretised against its own layer's stored bounds
+        DPC_REQUIRE(!keep_sym, DPC_EUNSUPPORTED, "symbolic bounds need a full traversal");
+        if (shared) relax(nullptr, nullptr, nullptr, nullptr);        // constants live in cst from here on
+        while (!waiting.empty()) {
+            const int tgt = waiting.front().target;
+            std::vector<Waiting> grp;
+            for (size_t k = 0; k < waiting.size();)
+                if (waiting[k].target == tgt) { grp.push_back(waiting[k]); waiting.erase(waiting.begin() + k); }
+                else ++k;
+            int gc = 0, gh = 0, gw = 0;
+            const bool sp = net->spatial(tgt, &gc, &gh, &gw);
+            Waiting w = grp[0];
+            if (grp.size() > 1) {
+                // blocks over one layer are one block of the expression (the sign split is taken on their sum): they are
+                // summed in the free row buffer, in the smallest patch that holds them all
+                int Pm = 0, phm = 1, pwm = 1;
+                for (const Waiting& x : grp) {
+                    DPC_REQUIRE(x.patch == w.patch && (!x.patch || x.S == w.S), DPC_EUNSUPPORTED, "waiting blocks of different forms");
+                    Pm = std::max(Pm, x.P);
+                }
+                for (const Waiting& x : grp) { phm = std::max(phm, Pm - x.P + x.ph); pwm = std::max(pwm, Pm - x.P + x.pw); }
+                const int n_t = net->size_of(tgt);
+                const int ldm = w.patch ? (int)round_up((int64_t)phm * pwm * gc, 4) : net->ld_of(tgt);
+                DPC_REQUIRE((size_t)M * ldm <= std::min(net->buf[0].count, net->buf[1].count), DPC_EUNSUPPORTED,
+                            "waiting blocks do not fit the workspace");
+                P.prof->begin(P_RELAX);
+                launch_fill_zero(nxt, M * ldm, P.s);
+                for (const Waiting& x : grp) {
+                    if (w.patch)
+                        launch_merge_block(nxt, ldm, M, R, f.pg.rows_C, phm, pwm, gc, x.kind, x.src, x.ld, x.ph, x.pw, Pm - x.P, P.s);
+                    else
+                        launch_merge_block(nxt, ldm, M, R, R, 1, 1, n_t, x.kind, x.src, x.ld, 1, 1, 0, P.s);
+                }
+                P.prof->end();
+                res->prof.relax_launches += 1 + (int)grp.size();
+                w.kind = 0; w.src = nxt; w.ld = ldm; w.ph = phm; w.pw = pwm; w.P = Pm;
+            }
+            DPC_REQUIRE(!w.patch || sp, DPC_EUNSUPPORTED, "patch-form block over a layer without a shape");
+            P.prof->begin(P_CONC);
+            launch_block_bound(cst, M, R, f.patch ? f.pg.rows_C : R, f.patch ? f.pg.rows_W : 1, B, nsides, net->size_of(tgt), w.kind,
+                               w.src, w.ld, res->l[tgt], res->u[tgt], w.patch ? 1 : 0, w.ph, w.pw, gc, w.S, w.P, gh, gw, P.s);
+            P.prof->end();
+            res->prof.concretise_launches++;
+        }
+        waiting.clear();
+    }
     const int n_at = net->size_of(at);
     if (keep_sym) {
         DPC_REQUIRE(at == 0 && !f.patch, DPC_EUNSUPPORTED, "symbolic bounds are kept for dense rows at the input only");
@@ -837,8 +884,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                             "dpc_certify: ReuseCert covers fully-connected networks with affine and ReLU layers alternating");
         }
         if (net->skip_depth > 0)
-            DPC_REQUIRE(!reuse_cert && opt.max_backsub_depth == -1 && opt.final_backsub_depth == -1, DPC_EUNSUPPORTED,
-                        "dpc_certify: networks with Add layers take full DeepPoly traversals only");
+            DPC_REQUIRE(!reuse_cert, DPC_EUNSUPPORTED, "dpc_certify: ReuseCert is specified for chain networks only");
         if (label) DPC_REQUIRE(last.kind == AFFINE && last.n_out >= 2, DPC_EUNSUPPORTED,
                                "dpc_certify: a label needs a fully-connected last layer with >= 2 outputs");
         DeviceGuard guard(net->device);
@@ -1096,9 +1142,19 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 if (merge_final && i == nl) continue;       // bounded together with the margins below
                 P.maxd = i == nl ? opt.final_backsub_depth : opt.max_backsub_depth;
                 if (L.kind == ADD) {
-                    // expressions of its neurons: the rows of the layer below + a unit block on the skip operand
+                    if (P.maxd == 0) {
+                        // no traverse iteration: simplify_* over prev0 + prev1 adds the stored bounds of the two operands
+                        prof.begin(P_CONC);
+                        launch_add_vectors(res->l[i - 1], res->l[L.skip], res->l[i], (int64_t)B * L.n_out, s);
+                        launch_add_vectors(res->u[i - 1], res->u[L.skip], res->u[i], (int64_t)B * L.n_out, s);
+                        prof.end();
+                        res->prof.concretise_launches += 2;
+                        continue;
+                    }
+                    // expressions of its neurons: the rows of the layer below (one traverse iteration already taken)
+                    // + a unit block on the skip operand
                     Layer& below = *net->layers[i - 2];
-                    run_pass(P, i - 2, 2, L.n_out, &below, res->l[i], res->u[i], opt.keep_symbolic && i == nl, 1.0, L.skip);
+                    run_pass(P, i - 2, 2, L.n_out, &below, res->l[i], res->u[i], opt.keep_symbolic && i == nl, 1.0, L.skip, 1);
                     continue;
                 }
                 run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);

@@ -143,6 +143,13 @@ int contract_split_terms();
 // kind 0: src[m][..]; kind 1: src[r % rows_C][..] (r = m % R); kind 2: += 1 on channel r % rows_C of position (d, d).
 void launch_merge_block(float* dst, int ld_dst, int64_t M, int R, int rows_C, int ph2, int pw2, int C, int kind,
                         const float* src, int ld_src, int ph1, int pw1, int d, hipStream_t s);
+// cst[m] += concretisation of a waiting block (kinds as above) against lo, hi [batch][n], the bounds of the layer
+// the block is over; patch != 0: the block is a ph x pw x C patch with origin index * S - P on a gh x gw grid.
+void launch_block_bound(double* cst, int64_t M, int R, int rows_C, int rows_W, int batch, int nsides, int n, int kind,
+                        const float* src, int ld_src, const float* lo, const float* hi, int patch, int ph, int pw, int C, int S,
+                        int P, int gh, int gw, hipStream_t s);
+void launch_add_vectors(const float* a, const float* b, float* out, int64_t n, hipStream_t s);
+void launch_fill_zero(float* p, int64_t n, hipStream_t s);     // a kernel, so that captured launch sequences hold no memset node
 // pk2[b][c] = (mu, nu with lambda in its sign bit: negative = 1), float2; columns n..ld-1 zero.
 void launch_pack_relax2(const float* lambda, const float* mu, const float* nu, int batch, int n, int ld, float* pk2,
                         hipStream_t s);

@@ -509,6 +509,52 @@ __global__ __launch_bounds__(kThreads) void merge_block_kernel(MergeArgs a)
     }
 }
 
+// Concretisation of a waiting block against the stored bounds of the layer it is over, added to the rows' constants
+// (a depth-limited traversal that ends while a block still waits on a skip connection: simplify_* maps over the
+// terms of both layers).  One wavefront per row; the block kinds are those of merge_block_kernel.
+struct BlockBoundArgs {
+    double* cst;
+    const float* src; int ld_src;
+    const float* lo; const float* hi;      // [batch][n] bounds of the block's layer
+    long long M; int R, rows_C, rows_W, batch, nsides, n;
+    int patch, ph, pw, C, S, P, gh, gw;    // patch geometry of the block (patch != 0)
+    int kind;
+};
+
+__global__ __launch_bounds__(kThreads) void block_bound_kernel(BlockBoundArgs a)
+{
+    const long long m = (long long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (m >= a.M) return;
+    const int lane = threadIdx.x & 63;
+    const int g = (int)(m / a.R), r = (int)(m - (long long)g * a.R);
+    const int side = a.nsides == 1 ? 0 : (g >= a.batch), b = g - (g >= a.batch ? a.batch : 0);
+    const float* lo = a.lo + (size_t)b * a.n;
+    const float* hi = a.hi + (size_t)b * a.n;
+    double acc = 0.0;
+    if (a.kind == 2) {
+        if (lane == 0) acc = side == 0 ? lo[r] : hi[r];                  // coefficient 1 on the row's own neuron
+    } else {
+        const float* src = a.src + (a.kind == 1 ? (size_t)(r % a.rows_C) : (size_t)m) * a.ld_src;
+        const int n1 = a.patch ? a.ph * a.pw * a.C : a.n;
+        const int wo = (r / a.rows_C) % a.rows_W, ho = r / (a.rows_C * a.rows_W);
+        const int oy = ho * a.S - a.P, ox = wo * a.S - a.P;
+        for (int e = lane; e < n1; e += 64) {
+            int idx = e;
+            if (a.patch) {
+                const int pos = e / a.C, c = e - pos * a.C;
+                const int py = pos / a.pw, px = pos - py * a.pw;
+                const int gy = oy + py, gx = ox + px;
+                if (gy < 0 || gy >= a.gh || gx < 0 || gx >= a.gw) continue;     // zero padding: no neuron there
+                idx = (gy * a.gw + gx) * a.C + c;
+            }
+            const float x = src[e];
+            acc += (double)x * (double)((x >= 0.0f) == (side == 0) ? lo[idx] : hi[idx]);
+        }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) a.cst[m] += acc;
+}
+
 // Compact parameters of a ReLU layer for kernels that apply the sign split themselves: (mu, nu) per (input, neuron)
 // with lambda (0 or 1) carried in the sign bit of nu (nu itself is never negative); columns n..ld-1 zero.
 __global__ __launch_bounds__(kThreads) void pack_relax2_kernel(
@@ -776,6 +822,50 @@ void launch_merge_block(float* dst, int ld_dst, int64_t M, int R, int rows_C, in
     if (M == 0) return;
     MergeArgs a{dst, ld_dst, src, ld_src, R, rows_C, ph1, pw1, pw2, C, d, kind};
     hipLaunchKernelGGL(merge_block_kernel, dim3((unsigned)M), dim3(kThreads), 0, s, a);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_block_bound(double* cst, int64_t M, int R, int rows_C, int rows_W, int batch, int nsides, int n, int kind,
+                        const float* src, int ld_src, const float* lo, const float* hi, int patch, int ph, int pw, int C, int S,
+                        int P, int gh, int gw, hipStream_t s)
+{
+    DPC_REQUIRE(cst && lo && hi && M >= 0 && R >= 1 && rows_C >= 1 && rows_W >= 1 && batch >= 1 && (nsides == 1 || nsides == 2) &&
+                    n >= 1 && kind >= 0 && kind <= 2 && M == (int64_t)nsides * batch * R, DPC_EINVAL, "block_bound: bad arguments");
+    DPC_REQUIRE(kind == 2 ? R <= n : (src && (patch ? (int64_t)ph * pw * C <= ld_src && (int64_t)gh * gw * C <= n : n <= ld_src)), DPC_EINVAL,
+                "block_bound: the block does not fit its layer");
+    if (M == 0) return;
+    BlockBoundArgs a{cst, src, ld_src, lo, hi, (long long)M, R, rows_C, rows_W, batch, nsides, n, patch, ph, pw, C, S, P, gh, gw, kind};
+    hipLaunchKernelGGL(block_bound_kernel, dim3((unsigned)ceil_div(M, kThreads / 64)), dim3(kThreads), 0, s, a);
+    DPC_HIP(hipGetLastError());
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* __restrict__ p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+void launch_fill_zero(float* p, int64_t n, hipStream_t s)
+{
+    DPC_REQUIRE(p && n >= 0 && ceil_div(n, kThreads) < ((int64_t)1 << 31), DPC_EINVAL, "fill_zero: bad arguments");
+    if (n == 0) return;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)ceil_div(n, kThreads)), dim3(kThreads), 0, s, p, n);
+    DPC_HIP(hipGetLastError());
+}
+
+// out[i] = a[i] + b[i]
+__global__ __launch_bounds__(kThreads) void add_vectors_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                               float* __restrict__ out, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) out[i] = a[i] + b[i];
+}
+
+void launch_add_vectors(const float* a, const float* b, float* out, int64_t n, hipStream_t s)
+{
+    DPC_REQUIRE(a && b && out && n >= 0, DPC_EINVAL, "add_vectors: bad arguments");
+    if (n == 0) return;
+    hipLaunchKernelGGL(add_vectors_kernel, dim3((unsigned)ceil_div(n, kThreads)), dim3(kThreads), 0, s, a, b, out, n);
     DPC_HIP(hipGetLastError());
 }
 

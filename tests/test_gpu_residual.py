@@ -75,15 +75,43 @@ def test_small_residual_conv(shape, width, blocks, k, tail, fcs):
     _check(net, lo, hi, label)
 
 
-def test_depth_limits_and_reusecert_are_refused_on_residual_networks():
+def test_reusecert_is_refused_on_residual_networks():
     b = _binding()
     net = wl.random_small_res(5, 6, 8, 1, 3)
     x, lo, hi = wl.random_box(6, 6, 2, 0.05)
     gnet = b.Network(net)
-    for kw in (dict(max_backsub_depth=2), dict(certifier="reusecert"), dict(final_backsub_depth=0)):
-        with pytest.raises(b.DpcError) as e:
-            gnet.certify(lo, hi, None, **kw)
-        assert e.value.code == 2
+    with pytest.raises(b.DpcError) as e:
+        gnet.certify(lo, hi, None, certifier="reusecert")
+    assert e.value.code == 2
+    gnet.close()
+
+
+def _depth_nets():
+    yield "fc", wl.random_small_res(41, 12, 36, 2, 4)
+    for name, net in _variants():
+        yield name, net
+    yield "conv", wl.random_small_res_conv(42, (2, 6, 6), 8, 1, 3, [(8, 4, 2, 1)], [5, 3])
+    yield "conv, two blocks", wl.random_small_res_conv(43, (3, 8, 8), 4, 2, 3, [], [6, 3])
+
+
+@pytest.mark.parametrize("name,net", list(_depth_nets()))
+def test_depth_limited_traversals_on_residual_networks(name, net):
+    """DeepPoly_p, IBP (p = 0) and CROWN-IBP on networks with Add layers: a traversal may stop while a block still waits
+    on a skip connection; the expression is then concretised over both layers it holds."""
+    b = _binding()
+    B = 2
+    x, lo, hi = wl.random_box(44, net.n_in, B, 0.03)
+    n_out = net.sizes()[-1]
+    label = (np.arange(B, dtype=np.int32) % n_out) if net.layers[-1].kind == "affine" else None
+    gnet = b.Network(net)
+    for depth, last in ((0, None), (1, None), (2, None), (3, None), (4, None), (5, None), (0, -1), (2, -1)):
+        o = oracle.run(net, lo, hi, label=label, max_depth=depth, max_depth_last=last)
+        for fuse in (1, 0):
+            g = gnet.certify(lo, hi, label, max_backsub_depth=depth, final_backsub_depth=-2 if last is None else last, fuse=fuse)
+            try:
+                compare_with_oracle(net, lo, hi, g, o, label)
+            except AssertionError as e:
+                raise AssertionError(f"{name}: depth {depth}, last {last}, fuse {fuse}: {e}")
     gnet.close()
 
 
