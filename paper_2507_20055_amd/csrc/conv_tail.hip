@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
     // Tiles are fetched (rows and ReLU parameters) one step ahead, across panel boundaries too: the loads of the next
     // step are in flight during the MFMAs of this one and during the gather and reduction phases.  Lanes whose entry
     // lies outside the panel, the row range or the layer's grid hold zeros, which contribute nothing below.
-    constexpr int T = CO8 >= 4 ? 1 : 2;                               // tiles per step
+    constexpr int T = 1;                               // tiles per step (two cost registers and with them a wavefront per SIMD)
     const int ipp = (ntiles + T * NW - 1) / (T * NW);                  // steps per wavefront per panel
     const unsigned long long magic_npos = (1ull << 32) / (unsigned)max(npos, 1) + 1;     // e / npos for e * npos < 2^32
     const unsigned long long magic_iw = (1ull << 32) / (unsigned)max(a.iw, 1) + 1;
@@ -219,13 +219,29 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
 
         // ---- gather the coefficients over the image and reduce them against the box ----
         const int total = a.RB * Pout, nky = (a.kh + S - 1) / S, nkx = (a.kw + S - 1) / S;
-        const size_t boxbase = (size_t)b * a.H * a.W * CI;
+        const __amdgpu_buffer_rsrc_t lores = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(a.lo + (size_t)b * a.H * a.W * CI), 0, a.H * a.W * CI * 4, 0x00020000);
+        const __amdgpu_buffer_rsrc_t hires = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(a.hi + (size_t)b * a.H * a.W * CI), 0, a.H * a.W * CI * 4, 0x00020000);
         for (int e = tid; e < total; e += kTailThreads) {
             const int ml = (int)(((unsigned long long)e * magic_pout) >> 32);
             const int q = e - ml * Pout;
             const int y = (int)(((unsigned long long)q * magic_ow) >> 32);
             const int x = q - y * a.ow;
             const int rbase = ml * npos;
+            // both bounds of this position of the image are requested before the taps are gathered, so their latency
+            // hides behind the LDS reads; a position off the image reads zeros (offset outside the resource)
+            const int gy = qy + y, gx = qx + x;
+            const int boff = (gy >= 0 && gy < a.H && gx >= 0 && gx < a.W) ? ((gy * a.W + gx) * CI) * 4 : (int)0x80000000;
+            float blo[4] = {0.f, 0.f, 0.f, 0.f}, bhi[4] = {0.f, 0.f, 0.f, 0.f};
+            if (a.RB > 0) {            // always true; inside a branch of their own the loads are not sunk to their use behind the loop
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (c < CI) {
+                        blo[c] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(lores, boff + 4 * c, 0, 0));
+                        bhi[c] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(hires, boff + 4 * c, 0, 0));
+                    }
+            }
             float o[4] = {0.f, 0.f, 0.f, 0.f};
             // taps that can reach this output: ky = y mod S + S * jy, read at patch row y / S - jy (same for x)
             const int ybase = y / S, ry = y - ybase * S, xbase = x / S, rx = x - xbase * S;
@@ -240,17 +256,10 @@ __global__ __launch_bounds__(kTailThreads, 2) void patch_tail_kernel(TailArgs a)
                     o[0] += src[0]; o[1] += src[1]; o[2] += src[2]; o[3] += src[3];      // columns past CI are not used
                 }
             }
-            const int gy = qy + y, gx = qx + x;
             float t = 0.0f;
-            if (gy >= 0 && gy < a.H && gx >= 0 && gx < a.W) {
-                const size_t bi = boxbase + ((size_t)gy * a.W + gx) * CI;
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (c < CI) {
-                        const bool take_lo = (o[c] >= 0.0f) == (side == 0);
-                        t = fmaf(o[c], take_lo ? a.lo[bi + c] : a.hi[bi + c], t);
-                    }
-            }
+            for (int c = 0; c < 4; ++c)
+                if (c < CI) t = fmaf(o[c], (o[c] >= 0.0f) == (side == 0) ? blo[c] : bhi[c], t);
             sC[e] = t;
         }
         __syncthreads();
