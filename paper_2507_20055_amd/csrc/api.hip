@@ -453,6 +453,29 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 return;
             }
         }
+        if (waiting.empty() && L.kind == RELU && at == 2 && !f.patch && !shared && P.opt->fuse && maxd < 0 && !keep_sym && net->pk2.p &&
+            net->layers[0]->kind == CONV && net->part.p && M <= net->part_stride && slots < dpc_network::kMaxSlots) {
+            // dense rows over the first ReLU layer: its step is applied while the first layer's transposed convolution
+            // loads the rows (no pass of its own over them); the constants it adds arrive in slots
+            const Layer& first = *net->layers[0];
+            const ReluOnLoad rl{net->pk2.p, net->ld_of(2), first.cw.bias_c, net->part.p + (size_t)slots * net->part_stride,
+                                net->part_stride, dpc_network::kMaxSlots - slots, R, B};
+            int used = 0;
+            P.prof->begin(P_CONTRACT);
+            const bool done = launch_conv_transpose_fast(cur, M, f.ld, first.g.Ho, first.g.Wo, first.g, first.cw, nxt, net->ld_of(0),
+                                                         first.g.H, first.g.W, first.g.pad, P.s, &rl, &used);
+            P.prof->end();
+            if (done) {
+                res->prof.contract_flop += useful * 2.0 * (double)M * first.g.Ho * first.g.Wo * first.g.Co * first.g.Ci * first.g.kh * first.g.kw;
+                res->prof.contract_launches++;
+                slots += used;
+                std::swap(cur, nxt);
+                f.ld = net->ld_of(0);
+                at = 0;
+                depth += 2;
+                break;
+            }
+        }
         if (L.kind == RELU) {
             const Layer& below = *net->layers[at - 2];
             // the bias of the layer below is folded in the same pass unless a block still has to join the rows there

@@ -70,8 +70,19 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
                                   const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
 
 // MFMA implicit-GEMM / small-channel kernels for the same operation; false = shape not covered.
+// relu != NULL: the rows are dense rows over the ReLU layer above g (few input channels: the network's first layer) and
+// that layer's sign-split step with the bias fold of g is applied as the rows are loaded; the row constants it adds go
+// to *slots_used slots part[k * part_stride + m], k < *slots_used <= max_slots, which the consumer adds in index
+// order.  Returns false, launching nothing, when the product-then-gather kernel cannot take the shape.
+struct ReluOnLoad {
+    const float* pk2; int ldpk;      // compact parameters (launch_pack_relax2) [batch][ldpk]
+    const float* bias_c;             // bias of g per output channel
+    float* part; long long part_stride; int max_slots;
+    int R, batch;                    // rows are [side][input][R]
+};
 bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
-                                const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
+                                const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s,
+                                const ReluOnLoad* relu = nullptr, int* slots_used = nullptr);
 // Tail of a traversal of patch-form rows in one kernel: the ReLU step of the network's first ReLU layer, the
 // transposed convolution through the first layer (at most 4 input channels) and the concretisation against the box
 // (see conv_tail.hip).  `form` describes the rows over the ReLU layer, `conv` the first layer.  Rows are

@@ -20,6 +20,8 @@
 // patches of all channels would leave room for only one workgroup per CU, the reduction runs over channel
 // chunks and LDS holds one chunk at a time.  Kernel values are read from global memory (L2-resident) one
 // (tap, 8-channel group) ahead into registers, so the (tap, group) loop has no barrier.
+#include <type_traits>
+
 #include "conv.h"
 
 namespace dpc {
@@ -340,12 +342,24 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_smallci_kernel(
 // each) so that the kernel-matrix fetch and the launch cost are spread over more work.
 constexpr int kPThreads = 256;         // workgroup of the product-then-gather kernel below
 
-template <int NT, int S, int CO8>
+// RELU: the rows are dense rows over the first ReLU layer and its sign-split step (with the bias fold of the convolution
+// below) is applied to them as they are loaded: stored value x * mult, row constant += x * k (see conv_tail.hip for
+// the arithmetic).  Every strip of output rows adds the constants of the input rows it owns (a partition of the
+// input rows) into its own slot, part[(slot0 + strip) * stride + m]; the consumer adds the slots in index order.
+struct PRelu {
+    const float2* pk2; int ldpk;          // (mu, nu with lambda in the sign bit) [batch][ldpk]
+    const float* bias_c;                  // [CO]
+    float* part; long long part_stride; int slot0;
+    int R, batch;                         // rows are [side][input][R]; RB divides R
+};
+
+template <int NT, int S, int CO8, bool RELU>
 __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
     const float* __restrict__ in, const float* __restrict__ taps, float* __restrict__ out, CtArgs a,
-    int yrows_per_block, int lds_rows, int panels)
+    int yrows_per_block, int lds_rows, int panels, PRelu rl)
 {
     constexpr int CO = CO8 * 8, NC = 32 * NT, PS = NC + 3, NW = kPThreads / 64;
+    constexpr int TU = (RELU && CO8 >= 4) ? 1 : 2;      // tiles of 32 entries per wavefront per step (registers decide)
     extern __shared__ float4 lds4[];
     float* sP = reinterpret_cast<float*>(lds4);        // [entries rounded up to 32][PS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
@@ -364,6 +378,13 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
     const unsigned long long magic_ow = (1ull << 32) / (unsigned)max(a.ow, 1) + 1;
     const int zoff = ((a.RB * lds_rows * a.iw + 31) & ~31) * PS;                         // four zeros behind the panel
     if (tid < 4) sP[zoff + tid] = 0.0f;
+    float* sK = sP + zoff + 4;                         // RELU: [entries] row-constant contribution of every entry
+    // input rows whose constants this strip adds: [own_lo, own_hi) partitions [0, ih) over the strips and lies
+    // inside the rows the strip stages
+    const int own_lo = blockIdx.y == 0 ? 0 : min(a.ih, (yb + a.off + S - 1) / S);
+    const int own_hi = ye >= a.oh ? a.ih : min(a.ih, (ye + a.off + S - 1) / S);
+    const unsigned long long magic_npos = (1ull << 32) / (unsigned)max(npos, 1) + 1;   // e / npos for e * npos < 2^32
+    const unsigned long long magic_iw = (1ull << 32) / (unsigned)max(a.iw, 1) + 1;
 
     // kernel matrix in the B-operand layout: step (g, s4) of the reduction multiplies channel 8g + 4kq + s4
     float bk[NT][CO8 * 4];
@@ -380,25 +401,57 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
 
     // The input tiles of a wavefront are fetched one step ahead, across panel boundaries too, so that the loads of
     // the next step are in flight during the MFMAs of this one and during the gather phase.
-    const int ipp = (ntiles + 2 * NW - 1) / (2 * NW);                  // steps (tile pairs) per wavefront per panel
-    auto fetch = [&](int pi, int it, vf4 (&r)[2][CO8]) __attribute__((always_inline)) {
-        const long long m0 = ((long long)blockIdx.x * panels + pi) * a.RB;
-        const int t0 = wave * 2 + it * 2 * NW;
+    const int ipp = (ntiles + TU * NW - 1) / (TU * NW);                // steps per wavefront per panel
+    constexpr int PU = RELU ? TU : 1, PG = RELU ? CO8 : 1;
+    float bias[PG][4];                                 // RELU: convolution bias of this lane's channels
+    if constexpr (RELU) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int g = 0; g < CO8; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bias[g][k] = rl.bias_c[8 * g + 4 * kq + k];
+    }
+    // Buffer loads: a lane outside the panel or the rows gets an offset outside the resource and reads zeros (no
+    // branch, no zero fill); the resource starts at the panel's first row, so 32-bit offsets suffice.
+    constexpr int kOutside = (int)0x80000000;
+    auto fetch = [&](int pi, int it, vf4 (&r)[TU][CO8], float4 (&pk)[PU][PG][2], int (&own)[TU]) __attribute__((always_inline)) {
+        const long long mraw = ((long long)blockIdx.x * panels + pi) * a.RB;
+        const bool livep = pi < panels && mraw < a.M;
+        const long long m0 = livep ? mraw : 0;
+        const long long prow = a.M - m0 < a.RB ? a.M - m0 : a.RB;       // rows of this panel that exist
+        const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(in + m0 * a.ld_in), 0, livep ? (int)(prow * a.ld_in * 4) : 0, 0x00020000);
+        __amdgpu_buffer_rsrc_t qres = xres;
+        if constexpr (RELU) {
+            const int b = ((int)m0 / rl.R) % rl.batch;                 // RB divides R: one (side, input) group per panel; M < 2^31
+            qres = __builtin_amdgcn_make_buffer_rsrc(const_cast<float2*>(rl.pk2 + (size_t)b * rl.ldpk), 0, livep ? rl.ldpk * 8 : 0,
+                                                     0x00020000);
+        }
+        const int t0 = (wave + it * NW) * TU;
+#pragma unroll
+        for (int u = 0; u < TU; ++u) {
             const int e = (t0 + u) * 32 + l32;
-            const int ml = e / max(npos, 1), pos = e - ml * npos;
-            const bool ok = pi < panels && t0 + u < ntiles && e < E && m0 + ml < a.M;
-            const float* p = in + (m0 + (ok ? ml : 0)) * a.ld_in + ((size_t)r_lo * a.iw + (ok ? pos : 0)) * CO + 4 * kq;
+            const int ml = (int)(((unsigned long long)e * magic_npos) >> 32), pos = e - ml * npos;
+            const bool ok = t0 + u < ntiles && e < E;
+            const int xo = ok ? (ml * a.ld_in + (r_lo * a.iw + pos) * CO + 4 * kq) * 4 : kOutside;
 #pragma unroll
-            for (int g = 0; g < CO8; ++g) {
-                r[u][g] = vf4{0.f, 0.f, 0.f, 0.f};
-                if (ok) r[u][g] = *reinterpret_cast<const vf4*>(p + 8 * g);
+            for (int g = 0; g < CO8; ++g)
+                r[u][g] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo + 32 * g, 0, 0));
+            if constexpr (RELU) {
+                const int py = r_lo + (int)(((unsigned long long)pos * magic_iw) >> 32);
+                own[u] = ok && py >= own_lo && py < own_hi;
+                const int qo = ok ? ((r_lo * a.iw + pos) * CO + 4 * kq) * 8 : kOutside;
+#pragma unroll
+                for (int g = 0; g < CO8; ++g) {
+                    pk[u][g][0] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(qres, qo + 64 * g, 0, 0));
+                    pk[u][g][1] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(qres, qo + 64 * g + 16, 0, 0));
+                }
             }
         }
     };
-    vf4 nxt[2][CO8];
-    fetch(0, 0, nxt);
+    vf4 nxt[TU][CO8];
+    float4 npk[PU][PG][2];
+    int nown[TU] = {};
+    fetch(0, 0, nxt, npk, nown);
 
     for (int pi = 0; pi < panels; ++pi) {
         const long long m0 = ((long long)blockIdx.x * panels + pi) * a.RB;
@@ -409,18 +462,53 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
                 if (m0 + ml < a.M) out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
             }
         for (int it = 0; it < ipp; ++it) {
-            const int t0 = wave * 2 + it * 2 * NW;
-            vf4 av[2][CO8];
+            const int t0 = (wave + it * NW) * TU;
+            vf4 av[TU][CO8];
+            if constexpr (RELU) {
+                // per element x with (mu, nu | lambda) and the bias of its channel: the part of x on which this side takes the
+                // upper relaxation is p (x >= 0 on the upper side, x < 0 on the lower side), the rest n:
+                //   y = p * mu + lambda * n,   constant += p * (mu * bias + nu) + lambda * n * bias
+                const bool upper_side = (int)m0 / rl.R >= rl.batch;
+                float ks[TU] = {};
+                auto relu_step = [&](auto up) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+                    for (int u = 0; u < TU; ++u)
 #pragma unroll
-                for (int g = 0; g < CO8; ++g) av[u][g] = nxt[u][g];
-            if (it + 1 < ipp) fetch(pi, it + 1, nxt);
-            else fetch(pi + 1, 0, nxt);
+                        for (int g = 0; g < CO8; ++g) {
+                            const vf4 x = nxt[u][g];
+                            const float4 p01 = npk[u][g][0], p23 = npk[u][g][1];
+                            const float mu[4] = {p01.x, p01.z, p23.x, p23.z}, nl[4] = {p01.y, p01.w, p23.y, p23.w};
+                            vf4 y;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const float p = decltype(up)::value ? fmaxf(x[k], 0.0f) : fminf(x[k], 0.0f);
+                                const float n = decltype(up)::value ? fminf(x[k], 0.0f) : fmaxf(x[k], 0.0f);
+                                const float ln = __uint_as_float(__float_as_uint(n) & (unsigned)((int)__float_as_uint(nl[k]) >> 31));
+                                y[k] = fmaf(p, mu[k], ln);
+                                ks[u] = fmaf(ln, bias[g][k], fmaf(p, fmaf(mu[k], bias[g][k], fabsf(nl[k])), ks[u]));
+                            }
+                            av[u][g] = y;
+                        }
+                };
+                if (upper_side) relu_step(std::true_type{});
+                else relu_step(std::false_type{});
+#pragma unroll
+                for (int u = 0; u < TU; ++u) {
+                    const float kt = ks[u] + __shfl_xor(ks[u], 32, 64);     // the two half-waves hold the two channel halves
+                    if (kq == 0 && t0 + u < ntiles) sK[(t0 + u) * 32 + l32] = nown[u] ? kt : 0.0f;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < TU; ++u)
+#pragma unroll
+                    for (int g = 0; g < CO8; ++g) av[u][g] = nxt[u][g];
+            }
+            if (it + 1 < ipp) fetch(pi, it + 1, nxt, npk, nown);
+            else fetch(pi + 1, 0, nxt, npk, nown);
             if (t0 >= ntiles) continue;
-            floatx16 acc[2][NT];
+            floatx16 acc[TU][NT];
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < TU; ++u)
 #pragma unroll
                 for (int n = 0; n < NT; ++n)
 #pragma unroll
@@ -432,10 +520,10 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
 #pragma unroll
                     for (int n = 0; n < NT; ++n)
 #pragma unroll
-                        for (int u = 0; u < 2; ++u)
+                        for (int u = 0; u < TU; ++u)
                             acc[u][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][g][s4], bk[n][4 * g + s4], acc[u][n], 0, 0, 0);
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < TU; ++u) {
                 if (t0 + u >= ntiles) break;
 #pragma unroll
                 for (int n = 0; n < NT; ++n)
@@ -476,6 +564,16 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
                 if (CI > 3) dst[3] = o3;
             }
         }
+        if constexpr (RELU) {
+            // per row: the contributions of its entries, 64 lanes of one wavefront per row, summed in a fixed order
+            for (int ml = wave; ml < a.RB; ml += NW) {
+                float t = 0.0f;
+                for (int q = ml * npos + lane; q < (ml + 1) * npos; q += 64) t += sK[q];
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) t += __shfl_xor(t, d, 64);
+                if (lane == 0 && m0 + ml < a.M) rl.part[(size_t)(rl.slot0 + blockIdx.y) * rl.part_stride + m0 + ml] = t;
+            }
+        }
         __syncthreads();                   // the panel is overwritten by the next one
     }
 }
@@ -485,9 +583,11 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
 // Returns false when the shape is outside what these kernels cover (the caller then uses the
 // generic gather kernel).
 bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
-                                const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s)
+                                const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s,
+                                const ReluOnLoad* relu, int* slots_used)
 {
     if (g.Co % 8 != 0 || ld_in % 4 != 0 || ((uintptr_t)in % 16) != 0) return false;
+    if (relu && (g.Ci > 4 || conv_algo() != 0)) return false;              // only the product-then-gather kernel applies it
     CtArgs a{};
     a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
     a.taps = w.taps; a.Ci = g.Ci; a.kh = g.kh; a.kw = g.kw; a.s = g.stride; a.off = off;
@@ -515,6 +615,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         int yr = oh, RB = 1, lds_rows = ih;
         if ((int64_t)ih * iw <= emax) {
             RB = (int)std::max<int64_t>(1, std::min<int64_t>(emax / ((int64_t)ih * iw), 64));
+            if (relu) while (relu->R % RB != 0) --RB;                       // a panel stays inside one (side, input) group
         } else {
             for (yr = oh; yr >= 1; --yr) {
                 lds_rows = 0;
@@ -522,19 +623,41 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
                 if ((int64_t)lds_rows * iw <= emax) break;
             }
         }
+        const int strips = yr >= 1 ? (int)ceil_div(oh, yr) : 0;
+        if (relu) {
+            // every input row must be staged by some strip (its constants are added by the strip that owns it), the
+            // strips need a slot each, and offsets must fit 32 bits
+            const bool all_rows = (oh - 1 + off) / g.stride + 1 >= ih;
+            if (!(yr >= 1 && (int64_t)RB * lds_rows * iw <= emax) || !all_rows || strips > relu->max_slots || M >= ((int64_t)1 << 31) ||
+                (int64_t)RB * ld_in * 4 >= ((int64_t)1 << 31) || (int64_t)relu->ldpk * 8 >= ((int64_t)1 << 31) ||
+                relu->ldpk < ih * iw * g.Co || ((uintptr_t)relu->pk2 % 16) != 0 || relu->part_stride < M)
+                return false;
+        }
         if (yr >= 1 && (int64_t)RB * lds_rows * iw <= emax) {
             a.RB = RB;
-            const size_t lds = sB_bytes + (size_t)round_up((int64_t)RB * lds_rows * iw, 32) * PS * 4;
+            const size_t e32 = (size_t)round_up((int64_t)RB * lds_rows * iw, 32);
+            const size_t lds = sB_bytes + e32 * PS * 4 + (relu ? e32 * 4 : 0);
             // panels per workgroup: as many as keep about eight workgroups per compute unit in the grid
             const int64_t units = ceil_div(M, RB) * ceil_div(oh, yr);
             const int panels = (int)std::max<int64_t>(1, std::min<int64_t>(16, units / 2048));
             dim3 grid((unsigned)ceil_div(ceil_div(M, RB), panels), (unsigned)ceil_div(oh, yr));
+            PRelu rl{};
+            if (relu) {
+                rl = PRelu{reinterpret_cast<const float2*>(relu->pk2), relu->ldpk, relu->bias_c, relu->part, relu->part_stride, 0, relu->R,
+                           relu->batch};
+                *slots_used = strips;
+            }
             auto launch = [&](auto kern) {
-                hipLaunchKernelGGL(kern, grid, dim3(kPThreads), lds, s, in, w.taps, out, a, yr, lds_rows, panels);
+                hipLaunchKernelGGL(kern, grid, dim3(kPThreads), lds, s, in, w.taps, out, a, yr, lds_rows, panels, rl);
             };
 #define DPC_P_CASE(NTV, SV, C8) if (NT == NTV && g.stride == SV && g.Co == 8 * C8) { \
-        ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_p_kernel<NTV, SV, C8>), 64 * 1024); \
-        launch(&conv_transpose_p_kernel<NTV, SV, C8>); }
+        if (relu) { \
+            ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_p_kernel<NTV, SV, C8, true>), 64 * 1024); \
+            launch(&conv_transpose_p_kernel<NTV, SV, C8, true>); \
+        } else { \
+            ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_p_kernel<NTV, SV, C8, false>), 64 * 1024); \
+            launch(&conv_transpose_p_kernel<NTV, SV, C8, false>); \
+        } }
             DPC_P_CASE(1, 1, 1) DPC_P_CASE(1, 1, 2) DPC_P_CASE(1, 1, 4) DPC_P_CASE(1, 1, 8)
             DPC_P_CASE(2, 1, 1) DPC_P_CASE(2, 1, 2) DPC_P_CASE(2, 1, 4) DPC_P_CASE(2, 1, 8)
             DPC_P_CASE(1, 2, 1) DPC_P_CASE(1, 2, 2) DPC_P_CASE(1, 2, 4) DPC_P_CASE(1, 2, 8)
@@ -544,6 +667,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
             return true;
         }
     }
+    if (relu) return false;
 
     if (g.Ci <= 4) {
         // output rows per workgroup: about 256 positions; input rows those can reach: yr/s + (kh-1)/s + 2
