@@ -130,6 +130,7 @@ struct dpc_network {
     // the box), and the slots that collect row-constant partial sums of the fused contractions
     std::vector<std::unique_ptr<DevBuf<float>>> pk;
     DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
+    std::vector<std::unique_ptr<DevBuf<float>>> pk2v;      // the same for ReLU layers above a convolution with > 4 input channels
     std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
     int skip_depth = 0;                    // how many skip connections span one layer at most
     DevBuf<float> part;
@@ -459,7 +460,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             // loads the rows (no pass of its own over them); the constants it adds arrive in slots
             const Layer& first = *net->layers[0];
             const ReluOnLoad rl{net->pk2.p, net->ld_of(2), first.cw.bias_c, net->part.p + (size_t)slots * net->part_stride,
-                                net->part_stride, dpc_network::kMaxSlots - slots, R, B};
+                                net->part_stride, dpc_network::kMaxSlots - slots, R, B, nullptr};
             int used = 0;
             P.prof->begin(P_CONTRACT);
             const bool done = launch_conv_transpose_fast(cur, M, f.ld, first.g.Ho, first.g.Wo, first.g, first.cw, nxt, net->ld_of(0),
@@ -474,6 +475,41 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 at = 0;
                 depth += 2;
                 break;
+            }
+        }
+        if (L.kind == RELU && at >= 3 && !shared && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.opt->fuse &&
+            (maxd < 0 || depth + 2 <= maxd) && (int)net->pk2v.size() > at && net->pk2v[at] && net->pk2v[at]->p && net->part.p &&
+            M <= net->part_stride && slots < dpc_network::kMaxSlots && !blocked(at - 1)) {
+            // ReLU step applied while the transposed convolution below stages the rows (no pass of its own over them); the
+            // constants it adds come back in one slot and are folded into the row constants right away
+            const Layer& cv = *net->layers[at - 2];
+            const ReluOnLoad rl{net->pk2v[at]->p, net->ld_of(at), cv.cw.bias_c, net->part.p + (size_t)slots * net->part_stride,
+                                net->part_stride, dpc_network::kMaxSlots - slots, R, B, f.patch ? &f.pg : nullptr};
+            int used = 0;
+            bool done;
+            Form o = f;
+            P.prof->begin(P_CONTRACT);
+            if (f.patch) {
+                o = through_conv(f, cv.g);
+                done = launch_conv_transpose_fast(cur, M, f.ld, f.pg.ph, f.pg.pw, cv.g, cv.cw, nxt, o.ld, o.pg.ph, o.pg.pw, 0, P.s, &rl, &used);
+            } else {
+                o.ld = net->ld_of(at - 2);
+                done = launch_conv_transpose_fast(cur, M, f.ld, cv.g.Ho, cv.g.Wo, cv.g, cv.cw, nxt, o.ld, cv.g.H, cv.g.W, cv.g.pad, P.s, &rl,
+                                                  &used);
+            }
+            if (done) launch_fold_slots(cst, net->part.p + (size_t)slots * net->part_stride, used, net->part_stride, M, P.s);
+            P.prof->end();
+            if (done) {
+                const double pos = f.patch ? (double)f.pg.ph * f.pg.pw : (double)cv.g.Ho * cv.g.Wo;
+                res->prof.contract_flop += useful * 2.0 * (double)M * pos * cv.g.Co * cv.g.Ci * cv.g.kh * cv.g.kw;
+                res->prof.contract_launches++;
+                std::swap(cur, nxt);
+                f = o;
+                bias_folded = false;
+                fused_relu = false;
+                at -= 2;
+                depth += 2;
+                continue;
             }
         }
         if (L.kind == RELU) {
@@ -995,6 +1031,12 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             }
             if (nl >= 3 && net->layers[0]->kind == CONV && net->layers[0]->g.Ci <= 4 && net->layers[1]->kind == RELU)
                 moved |= net->pk2.reserve((size_t)B * net->ld_of(2) * 2);
+            if ((int)net->pk2v.size() != nl + 1) net->pk2v.resize(nl + 1);
+            for (int i = 3; i <= nl; ++i) {
+                if (net->layers[i - 1]->kind != RELU || net->layers[i - 2]->kind != CONV || net->layers[i - 2]->g.Ci <= 4) continue;
+                if (!net->pk2v[i]) net->pk2v[i].reset(new DevBuf<float>());
+                moved |= net->pk2v[i]->reserve((size_t)B * net->ld_of(i) * 2);
+            }
             if (net->pk.size() != (size_t)nl + 1) net->pk.resize(nl + 1);
             for (int i = 0; i <= nl; ++i) {
                 const bool want = i == 0 ? !net->in_spatial || true : net->layers[i - 1]->kind == RELU;
@@ -1158,6 +1200,8 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                                           net->ld_of(i), net->pk[i]->p, s);
                     if (fuse && i == 2 && net->pk2.p)
                         launch_pack_relax2(res->lam[i], res->mu[i], res->nu[i], B, L.n_out, net->ld_of(i), net->pk2.p, s);
+                    if (fuse && i >= 3 && (int)net->pk2v.size() > i && net->pk2v[i] && net->pk2v[i]->p)
+                        launch_pack_relax2(res->lam[i], res->mu[i], res->nu[i], B, L.n_out, net->ld_of(i), net->pk2v[i]->p, s);
                     prof.end();
                     res->prof.other_launches++;
                     continue;

@@ -70,8 +70,8 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
                                   const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s);
 
 // MFMA implicit-GEMM / small-channel kernels for the same operation; false = shape not covered.
-// relu != NULL: the rows are dense rows over the ReLU layer above g (few input channels: the network's first layer) and
-// that layer's sign-split step with the bias fold of g is applied as the rows are loaded; the row constants it adds go
+// relu != NULL: the rows are rows over the ReLU layer above g (dense rows only when g has few input channels, i.e. is
+// the network's first layer) and that layer's sign-split step with the bias fold of g is applied as the rows are loaded; the row constants it adds go
 // to *slots_used slots part[k * part_stride + m], k < *slots_used <= max_slots, which the consumer adds in index
 // order.  Returns false, launching nothing, when the product-then-gather kernel cannot take the shape.
 struct ReluOnLoad {
@@ -79,6 +79,7 @@ struct ReluOnLoad {
     const float* bias_c;             // bias of g per output channel
     float* part; long long part_stride; int max_slots;
     int R, batch;                    // rows are [side][input][R]
+    const PatchGeom* form;           // patch rows: their geometry over the ReLU layer; NULL: dense rows
 };
 bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
                                 const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s,

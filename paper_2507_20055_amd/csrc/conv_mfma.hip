@@ -43,14 +43,26 @@ struct CtArgs {
     int rowstride;   // LDS floats per input row patch (ih*iw*pstride)
 };
 
-template <int NT>
-__global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs a)
+// RELU variants: the sign-split ReLU step of the layer above the convolution (with the bias fold of the convolution) is
+// applied to the rows while their patches are staged in LDS; the constants it adds go to part[m] (one slot).
+struct CtRelu {
+    const float2* pk2; int ldpk;          // (mu, nu with lambda in the sign bit) [batch][ldpk], index (gy*gw + gx)*Co + c
+    const float* bias_c;                  // [Co]
+    float* part;                          // [M]
+    int R, batch;                         // rows are [side][input][R]
+    int patch, rows_C, rows_W, pS, pP;    // patch rows: origin of row r's patch = ((r/rows_C/rows_W)*pS - pP, ((r/rows_C)%rows_W)*pS - pP)
+    int gh, gw;                           // grid of the ReLU layer
+};
+
+template <int NT, bool RELU>
+__global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs a, CtRelu rl)
 {
     extern __shared__ float4 lds4[];
     float* sIn = reinterpret_cast<float*>(lds4);                       // [RB*rowstride] + zero block [pstride]
     const int in_floats = a.RB * a.rowstride;
     const int zoff = in_floats;                                        // zero block
     int4* sTab = reinterpret_cast<int4*>(sIn + in_floats + a.pstride); // [256] {e0, py0, px0, outoff}
+    float* sRed = reinterpret_cast<float*>(sTab + kCtEntries);         // RELU: [RB][4] partial row constants
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
     const long long m0 = (long long)blockIdx.x * a.RB;
@@ -74,6 +86,74 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
         }
     };
 
+    // RELU staging: a wavefront takes a row at a time (4 / RB wavefronts share a row when the workgroup has fewer than four
+    // rows), so a row's side, input and patch origin are scalars and its constant is one wavefront reduction in a fixed
+    // order.  Positions off the layer's grid (zero padding: no neuron) are staged as zeros.
+    const unsigned long long magic_iw = (1ull << 32) / (unsigned)max(a.iw, 1) + 1;
+    auto stage_input_relu = [&](int c0) __attribute__((always_inline)) {
+        const int span = npos * cc4n;
+        const int wpr = a.RB >= 4 ? 1 : a.RB == 2 ? 2 : a.RB == 1 ? 4 : 1, pw = wave % wpr;
+        for (int ml = wave / wpr; ml < a.RB; ml += 4 / wpr) {
+            const bool rowok = m0 + ml < a.M;
+            const int m = rowok ? (int)(m0 + ml) : 0;                  // M < 2^31 (checked on the host)
+            const int g = m / rl.R, r = m - g * rl.R;
+            const bool upper_side = g >= rl.batch;
+            const int b = g - (upper_side ? rl.batch : 0);
+            int oy = 0, ox = 0;
+            if (rl.patch) {
+                const int wo = (r / rl.rows_C) % rl.rows_W, ho = r / (rl.rows_C * rl.rows_W);
+                oy = ho * rl.pS - rl.pP;
+                ox = wo * rl.pS - rl.pP;
+            }
+            const float* row = a.in + (size_t)m * a.ld_in + c0;
+            const float2* par = rl.pk2 + (size_t)b * rl.ldpk + c0;
+            float* dst = sIn + ml * a.rowstride;
+            float acc = 0.0f;
+            for (int i = pw * 64 + lane; i < span; i += 64 * wpr) {
+                const int pos = (int)(((unsigned long long)i * magic_cc4n) >> 32), c4 = i - pos * cc4n;
+                const int py = (int)(((unsigned long long)pos * magic_iw) >> 32), px = pos - py * a.iw;
+                const int gy = oy + py, gx = ox + px;
+                float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (rowok && gy >= 0 && gy < rl.gh && gx >= 0 && gx < rl.gw) {
+                    const float4 x4 = *reinterpret_cast<const float4*>(row + (size_t)pos * a.Co + c4 * 4);
+                    const float2* q = par + (size_t)(gy * rl.gw + gx) * a.Co + c4 * 4;
+                    const float4 p01 = *reinterpret_cast<const float4*>(q), p23 = *reinterpret_cast<const float4*>(q + 2);
+                    const float4 b4 = *reinterpret_cast<const float4*>(rl.bias_c + c0 + c4 * 4);
+                    const float x[4] = {x4.x, x4.y, x4.z, x4.w}, mu[4] = {p01.x, p01.z, p23.x, p23.z};
+                    const float nl[4] = {p01.y, p01.w, p23.y, p23.w}, bs[4] = {b4.x, b4.y, b4.z, b4.w};
+                    float o[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        // the part of x on which this side takes the upper relaxation is p, the rest n:
+                        //   y = p * mu + lambda * n,   constant += p * (mu * bias + nu) + lambda * n * bias
+                        const float p = upper_side ? fmaxf(x[k], 0.0f) : fminf(x[k], 0.0f);
+                        const float n = x[k] - p;
+                        const float ln = __uint_as_float(__float_as_uint(n) & (unsigned)((int)__float_as_uint(nl[k]) >> 31));
+                        o[k] = fmaf(p, mu[k], ln);
+                        acc = fmaf(ln, bs[k], fmaf(p, fmaf(mu[k], bs[k], fabsf(nl[k])), acc));
+                    }
+                    y = make_float4(o[0], o[1], o[2], o[3]);
+                }
+                *reinterpret_cast<float4*>(dst + pos * a.pstride + c4 * 4) = y;
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+            if (lane == 0) sRed[ml * 4 + pw] = acc;
+        }
+    };
+    // after the barrier behind a staging: the row constants of the staged channels, added once per row by the
+    // workgroups with blockIdx.y == 0 while they stage for their first class
+    bool consts_pending = RELU && blockIdx.y == 0;
+    auto add_consts = [&](bool first_chunk) __attribute__((always_inline)) {
+        if (!consts_pending) return;
+        const int wpr = a.RB >= 4 ? 1 : a.RB == 2 ? 2 : a.RB == 1 ? 4 : 1;
+        if (tid < a.RB && m0 + tid < a.M) {
+            float t = 0.0f;
+            for (int k = 0; k < wpr; ++k) t += sRed[tid * 4 + k];
+            rl.part[m0 + tid] = first_chunk ? t : rl.part[m0 + tid] + t;
+        }
+    };
+
     for (int i = tid; i < a.pstride; i += kCtThreads) sIn[zoff + i] = 0.0f;
     if (blockIdx.y == 0) {           // padding columns of the output rows
         const int elems = a.oh * a.ow * a.Ci, padn = a.ld_out - elems;
@@ -82,8 +162,12 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
             if (m0 + ml < a.M) a.out[(m0 + ml) * a.ld_out + elems + c] = 0.0f;
         }
     }
-    if (nchunks == 1) stage_input(0);
+    if (nchunks == 1) {
+        if constexpr (RELU) stage_input_relu(0);
+        else stage_input(0);
+    }
     __syncthreads();
+    if (nchunks == 1) { add_consts(true); consts_pending = false; }
 
     // kernel values straight from global memory (the whole kernel is a few hundred KB and is read by every
     // workgroup, so it lives in L2): lane (kq, l32) needs K[tap][co = 8g+4kq+s][ci = 32n + l32], s = 0..3
@@ -150,8 +234,10 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
             for (int cc = 0; cc < nchunks; ++cc) {
                 if (nchunks > 1) {
                     __syncthreads();                              // everyone is done with the previous chunk
-                    stage_input(cc * a.CC);
+                    if constexpr (RELU) stage_input_relu(cc * a.CC);
+                    else stage_input(cc * a.CC);
                     __syncthreads();
+                    add_consts(cc == 0);
                 }
                 const int nit = ntaps * ngr;                      // flattened (tap, group) iterations
                 // Kernel values through a buffer resource (one lane offset, scalar offsets for the rest), fetched three
@@ -248,6 +334,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                             if (ci_ok[n]) obase[oo + n * 32 + l32] = acc[t][n][4 * i + j];
                     }
             __syncthreads();          // the table is rebuilt by the next class
+            if (nchunks > 1) consts_pending = false;              // every chunk has been staged once
         }
     }
 }
@@ -587,7 +674,8 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
                                 const ReluOnLoad* relu, int* slots_used)
 {
     if (g.Co % 8 != 0 || ld_in % 4 != 0 || ((uintptr_t)in % 16) != 0) return false;
-    if (relu && (g.Ci > 4 || conv_algo() != 0)) return false;              // only the product-then-gather kernel applies it
+    if (relu && conv_algo() != 0) return false;
+    if (relu && g.Ci <= 4 && relu->form) return false;                     // few input channels: dense rows only
     CtArgs a{};
     a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
     a.taps = w.taps; a.Ci = g.Ci; a.kh = g.kh; a.kw = g.kw; a.s = g.stride; a.off = off;
@@ -667,7 +755,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
             return true;
         }
     }
-    if (relu) return false;
+    if (relu && g.Ci <= 4) return false;
 
     if (g.Ci <= 4) {
         // output rows per workgroup: about 256 positions; input rows those can reach: yr/s + (kh-1)/s + 2
@@ -702,7 +790,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     int RB = std::max(1, kCtEntries / std::max(Pc_max, 1));
     // channel chunk: all channels if two workgroups then fit a CU, otherwise the largest divisor of Co that does
     int CC = g.Co;
-    auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 16; };
+    auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 16 + (relu ? (size_t)rb * 16 : 0); };
     while (CC > 8 && lds_for(RB, CC) > 72 * 1024 && (CC / 2) % 8 == 0) CC /= 2;
     while (RB > 1 && lds_for(RB, CC) > 72 * 1024) --RB;
     if (lds_for(RB, CC) > kLdsBudget) return false;
@@ -710,17 +798,30 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     a.pstride = CC + 4;
     a.rowstride = ih * iw * a.pstride;
     const size_t row_bytes2 = (size_t)a.rowstride * 4;
-    const size_t fixed = (size_t)a.pstride * 4 + 256 * 16;
+    const size_t fixed = (size_t)a.pstride * 4 + 256 * 16 + (relu ? (size_t)RB * 16 : 0);
     a.RB = RB;
+    CtRelu rl{};
+    if (relu) {
+        const int gh = relu->form ? relu->form->gh : ih, gw = relu->form ? relu->form->gw : iw;
+        if (M >= ((int64_t)1 << 31) || relu->max_slots < 1 || relu->ldpk < gh * gw * g.Co || ((uintptr_t)relu->pk2 % 16) != 0 ||
+            relu->part_stride < M || g.Co % 4 != 0 || relu->ldpk % 2 != 0 || ((uintptr_t)relu->bias_c % 16) != 0 || !relu->bias_c ||
+            relu->R < 1 || relu->batch < 1 || (M != (int64_t)relu->R * relu->batch && M != 2 * (int64_t)relu->R * relu->batch) ||
+            (relu->form && (relu->form->rows_C < 1 || relu->form->rows_W < 1 || relu->R % (relu->form->rows_C * relu->form->rows_W) != 0 ||
+                            relu->form->C != g.Co || relu->form->ph != ih || relu->form->pw != iw)))
+            return false;
+        rl = CtRelu{reinterpret_cast<const float2*>(relu->pk2), relu->ldpk, relu->bias_c, relu->part, relu->R, relu->batch,
+                    relu->form ? 1 : 0, relu->form ? relu->form->rows_C : 1, relu->form ? relu->form->rows_W : 1,
+                    relu->form ? relu->form->S : 1, relu->form ? relu->form->P : 0, gh, gw};
+        *slots_used = 1;
+    }
     const size_t lds = (size_t)RB * row_bytes2 + fixed;
     dim3 grid((unsigned)ceil_div(M, RB), (unsigned)ceil_div((int64_t)RB * Pc_max, kCtEntries));
-    if (NT == 1) {
-        ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<1>), (int)kLdsBudget);
-        hipLaunchKernelGGL(conv_transpose_mfma_kernel<1>, grid, dim3(kCtThreads), lds, s, a);
-    } else {
-        ensure_dynamic_lds(reinterpret_cast<const void*>(&conv_transpose_mfma_kernel<2>), (int)kLdsBudget);
-        hipLaunchKernelGGL(conv_transpose_mfma_kernel<2>, grid, dim3(kCtThreads), lds, s, a);
-    }
+    auto launch = [&](auto kern) {
+        ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kLdsBudget);
+        hipLaunchKernelGGL(kern, grid, dim3(kCtThreads), lds, s, a, rl);
+    };
+    if (NT == 1) { if (relu) launch(&conv_transpose_mfma_kernel<1, true>); else launch(&conv_transpose_mfma_kernel<1, false>); }
+    else         { if (relu) launch(&conv_transpose_mfma_kernel<2, true>); else launch(&conv_transpose_mfma_kernel<2, false>); }
     DPC_HIP(hipGetLastError());
     return true;
 }
