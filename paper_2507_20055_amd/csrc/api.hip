@@ -131,6 +131,7 @@ struct dpc_network {
     std::vector<std::unique_ptr<DevBuf<float>>> pk;
     DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
     std::vector<std::unique_ptr<DevBuf<float>>> pk2v;      // the same for ReLU layers above a convolution with > 4 input channels
+    DevBuf<float> rpart;                   // one constant per row from a ReLU step applied inside a convolution kernel
     std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
     int skip_depth = 0;                    // how many skip connections span one layer at most
     DevBuf<float> part;
@@ -478,13 +479,13 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             }
         }
         if (L.kind == RELU && at >= 3 && !shared && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.opt->fuse &&
-            (maxd < 0 || depth + 2 <= maxd) && (int)net->pk2v.size() > at && net->pk2v[at] && net->pk2v[at]->p && net->part.p &&
-            M <= net->part_stride && slots < dpc_network::kMaxSlots && !blocked(at - 1)) {
+            (maxd < 0 || depth + 2 <= maxd) && (int)net->pk2v.size() > at && net->pk2v[at] && net->pk2v[at]->p && net->rpart.p &&
+            (size_t)M <= net->rpart.count && !blocked(at - 1)) {
             // ReLU step applied while the transposed convolution below stages the rows (no pass of its own over them); the
             // constants it adds come back in one slot and are folded into the row constants right away
             const Layer& cv = *net->layers[at - 2];
-            const ReluOnLoad rl{net->pk2v[at]->p, net->ld_of(at), cv.cw.bias_c, net->part.p + (size_t)slots * net->part_stride,
-                                net->part_stride, dpc_network::kMaxSlots - slots, R, B, f.patch ? &f.pg : nullptr};
+            const ReluOnLoad rl{net->pk2v[at]->p, net->ld_of(at), cv.cw.bias_c, net->rpart.p, (int64_t)net->rpart.count, 1, R, B,
+                                f.patch ? &f.pg : nullptr};
             int used = 0;
             bool done;
             Form o = f;
@@ -497,7 +498,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 done = launch_conv_transpose_fast(cur, M, f.ld, cv.g.Ho, cv.g.Wo, cv.g, cv.cw, nxt, o.ld, cv.g.H, cv.g.W, cv.g.pad, P.s, &rl,
                                                   &used);
             }
-            if (done) launch_fold_slots(cst, net->part.p + (size_t)slots * net->part_stride, used, net->part_stride, M, P.s);
+            if (done) launch_fold_slots(cst, net->rpart.p, used, (int64_t)net->rpart.count, M, P.s);
             P.prof->end();
             if (done) {
                 const double pos = f.patch ? (double)f.pg.ph * f.pg.pw : (double)cv.g.Ho * cv.g.Wo;
@@ -1032,6 +1033,13 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             if (nl >= 3 && net->layers[0]->kind == CONV && net->layers[0]->g.Ci <= 4 && net->layers[1]->kind == RELU)
                 moved |= net->pk2.reserve((size_t)B * net->ld_of(2) * 2);
             if ((int)net->pk2v.size() != nl + 1) net->pk2v.resize(nl + 1);
+            size_t rrows = 0;
+            for (int i = 3; i <= nl; ++i)
+                if (net->layers[i - 1]->kind == RELU && net->layers[i - 2]->kind == CONV && net->layers[i - 2]->g.Ci > 4)
+                    for (int k = i + 1; k <= nl; ++k)
+                        if (net->layers[k - 1]->kind != RELU) rrows = std::max(rrows, 2 * (size_t)B * net->size_of(k));
+            if (label) rrows = std::max(rrows, 2 * (size_t)B * RsMax);
+            if (rrows > 0) moved |= net->rpart.reserve(rrows);
             for (int i = 3; i <= nl; ++i) {
                 if (net->layers[i - 1]->kind != RELU || net->layers[i - 2]->kind != CONV || net->layers[i - 2]->g.Ci <= 4) continue;
                 if (!net->pk2v[i]) net->pk2v[i].reset(new DevBuf<float>());
