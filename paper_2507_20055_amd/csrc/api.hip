@@ -461,7 +461,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             // loads the rows (no pass of its own over them); the constants it adds arrive in slots
             const Layer& first = *net->layers[0];
             const ReluOnLoad rl{net->pk2.p, net->ld_of(2), first.cw.bias_c, net->part.p + (size_t)slots * net->part_stride,
-                                net->part_stride, dpc_network::kMaxSlots - slots, R, B, nullptr};
+                                net->part_stride, dpc_network::kMaxSlots - slots, R, B, nullptr, 0};
             int used = 0;
             P.prof->begin(P_CONTRACT);
             const bool done = launch_conv_transpose_fast(cur, M, f.ld, first.g.Ho, first.g.Wo, first.g, first.cw, nxt, net->ld_of(0),
@@ -478,27 +478,31 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 break;
             }
         }
-        if (L.kind == RELU && at >= 3 && !shared && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.opt->fuse &&
+        if (L.kind == RELU && at >= 3 && (!shared || cst_init) && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.opt->fuse &&
             (maxd < 0 || depth + 2 <= maxd) && (int)net->pk2v.size() > at && net->pk2v[at] && net->pk2v[at]->p && net->rpart.p &&
             (size_t)M <= net->rpart.count && !blocked(at - 1)) {
             // ReLU step applied while the transposed convolution below stages the rows (no pass of its own over them); the
             // constants it adds come back in one slot and are folded into the row constants right away
             const Layer& cv = *net->layers[at - 2];
+            // rows still shared by all inputs (first step of a pass): patch cores repeat every rows_C rows, weight rows every R
+            const int in_mod = shared ? (f.patch ? f.pg.rows_C : R) : 0;
+            const float* src = shared ? shared : cur;
+            const int ld_src = shared ? ld_shared : f.ld;
             const ReluOnLoad rl{net->pk2v[at]->p, net->ld_of(at), cv.cw.bias_c, net->rpart.p, (int64_t)net->rpart.count, 1, R, B,
-                                f.patch ? &f.pg : nullptr};
+                                f.patch ? &f.pg : nullptr, in_mod};
             int used = 0;
             bool done;
             Form o = f;
             P.prof->begin(P_CONTRACT);
             if (f.patch) {
                 o = through_conv(f, cv.g);
-                done = launch_conv_transpose_fast(cur, M, f.ld, f.pg.ph, f.pg.pw, cv.g, cv.cw, nxt, o.ld, o.pg.ph, o.pg.pw, 0, P.s, &rl, &used);
+                done = launch_conv_transpose_fast(src, M, ld_src, f.pg.ph, f.pg.pw, cv.g, cv.cw, nxt, o.ld, o.pg.ph, o.pg.pw, 0, P.s, &rl, &used);
             } else {
                 o.ld = net->ld_of(at - 2);
-                done = launch_conv_transpose_fast(cur, M, f.ld, cv.g.Ho, cv.g.Wo, cv.g, cv.cw, nxt, o.ld, cv.g.H, cv.g.W, cv.g.pad, P.s, &rl,
+                done = launch_conv_transpose_fast(src, M, ld_src, cv.g.Ho, cv.g.Wo, cv.g, cv.cw, nxt, o.ld, cv.g.H, cv.g.W, cv.g.pad, P.s, &rl,
                                                   &used);
             }
-            if (done) launch_fold_slots(cst, net->rpart.p, used, (int64_t)net->rpart.count, M, P.s);
+            if (done) launch_fold_slots(cst, net->rpart.p, used, (int64_t)net->rpart.count, M, P.s, shared ? cst_init : nullptr, in_mod);
             P.prof->end();
             if (done) {
                 const double pos = f.patch ? (double)f.pg.ph * f.pg.pw : (double)cv.g.Ho * cv.g.Wo;
@@ -506,6 +510,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 res->prof.contract_launches++;
                 std::swap(cur, nxt);
                 f = o;
+                shared = nullptr;
                 bias_folded = false;
                 fused_relu = false;
                 at -= 2;

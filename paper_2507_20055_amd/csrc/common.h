@@ -149,7 +149,8 @@ void launch_block_bound(double* cst, int64_t M, int R, int rows_C, int rows_W, i
                         const float* src, int ld_src, const float* lo, const float* hi, int patch, int ph, int pw, int C, int S,
                         int P, int gh, int gw, hipStream_t s);
 void launch_add_vectors(const float* a, const float* b, float* out, int64_t n, hipStream_t s);
-void launch_fold_slots(double* cst, const float* part, int nslots, int64_t stride, int64_t M, hipStream_t s);
+void launch_fold_slots(double* cst, const float* part, int nslots, int64_t stride, int64_t M, hipStream_t s, const float* init = nullptr,
+                       int init_mod = 0);
 void launch_fill_zero(float* p, int64_t n, hipStream_t s);     // a kernel, so that captured launch sequences hold no memset node
 // pk2[b][c] = (mu, nu with lambda in its sign bit: negative = 1), float2; columns n..ld-1 zero.
 void launch_pack_relax2(const float* lambda, const float* mu, const float* nu, int batch, int n, int ld, float* pk2,

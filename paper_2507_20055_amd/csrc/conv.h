@@ -79,7 +79,7 @@ struct ReluOnLoad {
     const float* bias_c;             // bias of g per output channel
     float* part; long long part_stride; int max_slots;
     int R, batch;                    // rows are [side][input][R]
-    const PatchGeom* form;           // patch rows: their geometry over the ReLU layer; NULL: dense rows
+    const PatchGeom* form; int in_mod;           // patch rows: their geometry over the ReLU layer; NULL: dense rows
 };
 bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, int iw, const ConvGeom& g,
                                 const ConvWeights& w, float* out, int ld_out, int oh, int ow, int off, hipStream_t s,

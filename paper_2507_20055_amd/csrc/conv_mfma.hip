@@ -52,6 +52,7 @@ struct CtRelu {
     int R, batch;                         // rows are [side][input][R]
     int patch, rows_C, rows_W, pS, pP;    // patch rows: origin of row r's patch = ((r/rows_C/rows_W)*pS - pP, ((r/rows_C)%rows_W)*pS - pP)
     int gh, gw;                           // grid of the ReLU layer
+    int in_mod;                           // > 0: rows shared by all inputs and sides, row m reads input row m % in_mod
 };
 
 template <int NT, bool RELU>
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                 oy = ho * rl.pS - rl.pP;
                 ox = wo * rl.pS - rl.pP;
             }
-            const float* row = a.in + (size_t)m * a.ld_in + c0;
+            const float* row = a.in + (size_t)(rl.in_mod > 0 ? m % rl.in_mod : m) * a.ld_in + c0;
             const float2* par = rl.pk2 + (size_t)b * rl.ldpk + c0;
             float* dst = sIn + ml * a.rowstride;
             float acc = 0.0f;
@@ -675,7 +676,8 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
 {
     if (g.Co % 8 != 0 || ld_in % 4 != 0 || ((uintptr_t)in % 16) != 0) return false;
     if (relu && conv_algo() != 0) return false;
-    if (relu && g.Ci <= 4 && relu->form) return false;                     // few input channels: dense rows only
+    if (relu && g.Ci <= 4 && (relu->form || relu->in_mod)) return false;   // few input channels: per-input dense rows only
+    if (relu && (int64_t)ld_in < (int64_t)ih * iw * g.Co) return false;
     CtArgs a{};
     a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
     a.taps = w.taps; a.Ci = g.Ci; a.kh = g.kh; a.kw = g.kw; a.s = g.stride; a.off = off;
@@ -805,13 +807,13 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         const int gh = relu->form ? relu->form->gh : ih, gw = relu->form ? relu->form->gw : iw;
         if (M >= ((int64_t)1 << 31) || relu->max_slots < 1 || relu->ldpk < gh * gw * g.Co || ((uintptr_t)relu->pk2 % 16) != 0 ||
             relu->part_stride < M || g.Co % 4 != 0 || relu->ldpk % 2 != 0 || ((uintptr_t)relu->bias_c % 16) != 0 || !relu->bias_c ||
-            relu->R < 1 || relu->batch < 1 || (M != (int64_t)relu->R * relu->batch && M != 2 * (int64_t)relu->R * relu->batch) ||
+            relu->R < 1 || relu->batch < 1 || relu->in_mod < 0 || (relu->in_mod > 0 && relu->R % relu->in_mod != 0) || (M != (int64_t)relu->R * relu->batch && M != 2 * (int64_t)relu->R * relu->batch) ||
             (relu->form && (relu->form->rows_C < 1 || relu->form->rows_W < 1 || relu->R % (relu->form->rows_C * relu->form->rows_W) != 0 ||
                             relu->form->C != g.Co || relu->form->ph != ih || relu->form->pw != iw)))
             return false;
         rl = CtRelu{reinterpret_cast<const float2*>(relu->pk2), relu->ldpk, relu->bias_c, relu->part, relu->R, relu->batch,
                     relu->form ? 1 : 0, relu->form ? relu->form->rows_C : 1, relu->form ? relu->form->rows_W : 1,
-                    relu->form ? relu->form->S : 1, relu->form ? relu->form->P : 0, gh, gw};
+                    relu->form ? relu->form->S : 1, relu->form ? relu->form->P : 0, gh, gw, relu->in_mod};
         *slots_used = 1;
     }
     const size_t lds = (size_t)RB * row_bytes2 + fixed;

@@ -854,21 +854,23 @@ void launch_fill_zero(float* p, int64_t n, hipStream_t s)
 }
 
 // cst[m] += sum over k < nslots of part[k * stride + m], in index order
+// (init given: cst[m] = init[m % init_mod] + that sum, the rows' first constants)
 __global__ __launch_bounds__(kThreads) void fold_slots_kernel(double* __restrict__ cst, const float* __restrict__ part, int nslots,
-                                                              long long stride, int64_t M)
+                                                              long long stride, int64_t M, const float* __restrict__ init, int init_mod)
 {
     const int64_t m = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (m >= M) return;
     double t = 0.0;
     for (int k = 0; k < nslots; ++k) t += (double)part[(size_t)k * stride + m];
-    cst[m] += t;
+    cst[m] = (init ? (double)init[m % init_mod] : cst[m]) + t;
 }
 
-void launch_fold_slots(double* cst, const float* part, int nslots, int64_t stride, int64_t M, hipStream_t s)
+void launch_fold_slots(double* cst, const float* part, int nslots, int64_t stride, int64_t M, hipStream_t s, const float* init, int init_mod)
 {
-    DPC_REQUIRE(cst && part && nslots >= 0 && stride >= M && M >= 0, DPC_EINVAL, "fold_slots: bad arguments");
-    if (M == 0 || nslots == 0) return;
-    hipLaunchKernelGGL(fold_slots_kernel, dim3((unsigned)ceil_div(M, kThreads)), dim3(kThreads), 0, s, cst, part, nslots, (long long)stride, M);
+    DPC_REQUIRE(cst && part && nslots >= 0 && stride >= M && M >= 0 && (!init || init_mod > 0), DPC_EINVAL, "fold_slots: bad arguments");
+    if (M == 0 || (nslots == 0 && !init)) return;
+    hipLaunchKernelGGL(fold_slots_kernel, dim3((unsigned)ceil_div(M, kThreads)), dim3(kThreads), 0, s, cst, part, nslots, (long long)stride, M,
+                       init, init_mod);
     DPC_HIP(hipGetLastError());
 }
 
