@@ -29,6 +29,7 @@ namespace dpc {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float vf4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCtThreads = 256;
 constexpr int kCtEntries = 256;          // list entries per class per workgroup (4 waves x 2 tiles x 32)
@@ -73,17 +74,35 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const int cc4n = a.CC >> 2;
     const unsigned long long magic_cc4n = (1ull << 32) / (unsigned)cc4n + 1, magic_npos = (1ull << 32) / (unsigned)npos + 1;
 
+    // Staging reads go through buffer resources (offsets past the range return zeros: no branches around the loads) and
+    // are issued kStageU at a time before the first LDS write, so a thread has several 16-byte loads in flight.
+    constexpr int kStageU = 4, kStageR = 2;       // plain rows / rows with the ReLU step (four loads each)
+    constexpr int kNoData = (int)0x80000000;
+    const bool in_shared = RELU && rl.in_mod > 0;
+    const long long rows_here = (a.M - m0 < a.RB) ? a.M - m0 : a.RB;
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(in_shared ? a.in : a.in + m0 * a.ld_in), 0, (int)((in_shared ? rl.in_mod : rows_here) * a.ld_in * 4), 0x00020000);
+
     // stage channels [c0, c0 + CC) of the input patches of this workgroup's rows
     auto stage_input = [&](int c0) __attribute__((always_inline)) {
         const int total = a.RB * npos * cc4n;
-        for (int idx = tid; idx < total; idx += kCtThreads) {
-            // quotients by the run-time extents through multiply-high (exact: idx * divisor < 2^32)
-            const int t = (int)(((unsigned long long)idx * magic_cc4n) >> 32), c4 = idx - t * cc4n;
-            const int ml = (int)(((unsigned long long)t * magic_npos) >> 32), pos = t - ml * npos;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m0 + ml < a.M)
-                v = *reinterpret_cast<const float4*>(a.in + (m0 + ml) * a.ld_in + (size_t)pos * a.Co + c0 + c4 * 4);
-            *reinterpret_cast<float4*>(sIn + ml * a.rowstride + pos * a.pstride + c4 * 4) = v;
+        for (int idx0 = tid; idx0 < total; idx0 += kCtThreads * kStageU) {
+            vf4 v[kStageU];
+            int dsto[kStageU];
+#pragma unroll
+            for (int u = 0; u < kStageU; ++u) {
+                const int idx = idx0 + u * kCtThreads;
+                // quotients by the run-time extents through multiply-high (exact: idx * divisor < 2^32)
+                const int t = (int)(((unsigned long long)idx * magic_cc4n) >> 32), c4 = idx - t * cc4n;
+                const int ml = (int)(((unsigned long long)t * magic_npos) >> 32), pos = t - ml * npos;
+                const bool ok = idx < total;                       // rows past M lie past the resource's range
+                v[u] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                   xres, ok ? (ml * a.ld_in + pos * a.Co + c0 + c4 * 4) * 4 : kNoData, 0, 0));
+                dsto[u] = ok ? ml * a.rowstride + pos * a.pstride + c4 * 4 : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < kStageU; ++u)
+                if (dsto[u] >= 0) *reinterpret_cast<vf4*>(sIn + dsto[u]) = v[u];
         }
     };
 
@@ -91,6 +110,8 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     // rows), so a row's side, input and patch origin are scalars and its constant is one wavefront reduction in a fixed
     // order.  Positions off the layer's grid (zero padding: no neuron) are staged as zeros.
     const unsigned long long magic_iw = (1ull << 32) / (unsigned)max(a.iw, 1) + 1;
+    const __amdgpu_buffer_rsrc_t qres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float2*>(rl.pk2), 0, RELU ? rl.batch * rl.ldpk * 8 : 0, 0x00020000);
     auto stage_input_relu = [&](int c0) __attribute__((always_inline)) {
         const int span = npos * cc4n;
         const int wpr = a.RB >= 4 ? 1 : a.RB == 2 ? 2 : a.RB == 1 ? 4 : 1, pw = wave % wpr;
@@ -106,23 +127,35 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                 oy = ho * rl.pS - rl.pP;
                 ox = wo * rl.pS - rl.pP;
             }
-            const float* row = a.in + (size_t)(rl.in_mod > 0 ? m % rl.in_mod : m) * a.ld_in + c0;
-            const float2* par = rl.pk2 + (size_t)b * rl.ldpk + c0;
+            const int xrow = ((in_shared ? m % rl.in_mod : ml) * a.ld_in + c0) * 4;     // bytes within xres
+            const int qrow = (b * rl.ldpk + c0) * 8;                                     // bytes within qres
             float* dst = sIn + ml * a.rowstride;
             float acc = 0.0f;
-            for (int i = pw * 64 + lane; i < span; i += 64 * wpr) {
-                const int pos = (int)(((unsigned long long)i * magic_cc4n) >> 32), c4 = i - pos * cc4n;
-                const int py = (int)(((unsigned long long)pos * magic_iw) >> 32), px = pos - py * a.iw;
-                const int gy = oy + py, gx = ox + px;
-                float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (rowok && gy >= 0 && gy < rl.gh && gx >= 0 && gx < rl.gw) {
-                    const float4 x4 = *reinterpret_cast<const float4*>(row + (size_t)pos * a.Co + c4 * 4);
-                    const float2* q = par + (size_t)(gy * rl.gw + gx) * a.Co + c4 * 4;
-                    const float4 p01 = *reinterpret_cast<const float4*>(q), p23 = *reinterpret_cast<const float4*>(q + 2);
-                    const float4 b4 = *reinterpret_cast<const float4*>(rl.bias_c + c0 + c4 * 4);
-                    const float x[4] = {x4.x, x4.y, x4.z, x4.w}, mu[4] = {p01.x, p01.z, p23.x, p23.z};
-                    const float nl[4] = {p01.y, p01.w, p23.y, p23.w}, bs[4] = {b4.x, b4.y, b4.z, b4.w};
-                    float o[4];
+            for (int i0 = pw * 64 + lane; i0 < span; i0 += 64 * wpr * kStageR) {
+                vf4 x4[kStageR], p01[kStageR], p23[kStageR], b4[kStageR];
+                int dsto[kStageR];
+#pragma unroll
+                for (int u = 0; u < kStageR; ++u) {
+                    const int i = i0 + u * 64 * wpr;
+                    const int pos = (int)(((unsigned long long)i * magic_cc4n) >> 32), c4 = i - pos * cc4n;
+                    const int py = (int)(((unsigned long long)pos * magic_iw) >> 32), px = pos - py * a.iw;
+                    const int gy = oy + py, gx = ox + px;
+                    const bool in = i < span;
+                    const bool ok = in && rowok && gy >= 0 && gy < rl.gh && gx >= 0 && gx < rl.gw;
+                    x4[u] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                        xres, ok ? xrow + (pos * a.Co + c4 * 4) * 4 : kNoData, 0, 0));
+                    const int qo = ok ? qrow + ((gy * rl.gw + gx) * a.Co + c4 * 4) * 8 : kNoData;
+                    p01[u] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(qres, qo, 0, 0));
+                    p23[u] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(qres, qo, 16, 0));
+                    b4[u] = *reinterpret_cast<const vf4*>(rl.bias_c + c0 + (in ? c4 * 4 : 0));
+                    dsto[u] = in ? pos * a.pstride + c4 * 4 : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < kStageR; ++u) {
+                    // off the grid or past the rows: x and the parameters read as zeros, so y = 0 and nothing is added
+                    const float x[4] = {x4[u][0], x4[u][1], x4[u][2], x4[u][3]}, mu[4] = {p01[u][0], p01[u][2], p23[u][0], p23[u][2]};
+                    const float nl[4] = {p01[u][1], p01[u][3], p23[u][1], p23[u][3]}, bs[4] = {b4[u][0], b4[u][1], b4[u][2], b4[u][3]};
+                    vf4 y;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         // the part of x on which this side takes the upper relaxation is p, the rest n:
@@ -130,12 +163,11 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                         const float p = upper_side ? fmaxf(x[k], 0.0f) : fminf(x[k], 0.0f);
                         const float n = x[k] - p;
                         const float ln = __uint_as_float(__float_as_uint(n) & (unsigned)((int)__float_as_uint(nl[k]) >> 31));
-                        o[k] = fmaf(p, mu[k], ln);
+                        y[k] = fmaf(p, mu[k], ln);
                         acc = fmaf(ln, bs[k], fmaf(p, fmaf(mu[k], bs[k], fabsf(nl[k])), acc));
                     }
-                    y = make_float4(o[0], o[1], o[2], o[3]);
+                    if (dsto[u] >= 0) *reinterpret_cast<vf4*>(dst + dsto[u]) = y;
                 }
-                *reinterpret_cast<float4*>(dst + pos * a.pstride + c4 * 4) = y;
             }
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
@@ -461,7 +493,6 @@ __global__ __launch_bounds__(kPThreads) void conv_transpose_p_kernel(
     const int npos = nrows * a.iw, E = a.RB * npos, ntiles = (E + 31) >> 5;
     const int Pout = a.oh * a.ow, elems = Pout * CI, padn = a.ld_out - elems;
     const int span = (ye - yb) * a.ow, total = a.RB * span, nky = (a.kh + S - 1) / S, nkx = (a.kw + S - 1) / S;
-    typedef float vf4 __attribute__((ext_vector_type(4)));
     const unsigned long long magic_span = (1ull << 32) / (unsigned)max(span, 1) + 1;   // e / span for e * span < 2^32
     const unsigned long long magic_ow = (1ull << 32) / (unsigned)max(a.ow, 1) + 1;
     const int zoff = ((a.RB * lds_rows * a.iw + 31) & ~31) * PS;                         // four zeros behind the panel
@@ -678,6 +709,8 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     if (relu && conv_algo() != 0) return false;
     if (relu && g.Ci <= 4 && (relu->form || relu->in_mod)) return false;   // few input channels: per-input dense rows only
     if (relu && (int64_t)ld_in < (int64_t)ih * iw * g.Co) return false;
+    if ((int64_t)ld_in * 4 * 256 >= ((int64_t)1 << 31)) return false;              // staging uses 32-bit byte offsets per workgroup
+    if (relu && ((int64_t)relu->batch * relu->ldpk * 8 >= ((int64_t)1 << 31) || (int64_t)relu->in_mod * ld_in * 4 >= ((int64_t)1 << 31))) return false;
     CtArgs a{};
     a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
     a.taps = w.taps; a.Ci = g.Ci; a.kh = g.kh; a.kw = g.kw; a.s = g.stride; a.off = off;
