@@ -330,6 +330,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     const int ld_shared = own ? (f.patch ? own->cw.ld_core : own->ldw) : 0;
     const float* cst_init = own ? (f.patch ? own->cw.bias_c : own->dBias.p) : nullptr;
     bool bias_folded = false;
+    bool bias_below_add = false;           // the ReLU step above an Add layer has already folded the bias of the layer below the Add
     int depth = depth0;
     const int64_t M = (int64_t)nsides * B * R;
     bool fused_relu = false;
@@ -434,7 +435,8 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 w.src = dst; w.ld = f.ld;
             }
             waiting.push_back(w);
-            bias_folded = false;
+            bias_folded = bias_below_add;
+            bias_below_add = false;
             fused_relu = false;
             --at;
             ++depth;
@@ -522,7 +524,16 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             const Layer& below = *net->layers[at - 2];
             // the bias of the layer below is folded in the same pass unless a block still has to join the rows there
             const bool fold = (maxd < 0 || depth + 2 <= maxd) && !blocked(at - 1);
-            relax(res->lam[at], res->mu[at], res->nu[at], fold ? &below : nullptr);
+            // an Add layer passes the coefficients on unchanged to the layer below it, whose bias can be folded in this
+            // same pass (full traversals only, and only if no block joins the rows between here and there)
+            const Layer* bias_src = &below;
+            bias_below_add = false;
+            if (fold && below.kind == ADD && maxd < 0 && at >= 3 && !blocked(at - 2) &&
+                (net->layers[at - 3]->kind == AFFINE || net->layers[at - 3]->kind == CONV)) {
+                bias_src = net->layers[at - 3].get();
+                bias_below_add = true;
+            }
+            relax(res->lam[at], res->mu[at], res->nu[at], fold ? bias_src : nullptr);
             bias_folded = fold;
         } else {
             if (!bias_folded) relax(nullptr, nullptr, nullptr, &L);   // affine layer entered without a ReLU step above it
