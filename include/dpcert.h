@@ -237,6 +237,8 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
  * coefficient rows resident in LDS (-1 = by problem shape, the default; 0 = never; 1 = whenever the
  * layer widths fit) and "chain_rows" its row block for panels up to 512 columns (64, the default, or 32 with two
  * workgroups per compute unit); "conv_algo" = 2 sends few-input-channel layers to the plain-ALU kernel;
+ * "conv_half_tiles" = 0 keeps 32 x 32 tiles in the matrix-unit convolution kernel also for layers with at most 16
+ * input channels (1, the default, uses 16 x 16 tiles there);
  * "merge_final" = 0 bounds the output layer and the margins in two traversals instead
  * of one; "contract_remap", "rows_per_wave", "rows_stream" select launch shapes of the contraction and
  * row kernels.  Results do not depend on any of them beyond rounding order.

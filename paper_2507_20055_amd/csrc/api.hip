@@ -1513,6 +1513,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
         else if (strcmp(key, "contract_remap") == 0) set_contract_remap(value);
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
+        else if (strcmp(key, "conv_half_tiles") == 0) set_conv_half_tiles(value);
         else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
         else if (strcmp(key, "chain") == 0) set_chain_mode(value);
         else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);

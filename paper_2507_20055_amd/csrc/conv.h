@@ -103,6 +103,8 @@ bool launch_patch_tail(const PatchTail& d, hipStream_t s);
 
 void set_conv_algo(int v);
 int conv_algo();
+void set_conv_half_tiles(int v);
+int conv_half_tiles();
 
 // Validation of certify inputs on the device.  Returns 0 = fine, 1 = lo > hi or non-finite, 2 = bad label.
 // `flag` is a device int32 scratch word.  Synchronises the stream.

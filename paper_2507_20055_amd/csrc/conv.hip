@@ -268,6 +268,9 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
 
 void set_conv_algo(int v) { g_conv_algo = v; }
 int conv_algo() { return g_conv_algo; }
+static int g_conv_half_tiles = 1;   // 1: 16 x 16 tiles in the MFMA kernel for layers with at most 16 input channels; 0: 32 x 32 always
+void set_conv_half_tiles(int v) { g_conv_half_tiles = v; }
+int conv_half_tiles() { return g_conv_half_tiles; }
 
 int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
                  int32_t* flag, hipStream_t s)

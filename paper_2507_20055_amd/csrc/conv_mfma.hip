@@ -66,7 +66,17 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     int4* sTab = reinterpret_cast<int4*>(sIn + in_floats + a.pstride); // [256] {e0, py0, px0, outoff}
     float* sRed = reinterpret_cast<float*>(sTab + kCtEntries);         // RELU: [RB][4] partial row constants
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
+    // NT = 0: at most 16 input channels.  Tiles are then 16 entries x 16 channels (16x16x4 MFMA, four tiles per wavefront,
+    // groups of 16 reduction channels) instead of 32 x 32 (32x32x2, two tiles, groups of 8): half of every 32-column
+    // tile would be padding otherwise.
+    constexpr bool HALF = NT == 0;
+    constexpr int NTN = HALF ? 1 : NT;            // accumulators per tile
+    constexpr int TT = HALF ? 4 : 2;              // tiles per wavefront
+    constexpr int TE = HALF ? 16 : 32;            // list entries per tile
+    constexpr int GC = HALF ? 16 : 8;             // reduction channels per (tap, group) step
+    constexpr int AV = HALF ? 4 : 16;             // accumulator registers per tile
+    using AccT = typename std::conditional<HALF, vf4, floatx16>::type;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & (TE - 1), kq = lane / TE;
     const long long m0 = (long long)blockIdx.x * a.RB;
     const int q0 = blockIdx.y * kCtEntries;
     const int npos = a.ih * a.iw;
@@ -204,10 +214,10 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 
     // kernel values straight from global memory (the whole kernel is a few hundred KB and is read by every
     // workgroup, so it lives in L2): lane (kq, l32) needs K[tap][co = 8g+4kq+s][ci = 32n + l32], s = 0..3
-    bool ci_ok[NT];
-    int kvoff[NT];                                    // byte offset of this lane's kernel column (clamped into range)
+    bool ci_ok[NTN];
+    int kvoff[NTN];                                   // byte offset of this lane's kernel column (clamped into range)
 #pragma unroll
-    for (int n = 0; n < NT; ++n) {
+    for (int n = 0; n < NTN; ++n) {
         ci_ok[n] = n * 32 + l32 < a.Ci;
         kvoff[n] = (4 * kq * a.Ci + min(n * 32 + l32, a.Ci - 1)) * 4;
     }
@@ -247,23 +257,23 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
             }
             __syncthreads();
 
-            int e0[2], py0[2], px0[2];
-            bool live[2];
+            int e0[TT], py0[TT], px0[TT];
+            bool live[TT];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int4 e = sTab[wave * 64 + t * 32 + l32];
+            for (int t = 0; t < TT; ++t) {
+                const int4 e = sTab[wave * 64 + t * TE + l32];
                 e0[t] = e.x + 4 * kq; py0[t] = e.y; px0[t] = e.z; live[t] = e.w >= 0;
             }
-            floatx16 acc[2][NT];
+            AccT acc[TT][NTN];
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < TT; ++t)
 #pragma unroll
-                for (int n = 0; n < NT; ++n)
+                for (int n = 0; n < NTN; ++n)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[t][n][v] = 0.0f;
+                    for (int v = 0; v < AV; ++v) acc[t][n][v] = 0.0f;
 
             const int ntaps = nky * nkx;
-            const int ngr = a.CC >> 3;                            // groups of 8 channels per chunk
+            const int ngr = a.CC / GC;                            // groups of 8 (16) channels per chunk
             for (int cc = 0; cc < nchunks; ++cc) {
                 if (nchunks > 1) {
                     __syncthreads();                              // everyone is done with the previous chunk
@@ -283,12 +293,12 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                     return (((cy + a.s * jy) * a.kw + (cx + a.s * jx)) * a.Co + cc * a.CC) * a.Ci * 4;   // bytes, wave-uniform
                 };
                 int lg = 0, ljx = 0, ljy = 0, lbase = tap_off(0, 0);      // (group, tap) of the next load
-                auto load_b = [&](float (&bb)[4][NT]) __attribute__((always_inline)) {
-                    const int so = lbase + lg * 8 * a.Ci * 4;
+                auto load_b = [&](float (&bb)[4][NTN]) __attribute__((always_inline)) {
+                    const int so = lbase + lg * GC * a.Ci * 4;
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
-                        for (int n = 0; n < NT; ++n) {
+                        for (int n = 0; n < NTN; ++n) {
                             // columns past Ci read a clamped (valid) column: they only feed accumulator columns that
                             // are never stored, and touching the value here would force a wait right behind the load
                             bb[s][n] = __builtin_bit_cast(
@@ -300,37 +310,44 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                         lbase = tap_off(ljy, ljx);
                     }
                 };
-                int addr[2] = {zoff + 4 * kq, zoff + 4 * kq};
+                int addr[TT];
+#pragma unroll
+                for (int t = 0; t < TT; ++t) addr[t] = zoff + 4 * kq;
                 int sg = 0, sjx = 0, sjy = 0;                              // (group, tap) of the next step
-                auto step = [&](float (&bb)[4][NT]) __attribute__((always_inline)) {
+                auto step = [&](float (&bb)[4][NTN]) __attribute__((always_inline)) {
                     const int g = sg;
                     if (g == 0) {
                         const int jy = sjy, jx = sjx;
 #pragma unroll
-                        for (int t = 0; t < 2; ++t) {
+                        for (int t = 0; t < TT; ++t) {
                             const int py = py0[t] - jy, px = px0[t] - jx;
                             const bool ok = live[t] && py >= 0 && py < a.ih && px >= 0 && px < a.iw;
                             addr[t] = ok ? e0[t] - (jy * a.iw + jx) * a.pstride : zoff + 4 * kq;
                         }
                     }
-                    float4 av[2];
+                    float4 av[TT];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) av[t] = *reinterpret_cast<const float4*>(sIn + addr[t] + 8 * g);
+                    for (int t = 0; t < TT; ++t) av[t] = *reinterpret_cast<const float4*>(sIn + addr[t] + GC * g);
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
 #pragma unroll
-                        for (int t = 0; t < 2; ++t) {
+                        for (int t = 0; t < TT; ++t) {
                             const float x = s == 0 ? av[t].x : s == 1 ? av[t].y : s == 2 ? av[t].z : av[t].w;
+                            if constexpr (HALF) {
+                                // lane (kq, l) holds A[entry l][k = kq] and B[k = kq][channel l]: k runs over channels 16g + 4kq + s
+                                acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(x, bb[s][0], acc[t][0], 0, 0, 0);
+                            } else {
 #pragma unroll
-                            for (int n = 0; n < NT; ++n)
-                                acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, bb[s][n], acc[t][n], 0, 0, 0);
+                                for (int n = 0; n < NTN; ++n)
+                                    acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, bb[s][n], acc[t][n], 0, 0, 0);
+                            }
                         }
                     if (++sg == ngr) {
                         sg = 0;
                         if (++sjx == nkx) { sjx = 0; ++sjy; }
                     }
                 };
-                float b0[4][NT], b1[4][NT], b2[4][NT], b3[4][NT];
+                float b0[4][NTN], b1[4][NTN], b2[4][NTN], b3[4][NTN];
                 if (nit > 0) load_b(b0);
                 if (nit > 1) load_b(b1);
                 if (nit > 2) load_b(b2);
@@ -354,6 +371,17 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 
             // ---- epilogue: accumulator register 4*i+j of a lane is list entry 8*i + 4*kq + j, channel l32 ----
             float* obase = a.out + m0 * a.ld_out;
+            if constexpr (HALF) {
+                // accumulator register i of a lane is list entry 4*kq + i of the tile, channel l
+#pragma unroll
+                for (int t = 0; t < TT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int oo = sTab[wave * 64 + t * TE + 4 * kq + i].w;
+                        if (oo < 0) continue;
+                        if (ci_ok[0]) obase[oo + l32] = acc[t][0][i];
+                    }
+            } else
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -819,14 +847,17 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     }
 
     if (g.Ci > 64) return false;
-    const int NT = (g.Ci + 31) / 32;
+    // at most 16 input channels (and reduction channels in groups of 16): half-width tiles
+    const bool half = g.Ci <= 16 && g.Co % 16 == 0 && conv_half_tiles() != 0;
+    const int NT = half ? 0 : (g.Ci + 31) / 32;
+    const int gc = half ? 16 : 8;
     // largest class decides how many rows fill the 256 list entries of a workgroup
     const int Pc_max = (int)(ceil_div(oh, g.stride) * ceil_div(ow, g.stride));
     int RB = std::max(1, kCtEntries / std::max(Pc_max, 1));
     // channel chunk: all channels if two workgroups then fit a CU, otherwise the largest divisor of Co that does
     int CC = g.Co;
     auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 16 + (relu ? (size_t)rb * 16 : 0); };
-    while (CC > 8 && lds_for(RB, CC) > 72 * 1024 && (CC / 2) % 8 == 0) CC /= 2;
+    while (CC > gc && lds_for(RB, CC) > 72 * 1024 && (CC / 2) % gc == 0) CC /= 2;
     while (RB > 1 && lds_for(RB, CC) > 72 * 1024) --RB;
     if (lds_for(RB, CC) > kLdsBudget) return false;
     a.CC = CC;
@@ -855,7 +886,8 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kLdsBudget);
         hipLaunchKernelGGL(kern, grid, dim3(kCtThreads), lds, s, a, rl);
     };
-    if (NT == 1) { if (relu) launch(&conv_transpose_mfma_kernel<1, true>); else launch(&conv_transpose_mfma_kernel<1, false>); }
+    if (NT == 0) { if (relu) launch(&conv_transpose_mfma_kernel<0, true>); else launch(&conv_transpose_mfma_kernel<0, false>); }
+    else if (NT == 1) { if (relu) launch(&conv_transpose_mfma_kernel<1, true>); else launch(&conv_transpose_mfma_kernel<1, false>); }
     else         { if (relu) launch(&conv_transpose_mfma_kernel<2, true>); else launch(&conv_transpose_mfma_kernel<2, false>); }
     DPC_HIP(hipGetLastError());
     return true;

@@ -137,6 +137,10 @@ CONV_CASES = [
     (7, 5, 64, 4, 4, 2, 0, False),
     (40, 24, 16, 3, 4, 2, 1, True),     # strips of output rows, stride 2
     (33, 31, 32, 4, 3, 1, 1, True),     # strips, ragged widths, 36 of 64 product columns
+    (5, 7, 16, 12, 3, 2, 0, False),     # at most 16 input channels, reduction channels in groups of 16: 16 x 16 tiles
+    (4, 4, 48, 16, 3, 1, 0, False),
+    (28, 28, 16, 16, 3, 1, 1, True),    # several entry blocks per row
+    (9, 9, 32, 9, 4, 2, 1, True),
 ]
 
 
