@@ -64,7 +64,8 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const int in_floats = a.RB * a.rowstride;
     const int zoff = in_floats;                                        // zero block
     int4* sTab = reinterpret_cast<int4*>(sIn + in_floats + a.pstride); // [256] {e0, py0, px0, outoff}
-    float* sRed = reinterpret_cast<float*>(sTab + kCtEntries);         // RELU: [RB][4] partial row constants
+    int* sOut = reinterpret_cast<int*>(sTab + kCtEntries);             // [256] outoff again, packed for 16-byte reads
+    float* sRed = reinterpret_cast<float*>(sOut + kCtEntries);         // RELU: [RB][4] partial row constants
 
     // NT = 0: at most 16 input channels.  Tiles are then 16 entries x 16 channels (16x16x4 MFMA, four tiles per wavefront,
     // groups of 16 reduction channels) instead of 32 x 32 (32x32x2, two tiles, groups of 8): half of every 32-column
@@ -92,6 +93,9 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const long long rows_here = (a.M - m0 < a.RB) ? a.M - m0 : a.RB;
     const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(in_shared ? a.in : a.in + m0 * a.ld_in), 0, (int)((in_shared ? rl.in_mod : rows_here) * a.ld_in * 4), 0x00020000);
+
+    const __amdgpu_buffer_rsrc_t ores =
+        __builtin_amdgcn_make_buffer_rsrc(a.out + m0 * a.ld_out, 0, (int)(rows_here * a.ld_out * 4), 0x00020000);
 
     // stage channels [c0, c0 + CC) of the input patches of this workgroup's rows
     auto stage_input = [&](int c0) __attribute__((always_inline)) {
@@ -254,6 +258,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                     }
                 }
                 sTab[tid] = e;
+                sOut[tid] = e.w;
             }
             __syncthreads();
 
@@ -370,30 +375,43 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
             }
 
             // ---- epilogue: accumulator register 4*i+j of a lane is list entry 8*i + 4*kq + j, channel l32 ----
-            float* obase = a.out + m0 * a.ld_out;
+            // Buffer stores: an entry past the list (offset -1) or a channel past Ci gets an offset outside the
+            // resource and is dropped, so the epilogue has no branches; the offsets of four consecutive entries come
+            // from one 16-byte LDS read.
             if constexpr (HALF) {
                 // accumulator register i of a lane is list entry 4*kq + i of the tile, channel l
 #pragma unroll
-                for (int t = 0; t < TT; ++t)
+                for (int t = 0; t < TT; ++t) {
+                    const int4 o4 = *reinterpret_cast<const int4*>(sOut + wave * 64 + t * TE + 4 * kq);
+                    const int oo[4] = {o4.x, o4.y, o4.z, o4.w};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int oo = sTab[wave * 64 + t * TE + 4 * kq + i].w;
-                        if (oo < 0) continue;
-                        if (ci_ok[0]) obase[oo + l32] = acc[t][0][i];
+                        // through a VGPR of its own: with the accumulator element as the direct operand the compiler emitted
+                        // the first register of the tile for all four stores
+                        float v = acc[t][0][i];
+                        asm volatile("" : "+v"(v));
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), ores,
+                                                              oo[i] >= 0 && ci_ok[0] ? (oo[i] + l32) * 4 : kNoData, 0, 0);
                     }
-            } else
+                }
+            } else {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < 4; ++i) {
+                        const int4 o4 = *reinterpret_cast<const int4*>(sOut + wave * 64 + t * 32 + 8 * i + 4 * kq);
+                        const int oo[4] = {o4.x, o4.y, o4.z, o4.w};
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int oo = sTab[wave * 64 + t * 32 + 8 * i + 4 * kq + j].w;
-                        if (oo < 0) continue;
+                        for (int j = 0; j < 4; ++j)
 #pragma unroll
-                        for (int n = 0; n < NT; ++n)
-                            if (ci_ok[n]) obase[oo + n * 32 + l32] = acc[t][n][4 * i + j];
+                            for (int n = 0; n < NT; ++n) {
+                                float v = acc[t][n][4 * i + j];
+                                asm volatile("" : "+v"(v));            // see above
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), ores,
+                                                                      oo[j] >= 0 && ci_ok[n] ? (oo[j] + n * 32 + l32) * 4 : kNoData, 0, 0);
+                            }
                     }
+            }
             __syncthreads();          // the table is rebuilt by the next class
             if (nchunks > 1) consts_pending = false;              // every chunk has been staged once
         }
@@ -737,7 +755,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     if (relu && conv_algo() != 0) return false;
     if (relu && g.Ci <= 4 && (relu->form || relu->in_mod)) return false;   // few input channels: per-input dense rows only
     if (relu && (int64_t)ld_in < (int64_t)ih * iw * g.Co) return false;
-    if ((int64_t)ld_in * 4 * 256 >= ((int64_t)1 << 31)) return false;              // staging uses 32-bit byte offsets per workgroup
+    if ((int64_t)ld_in * 4 * 256 >= ((int64_t)1 << 31) || (int64_t)ld_out * 4 * 256 >= ((int64_t)1 << 31)) return false;              // staging uses 32-bit byte offsets per workgroup
     if (relu && ((int64_t)relu->batch * relu->ldpk * 8 >= ((int64_t)1 << 31) || (int64_t)relu->in_mod * ld_in * 4 >= ((int64_t)1 << 31))) return false;
     CtArgs a{};
     a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
@@ -856,7 +874,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     int RB = std::max(1, kCtEntries / std::max(Pc_max, 1));
     // channel chunk: all channels if two workgroups then fit a CU, otherwise the largest divisor of Co that does
     int CC = g.Co;
-    auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 16 + (relu ? (size_t)rb * 16 : 0); };
+    auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 20 + (relu ? (size_t)rb * 16 : 0); };
     while (CC > gc && lds_for(RB, CC) > 72 * 1024 && (CC / 2) % gc == 0) CC /= 2;
     while (RB > 1 && lds_for(RB, CC) > 72 * 1024) --RB;
     if (lds_for(RB, CC) > kLdsBudget) return false;
@@ -864,7 +882,7 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     a.pstride = CC + 4;
     a.rowstride = ih * iw * a.pstride;
     const size_t row_bytes2 = (size_t)a.rowstride * 4;
-    const size_t fixed = (size_t)a.pstride * 4 + 256 * 16 + (relu ? (size_t)RB * 16 : 0);
+    const size_t fixed = (size_t)a.pstride * 4 + 256 * 20 + (relu ? (size_t)RB * 16 : 0);
     a.RB = RB;
     CtRelu rl{};
     if (relu) {
