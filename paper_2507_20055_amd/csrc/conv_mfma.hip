@@ -244,11 +244,15 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 
             // ---- table of this class's list entries ----
             {
+                const float rPc = 1.0f / (float)Pc, rWc = 1.0f / (float)Wc;
                 const int q = q0 + tid;
                 int4 e = make_int4(0, 0, 0, -1);
                 if (q < a.RB * Pc) {
-                    const int ml = q / Pc, pc = q - ml * Pc;
-                    const int iy = pc / Wc, ix = pc - iy * Wc;
+                    // quotients through a float reciprocal with one correction step (exact: q < 2^22 on the host side)
+                    int ml = (int)((float)q * rPc), pc = q - ml * Pc;
+                    if (pc < 0) { --ml; pc += Pc; } else if (pc >= Pc) { ++ml; pc -= Pc; }
+                    int iy = (int)((float)pc * rWc), ix = pc - iy * Wc;
+                    if (ix < 0) { --iy; ix += Wc; } else if (ix >= Wc) { ++iy; ix -= Wc; }
                     if (m0 + ml < a.M) {
                         const int y = y0 + a.s * iy, x = x0 + a.s * ix;
                         e.x = ml * a.rowstride + ((base_y + iy) * a.iw + (base_x + ix)) * a.pstride;
@@ -755,7 +759,8 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     if (relu && conv_algo() != 0) return false;
     if (relu && g.Ci <= 4 && (relu->form || relu->in_mod)) return false;   // few input channels: per-input dense rows only
     if (relu && (int64_t)ld_in < (int64_t)ih * iw * g.Co) return false;
-    if ((int64_t)ld_in * 4 * 256 >= ((int64_t)1 << 31) || (int64_t)ld_out * 4 * 256 >= ((int64_t)1 << 31)) return false;              // staging uses 32-bit byte offsets per workgroup
+    if ((int64_t)ld_in * 4 * 256 >= ((int64_t)1 << 31) || (int64_t)ld_out * 4 * 256 >= ((int64_t)1 << 31)) return false;
+    if ((int64_t)oh * ow + kCtEntries >= ((int64_t)1 << 22)) return false;          // entry indices stay exact in fp32              // staging uses 32-bit byte offsets per workgroup
     if (relu && ((int64_t)relu->batch * relu->ldpk * 8 >= ((int64_t)1 << 31) || (int64_t)relu->in_mod * ld_in * 4 >= ((int64_t)1 << 31))) return false;
     CtArgs a{};
     a.in = in; a.M = M; a.ld_in = ld_in; a.ih = ih; a.iw = iw; a.Co = g.Co;
