@@ -83,7 +83,33 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const int npos = a.ih * a.iw;
     const int nchunks = a.Co / a.CC;                                   // channel chunks of the reduction
     const int cc4n = a.CC >> 2;
-    const unsigned long long magic_cc4n = (1ull << 32) / (unsigned)cc4n + 1, magic_npos = (1ull << 32) / (unsigned)npos + 1;
+    // A single-row workgroup that is one of several entry blocks of its row reaches only a band of input rows (its 256
+    // entries of every class cover a few output rows): only that band is staged.  With the ReLU step the first block
+    // still stages everything, because it also adds up the row's constant.
+    int band_lo = 0, band_n = npos;
+    if (a.RB == 1 && gridDim.y > 1 && (!RELU || blockIdx.y > 0)) {
+        int lo = a.ih, hi = -1;
+        for (int cy = 0; cy < a.s; ++cy) {
+            const int y0 = ((cy - a.off) % a.s + a.s) % a.s;
+            const int Hc = y0 < a.oh ? (a.oh - y0 + a.s - 1) / a.s : 0;
+            const int base_y = (y0 + a.off - cy) / a.s;
+            const int nky = cy < a.kh ? (a.kh - cy + a.s - 1) / a.s : 0;
+            for (int cx = 0; cx < a.s; ++cx) {
+                const int x0 = ((cx - a.off) % a.s + a.s) % a.s;
+                const int Wc = x0 < a.ow ? (a.ow - x0 + a.s - 1) / a.s : 0;
+                const int Pc = Hc * Wc;
+                if (Pc == 0 || q0 >= Pc || nky == 0) continue;
+                const int qe = min(q0 + kCtEntries, Pc) - 1;
+                lo = min(lo, base_y + q0 / Wc - (nky - 1));
+                hi = max(hi, base_y + qe / Wc);
+            }
+        }
+        lo = max(lo, 0);
+        hi = min(hi, a.ih - 1);
+        band_lo = hi >= lo ? lo * a.iw : 0;
+        band_n = hi >= lo ? (hi - lo + 1) * a.iw : 0;
+    }
+    const unsigned long long magic_cc4n = (1ull << 32) / (unsigned)cc4n + 1, magic_npos = (1ull << 32) / (unsigned)max(band_n, 1) + 1;
 
     // Staging reads go through buffer resources (offsets past the range return zeros: no branches around the loads) and
     // are issued kStageU at a time before the first LDS write, so a thread has several 16-byte loads in flight.
@@ -99,7 +125,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 
     // stage channels [c0, c0 + CC) of the input patches of this workgroup's rows
     auto stage_input = [&](int c0) __attribute__((always_inline)) {
-        const int total = a.RB * npos * cc4n;
+        const int total = a.RB * band_n * cc4n;
         for (int idx0 = tid; idx0 < total; idx0 += kCtThreads * kStageU) {
             vf4 v[kStageU];
             int dsto[kStageU];
@@ -108,7 +134,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                 const int idx = idx0 + u * kCtThreads;
                 // quotients by the run-time extents through multiply-high (exact: idx * divisor < 2^32)
                 const int t = (int)(((unsigned long long)idx * magic_cc4n) >> 32), c4 = idx - t * cc4n;
-                const int ml = (int)(((unsigned long long)t * magic_npos) >> 32), pos = t - ml * npos;
+                const int ml = (int)(((unsigned long long)t * magic_npos) >> 32), pos = band_lo + t - ml * band_n;
                 const bool ok = idx < total;                       // rows past M lie past the resource's range
                 v[u] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(
                                                    xres, ok ? (ml * a.ld_in + pos * a.Co + c0 + c4 * 4) * 4 : kNoData, 0, 0));
@@ -127,7 +153,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const __amdgpu_buffer_rsrc_t qres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float2*>(rl.pk2), 0, RELU ? rl.batch * rl.ldpk * 8 : 0, 0x00020000);
     auto stage_input_relu = [&](int c0) __attribute__((always_inline)) {
-        const int span = npos * cc4n;
+        const int span = band_n * cc4n;
         const int wpr = a.RB >= 4 ? 1 : a.RB == 2 ? 2 : a.RB == 1 ? 4 : 1, pw = wave % wpr;
         for (int ml = wave / wpr; ml < a.RB; ml += 4 / wpr) {
             const bool rowok = m0 + ml < a.M;
@@ -151,7 +177,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 #pragma unroll
                 for (int u = 0; u < kStageR; ++u) {
                     const int i = i0 + u * 64 * wpr;
-                    const int pos = (int)(((unsigned long long)i * magic_cc4n) >> 32), c4 = i - pos * cc4n;
+                    const int pb = (int)(((unsigned long long)i * magic_cc4n) >> 32), c4 = i - pb * cc4n, pos = band_lo + pb;
                     const int py = (int)(((unsigned long long)pos * magic_iw) >> 32), px = pos - py * a.iw;
                     const int gy = oy + py, gx = ox + px;
                     const bool in = i < span;

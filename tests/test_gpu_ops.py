@@ -141,6 +141,8 @@ CONV_CASES = [
     (4, 4, 48, 16, 3, 1, 0, False),
     (28, 28, 16, 16, 3, 1, 1, True),    # several entry blocks per row
     (9, 9, 32, 9, 4, 2, 1, True),
+    (20, 20, 16, 16, 4, 2, 1, True),    # stride 2 with several entry blocks per row: each block stages a band of input rows
+    (18, 18, 16, 32, 3, 1, 1, True),
 ]
 
 

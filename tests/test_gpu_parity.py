@@ -66,7 +66,9 @@ def test_hand_example_on_gpu():
                                              # one kernel for ReLU step + first layer + concretisation: 32 and 8 channels,
                                              # 4 and 1 input channels, both strides
                                              ([(32, 3, 1, 1), (16, 4, 2, 0)], [8, 3], (4, 9, 9)),
-                                             ([(8, 4, 2, 1), (8, 3, 1, 1), (16, 3, 1, 1)], [5, 3], (1, 10, 10))])
+                                             ([(8, 4, 2, 1), (8, 3, 1, 1), (16, 3, 1, 1)], [5, 3], (1, 10, 10)),
+                                             # more than 256 positions per row: several entry blocks, bands of input rows
+                                             ([(8, 3, 1, 1), (8, 3, 1, 1)], [6, 3], (1, 17, 17))])
 def test_small_conv(convs, fcs, shape):
     net = wl.random_small_conv(7, shape, convs, fcs)
     B = 3
