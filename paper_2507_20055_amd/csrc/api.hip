@@ -1217,15 +1217,17 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 Layer& L = *net->layers[i - 1];
                 if (L.kind == RELU) {
                     prof.begin(P_OTHER);
-                    launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
-                                        (int64_t)B * L.n_out, s);
-                    if (fuse)
-                        launch_pack_relax(res->lam[i], res->mu[i], res->nu[i], net->layers[i - 2]->dBias.p, B, L.n_out,
-                                          net->ld_of(i), net->pk[i]->p, s);
-                    if (fuse && i == 2 && net->pk2.p)
-                        launch_pack_relax2(res->lam[i], res->mu[i], res->nu[i], B, L.n_out, net->ld_of(i), net->pk2.p, s);
-                    if (fuse && i >= 3 && (int)net->pk2v.size() > i && net->pk2v[i] && net->pk2v[i]->p)
-                        launch_pack_relax2(res->lam[i], res->mu[i], res->nu[i], B, L.n_out, net->ld_of(i), net->pk2v[i]->p, s);
+                    if (fuse) {
+                        // the layer's parameters and their packed forms (for the fused epilogues and the kernels that apply
+                        // the ReLU step while they load rows) in one launch
+                        float* pk2 = i == 2 ? net->pk2.p
+                                            : ((int)net->pk2v.size() > i && net->pk2v[i]) ? net->pk2v[i]->p : nullptr;
+                        launch_relax_params_pack(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
+                                                 net->layers[i - 2]->dBias.p, B, L.n_out, net->ld_of(i), net->pk[i]->p, pk2, s);
+                    } else {
+                        launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
+                                            (int64_t)B * L.n_out, s);
+                    }
                     prof.end();
                     res->prof.other_launches++;
                     continue;

@@ -43,6 +43,8 @@ constexpr int kLdAlign = 32;
 
 // Per-ReLU-neuron relaxation from the predecessor's concrete bounds (DeepPoly ReLU transformer).
 // l,u: [count]; writes lambda, mu, nu and the ReLU neuron's own bounds rl, ru: [count].
+void launch_relax_params_pack(const float* l, const float* u, float* lambda, float* mu, float* nu, float* rl, float* ru,
+                              const float* bias, int batch, int n, int ld, float* pk, float* pk2, hipStream_t s);
 void launch_relax_params(const float* l, const float* u, float* lambda, float* mu, float* nu,
                          float* rl, float* ru, int64_t count, hipStream_t s);
 

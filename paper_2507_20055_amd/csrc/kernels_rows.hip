@@ -573,6 +573,48 @@ __global__ __launch_bounds__(kThreads) void pack_relax2_kernel(
     pk2[i] = o;
 }
 
+// relax_params_kernel, pack_relax_kernel and pack_relax2_kernel in one launch (the same arithmetic, value by value):
+// one thread per (input, padded column); pk and pk2 may be NULL.
+__global__ __launch_bounds__(kThreads) void relax_params_pack_kernel(
+    const float* __restrict__ l, const float* __restrict__ u, float* __restrict__ lambda, float* __restrict__ mu,
+    float* __restrict__ nu, float* __restrict__ rl, float* __restrict__ ru, const float* __restrict__ bias, int batch, int n,
+    int ld, float4* __restrict__ pk, float2* __restrict__ pk2)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;       // over [batch][ld]
+    if (i >= (int64_t)batch * ld) return;
+    const int col = (int)(i % ld), b = (int)(i / ld);
+    float4 lo4 = make_float4(0.f, 0.f, 0.f, 0.f), up4 = lo4;
+    float2 o2 = make_float2(0.f, 0.f);
+    if (col < n) {
+        const size_t k = (size_t)b * n + col;
+        const float lv = l[k], uv = u[k];
+        const float la = (lv + uv >= 0.0f) ? 1.0f : 0.0f;
+        float m, v;
+        if (lv >= 0.0f) { m = 1.0f; v = 0.0f; }
+        else if (uv <= 0.0f) { m = 0.0f; v = 0.0f; }
+        else {
+            const float d = uv - lv;
+            m = uv / d;
+            v = -(uv * lv) / d;
+        }
+        lambda[k] = la;
+        mu[k] = m;
+        nu[k] = v;
+        rl[k] = lv >= 0.0f ? lv : 0.0f;
+        ru[k] = uv >= 0.0f ? uv : 0.0f;
+        const float bj = bias ? bias[col] : 0.0f;
+        lo4 = make_float4(la, m, 0.0f + la * bj, v + m * bj);          // lower side: (lambda, mu | ., nu)
+        up4 = make_float4(m, la, v + m * bj, 0.0f + la * bj);          // upper side: (mu, lambda | nu, .)
+        const float av = fabsf(v);
+        o2 = make_float2(m, la != 0.0f ? -av : av);
+    }
+    if (pk) {
+        pk[i] = lo4;
+        pk[(size_t)batch * ld + i] = up4;
+    }
+    if (pk2) pk2[i] = o2;
+}
+
 __global__ __launch_bounds__(kThreads) void pack_bounds_kernel(
     const float* __restrict__ lo, const float* __restrict__ hi, int batch, int n, int ld, float4* __restrict__ pk)
 {
@@ -707,6 +749,18 @@ int pick_rows_per_wave(int R, int groups, bool streaming_rows)
 
 void set_rows_per_wave(int v) { g_rows_per_wave = v; }
 void set_rows_stream(int v) { g_stream = v; }
+
+void launch_relax_params_pack(const float* l, const float* u, float* lambda, float* mu, float* nu, float* rl, float* ru,
+                              const float* bias, int batch, int n, int ld, float* pk, float* pk2, hipStream_t s)
+{
+    DPC_REQUIRE(l && u && lambda && mu && nu && rl && ru && ld >= n && ((uintptr_t)pk % 16) == 0 && ((uintptr_t)pk2 % 8) == 0,
+                DPC_EINVAL, "relax_params_pack: bad arguments");
+    const int64_t tot = (int64_t)batch * ld;
+    if (tot <= 0) return;
+    hipLaunchKernelGGL(relax_params_pack_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, l, u, lambda, mu,
+                       nu, rl, ru, bias, batch, n, ld, reinterpret_cast<float4*>(pk), reinterpret_cast<float2*>(pk2));
+    DPC_HIP(hipGetLastError());
+}
 
 void launch_relax_params(const float* l, const float* u, float* lambda, float* mu, float* nu,
                          float* rl, float* ru, int64_t count, hipStream_t s)
