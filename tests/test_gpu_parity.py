@@ -173,6 +173,23 @@ def test_depth_limited(depth):
     gnet.close()
 
 
+@pytest.mark.parametrize("depth,final", [(1, -2), (2, -2), (3, -2), (4, -2), (6, -2), (0, -1), (2, 5)])
+def test_depth_limited_conv(depth, final):
+    """Depth limits on a convolutional network whose layers take the kernels that apply the ReLU step while they
+    load rows: a traversal that stops between a ReLU layer and the convolution below it must not use them."""
+    net = wl.random_small_conv(17, (3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4])
+    x, lo, hi = wl.random_box(18, net.n_in, 3, 0.05)
+    label = np.array([0, 1, 3], np.int32)
+    b = _binding()
+    gnet = b.Network(net)
+    kw = dict(max_backsub_depth=depth) if final == -2 else dict(max_backsub_depth=depth, final_backsub_depth=final)
+    g = gnet.certify(lo, hi, label, **kw)
+    o = oracle.run(net, lo, hi, label=label, max_depth=depth) if final == -2 else \
+        oracle.run(net, lo, hi, label=label, max_depth=depth, max_depth_last=final)
+    compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
+
+
 def test_edge_cases():
     b = _binding()
     net = wl.random_small_net(21, [6, 8, 4])
