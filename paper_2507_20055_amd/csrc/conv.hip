@@ -110,6 +110,46 @@ __global__ __launch_bounds__(kThreads) void concretise_patch_kernel(
     }
 }
 
+// Shared small cores (a convolution layer's own kernel as the expressions of its neurons: interval bounds of the first
+// layer): one THREAD per row.  The cores sit in LDS, the lanes of a wavefront are consecutive channels of a few
+// positions, so the box values they read are broadcasts; a row's products are added in element order in fp64.
+__global__ __launch_bounds__(kThreads) void concretise_patch_small_kernel(
+    int batch, int R, PatchArgs pa, const float* __restrict__ lo, const float* __restrict__ hi, float* __restrict__ out_l,
+    float* __restrict__ out_u, const float* __restrict__ core, int ld_core, const float* __restrict__ cst_init_c)
+{
+    extern __shared__ float s_core[];                  // [rows_C][elems + 1]
+    const int es = pa.elems + 1;
+    for (int i = threadIdx.x; i < pa.rows_C * pa.elems; i += kThreads) {
+        const int co = i / pa.elems, e = i - co * pa.elems;
+        s_core[co * es + e] = core[(size_t)co * ld_core + e];
+    }
+    __syncthreads();
+    const int sb = blockIdx.y;
+    const int side = sb / batch, b = sb - side * batch;
+    const int r = blockIdx.x * kThreads + threadIdx.x;
+    if (r >= R) return;
+    const int co = r % pa.rows_C, wo = (r / pa.rows_C) % pa.rows_W, ho = r / (pa.rows_C * pa.rows_W);
+    const int oy = ho * pa.S - pa.P, ox = wo * pa.S - pa.P;
+    const size_t pbase = (size_t)b * pa.gh * pa.gw * pa.C;
+    const float* in = s_core + co * es;
+    double a = 0.0;
+    for (int py = 0; py < pa.ph; ++py) {
+        const int gy = oy + py;
+        if (gy < 0 || gy >= pa.gh) continue;
+        for (int px = 0; px < pa.pw; ++px) {
+            const int gx = ox + px;
+            if (gx < 0 || gx >= pa.gw) continue;
+            const size_t idx = pbase + ((size_t)gy * pa.gw + gx) * pa.C;
+            const float* x = in + (py * pa.pw + px) * pa.C;
+            for (int c = 0; c < pa.C; ++c) {
+                const float bound = (x[c] >= 0.0f) == (side == 0) ? lo[idx + c] : hi[idx + c];
+                a += (double)x[c] * (double)bound;
+            }
+        }
+    }
+    (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)((double)cst_init_c[co] + a);
+}
+
 // Transposed convolution of coefficient rows, one thread per output element (gather form: every
 // output is produced by exactly one thread, so the summation order is fixed).
 __global__ __launch_bounds__(kThreads) void conv_transpose_rows_kernel(
@@ -240,7 +280,12 @@ void launch_concretise_patch(const float* C, int ldc, const double* cst, int nsi
     if (batch == 0 || R == 0) return;
     const int rpw = rows_per_wave_for(R, nsides * batch);
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
-    if (shared_core)
+    const size_t small_lds = (size_t)pg.rows_C * (pg.elems() + 1) * sizeof(float);
+    if (shared_core && pg.elems() <= 256 && small_lds <= 32 * 1024) {
+        dim3 g2((unsigned)ceil_div(R, kThreads), (unsigned)(nsides * batch));
+        hipLaunchKernelGGL(concretise_patch_small_kernel, g2, dim3(kThreads), small_lds, s, batch, R, to_args(pg), lo, hi, out_l, out_u,
+                           shared_core, ld_core, cst_init_c);
+    } else if (shared_core)
         hipLaunchKernelGGL(concretise_patch_kernel<true>, grid, dim3(kThreads), 0, s, C, ldc, cst, batch, R, to_args(pg),
                            lo, hi, out_l, out_u, shared_core, ld_core, cst_init_c, rpw);
     else
