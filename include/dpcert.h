@@ -138,7 +138,11 @@ dpc_status dpc_options_default(dpc_options* opt);
  *            call on the same network with the same batch and keep_symbolic ->
  *            it is reused and no device memory is allocated.
  * Work is enqueued on opt->stream; the call returns after the stream has been
- * synchronised, so results are ready.  Calls on one network must not overlap
+ * synchronised, so results are ready.  The boxes and labels are validated on the
+ * device while the certifier runs (lo > hi, a non-finite bound or a label out of
+ * range -> DPC_EINVAL, found when the stream is synchronised; a label out of range is
+ * clamped inside the kernels so that nothing is read out of bounds); after such an
+ * error the contents of a reused result are unspecified and no new result is returned.  Calls on one network must not overlap
  * (the network owns the coefficient workspace). */
 dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const float* hi,
                        const int32_t* label, const dpc_options* opt, dpc_result** result);

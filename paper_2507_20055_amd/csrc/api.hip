@@ -132,6 +132,8 @@ struct dpc_network {
     DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
     std::vector<std::unique_ptr<DevBuf<float>>> pk2v;      // the same for ReLU layers above a convolution with > 4 input channels
     DevBuf<float> rpart;                   // one constant per row from a ReLU step applied inside a convolution kernel
+    int32_t* h_flag = nullptr;             // pinned host word the input validation reports into
+    ~dpc_network() { if (h_flag) (void)hipHostFree(h_flag); }
     std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
     int skip_depth = 0;                    // how many skip connections span one layer at most
     DevBuf<float> part;
@@ -1120,12 +1122,12 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             DPC_HIP(hipMemcpyAsync(res->u[0], hi, box * 4, hipMemcpyDefault, s));
         }
         if (label) DPC_HIP(hipMemcpyAsync(res->label.p, label, (size_t)B * 4, hipMemcpyDefault, s));
-        {   // validate lo <= hi, finite, labels in range (on the device; one flag comes back)
-            int bad = check_inputs(res->l[0], res->u[0], box, label ? res->label.p : nullptr, B, nK,
-                                   reinterpret_cast<int32_t*>(net->stage.p + 2 * box), s);
-            DPC_REQUIRE(bad == 0, DPC_EINVAL,
-                        bad == 1 ? "dpc_certify: lo > hi or a non-finite bound" : "dpc_certify: label out of range");
-        }
+        // validate lo <= hi, finite, labels in range on the device; the flag word is read after the stream has been
+        // synchronised at the end of the call (no round trip in front of the kernels)
+        if (!net->h_flag) DPC_HIP(hipHostMalloc(reinterpret_cast<void**>(&net->h_flag), sizeof(int32_t), hipHostMallocDefault));
+        *net->h_flag = 0;
+        check_inputs_enqueue(res->l[0], res->u[0], box, label ? res->label.p : nullptr, B, nK,
+                             reinterpret_cast<int32_t*>(net->stage.p + 2 * box), net->h_flag, s);
 
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
         // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
@@ -1314,6 +1316,11 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         prof.finish();
         if (prof.on) DPC_HIP(hipEventRecord(t1, s));
         DPC_HIP(hipStreamSynchronize(s));
+        {
+            const int32_t h = *static_cast<volatile int32_t*>(net->h_flag);
+            DPC_REQUIRE(!(h & 1), DPC_EINVAL, "dpc_certify: lo > hi or a non-finite bound");
+            DPC_REQUIRE(!(h & 2), DPC_EINVAL, "dpc_certify: label out of range");
+        }
         if (prof.on) {
             float ms = 0.f;
             DPC_HIP(hipEventElapsedTime(&ms, t0, t1));

@@ -108,6 +108,9 @@ int conv_half_tiles();
 
 // Validation of certify inputs on the device.  Returns 0 = fine, 1 = lo > hi or non-finite, 2 = bad label.
 // `flag` is a device int32 scratch word.  Synchronises the stream.
+// The same checks without waiting: the flag word lands in pinned host memory once the stream reaches the copy.
+void check_inputs_enqueue(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
+                          int32_t* flag, int32_t* pinned_host_flag, hipStream_t s);
 int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
                  int32_t* flag, hipStream_t s);
 

@@ -330,4 +330,14 @@ int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* 
     return (h & 1) ? 1 : (h & 2) ? 2 : 0;
 }
 
+void check_inputs_enqueue(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
+                          int32_t* flag, int32_t* pinned_host_flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, s, flag);
+    const unsigned blocks = (unsigned)std::min<size_t>(1024, ceil_div((int64_t)std::max<size_t>(count, 1), 256));
+    hipLaunchKernelGGL(check_inputs_kernel, dim3(blocks), dim3(256), 0, s, lo, hi, count, label, batch, nK, flag);
+    DPC_HIP(hipGetLastError());
+    DPC_HIP(hipMemcpyAsync(pinned_host_flag, flag, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+}
+
 }  // namespace dpc

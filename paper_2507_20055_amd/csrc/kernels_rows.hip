@@ -652,7 +652,7 @@ __global__ __launch_bounds__(kThreads) void margin_rows_kernel(
 {
     const int m = blockIdx.x;                // b * (nK-1) + q
     const int b = m / (nK - 1), q = m - b * (nK - 1);
-    const int t = label[b];
+    const int t = min(max(label[b], 0), nK - 1);       // labels are validated while this runs: never index out of range
     const int o = q < t ? q : q + 1;
     for (int i = threadIdx.x; i < ldc; i += kThreads)
         C[(size_t)m * ldc + i] = i < n ? W[(size_t)t * ldw + i] - W[(size_t)o * ldw + i] : 0.0f;
@@ -674,7 +674,7 @@ __global__ __launch_bounds__(kThreads) void final_rows_kernel(
     int t = pad ? 0 : r, o = -1;
     if (!pad && r >= nK) {
         const int q = r - nK;
-        t = label[b];
+        t = min(max(label[b], 0), nK - 1);             // labels are validated while this runs: never index out of range
         o = q < t ? q : q + 1;
     }
     for (int i = threadIdx.x; i < ldc; i += kThreads) {
