@@ -133,6 +133,7 @@ struct dpc_network {
     std::vector<std::unique_ptr<DevBuf<float>>> pk2v;      // the same for ReLU layers above a convolution with > 4 input channels
     DevBuf<float> rpart;                   // one constant per row from a ReLU step applied inside a convolution kernel
     int32_t* h_flag = nullptr;             // pinned host word the input validation reports into
+    DevBuf<int32_t> dflag;                 // its device word for inputs that are ingested by one kernel (zero between calls)
     ~dpc_network() { if (h_flag) (void)hipHostFree(h_flag); }
     std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
     int skip_depth = 0;                    // how many skip connections span one layer at most
@@ -1112,7 +1113,23 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
 
         // ---- box and labels to the device, in the internal neuron order ----
         const size_t box = (size_t)B * n0;
-        if (net->in_spatial) {
+        // pointers into this device's memory: one kernel copies, reorders and validates
+        auto on_device = [&](const void* p) {
+            hipPointerAttribute_t at{};
+            if (hipPointerGetAttributes(&at, p) != hipSuccess) { (void)hipGetLastError(); return false; }
+            return at.type == hipMemoryTypeDevice && at.device == net->device;
+        };
+        const bool resident = B > 0 && on_device(lo) && on_device(hi) && (!label || on_device(label));
+        if (!net->h_flag) DPC_HIP(hipHostMalloc(reinterpret_cast<void**>(&net->h_flag), sizeof(int32_t), hipHostMallocDefault));
+        *net->h_flag = 0;
+        if (resident) {
+            if (!net->dflag.p) {
+                net->dflag.reserve(1);
+                DPC_HIP(hipMemsetAsync(net->dflag.p, 0, sizeof(int32_t), s));
+            }
+            ingest_enqueue(lo, hi, label, res->l[0], res->u[0], label ? res->label.p : nullptr, B, n0, net->in_spatial ? net->inC : 0,
+                           net->inH, net->inW, nK, net->dflag.p, net->h_flag, s);
+        } else if (net->in_spatial) {
             DPC_HIP(hipMemcpyAsync(net->stage.p, lo, box * 4, hipMemcpyDefault, s));
             DPC_HIP(hipMemcpyAsync(net->stage.p + box, hi, box * 4, hipMemcpyDefault, s));
             launch_chw_to_hwc(net->stage.p, res->l[0], B, net->inC, net->inH, net->inW, s);
@@ -1121,12 +1138,11 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             DPC_HIP(hipMemcpyAsync(res->l[0], lo, box * 4, hipMemcpyDefault, s));
             DPC_HIP(hipMemcpyAsync(res->u[0], hi, box * 4, hipMemcpyDefault, s));
         }
-        if (label) DPC_HIP(hipMemcpyAsync(res->label.p, label, (size_t)B * 4, hipMemcpyDefault, s));
+        if (label && !resident) DPC_HIP(hipMemcpyAsync(res->label.p, label, (size_t)B * 4, hipMemcpyDefault, s));
         // validate lo <= hi, finite, labels in range on the device; the flag word is read after the stream has been
         // synchronised at the end of the call (no round trip in front of the kernels)
-        if (!net->h_flag) DPC_HIP(hipHostMalloc(reinterpret_cast<void**>(&net->h_flag), sizeof(int32_t), hipHostMallocDefault));
-        *net->h_flag = 0;
-        check_inputs_enqueue(res->l[0], res->u[0], box, label ? res->label.p : nullptr, B, nK,
+        if (!resident)
+            check_inputs_enqueue(res->l[0], res->u[0], box, label ? res->label.p : nullptr, B, nK,
                              reinterpret_cast<int32_t*>(net->stage.p + 2 * box), net->h_flag, s);
 
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
@@ -1318,6 +1334,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         DPC_HIP(hipStreamSynchronize(s));
         {
             const int32_t h = *static_cast<volatile int32_t*>(net->h_flag);
+            if (h && resident) zero_word_enqueue(net->dflag.p, s);          // the next call expects a clean flag
             DPC_REQUIRE(!(h & 1), DPC_EINVAL, "dpc_certify: lo > hi or a non-finite bound");
             DPC_REQUIRE(!(h & 2), DPC_EINVAL, "dpc_certify: label out of range");
         }

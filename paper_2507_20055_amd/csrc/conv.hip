@@ -196,6 +196,37 @@ __global__ void check_inputs_kernel(const float* __restrict__ lo, const float* _
     if (bad) atomicOr(flag, bad);
 }
 
+// Boxes and labels that already live in device memory: copied into the result's buffers (spatial inputs go from the
+// caller's (C,H,W) order to the internal (H,W,C) order) and validated in the same pass.  The flag word must be zero
+// when the kernel starts.
+__global__ void ingest_kernel(const float* __restrict__ lo, const float* __restrict__ hi, const int32_t* __restrict__ label,
+                              float* __restrict__ l0, float* __restrict__ u0, int32_t* __restrict__ lab, int batch, int n0,
+                              int Cc, int H, int W, int nK, int32_t* __restrict__ flag)
+{
+    int bad = 0;
+    const size_t count = (size_t)batch * n0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+        const float a = lo[i], b = hi[i];
+        if (!(a <= b) || !isfinite(a) || !isfinite(b)) bad |= 1;
+        size_t d = i;
+        if (Cc > 0) {
+            const size_t bi = i / n0;
+            const int e = (int)(i - bi * n0);
+            const int w = e % W, h = (e / W) % H, c = e / (W * H);
+            d = bi * n0 + ((size_t)h * W + w) * Cc + c;
+        }
+        l0[d] = a;
+        u0[d] = b;
+    }
+    if (label)
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)batch; i += (size_t)gridDim.x * blockDim.x) {
+            const int32_t v = label[i];
+            lab[i] = v;
+            if (v < 0 || v >= nK) bad |= 2;
+        }
+    if (bad) atomicOr(flag, bad);
+}
+
 __global__ void zero_word_kernel(int32_t* p) { *p = 0; }
 
 PatchArgs to_args(const PatchGeom& g)
@@ -328,6 +359,22 @@ int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* 
     DPC_HIP(hipMemcpyAsync(&h, flag, sizeof h, hipMemcpyDeviceToHost, s));
     DPC_HIP(hipStreamSynchronize(s));
     return (h & 1) ? 1 : (h & 2) ? 2 : 0;
+}
+
+void ingest_enqueue(const float* lo, const float* hi, const int32_t* label, float* l0, float* u0, int32_t* lab, int batch, int n0,
+                    int Cc, int H, int W, int nK, int32_t* flag, int32_t* pinned_host_flag, hipStream_t s)
+{
+    const size_t count = (size_t)batch * n0;
+    const unsigned blocks = (unsigned)std::min<size_t>(1024, ceil_div((int64_t)std::max<size_t>(count, 1), 256));
+    hipLaunchKernelGGL(ingest_kernel, dim3(blocks), dim3(256), 0, s, lo, hi, label, l0, u0, lab, batch, n0, Cc, H, W, nK, flag);
+    DPC_HIP(hipGetLastError());
+    DPC_HIP(hipMemcpyAsync(pinned_host_flag, flag, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+}
+
+void zero_word_enqueue(int32_t* flag, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, s, flag);
+    DPC_HIP(hipGetLastError());
 }
 
 void check_inputs_enqueue(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,

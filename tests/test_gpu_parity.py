@@ -241,6 +241,32 @@ def test_device_inputs_and_stream():
     np.testing.assert_array_equal(ref.verdict()[1], got.verdict()[1])
     p = got.profile()
     assert p["contract_launches"] == 1 + 2 and p["total_ms"] > 0 and p["contract_flop"] > 0   # layer 3: 1; output + margins (one pass): 2
+    # malformed device-resident inputs: found by the kernel that ingests them, reported by the same call; the next
+    # call starts from a clean flag
+    bad_lab = torch.from_numpy(np.array([0, 1, 7, 3], np.int32)).cuda()
+    with pytest.raises(b.DpcError):
+        gnet.certify(dlo, dhi, bad_lab, stream=s.cuda_stream)
+    with pytest.raises(b.DpcError):
+        gnet.certify(dhi + 1.0, dlo, dlab, stream=s.cuda_stream)
+    nan_lo = dlo.clone(); nan_lo[1, 3] = float("nan")
+    with pytest.raises(b.DpcError):
+        gnet.certify(nan_lo, dhi, dlab)
+    again = gnet.certify(dlo, dhi, dlab, stream=s.cuda_stream)
+    for k in (1, 3, 5):
+        np.testing.assert_array_equal(ref.concrete(k)[0], again.concrete(k)[0])
+    np.testing.assert_array_equal(ref.verdict()[0], again.verdict()[0])
+    # a convolutional network takes device inputs in (C,H,W) order like host inputs
+    cnet = wl.random_small_conv(7, (3, 8, 8), [(4, 3, 1, 1), (8, 4, 2, 1)], [6, 3])
+    x, clo, chi = wl.random_box(8, cnet.n_in, 3, 0.05)
+    clab = np.array([0, 1, 2], np.int32)
+    g2 = b.Network(cnet)
+    r_host = g2.certify(clo, chi, clab)
+    r_dev = g2.certify(torch.from_numpy(clo).cuda(), torch.from_numpy(chi).cuda(), torch.from_numpy(clab).cuda())
+    for k in (0, 1, len(cnet.layers)):
+        np.testing.assert_array_equal(r_host.concrete(k)[0], r_dev.concrete(k)[0])
+        np.testing.assert_array_equal(r_host.concrete(k)[1], r_dev.concrete(k)[1])
+    np.testing.assert_array_equal(r_host.verdict()[1], r_dev.verdict()[1])
+    g2.close()
     gnet.close()
 
 
