@@ -383,10 +383,11 @@ int g_variant = -1;      // -1: chosen from the problem shape
 //  * fewer than 512 tiles of 128x128: 64x64 tiles, so that the grid still covers the 256 CUs;
 //  * otherwise 128x256 tiles (8 wavefronts of 64x64, K tile 16), unless the last 256-wide column tile
 //    would be at most half used (e.g. 784 columns), where 128x128 tiles waste less.
-int pick_variant(int64_t M, int ldc)
+int pick_variant(int64_t M, int ldc, int K)
 {
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(ldc, 128);
-    if (tiles128 < 512) return 9;
+    // small problems are bound by the latency of their K loop: fewer, longer K steps (64 x 64 tiles, 64 or 32 deep)
+    if (tiles128 < 512) return K >= 256 ? 18 : K >= 64 ? 19 : 9;
     const int rem = ldc % 256;
     return (rem != 0 && rem <= 128) ? 17 : 7;
 }
@@ -406,7 +407,7 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
     DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0, DPC_EINVAL,
                 "contract: buffers must be 16-byte aligned");
     if (M == 0) return;
-    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc);
+    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc, K);
     switch (variant) {
         case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
         case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
@@ -447,7 +448,7 @@ void launch_contract_batched(const float* A, int64_t strideA, int64_t M, int K, 
     EpiArgs ep{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap, (long long)strideA, (long long)strideW, (long long)strideC};
     // tile choice as for one problem of batches * M rows; problems of at most 512 rows tile better with 64x64
     // (measured on the 500-row steps of ReuseCert)
-    const int variant = g_variant >= 0 ? g_variant : M <= 512 ? 9 : pick_variant(M * batches, ldc);
+    const int variant = g_variant >= 0 ? g_variant : M <= 512 ? 9 : pick_variant(M * batches, ldc, 0);
     switch (variant) {
         case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
         case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
@@ -467,13 +468,15 @@ int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float
     DPC_REQUIRE(e.ldpk >= ldc && e.R >= 32 && e.nsb >= 1 && (int64_t)e.nsb * e.R == M && e.part_stride >= M, DPC_EINVAL,
                 "contract_fused: epilogue geometry does not match the rows");
     if (M == 0) return 0;
-    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc);
+    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc, K);
     EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store, g_remap};
     switch (variant) {      // the fused epilogue is instantiated for the tiles the shape heuristic can pick
         case 17: return launch_variant<Tile<128, 128, 16, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
         case 7:  return launch_variant<Tile<128, 256, 16, 64, 64>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
         case 9:  return launch_variant<Tile<64, 64, 16, 32, 32>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
         case 10: return launch_variant<Tile<128, 128, 8, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+        case 19: return launch_variant<Tile<64, 64, 32, 32, 32>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
+        case 18: return launch_variant<Tile<64, 64, 64, 32, 32>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
         default: return -1;
     }
 }
