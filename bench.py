@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--host-inputs", action="store_true", help="pass host arrays (adds the PCIe upload of the boxes to every step)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE", help="dpc_tuning_set(KEY, VALUE) before the run")
     ap.add_argument("--fuse", type=int, default=1)
+    ap.add_argument("--use-graph", type=int, default=-1, help="dpc_options.use_graph (-1: the library default)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 256 MiB device-to-device copy first (known size, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -91,7 +92,7 @@ def main():
 
     def step(profile):
         for i, (lo, hi, lab) in enumerate(dev):
-            results[i] = net.certify(lo, hi, lab, stream=stream.cuda_stream, profile=profile, fuse=args.fuse, reuse=results[i],
+            results[i] = net.certify(lo, hi, lab, stream=stream.cuda_stream, profile=profile, fuse=args.fuse, reuse=results[i], **({} if args.use_graph < 0 else {"use_graph": args.use_graph}),
                                      certifier=args.certifier, max_backsub_depth=args.max_depth,
                                      final_backsub_depth=args.final_depth)
 
