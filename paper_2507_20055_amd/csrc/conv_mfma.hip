@@ -906,8 +906,11 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     // channel chunk: all channels if two workgroups then fit a CU, otherwise the largest divisor of Co that does
     int CC = g.Co;
     auto lds_for = [&](int rb, int cc) { return (size_t)rb * ih * iw * (cc + 4) * 4 + (size_t)(cc + 4) * 4 + 256 * 20 + (relu ? (size_t)rb * 16 : 0); };
-    while (CC > gc && lds_for(RB, CC) > 72 * 1024 && (CC / 2) % gc == 0) CC /= 2;
-    while (RB > 1 && lds_for(RB, CC) > 72 * 1024) --RB;
+    // two workgroups per CU with all channels staged at once when a workgroup holds several rows (measured: one chunk beats
+    // two chunks at three workgroups per CU there); a single-row workgroup prefers the smaller chunk and three per CU
+    const size_t cap = (RB >= 2 ? 77 : 72) * 1024;
+    while (CC > gc && lds_for(RB, CC) > cap && (CC / 2) % gc == 0) CC /= 2;
+    while (RB > 1 && lds_for(RB, CC) > cap) --RB;
     if (lds_for(RB, CC) > kLdsBudget) return false;
     a.CC = CC;
     a.pstride = CC + 4;
