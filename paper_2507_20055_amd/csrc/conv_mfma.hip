@@ -356,7 +356,8 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 #pragma unroll
                         for (int t = 0; t < TT; ++t) {
                             const int py = py0[t] - jy, px = px0[t] - jx;
-                            const bool ok = live[t] && py >= 0 && py < a.ih && px >= 0 && px < a.iw;
+                            // one select, no branches: unsigned compares fold the two range tests of each coordinate
+                            const bool ok = live[t] & ((unsigned)py < (unsigned)a.ih) & ((unsigned)px < (unsigned)a.iw);
                             addr[t] = ok ? e0[t] - (jy * a.iw + jx) * a.pstride : zoff + 4 * kq;
                         }
                     }
@@ -386,7 +387,15 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                 if (nit > 0) load_b(b0);
                 if (nit > 1) load_b(b1);
                 if (nit > 2) load_b(b2);
-                for (int it = 0; it < nit; it += 4) {
+                int it = 0;
+                // full rounds of four steps while at least seven steps remain: no per-step bound checks
+                for (; it + 7 <= nit; it += 4) {
+                    load_b(b3); step(b0);
+                    load_b(b0); step(b1);
+                    load_b(b1); step(b2);
+                    load_b(b2); step(b3);
+                }
+                for (; it < nit; it += 4) {
                     if (it + 3 < nit) load_b(b3);
                     step(b0);
                     if (it + 1 < nit) {
