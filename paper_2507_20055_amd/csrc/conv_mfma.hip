@@ -42,6 +42,8 @@ struct CtArgs {
     int CC;          // channels of the reduction staged in LDS at a time (divides Co, multiple of 8)
     int pstride;     // LDS floats per input position (CC + 4)
     int rowstride;   // LDS floats per input row patch (ih*iw*pstride)
+    // multiply-high constants 2^32 / d + 1 of the staging loops (d = CC / 4, ih * iw, iw), worked out on the host
+    unsigned magic_cc4n, magic_npos, magic_iw;   // (0 for d = 1: the quotient is the dividend)
 };
 
 // RELU variants: the sign-split ReLU step of the layer above the convolution (with the bias fold of the convolution) is
@@ -80,6 +82,9 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & (TE - 1), kq = lane / TE;
     const long long m0 = (long long)blockIdx.x * a.RB;
     const int q0 = blockIdx.y * kCtEntries;
+    // quotient and remainder by the stride (non-negative x): strides 1 and 2 take no division
+    auto divs = [&](int x) __attribute__((always_inline)) { return a.s == 1 ? x : a.s == 2 ? x >> 1 : x / a.s; };
+    auto mods = [&](int x) __attribute__((always_inline)) { return a.s == 1 ? 0 : a.s == 2 ? x & 1 : x % a.s; };
     const int npos = a.ih * a.iw;
     const int nchunks = a.Co / a.CC;                                   // channel chunks of the reduction
     const int cc4n = a.CC >> 2;
@@ -90,13 +95,13 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     if (a.RB == 1 && gridDim.y > 1 && (!RELU || blockIdx.y > 0)) {
         int lo = a.ih, hi = -1;
         for (int cy = 0; cy < a.s; ++cy) {
-            const int y0 = ((cy - a.off) % a.s + a.s) % a.s;
-            const int Hc = y0 < a.oh ? (a.oh - y0 + a.s - 1) / a.s : 0;
-            const int base_y = (y0 + a.off - cy) / a.s;
-            const int nky = cy < a.kh ? (a.kh - cy + a.s - 1) / a.s : 0;
+            const int y0 = mods(cy + a.s * a.off - a.off);          // (cy - off) mod s, argument kept non-negative
+            const int Hc = y0 < a.oh ? divs(a.oh - y0 + a.s - 1) : 0;
+            const int base_y = divs(y0 + a.off - cy);
+            const int nky = cy < a.kh ? divs(a.kh - cy + a.s - 1) : 0;
             for (int cx = 0; cx < a.s; ++cx) {
-                const int x0 = ((cx - a.off) % a.s + a.s) % a.s;
-                const int Wc = x0 < a.ow ? (a.ow - x0 + a.s - 1) / a.s : 0;
+                const int x0 = mods(cx + a.s * a.off - a.off);
+                const int Wc = x0 < a.ow ? divs(a.ow - x0 + a.s - 1) : 0;
                 const int Pc = Hc * Wc;
                 if (Pc == 0 || q0 >= Pc || nky == 0) continue;
                 const int qe = min(q0 + kCtEntries, Pc) - 1;
@@ -109,7 +114,9 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
         band_lo = hi >= lo ? lo * a.iw : 0;
         band_n = hi >= lo ? (hi - lo + 1) * a.iw : 0;
     }
-    const unsigned long long magic_cc4n = (1ull << 32) / (unsigned)cc4n + 1, magic_npos = (1ull << 32) / (unsigned)max(band_n, 1) + 1;
+    const unsigned magic_cc4n = a.magic_cc4n;
+    const unsigned magic_npos = band_n == npos ? a.magic_npos : band_n > 1 ? (unsigned)((1ull << 32) / (unsigned)band_n + 1) : 0u;
+    auto quot = [](int x, unsigned magic) __attribute__((always_inline)) { return magic ? (int)__umulhi((unsigned)x, magic) : x; };
 
     // Staging reads go through buffer resources (offsets past the range return zeros: no branches around the loads) and
     // are issued kStageU at a time before the first LDS write, so a thread has several 16-byte loads in flight.
@@ -133,8 +140,8 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
             for (int u = 0; u < kStageU; ++u) {
                 const int idx = idx0 + u * kCtThreads;
                 // quotients by the run-time extents through multiply-high (exact: idx * divisor < 2^32)
-                const int t = (int)(((unsigned long long)idx * magic_cc4n) >> 32), c4 = idx - t * cc4n;
-                const int ml = (int)(((unsigned long long)t * magic_npos) >> 32), pos = band_lo + t - ml * band_n;
+                const int t = quot(idx, magic_cc4n), c4 = idx - t * cc4n;
+                const int ml = quot(t, magic_npos), pos = band_lo + t - ml * band_n;
                 const bool ok = idx < total;                       // rows past M lie past the resource's range
                 v[u] = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(
                                                    xres, ok ? (ml * a.ld_in + pos * a.Co + c0 + c4 * 4) * 4 : kNoData, 0, 0));
@@ -149,7 +156,7 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     // RELU staging: a wavefront takes a row at a time (4 / RB wavefronts share a row when the workgroup has fewer than four
     // rows), so a row's side, input and patch origin are scalars and its constant is one wavefront reduction in a fixed
     // order.  Positions off the layer's grid (zero padding: no neuron) are staged as zeros.
-    const unsigned long long magic_iw = (1ull << 32) / (unsigned)max(a.iw, 1) + 1;
+    const unsigned magic_iw = a.magic_iw;
     const __amdgpu_buffer_rsrc_t qres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float2*>(rl.pk2), 0, RELU ? rl.batch * rl.ldpk * 8 : 0, 0x00020000);
     auto stage_input_relu = [&](int c0) __attribute__((always_inline)) {
@@ -177,8 +184,8 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 #pragma unroll
                 for (int u = 0; u < kStageR; ++u) {
                     const int i = i0 + u * 64 * wpr;
-                    const int pb = (int)(((unsigned long long)i * magic_cc4n) >> 32), c4 = i - pb * cc4n, pos = band_lo + pb;
-                    const int py = (int)(((unsigned long long)pos * magic_iw) >> 32), px = pos - py * a.iw;
+                    const int pb = quot(i, magic_cc4n), c4 = i - pb * cc4n, pos = band_lo + pb;
+                    const int py = quot(pos, magic_iw), px = pos - py * a.iw;
                     const int gy = oy + py, gx = ox + px;
                     const bool in = i < span;
                     const bool ok = in && rowok && gy >= 0 && gy < rl.gh && gx >= 0 && gx < rl.gw;
@@ -256,15 +263,15 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
 
     for (int cy = 0; cy < a.s; ++cy) {
         // rows y of this class: (y + off) mod s == cy  ->  y = y0 + s*iy
-        const int y0 = ((cy - a.off) % a.s + a.s) % a.s;
-        const int Hc = y0 < a.oh ? (a.oh - y0 + a.s - 1) / a.s : 0;
-        const int base_y = (y0 + a.off - cy) / a.s;
-        const int nky = cy < a.kh ? (a.kh - cy + a.s - 1) / a.s : 0;
+        const int y0 = mods(cy + a.s * a.off - a.off);
+        const int Hc = y0 < a.oh ? divs(a.oh - y0 + a.s - 1) : 0;
+        const int base_y = divs(y0 + a.off - cy);
+        const int nky = cy < a.kh ? divs(a.kh - cy + a.s - 1) : 0;
         for (int cx = 0; cx < a.s; ++cx) {
-            const int x0 = ((cx - a.off) % a.s + a.s) % a.s;
-            const int Wc = x0 < a.ow ? (a.ow - x0 + a.s - 1) / a.s : 0;
-            const int base_x = (x0 + a.off - cx) / a.s;
-            const int nkx = cx < a.kw ? (a.kw - cx + a.s - 1) / a.s : 0;
+            const int x0 = mods(cx + a.s * a.off - a.off);
+            const int Wc = x0 < a.ow ? divs(a.ow - x0 + a.s - 1) : 0;
+            const int base_x = divs(x0 + a.off - cx);
+            const int nkx = cx < a.kw ? divs(a.kw - cx + a.s - 1) : 0;
             const int Pc = Hc * Wc;
             if (Pc == 0 || q0 >= a.RB * Pc) continue;           // uniform over the workgroup
 
@@ -924,6 +931,10 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
     a.CC = CC;
     a.pstride = CC + 4;
     a.rowstride = ih * iw * a.pstride;
+    auto magic_of = [](int d) { return d > 1 ? (unsigned)((((uint64_t)1) << 32) / (unsigned)d + 1) : 0u; };
+    a.magic_cc4n = magic_of(CC / 4);
+    a.magic_npos = magic_of(ih * iw);
+    a.magic_iw = magic_of(iw);
     const size_t row_bytes2 = (size_t)a.rowstride * 4;
     const size_t fixed = (size_t)a.pstride * 4 + 256 * 20 + (relu ? (size_t)RB * 16 : 0);
     a.RB = RB;
