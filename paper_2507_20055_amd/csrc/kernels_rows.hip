@@ -639,7 +639,16 @@ __global__ __launch_bounds__(kThreads) void finalize_bounds_kernel(
     const long long m = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (m >= M) return;
     double v = cst[m];
-    for (int t = 0; t < nslots; ++t) v += (double)part[(size_t)t * part_stride + m];
+    // eight slots requested at a time, added in index order (the loads are independent, the sum is not reordered)
+    int t = 0;
+    for (; t + 8 <= nslots; t += 8) {
+        float p[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p[k] = part[(size_t)(t + k) * part_stride + m];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v += (double)p[k];
+    }
+    for (; t < nslots; ++t) v += (double)part[(size_t)t * part_stride + m];
     const long long sb = m / R;
     const int r = (int)(m - sb * R);
     const int side = (int)(sb / batch), b = (int)(sb - (long long)side * batch);
