@@ -175,3 +175,41 @@ def test_conv_transpose(case, algo):
         mag = ops.conv_transpose_rows(np.abs(rows), ih, iw, np.abs(K), s, off, oh, ow)
         assert np.all(np.abs(got[:, :n_out] - ref) <= 2e-6 * mag + 1e-6), np.abs(got[:, :n_out] - ref).max()
         assert np.all(got[:, n_out:] == 0.0)
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_conv_transpose_random_shapes(block):
+    """Seeded sweep of shapes for the transposed convolution (strides 1-3, kernels 1-5, odd extents, channel counts on
+    and off the MFMA kernels' multiples, patch and dense windows) against the expanded-matrix definition."""
+    from paper_2507_20055_amd import binding as b
+    done = 0
+    for t in range(40):
+        rng = np.random.default_rng(7000 + 40 * block + t)
+        s = int(rng.choice([1, 1, 2, 2, 3])); k = int(rng.integers(1, 6))
+        ih = int(rng.integers(1, 24)); iw = int(rng.integers(1, 24))
+        Co = int(rng.choice([4, 8, 16, 24, 32, 48, 64, 6])); Ci = int(rng.choice([1, 3, 4, 5, 8, 12, 16, 24, 32, 40, 64]))
+        if rng.random() < 0.5:                       # dense window: `off` rows / columns of the full extent cut off all round
+            off = int(rng.integers(0, k))
+            oh, ow = (ih - 1) * s + k - 2 * off, (iw - 1) * s + k - 2 * off
+            if rng.random() < 0.3:
+                oh += min(off, int(rng.integers(0, s))); ow += min(off, int(rng.integers(0, s)))
+        else:
+            off = 0
+            oh, ow = (ih - 1) * s + k, (iw - 1) * s + k
+        if oh < 1 or ow < 1 or oh * ow * Ci > 40000 or ih * iw * Co > 40000:
+            continue
+        M = int(rng.choice([1, 2, 3, 5, 17, 37, 64, 129, 300]))
+        n_in, n_out = ih * iw * Co, oh * ow * Ci
+        ld_in, ld_out = (n_in + 3) // 4 * 4, (n_out + 31) // 32 * 32
+        rows, rows_f = _rows(rng, M, n_in, ld_in)
+        K = rng.normal(size=(Co, Ci, k, k)).astype(np.float32)
+        out = torch.full((M, ld_out), float("nan"), device="cuda")
+        b.dpc_op_conv_transpose(_dev(rows_f), ih, iw, Co, K, s, off, out, oh, ow)
+        got = out.cpu().numpy()
+        ref = ops.conv_transpose_rows(rows, ih, iw, K, s, off, oh, ow)
+        mag = ops.conv_transpose_rows(np.abs(rows), ih, iw, np.abs(K), s, off, oh, ow)
+        case = (ih, iw, Co, Ci, k, s, off, oh, ow, M)
+        assert np.all(np.abs(got[:, :n_out] - ref) <= 2e-6 * mag + 1e-6), case
+        assert np.all(got[:, n_out:] == 0.0), case
+        done += 1
+    assert done >= 20
