@@ -309,7 +309,7 @@ struct Waiting {
     int kind;              // 0: rows of its own (src = a skip buffer), 1: the bounded layer's shared rows / cores, 2: unit block
     const float* src;
     int ld;
-    int slot;              // skip buffer held (kind 0), else -1
+    int slot;              // kind 0: 0 when src is a buffer of the pool (returned when the block is merged), else -1
     bool patch;
     int ph, pw, S, P;      // patch geometry of the block when it was set aside
 };
@@ -343,8 +343,17 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     const bool may_fuse = P.opt->fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
 
     std::vector<Waiting> waiting;
-    std::vector<int> free_slots;
-    for (int k = (int)net->skipbuf.size() - 1; k >= 0; --k) free_slots.push_back(k);
+    // Row buffers: cur / nxt plus the pool of skip buffers (all of one size).  When the rows cross an Add layer they are
+    // not copied: the buffer they sit in is kept for the waiting block and, once the next contraction has read it, a
+    // buffer from the pool takes its place in the cur / nxt pair (nothing writes the rows in place before that
+    // contraction: the layer below an Add layer is affine or convolution).
+    std::vector<float*> pool;
+    for (int k = (int)net->skipbuf.size() - 1; k >= 0; --k) pool.push_back(net->skipbuf[k]->p);
+    float* held = nullptr;         // buffer of the rows set aside at the last Add layer while it is still `cur`
+    float* spare = nullptr;        // the pool buffer that replaces it
+    auto after_swap = [&]() {
+        if (held && nxt == held) { nxt = spare; held = nullptr; spare = nullptr; }
+    };
     if (diag_target >= 0) waiting.push_back(Waiting{diag_target, 2, nullptr, 0, -1, f.patch, 1, 1, 1, 0});
     auto blocked = [&](int idx) {
         for (const Waiting& w : waiting)
@@ -416,7 +425,12 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             }
             P.prof->end();
             res->prof.relax_launches++;
-            if (w.slot >= 0) free_slots.push_back(w.slot);
+            if (w.slot >= 0) {
+                // back to the pool -- unless the block's buffer is still one of the pair (no contraction since the Add
+                // layer): then the spare one goes back instead
+                if (w.src == held) { pool.push_back(spare); held = nullptr; spare = nullptr; }
+                else pool.push_back(const_cast<float*>(w.src));
+            }
             waiting.erase(waiting.begin() + k);
         }
     };
@@ -430,12 +444,22 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             if (shared) {
                 w.kind = 1; w.src = shared; w.ld = ld_shared;
             } else {
-                DPC_REQUIRE(!free_slots.empty(), DPC_EUNSUPPORTED, "skip connections nested deeper than the workspace allows");
-                w.slot = free_slots.back();
-                free_slots.pop_back();
-                float* dst = net->skipbuf[w.slot]->p;
-                DPC_HIP(hipMemcpyAsync(dst, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
-                w.src = dst; w.ld = f.ld;
+                DPC_REQUIRE(!pool.empty(), DPC_EUNSUPPORTED, "skip connections nested deeper than the workspace allows");
+                w.slot = 0;
+                w.ld = f.ld;
+                if (held || blocked(at - 1) || L.skip == at - 1) {
+                    // another block joins the rows at the layer below (in place), or the previous Add layer's buffer is
+                    // still one of the pair: a copy waits
+                    float* dst = pool.back();
+                    pool.pop_back();
+                    DPC_HIP(hipMemcpyAsync(dst, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
+                    w.src = dst;
+                } else {
+                    held = cur;
+                    spare = pool.back();
+                    pool.pop_back();
+                    w.src = cur;
+                }
             }
             waiting.push_back(w);
             bias_folded = bias_below_add;
@@ -477,6 +501,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 res->prof.contract_launches++;
                 slots += used;
                 std::swap(cur, nxt);
+                after_swap();
                 f.ld = net->ld_of(0);
                 at = 0;
                 depth += 2;
@@ -514,6 +539,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 res->prof.contract_flop += useful * 2.0 * (double)M * pos * cv.g.Co * cv.g.Ci * cv.g.kh * cv.g.kw;
                 res->prof.contract_launches++;
                 std::swap(cur, nxt);
+                after_swap();
                 f = o;
                 shared = nullptr;
                 bias_folded = false;
@@ -587,6 +613,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             P.prof->end();
             res->prof.contract_launches++;
             std::swap(cur, nxt);
+            after_swap();
             bias_folded = fused_relu;
         }
         --at;
