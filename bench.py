@@ -20,7 +20,7 @@ PEAK_HBM_GBS = 8000.0
 # L2-miss traffic of the dominant MFMA kernel per launch, bytes (fetch + write), from the two rocprofv3 --pmc
 # runs summarised in profiles/pmc_<workload>.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after calibration on a
 # plain 256 MiB copy); mean over the launches of one step.  Only valid for the default tuning.
-TRAFFIC = {"cfg2": 7.352e7, "cfg3": 1.540e8, "cfg4": 1.985e9, "cfg5": 2.561e9, "res_fc": 1.450e8, "res_conv": 3.711e8}
+TRAFFIC = {"cfg2": 7.352e7, "cfg3": 1.540e8, "cfg4": 1.985e9, "cfg5": 2.561e9, "res_fc": 1.449e8, "res_conv": 1.136e9}
 
 DESCR = {
     "cfg1": "cfg1: FC 784-100-100-100-10, B=1, eps=0.01",
