@@ -300,6 +300,8 @@ struct Pass {
     Prof* prof;
     int B;
     int maxd;             // traversal limit of this pass (-1: to the input)
+    bool fuse;            // the call filled the packed ReLU parameters (pk, pk2, pk2v) of every layer: only then may a
+                          // kernel that applies a ReLU step from them be chosen (an earlier call's are stale)
 };
 
 // A block of the expression that waits on a skip connection until the traversal reaches the layer it is over
@@ -340,7 +342,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     int slots = 0;                 // row-constant partial-sum slots written by fused epilogues so far
     bool concretised = false;      // the last contraction already reduced the rows against the box
     const int split = contract_split_terms();       // > 0: contractions on the bf16 MFMA units, every step its own kernel
-    const bool may_fuse = P.opt->fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
+    const bool may_fuse = P.fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
 
     std::vector<Waiting> waiting;
     // Row buffers: cur / nxt plus the pool of skip buffers (all of one size).  When the rows cross an Add layer they are
@@ -469,7 +471,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             ++depth;
             continue;
         }
-        if (waiting.empty() && L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.opt->fuse && maxd < 0 && !keep_sym && net->pk2.p &&
+        if (waiting.empty() && L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.fuse && maxd < 0 && !keep_sym && net->pk2.p &&
             net->layers[0]->kind == CONV && (shared != nullptr || bias_folded || depth > 0)) {
             // patch rows over the first ReLU layer: ReLU step, first layer and concretisation in one kernel
             const Layer& first = *net->layers[0];
@@ -484,7 +486,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 return;
             }
         }
-        if (waiting.empty() && L.kind == RELU && at == 2 && !f.patch && !shared && P.opt->fuse && maxd < 0 && !keep_sym && net->pk2.p &&
+        if (waiting.empty() && L.kind == RELU && at == 2 && !f.patch && !shared && P.fuse && maxd < 0 && !keep_sym && net->pk2.p &&
             net->layers[0]->kind == CONV && net->part.p && M <= net->part_stride && slots < dpc_network::kMaxSlots) {
             // dense rows over the first ReLU layer: its step is applied while the first layer's transposed convolution
             // loads the rows (no pass of its own over them); the constants it adds arrive in slots
@@ -508,7 +510,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 break;
             }
         }
-        if (L.kind == RELU && at >= 3 && (!shared || cst_init) && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.opt->fuse &&
+        if (L.kind == RELU && at >= 3 && (!shared || cst_init) && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.fuse &&
             (maxd < 0 || depth + 2 <= maxd) && (int)net->pk2v.size() > at && net->pk2v[at] && net->pk2v[at]->p && net->rpart.p &&
             (size_t)M <= net->rpart.count && !blocked(at - 1)) {
             // ReLU step applied while the transposed convolution below stages the rows (no pass of its own over them); the
@@ -1178,7 +1180,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws_epoch};
         const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
         auto enqueue_reusecert = [&]() {
-            Pass P{net, res, &opt, s, &prof, B, -1};
+            Pass P{net, res, &opt, s, &prof, B, -1, false};
             float* E = net->buf[0].p;            // stored bounds of the current affine layer: [side][b][n][ldE]
             float* Rr = net->buf[1].p;           // [b][2n + 1][ldE]: the ReLU layer's input-level bounds + unit row
             double* cst = net->cst.p;
@@ -1257,7 +1259,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         auto enqueue_all = [&]() {
             if (reuse_cert && nl >= 3) { enqueue_reusecert(); return; }
             if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
-            Pass P{net, res, &opt, s, &prof, B, opt.max_backsub_depth};
+            Pass P{net, res, &opt, s, &prof, B, opt.max_backsub_depth, fuse};
             for (int i = 1; i <= nl; ++i) {
                 Layer& L = *net->layers[i - 1];
                 if (L.kind == RELU) {

@@ -11,7 +11,7 @@ def close(a, b, scale=1.0):
 
 
 def compare_with_oracle(net, lo, hi, gpu, ora, label=None, max_flipped_inputs=0, check_samples=2000, seed=0,
-                        relu_bounds=True):
+                        relu_bounds=True, min_flip_layer=0):
     """Element-by-element comparison of every layer's l,u (and lambda/mu/nu, margins, verdicts).
 
     lambda = [l+u >= 0] is a discontinuous decision taken on floating-point values: when the oracle's
@@ -19,10 +19,13 @@ def compare_with_oracle(net, lo, hi, gpu, ora, label=None, max_flipped_inputs=0,
     two runs bound *different* (both valid) relaxations for that input.  Such inputs are compared up to
     the flipped layer, the flip is checked to be a genuine near-tie, and everything after it is checked
     for validity instead (l <= u, sampled concrete activations contained).  At most
-    `max_flipped_inputs` inputs may take that route.
+    `max_flipped_inputs` inputs may take that route, and none of them at a layer below `min_flip_layer`.
+    mu, nu are compared with the oracle's wherever the oracle's u - l exceeds 1e-3 (tolerance: what the
+    stated tolerance on l, u allows to first order, doubled), and everywhere with the transformer's formula
+    evaluated on the bounds the kernel itself was given.
     relu_bounds=False: the certifier's specification leaves l, u of ReLU neurons unset (ReuseCert), so only affine
     layers are compared with the oracle (what the library returns for ReLU layers is still checked for soundness).
-    Returns the list of flipped inputs."""
+    Returns ({flipped input: layer of its first flip}, worst |gpu - oracle| / tolerance)."""
     B = lo.shape[0]
     nl = len(net.layers)
     flipped = {}
@@ -57,9 +60,21 @@ def compare_with_oracle(net, lo, hi, gpu, ora, label=None, max_flipped_inputs=0,
                     f"lambda differs at layer {k} [{b},{i}] but l+u = {pl + pu} is not a near-tie"
                 flipped.setdefault(int(b), k)
             ok_rows = np.array([b not in flipped for b in range(B)])
-            # mu, nu: the ReLU transformer's formulas (Appendix C, compute_upper) evaluated in float64
-            # on the bounds the kernel was given; their end-to-end effect is covered by the l,u
-            # comparison of the layers above
+            # mu, nu against the oracle's.  d(mu) = (-l du + u dl) / (u-l)^2, d(nu) = (l^2 du - u^2 dl) / (u-l)^2 with
+            # |dl|, |du| up to the stated tolerance on the bounds (a neuron whose stability the two sides decide
+            # differently has l or u within that tolerance of 0, which the same bound covers)
+            ol, ou = ora.l[k - 1], ora.u[k - 1]
+            wide = ((ou - ol) > 1e-3) & ok_rows[:, None]
+            tl, tu = ATOL + RTOL * np.abs(ol), ATOL + RTOL * np.abs(ou)
+            w2 = np.where(wide, (ou - ol) ** 2, 1.0)
+            tol_mu = 2 * (np.abs(ol) * tu + np.abs(ou) * tl) / w2 + 1e-6
+            tol_nu = 2 * (ol * ol * tu + ou * ou * tl) / w2 + 1e-6 * (1 + np.abs(ora.nu[k]))
+            for g, o, t, name in ((gmu, ora.mu[k], tol_mu, "mu"), (gnu, ora.nu[k], tol_nu, "nu")):
+                bad = wide & (np.abs(g - o) > t)
+                assert not bad.any(), f"{name} differs from the oracle at layer {k} {np.argwhere(bad)[0]}: " \
+                                      f"gpu {g[tuple(np.argwhere(bad)[0])]!r} oracle {o[tuple(np.argwhere(bad)[0])]!r}"
+            # the ReLU transformer's formulas (Appendix C, compute_upper) evaluated in float64 on the bounds the
+            # kernel was given
             pl, pu = (a.astype(np.float64) for a in gpu_layer(k - 1))
             unstable = (pl < 0) & (pu > 0)
             d = np.where(unstable, pu - pl, 1.0)
@@ -78,6 +93,7 @@ def compare_with_oracle(net, lo, hi, gpu, ora, label=None, max_flipped_inputs=0,
         near0 = (np.abs(ora.margin) <= ATOL).any(axis=1)
         assert np.array_equal(gv[ok_rows & ~near0], ora.verdict[ok_rows & ~near0])
     assert len(flipped) <= max_flipped_inputs, f"lambda flipped on inputs {flipped}"
+    assert all(k >= min_flip_layer for k in flipped.values()), f"lambda flipped below layer {min_flip_layer}: {flipped}"
     # validity of everything (also the flipped inputs): l <= u and sampled activations contained
     if check_samples:
         rng = np.random.default_rng(seed)

@@ -62,7 +62,10 @@ def _check(net, rng, seed, allow_final=True):
     try:
         g = gnet.certify(lo, hi, label, fuse=fuse, **kw)
         o = oracle.run(net, lo, hi, label=label, **okw)
-        compare_with_oracle(net, lo, hi, g, o, label, max_flipped_inputs=B)
+        # at most one input may leave the element-by-element comparison after a lambda near-tie, and only at the
+        # network's last ReLU layer (everything below it is then still compared)
+        last_relu = max(i + 1 for i, L in enumerate(net.layers) if L.kind == "relu")
+        compare_with_oracle(net, lo, hi, g, o, label, max_flipped_inputs=1, min_flip_layer=last_relu)
     finally:
         gnet.close()
 
