@@ -1,13 +1,15 @@
 """Benchmark of the DeepPoly back-substitution hot path on one MI355X.
 
 A step is one pass of the whole hot path (all layers' traversals, concretisations, margin rows and
-verdicts) over one batch of synthetic boxes of the named workload; for cfg2 that is the three
-perturbation sizes, 96 instances.  Inputs are resident in HBM before the timed region.  Prints ONE
-JSON line.
+verdicts) over one batch of synthetic boxes of the named workload.  The headline line is cfg5, the
+largest configuration (9.9 TFLOP of back-substitution per step); the default run also measures every
+other configuration the same way and reports them under "per_config" (cfg2: the three perturbation
+sizes, 96 instances per step).  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -17,10 +19,17 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# L2-miss traffic of the dominant MFMA kernel per launch, bytes (fetch + write), from the two rocprofv3 --pmc
-# runs summarised in profiles/pmc_<workload>.txt (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 after calibration on a
-# plain 256 MiB copy); mean over the launches of one step.  Only valid for the default tuning.
-TRAFFIC = {"cfg2": 7.352e7, "cfg3": 1.540e8, "cfg4": 1.985e9, "cfg5": 2.561e9, "res_fc": 1.449e8, "res_conv": 1.136e9}
+
+def counter_traffic(workload):
+    """L2-miss traffic of the dominant MFMA kernel per launch in bytes (fetch + write, calibrated on a plain copy of
+    known size), as the committed rocprofv3 --pmc summary of this workload states it; None when there is none."""
+    try:
+        text = open(os.path.join(ROOT, "profiles", f"pmc_{workload}.txt")).read()
+    except OSError:
+        return None
+    m = re.search(r"HBM traffic per launch.*total ([0-9.e+]+) bytes", text)
+    return float(m.group(1)) if m else None
+
 
 DESCR = {
     "cfg1": "cfg1: FC 784-100-100-100-10, B=1, eps=0.01",
@@ -33,12 +42,13 @@ DESCR = {
 }
 
 
-def main():
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(DESCR))
+    ap.add_argument("--workload", default="cfg5", choices=sorted(DESCR))
+    ap.add_argument("--no-per-config", action="store_true", help="measure --workload only (profiler runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="inputs per eps given to the CPU oracle (0 = default)")
     ap.add_argument("--variant", type=int, default=-1, help="contraction tile variant (tuning)")
@@ -54,32 +64,21 @@ def main():
     ap.add_argument("--use-graph", type=int, default=-1, help="dpc_options.use_graph (-1: the library default)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 256 MiB device-to-device copy first (known size, to scale rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
-        sys.exit(2)
+    return ap.parse_args()
 
+
+# inputs per eps setting handed to the float64 oracle for the CPU baseline (bounded: a few seconds to ~15 s each)
+CPU_SAMPLE = {"cfg1": 1, "cfg2": 32, "cfg3": 32, "cfg4": 2, "cfg5": 16, "res_fc": 16, "res_conv": 2}
+
+
+def measure(workload, args, steps, warmup, cpu_baseline):
+    """Times `steps` steps of one workload; returns the record (the headline line's fields for that workload)."""
     import numpy as np
     import torch
     from paper_2507_20055_amd import binding, workloads as wl
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.variant >= 0:
-        binding.dpc_tuning_set("contract_variant", args.variant)
-    for kv in args.tune:
-        key, _, val = kv.partition("=")
-        binding.dpc_tuning_set(key, int(val))
-
-    if args.calibrate_copy:
-        src = torch.empty(64 * 1024 * 1024, device="cuda", dtype=torch.float32).normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    n_eps = len(wl.CONFIGS[args.workload]["eps"])
-    loads = [wl.make_workload(args.workload, eps_index=i) for i in range(n_eps)]
+    n_eps = len(wl.CONFIGS[workload]["eps"])
+    loads = [wl.make_workload(workload, eps_index=i) for i in range(n_eps)]
     net = binding.Network(loads[0].net, device=0)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -96,12 +95,12 @@ def main():
                                      certifier=args.certifier, max_backsub_depth=args.max_depth,
                                      final_backsub_depth=args.final_depth)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(0)
     torch.cuda.synchronize()
     # timed region: K steps as a caller would run them
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(0)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -109,7 +108,7 @@ def main():
     # (per-class durations for the roofline figures; the events themselves cost a few percent)
     prof_tot = None
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(1)
         for r in results:
             p = r.profile()
@@ -120,6 +119,10 @@ def main():
     inputs_per_step = B * n_eps
     verified = int(sum(int(r.verdict()[0].sum()) for r in results))
     min_abs_margin = float(min(float(np.abs(r.verdict()[1]).min()) for r in results))
+    last = len(loads[0].net.layers)
+    # mean width u - l of the output layer's bounds over the batch (every eps setting): shows at a glance whether the
+    # perturbation is one the relaxation can still say something about, or the bounds have blown up
+    widths = [float(np.mean(np.subtract(*r.concrete(last)[::-1]))) for r in results]
 
     P = prof_tot
     # dominant MFMA kernel: the LDS-resident traversal kernel where it runs, else the per-layer contraction
@@ -130,25 +133,35 @@ def main():
     dom_tflops = dom_flop / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     mfma_ms = P["chain_ms"] + P["contract_ms"]
     mfma_tflops = (P["chain_flop"] + P["contract_flop"]) / (mfma_ms * 1e-3) / 1e12 if mfma_ms > 0 else 0.0
-    relax_gbs = P["relax_bytes"] / (P["relax_ms"] * 1e-3) / 1e9 if P["relax_ms"] > 0 else 0.0
-    conc_gbs = P["concretise_bytes"] / (P["concretise_ms"] * 1e-3) / 1e9 if P["concretise_ms"] > 0 else 0.0
+    default_run = not args.tune and args.variant < 0 and args.fuse == 1 and args.certifier == "deeppoly" and args.max_depth < 0 and args.final_depth in (-2, -1)
+
+    def hbm_pass(key):
+        # launches of a few rows (the output / margin rows of the fully-connected workloads) finish out of L2 and are
+        # launch-bound: time and launch count only; a bandwidth figure is given from 64 MB of rows per launch up
+        ms, launches, nbytes = P[key + "_ms"], P[key + "_launches"], P[key + "_bytes"]
+        rec = {"launches": launches, "ms_per_step": ms / steps}
+        if launches and ms > 0 and nbytes / launches >= 64e6:
+            gbs = nbytes / (ms * 1e-3) / 1e9
+            rec.update({"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS})
+        return rec
 
     out = {
         "metric": "certified inputs/sec",
-        "value": inputs_per_step * args.steps / dt,
+        "value": inputs_per_step * steps / dt,
         "unit": "inputs/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": dt / args.steps * 1e3,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": dt / steps * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": {"0": "f32", "2": "bf16x3 (operands split into two bf16 terms, fp32 accumulation)",
                   "3": "bf16x6 (operands split into three bf16 terms, fp32 accumulation)"}[dict(kv.partition("=")[::2] for kv in args.tune).get("contract_split", "0")],
         "data": "synthetic",
-        "config": {"workload": DESCR[args.workload], "inputs_per_step": inputs_per_step,
-                   "verified": verified, "min_abs_margin": min_abs_margin, "fuse": args.fuse,
+        "config": {"workload": DESCR[workload], "inputs_per_step": inputs_per_step,
+                   "verified": verified, "min_abs_margin": min_abs_margin, "mean_output_bound_width": sum(widths) / len(widths),
+                   "fuse": args.fuse,
                    "inputs": "host" if args.host_inputs else "resident in HBM", "certifier": args.certifier, "max_backsub_depth": args.max_depth, "final_backsub_depth": args.final_depth},
         "roofline": {
             "kernel": dom_name,
@@ -156,21 +169,16 @@ def main():
             "frac": dom_tflops / PEAK_FP32_MFMA_TFLOPS,
             "launches": dom_launches, "avg_launch_ms": dom_ms / max(dom_launches, 1),
             "flop_per_launch": dom_flop / max(dom_launches, 1),
-            "traffic": TRAFFIC.get(args.workload) if not args.tune and args.variant < 0 and args.fuse == 1 and args.certifier == "deeppoly" and args.max_depth < 0 and args.final_depth in (-2, -1) else None,
+            "traffic": counter_traffic(workload) if default_run else None,
             "all_mfma_kernels": {"achieved": mfma_tflops, "frac": mfma_tflops / PEAK_FP32_MFMA_TFLOPS,
-                                 "flop_per_step": (P["chain_flop"] + P["contract_flop"]) / args.steps,
-                                 "ms_per_step": mfma_ms / args.steps},
+                                 "flop_per_step": (P["chain_flop"] + P["contract_flop"]) / steps,
+                                 "ms_per_step": mfma_ms / steps},
         },
-        # the row passes left outside the MFMA kernels' epilogues in this run (on the fully-connected workloads
-        # only the few margin / output rows: launch-bound; the kernels themselves are measured below)
-        "hbm_passes_in_run": {
-            "relax_step": {"achieved": relax_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": relax_gbs / PEAK_HBM_GBS,
-                           "launches": P["relax_launches"], "ms_per_step": P["relax_ms"] / args.steps},
-            "concretise": {"achieved": conc_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": conc_gbs / PEAK_HBM_GBS,
-                           "launches": P["concretise_launches"], "ms_per_step": P["concretise_ms"] / args.steps},
-        },
-        "time_split_ms_per_step": {k: P[k] / args.steps for k in ("chain_ms", "contract_ms", "relax_ms", "concretise_ms", "other_ms", "total_ms")},
-        "value_with_kernel_events": inputs_per_step * args.steps / dt_events,
+        # the row passes left outside the MFMA kernels' epilogues in this run (the kernels themselves are measured
+        # standalone below)
+        "hbm_passes_in_run": {"relax_step": hbm_pass("relax"), "concretise": hbm_pass("concretise")},
+        "time_split_ms_per_step": {k: P[k] / steps for k in ("chain_ms", "contract_ms", "relax_ms", "concretise_ms", "other_ms", "total_ms")},
+        "value_with_kernel_events": inputs_per_step * steps / dt_events,
     }
 
     # The two HBM-bound passes as standalone kernels at this workload's dominant shape (both sides of the widest
@@ -213,11 +221,10 @@ def main():
         }
         del C, cst
 
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-        default_sample = {"cfg1": 1, "cfg2": 32, "cfg3": 32, "cfg4": 2, "cfg5": 16, "res_fc": 16, "res_conv": 2}[args.workload]
-        ns = min(B, args.cpu_sample or default_sample)
+        ns = min(B, args.cpu_sample or CPU_SAMPLE[workload])
         tc = time.perf_counter()
         for w in loads:
             oracle.run(w.net, w.lo[:ns], w.hi[:ns], label=w.label[:ns], threads=cores, certifier=args.certifier,
@@ -225,6 +232,56 @@ def main():
         tcpu = time.perf_counter() - tc
         out["cpu_baseline"] = {"value": ns * n_eps / tcpu, "unit": "inputs/s", "cores": cores, "kind": "oracle",
                                "sample": f"first {ns} of {B} inputs of each of the {n_eps} eps settings, float64 oracle, {tcpu:.1f} s"}
+    results.clear()
+    net.close()
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_20055_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.variant >= 0:
+        binding.dpc_tuning_set("contract_variant", args.variant)
+    for kv in args.tune:
+        key, _, val = kv.partition("=")
+        binding.dpc_tuning_set(key, int(val))
+
+    if args.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, device="cuda", dtype=torch.float32).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    out = measure(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline)
+    if not args.no_per_config and args.workload == "cfg5":
+        # every other configuration, measured the same way in this same run (each its own timed region of K steps)
+        per = []
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "res_fc", "res_conv"):
+            if args.certifier == "reusecert" and name in ("res_fc", "res_conv"):
+                continue
+            r = measure(name, args, args.steps, args.warmup, not args.no_cpu_baseline)
+            rec = {"workload": r["config"]["workload"], "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+                   "inputs_per_step": r["config"]["inputs_per_step"], "verified": r["config"]["verified"],
+                   "mean_output_bound_width": r["config"]["mean_output_bound_width"],
+                   "roofline": {k: r["roofline"][k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "launches", "avg_launch_ms", "traffic")},
+                   "all_mfma_kernels_frac": r["roofline"]["all_mfma_kernels"]["frac"],
+                   "time_split_ms_per_step": r["time_split_ms_per_step"]}
+            if "hbm_passes_standalone" in r:
+                h = r["hbm_passes_standalone"]
+                rec["hbm_passes_standalone"] = {"shape": h["shape"], "relax_step_frac": h["relax_step"]["frac"], "concretise_frac": h["concretise"]["frac"]}
+            if "cpu_baseline" in r:
+                rec["cpu_baseline"] = r["cpu_baseline"]
+            per.append(rec)
+        out["per_config"] = per
     print(json.dumps(out))
 
 
