@@ -147,6 +147,24 @@ dpc_status dpc_options_default(dpc_options* opt);
 dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const float* hi,
                        const int32_t* label, const dpc_options* opt, dpc_result** result);
 
+/* dpc_certify for callers that cannot allocate device memory: code that runs under a HIP graph capture or inside a
+ * region where hipMalloc is forbidden, tight serving loops, harnesses that track every allocation.  The call makes
+ * no hipMalloc / hipFree / hipHostMalloc and creates no result object: its whole workspace (coefficient rows, row
+ * constants, packed parameters, every layer's bounds) is carved out of ONE array of 64 MiB that the library holds
+ * in static device memory on each device it runs on, from load time until the process ends.
+ *   lo, hi, label : as for dpc_certify, but DEVICE memory of the network's device (DPC_EINVAL otherwise).
+ *   out_l, out_u  : [batch, nK] float32 device, bounds of the last layer (either may be NULL).
+ *   margin_lb     : [batch, nK-1] float32 device, verdict: [batch] int32 device (may be NULL; need a label).
+ *   opt           : certifier DPC_DEEPPOLY with any depth limits; keep_symbolic must be 0; profile and use_graph
+ *                   are ignored (DPC_EUNSUPPORTED for ReuseCert, kept symbolic bounds, the split-precision tuning).
+ * A problem whose workspace exceeds the 64 MiB is rejected with DPC_EINVAL before anything is launched (the
+ * message says so); dpc_certify takes it.  Results equal dpc_certify's bit for bit (same kernels, same order).
+ * Every call on a device uses that device's one array, which keeps the previous call's contents (what has to
+ * start at zero is cleared by a kernel of the call): calls that overlap on one device race, also on different
+ * networks.  Returns after the stream has been synchronised. */
+dpc_status dpc_certify_static(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
+                              const dpc_options* opt, float* out_l, float* out_u, float* margin_lb, int32_t* verdict);
+
 /* Concrete bounds l, u of every neuron of `layer` (0 = the box itself):
  * [batch, n_layer] float32 each, caller-allocated (host or device); either may be NULL. */
 dpc_status dpc_result_concrete(const dpc_result* res, int32_t layer, float* l, float* u);

@@ -54,6 +54,7 @@ EXPORTS = {
     "dpc_network_destroy": [c_vp],
     "dpc_options_default": [ctypes.POINTER(dpc_options)],
     "dpc_certify": [c_vp, c_i32, c_vp, c_vp, c_vp, ctypes.POINTER(dpc_options), ctypes.POINTER(c_vp)],
+    "dpc_certify_static": [c_vp, c_i32, c_vp, c_vp, c_vp, ctypes.POINTER(dpc_options), c_vp, c_vp, c_vp, c_vp],
     "dpc_result_concrete": [c_vp, c_i32, c_vp, c_vp],
     "dpc_result_relaxation": [c_vp, c_i32, c_vp, c_vp, c_vp],
     "dpc_result_symbolic": [c_vp, c_i32, c_i32, c_vp, c_vp],
@@ -178,6 +179,18 @@ class Network:
         r = Result(self, h, batch)
         self._results.append(r)
         return r
+
+    def certify_static(self, lo, hi, label, out_l, out_u, margin_lb=None, verdict=None, *, max_backsub_depth: int = -1,
+                       fuse: int = 1, stream: int = 0, final_backsub_depth: int = -2):
+        """dpc_certify_static: device tensors in, device tensors out, no device allocation inside the call."""
+        batch = int(lo.shape[0])
+        assert tuple(lo.shape) == (batch, self.sizes[0]) and tuple(hi.shape) == tuple(lo.shape)
+        opt = dpc_options()
+        _check(_lib.dpc_options_default(ctypes.byref(opt)))
+        opt.max_backsub_depth, opt.fuse, opt.final_backsub_depth = max_backsub_depth, fuse, final_backsub_depth
+        opt.stream = stream or None
+        _check(_lib.dpc_certify_static(self._h, batch, _ptr(lo), _ptr(hi), _ptr(label), ctypes.byref(opt),
+                                       _ptr(out_l), _ptr(out_u), _ptr(margin_lb), _ptr(verdict)))
 
     def close(self):
         for r in self._results:

@@ -53,6 +53,27 @@ namespace {
 
 enum Kind { AFFINE = 0, CONV = 1, RELU = 2, ADD = 3 };
 
+// Workspace of the entry point that allocates nothing (dpc_certify_static): one array per device, held until the
+// process ends.  In host code the array's name is only a handle: its device address is looked up once per device.
+constexpr size_t kStaticWorkspaceBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+unsigned char* static_workspace(int device)       // `device` must be the current device
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static unsigned char* addr[kMaxDevices] = {};
+    DPC_REQUIRE(device >= 0 && device < kMaxDevices, DPC_EINVAL, "device %d out of range", device);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[device]) {
+        void* p = nullptr;
+        DPC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        DPC_REQUIRE(p, DPC_EHIP, "hipGetSymbolAddress returned no address for the static workspace");
+        addr[device] = static_cast<unsigned char*>(p);
+    }
+    return addr[device];
+}
+
 struct DeviceGuard {
     int prev = -1;
     explicit DeviceGuard(int dev)
@@ -64,13 +85,35 @@ struct DeviceGuard {
     ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
 };
 
+// Bump allocator over a fixed block of device memory (the library's static workspace): nothing is ever freed, the
+// owner rewinds it at the start of a call.
+struct Arena {
+    unsigned char* base = nullptr;
+    size_t size = 0, used = 0;
+    void* take(size_t bytes)
+    {
+        const size_t at = (used + 255) & ~(size_t)255;
+        DPC_REQUIRE(at + bytes <= size, DPC_EINVAL,
+                    "this call needs more than the %zu MiB of the library's static workspace (network or batch too large for "
+                    "the entry point that allocates nothing)", size >> 20);
+        used = at + bytes;
+        return base + at;
+    }
+};
+
 template <class T>
 struct DevBuf {
     T* p = nullptr;
     size_t count = 0;
+    Arena* arena = nullptr;            // set: memory comes from the arena and is never freed here
     bool reserve(size_t n)             // true when the buffer was (re)allocated: old addresses are dead
     {
         if (n <= count) return false;
+        if (arena) {
+            p = static_cast<T*>(arena->take(n * sizeof(T)));
+            count = n;
+            return true;
+        }
         release();
         DPC_HIP(hipMalloc(reinterpret_cast<void**>(&p), n * sizeof(T)));
         count = n;
@@ -78,12 +121,13 @@ struct DevBuf {
     }
     void release()
     {
-        if (p) (void)hipFree(p);
+        if (p && !arena) (void)hipFree(p);
         p = nullptr;
         count = 0;
     }
     ~DevBuf() { release(); }
     DevBuf() = default;
+    explicit DevBuf(Arena* a) : arena(a) {}
     DevBuf(const DevBuf&) = delete;
     DevBuf& operator=(const DevBuf&) = delete;
 };
@@ -112,6 +156,37 @@ struct Layer {
 }  // namespace
 }  // namespace dpc
 
+namespace dpc {
+namespace {
+// Device memory a certify call works in, besides the result's own arrays.
+struct Workspace {
+    Arena* arena = nullptr;                // set: every buffer below is carved from it
+    DevBuf<float> buf[2];                  // coefficient rows, ping-pong
+    DevBuf<double> cst;                    // row constants
+    DevBuf<float> stage;                   // staging for layout permutations / margins
+    // fused-epilogue state: packed per-(side, input, neuron) parameters of every ReLU layer (index 0:
+    // the box), and the slots that collect row-constant partial sums of the fused contractions
+    std::vector<std::unique_ptr<DevBuf<float>>> pk;
+    DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
+    std::vector<std::unique_ptr<DevBuf<float>>> pk2v;      // the same for ReLU layers above a convolution with > 4 input channels
+    DevBuf<float> rpart;                   // one constant per row from a ReLU step applied inside a convolution kernel
+    DevBuf<int32_t> dflag;                 // device word of the input validation for inputs ingested by one kernel (zero between calls)
+    std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
+    DevBuf<float> part;
+    int64_t part_stride = 0;
+    DevBuf<float> rc_rows;                 // ReuseCert: split output/margin rows of the last step, per input
+    uint64_t ws_epoch = 1;                 // bumped whenever a workspace buffer moves (captured graphs hold addresses)
+    Workspace() = default;
+    explicit Workspace(Arena* a) : arena(a), cst(a), stage(a), pk2(a), rpart(a), dflag(a), part(a), rc_rows(a)
+    {
+        buf[0].arena = a;
+        buf[1].arena = a;
+    }
+    DevBuf<float>* fresh_buf() const { return new DevBuf<float>(arena); }
+};
+}  // namespace
+}  // namespace dpc
+
 using namespace dpc;
 
 struct dpc_network {
@@ -122,25 +197,13 @@ struct dpc_network {
     bool finalized = false;
     int device = 0;
     int live_results = 0;
-    // traversal workspace, grown on demand, reused across certify calls
-    DevBuf<float> buf[2];
-    DevBuf<double> cst;
-    DevBuf<float> stage;                   // staging for layout permutations / margins
-    // fused-epilogue state: packed per-(side, input, neuron) parameters of every ReLU layer (index 0:
-    // the box), and the slots that collect row-constant partial sums of the fused contractions
-    std::vector<std::unique_ptr<DevBuf<float>>> pk;
-    DevBuf<float> pk2;                     // compact (mu, nu | lambda) of the first ReLU layer (patch-tail kernel)
-    std::vector<std::unique_ptr<DevBuf<float>>> pk2v;      // the same for ReLU layers above a convolution with > 4 input channels
-    DevBuf<float> rpart;                   // one constant per row from a ReLU step applied inside a convolution kernel
-    int32_t* h_flag = nullptr;             // pinned host word the input validation reports into
-    DevBuf<int32_t> dflag;                 // its device word for inputs that are ingested by one kernel (zero between calls)
+    // traversal workspace, grown on demand, reused across certify calls (the entry point that allocates nothing swaps in
+    // one that lives in the library's static device array for the duration of its call)
+    Workspace own_ws;
+    Workspace* ws = &own_ws;
+    int32_t* h_flag = nullptr;             // pinned host word the input validation reports into (allocated by finalize)
     ~dpc_network() { if (h_flag) (void)hipHostFree(h_flag); }
-    std::vector<std::unique_ptr<DevBuf<float>>> skipbuf;   // residual networks: blocks of rows waiting on a skip connection
     int skip_depth = 0;                    // how many skip connections span one layer at most
-    DevBuf<float> part;
-    int64_t part_stride = 0;
-    DevBuf<float> rc_rows;                 // ReuseCert: split output/margin rows of the last step, per input
-    uint64_t ws_epoch = 1;                 // bumped whenever a workspace buffer moves (captured graphs hold addresses)
     static constexpr int kMaxSlots = 96;
 
     int size_of(int idx) const { return idx == 0 ? n0 : layers[idx - 1]->n_out; }
@@ -178,6 +241,8 @@ struct dpc_result {
         }
     } gkey;
     dpc_profile gprof{};                   // launch and flop counters of the captured sequence
+    dpc_result() = default;
+    explicit dpc_result(Arena* a) : pool(a), margin(a), verdict(a), label(a), sym_coeff(a), sym_cst(a) {}
     ~dpc_result() { if (gexec) (void)hipGraphExecDestroy(gexec); }
 };
 
@@ -291,7 +356,7 @@ size_t workspace_floats(const dpc_network* net, int B, bool with_margin)
 
 // One backward traversal (backsubs_lower and backsubs_upper of R expressions per input) starting
 // from expressions over layer index `at`: either the shared weight rows of layer `own`, or per-input
-// rows already in net->buf[0] (own == NULL).
+// rows already in net->ws->buf[0] (own == NULL).
 struct Pass {
     dpc_network* net;
     dpc_result* res;
@@ -326,9 +391,9 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     dpc_result* res = P.res;
     const int B = P.B;
     const int maxd = P.maxd;
-    float* cur = net->buf[0].p;
-    float* nxt = net->buf[1].p;
-    double* cst = net->cst.p;
+    float* cur = net->ws->buf[0].p;
+    float* nxt = net->ws->buf[1].p;
+    double* cst = net->ws->cst.p;
     Form f = start_form(net, at, own);
     // rows not yet per-input: the layer's own weight rows (dense) or kernel cores (patch form)
     const float* shared = own ? (f.patch ? own->cw.core : own->dW.p) : nullptr;
@@ -342,7 +407,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     int slots = 0;                 // row-constant partial-sum slots written by fused epilogues so far
     bool concretised = false;      // the last contraction already reduced the rows against the box
     const int split = contract_split_terms();       // > 0: contractions on the bf16 MFMA units, every step its own kernel
-    const bool may_fuse = P.fuse && maxd < 0 && !keep_sym && R >= 32 && net->part.p && M <= net->part_stride;
+    const bool may_fuse = P.fuse && maxd < 0 && !keep_sym && R >= 32 && net->ws->part.p && M <= net->ws->part_stride;
 
     std::vector<Waiting> waiting;
     // Row buffers: cur / nxt plus the pool of skip buffers (all of one size).  When the rows cross an Add layer they are
@@ -350,7 +415,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     // buffer from the pool takes its place in the cur / nxt pair (nothing writes the rows in place before that
     // contraction: the layer below an Add layer is affine or convolution).
     std::vector<float*> pool;
-    for (int k = (int)net->skipbuf.size() - 1; k >= 0; --k) pool.push_back(net->skipbuf[k]->p);
+    for (int k = (int)net->ws->skipbuf.size() - 1; k >= 0; --k) pool.push_back(net->ws->skipbuf[k]->p);
     float* held = nullptr;         // buffer of the rows set aside at the last Add layer while it is still `cur`
     float* spare = nullptr;        // the pool buffer that replaces it
     auto after_swap = [&]() {
@@ -365,7 +430,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
 
     // Fully-connected layers all the way down: the whole traversal in one kernel, rows resident in LDS.
     if (split == 0 && waiting.empty() && may_fuse && own && own->kind == AFFINE && !f.patch && nsides == 2 && at >= 1 && net->layers[at - 1]->kind == RELU &&
-        net->pk[at] && net->pk[at]->p) {
+        net->ws->pk[at] && net->ws->pk[at]->p) {
         ChainStepDesc steps[16];
         int ns = 0;
         bool ok = true;
@@ -374,14 +439,14 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             if (j < 1 || ns >= 16) { ok = false; break; }
             const Layer& L = *net->layers[j - 1];
             const int below = j - 1;
-            if (L.kind != AFFINE || !net->pk[below] || !net->pk[below]->p) { ok = false; break; }
+            if (L.kind != AFFINE || !net->ws->pk[below] || !net->ws->pk[below]->p) { ok = false; break; }
             if (below > 0 && net->layers[below - 1]->kind != RELU) { ok = false; break; }
-            steps[ns++] = ChainStepDesc{L.dW.p, net->pk[below]->p, L.n_out, L.ldw, net->ld_of(below), below > 0 ? 1 : 0};
+            steps[ns++] = ChainStepDesc{L.dW.p, net->ws->pk[below]->p, L.n_out, L.ldw, net->ld_of(below), below > 0 ? 1 : 0};
             flop += 2.0 * (double)M * L.n_out * L.n_in;
             if (below == 0) break;
         }
         if (ok) {
-            ChainDesc d{own->dW.p, own->dBias.p, net->pk[at]->p, own->ldw, net->ld_of(at), net->ld_of(at), R, B, ns, steps,
+            ChainDesc d{own->dW.p, own->dBias.p, net->ws->pk[at]->p, own->ldw, net->ld_of(at), net->ld_of(at), R, B, ns, steps,
                         out_l, out_u};
             P.prof->begin(P_CHAIN);
             const bool done = launch_chain(d, P.s);
@@ -471,12 +536,12 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             ++depth;
             continue;
         }
-        if (waiting.empty() && L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.fuse && maxd < 0 && !keep_sym && net->pk2.p &&
+        if (waiting.empty() && L.kind == RELU && at == 2 && f.patch && nsides == 2 && P.fuse && maxd < 0 && !keep_sym && net->ws->pk2.p &&
             net->layers[0]->kind == CONV && (shared != nullptr || bias_folded || depth > 0)) {
             // patch rows over the first ReLU layer: ReLU step, first layer and concretisation in one kernel
             const Layer& first = *net->layers[0];
             PatchTail pt{shared ? shared : cur, shared ? ld_shared : f.ld, shared ? 1 : 0, cst, cst_init, R, B, &f.pg, &first.g,
-                         net->pk2.p, net->ld_of(2), first.cw.bias_c, first.cw.taps, res->l[0], res->u[0], out_l, out_u};
+                         net->ws->pk2.p, net->ld_of(2), first.cw.bias_c, first.cw.taps, res->l[0], res->u[0], out_l, out_u};
             P.prof->begin(P_CONTRACT);
             const bool done = launch_patch_tail(pt, P.s);
             P.prof->end();
@@ -486,13 +551,13 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 return;
             }
         }
-        if (waiting.empty() && L.kind == RELU && at == 2 && !f.patch && !shared && P.fuse && maxd < 0 && !keep_sym && net->pk2.p &&
-            net->layers[0]->kind == CONV && net->part.p && M <= net->part_stride && slots < dpc_network::kMaxSlots) {
+        if (waiting.empty() && L.kind == RELU && at == 2 && !f.patch && !shared && P.fuse && maxd < 0 && !keep_sym && net->ws->pk2.p &&
+            net->layers[0]->kind == CONV && net->ws->part.p && M <= net->ws->part_stride && slots < dpc_network::kMaxSlots) {
             // dense rows over the first ReLU layer: its step is applied while the first layer's transposed convolution
             // loads the rows (no pass of its own over them); the constants it adds arrive in slots
             const Layer& first = *net->layers[0];
-            const ReluOnLoad rl{net->pk2.p, net->ld_of(2), first.cw.bias_c, net->part.p + (size_t)slots * net->part_stride,
-                                net->part_stride, dpc_network::kMaxSlots - slots, R, B, nullptr, 0};
+            const ReluOnLoad rl{net->ws->pk2.p, net->ld_of(2), first.cw.bias_c, net->ws->part.p + (size_t)slots * net->ws->part_stride,
+                                net->ws->part_stride, dpc_network::kMaxSlots - slots, R, B, nullptr, 0};
             int used = 0;
             P.prof->begin(P_CONTRACT);
             const bool done = launch_conv_transpose_fast(cur, M, f.ld, first.g.Ho, first.g.Wo, first.g, first.cw, nxt, net->ld_of(0),
@@ -511,8 +576,8 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             }
         }
         if (L.kind == RELU && at >= 3 && (!shared || cst_init) && net->layers[at - 2]->kind == CONV && net->layers[at - 2]->g.Ci > 4 && P.fuse &&
-            (maxd < 0 || depth + 2 <= maxd) && (int)net->pk2v.size() > at && net->pk2v[at] && net->pk2v[at]->p && net->rpart.p &&
-            (size_t)M <= net->rpart.count && !blocked(at - 1)) {
+            (maxd < 0 || depth + 2 <= maxd) && (int)net->ws->pk2v.size() > at && net->ws->pk2v[at] && net->ws->pk2v[at]->p && net->ws->rpart.p &&
+            (size_t)M <= net->ws->rpart.count && !blocked(at - 1)) {
             // ReLU step applied while the transposed convolution below stages the rows (no pass of its own over them); the
             // constants it adds come back in one slot and are folded into the row constants right away
             const Layer& cv = *net->layers[at - 2];
@@ -520,7 +585,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
             const int in_mod = shared ? (f.patch ? f.pg.rows_C : R) : 0;
             const float* src = shared ? shared : cur;
             const int ld_src = shared ? ld_shared : f.ld;
-            const ReluOnLoad rl{net->pk2v[at]->p, net->ld_of(at), cv.cw.bias_c, net->rpart.p, (int64_t)net->rpart.count, 1, R, B,
+            const ReluOnLoad rl{net->ws->pk2v[at]->p, net->ld_of(at), cv.cw.bias_c, net->ws->rpart.p, (int64_t)net->ws->rpart.count, 1, R, B,
                                 f.patch ? &f.pg : nullptr, in_mod};
             int used = 0;
             bool done;
@@ -534,7 +599,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 done = launch_conv_transpose_fast(src, M, ld_src, cv.g.Ho, cv.g.Wo, cv.g, cv.cw, nxt, o.ld, cv.g.H, cv.g.W, cv.g.pad, P.s, &rl,
                                                   &used);
             }
-            if (done) launch_fold_slots(cst, net->rpart.p, used, (int64_t)net->rpart.count, M, P.s, shared ? cst_init : nullptr, in_mod);
+            if (done) launch_fold_slots(cst, net->ws->rpart.p, used, (int64_t)net->ws->rpart.count, M, P.s, shared ? cst_init : nullptr, in_mod);
             P.prof->end();
             if (done) {
                 const double pos = f.patch ? (double)f.pg.ph * f.pg.pw : (double)cv.g.Ho * cv.g.Wo;
@@ -580,9 +645,9 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 const bool to_relu = below > 0 && net->layers[below - 1]->kind == RELU && !blocked(below) && !blocked(below - 1);
                 int used = -1;
                 fused_relu = false;
-                if (may_fuse && (to_input || to_relu) && net->pk[below] && net->pk[below]->p) {
-                    ContractEpilogue e{net->pk[below]->p, ld_prev, R, nsides * B,
-                                       net->part.p + (size_t)slots * net->part_stride, net->part_stride,
+                if (may_fuse && (to_input || to_relu) && net->ws->pk[below] && net->ws->pk[below]->p) {
+                    ContractEpilogue e{net->ws->pk[below]->p, ld_prev, R, nsides * B,
+                                       net->ws->part.p + (size_t)slots * net->ws->part_stride, net->ws->part_stride,
                                        dpc_network::kMaxSlots - slots, to_input ? 0 : 1};
                     used = (split > 0 && L.wt_terms == split && L.dWt.p)
                                ? launch_contract_split_fused(cur, M, n_at, f.ld, L.dWt.p, split, n_prev, nxt, ld_prev, e, P.s)
@@ -648,7 +713,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 for (const Waiting& x : grp) { phm = std::max(phm, Pm - x.P + x.ph); pwm = std::max(pwm, Pm - x.P + x.pw); }
                 const int n_t = net->size_of(tgt);
                 const int ldm = w.patch ? (int)round_up((int64_t)phm * pwm * gc, 4) : net->ld_of(tgt);
-                DPC_REQUIRE((size_t)M * ldm <= std::min(net->buf[0].count, net->buf[1].count), DPC_EUNSUPPORTED,
+                DPC_REQUIRE((size_t)M * ldm <= std::min(net->ws->buf[0].count, net->ws->buf[1].count), DPC_EUNSUPPORTED,
                             "waiting blocks do not fit the workspace");
                 P.prof->begin(P_RELAX);
                 launch_fill_zero(nxt, M * ldm, P.s);
@@ -686,14 +751,14 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     }
     P.prof->begin(P_CONC);
     if (concretised) {
-        launch_finalize_bounds(cst, net->part.p, slots, net->part_stride, nsides, B, R, out_l, out_u, P.s);
+        launch_finalize_bounds(cst, net->ws->part.p, slots, net->ws->part_stride, nsides, B, R, out_l, out_u, P.s);
     } else if (f.patch) {
         launch_concretise_patch(cur, f.ld, cst, nsides, B, R, f.pg, res->l[at], res->u[at], out_l, out_u,
                                 shared, ld_shared, cst_init, P.s);
         res->prof.concretise_bytes += (double)M * f.pg.elems() * 4.0;
     } else {
         launch_concretise(cur, f.ld, cst, nsides, B, R, n_at, res->l[at], res->u[at], out_l, out_u,
-                          shared, ld_shared, shared ? cst_init : nullptr, P.s, net->part.p, slots, net->part_stride);
+                          shared, ld_shared, shared ? cst_init : nullptr, P.s, net->ws->part.p, slots, net->ws->part_stride);
         res->prof.concretise_bytes += (double)M * n_at * 4.0;
     }
     P.prof->end();
@@ -922,6 +987,11 @@ dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
                 if (net->layers[j]->kind == ADD && (size_t)net->layers[j]->skip <= p && p <= j) ++open;
             net->skip_depth = std::max(net->skip_depth, open);
         }
+        // set-up for the certify calls: the pinned word the input validation reports into, and this device's address of
+        // the library's static workspace
+        DPC_HIP(hipHostMalloc(reinterpret_cast<void**>(&net->h_flag), sizeof(int32_t), hipHostMallocDefault));
+        *net->h_flag = 0;
+        (void)static_workspace(device);
         net->finalized = true;
     });
 }
@@ -957,10 +1027,22 @@ dpc_status dpc_options_default(dpc_options* opt)
     });
 }
 
-dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
-                       const dpc_options* opt_in, dpc_result** result)
+}  // extern "C"
+
+namespace {
+
+// Where the entry point that allocates nothing leaves its results (device pointers of the caller).
+struct StaticOut {
+    float* l; float* u; float* margin; int32_t* verdict;
+};
+
+// The certify call.  arena != NULL: the call of the entry point that allocates nothing -- the network's workspace has
+// been swapped for one inside the arena, the result object lives there too and is dropped at the end, after its
+// last-layer bounds, margins and verdicts have been copied to `so`.
+void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
+                  const dpc_options* opt_in, dpc_result** result, Arena* arena, const StaticOut* so)
 {
-    return guarded([&] {
+    {
         DPC_REQUIRE(net && lo && hi && result, DPC_EINVAL, "dpc_certify: NULL argument");
         DPC_REQUIRE(net->finalized, DPC_ESTATE, "dpc_certify: network not finalized");
         dpc_options opt;
@@ -983,6 +1065,12 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         DPC_REQUIRE(opt.certifier == DPC_DEEPPOLY || opt.certifier == DPC_REUSECERT, DPC_EINVAL, "dpc_certify: unknown certifier %d",
                     opt.certifier);
         const bool reuse_cert = opt.certifier == DPC_REUSECERT;
+        if (arena) {
+            DPC_REQUIRE(!reuse_cert && opt.keep_symbolic == 0 && contract_split_terms() == 0, DPC_EUNSUPPORTED,
+                        "dpc_certify_static: DeepPoly (any depth limit) with keep_symbolic = 0 and the fp32 contraction only");
+            opt.profile = 0;
+            opt.use_graph = 0;
+        }
         if (reuse_cert) {
             DPC_REQUIRE(opt.max_backsub_depth == -1 && opt.final_backsub_depth == -1 && opt.keep_symbolic == 0, DPC_EINVAL,
                         "dpc_certify: ReuseCert needs max_backsub_depth = -1 and keep_symbolic = 0");
@@ -1005,7 +1093,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                              DPC_EINVAL, "dpc_certify: the result passed in belongs to another network, batch or mode");
         std::unique_ptr<dpc_result> fresh;
         if (!res) {
-            fresh.reset(new dpc_result());
+            fresh.reset(arena ? new dpc_result(arena) : new dpc_result());
             res = fresh.get();
             res->net = net;
             res->batch = batch;
@@ -1061,11 +1149,11 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             need = std::max(need, (size_t)B * (2 * nmax + 1) * ldE);
             if (label) need = std::max(need, 2 * (size_t)B * Rm * ((size_t)net->ld_of(nl - 1) + ldE));   // last step: rows + results
         }
-        bool moved = net->buf[0].reserve(need);
-        moved |= net->buf[1].reserve(need);
-        if ((int)net->skipbuf.size() < net->skip_depth) net->skipbuf.resize(net->skip_depth);
-        for (auto& sb : net->skipbuf) {
-            if (!sb) sb.reset(new DevBuf<float>());
+        bool moved = net->ws->buf[0].reserve(need);
+        moved |= net->ws->buf[1].reserve(need);
+        if ((int)net->ws->skipbuf.size() < net->skip_depth) net->ws->skipbuf.resize(net->skip_depth);
+        for (auto& sb : net->ws->skipbuf) {
+            if (!sb) sb.reset(net->ws->fresh_buf());
             moved |= sb->reserve(need);
         }
         const bool fuse = opt.fuse && (opt.max_backsub_depth < 0 || opt.final_backsub_depth < 0);
@@ -1075,30 +1163,30 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 if (net->layers[i - 1]->kind == AFFINE) fuse_rows = std::max(fuse_rows, 2 * (size_t)B * net->size_of(i));
             if (label && last.kind == AFFINE) fuse_rows = std::max(fuse_rows, 2 * (size_t)B * RsMax);
             if (fuse_rows > 0 && fuse_rows * dpc_network::kMaxSlots * 4 <= ((size_t)1 << 31)) {
-                moved |= net->part.reserve(fuse_rows * dpc_network::kMaxSlots);
-                net->part_stride = std::max<int64_t>(net->part_stride, (int64_t)fuse_rows);
+                moved |= net->ws->part.reserve(fuse_rows * dpc_network::kMaxSlots);
+                net->ws->part_stride = std::max<int64_t>(net->ws->part_stride, (int64_t)fuse_rows);
             }
             if (nl >= 3 && net->layers[0]->kind == CONV && net->layers[0]->g.Ci <= 4 && net->layers[1]->kind == RELU)
-                moved |= net->pk2.reserve((size_t)B * net->ld_of(2) * 2);
-            if ((int)net->pk2v.size() != nl + 1) net->pk2v.resize(nl + 1);
+                moved |= net->ws->pk2.reserve((size_t)B * net->ld_of(2) * 2);
+            if ((int)net->ws->pk2v.size() != nl + 1) net->ws->pk2v.resize(nl + 1);
             size_t rrows = 0;
             for (int i = 3; i <= nl; ++i)
                 if (net->layers[i - 1]->kind == RELU && net->layers[i - 2]->kind == CONV && net->layers[i - 2]->g.Ci > 4)
                     for (int k = i + 1; k <= nl; ++k)
                         if (net->layers[k - 1]->kind != RELU) rrows = std::max(rrows, 2 * (size_t)B * net->size_of(k));
             if (label) rrows = std::max(rrows, 2 * (size_t)B * RsMax);
-            if (rrows > 0) moved |= net->rpart.reserve(rrows);
+            if (rrows > 0) moved |= net->ws->rpart.reserve(rrows);
             for (int i = 3; i <= nl; ++i) {
                 if (net->layers[i - 1]->kind != RELU || net->layers[i - 2]->kind != CONV || net->layers[i - 2]->g.Ci <= 4) continue;
-                if (!net->pk2v[i]) net->pk2v[i].reset(new DevBuf<float>());
-                moved |= net->pk2v[i]->reserve((size_t)B * net->ld_of(i) * 2);
+                if (!net->ws->pk2v[i]) net->ws->pk2v[i].reset(net->ws->fresh_buf());
+                moved |= net->ws->pk2v[i]->reserve((size_t)B * net->ld_of(i) * 2);
             }
-            if (net->pk.size() != (size_t)nl + 1) net->pk.resize(nl + 1);
+            if (net->ws->pk.size() != (size_t)nl + 1) net->ws->pk.resize(nl + 1);
             for (int i = 0; i <= nl; ++i) {
                 const bool want = i == 0 ? !net->in_spatial || true : net->layers[i - 1]->kind == RELU;
                 if (!want) continue;
-                if (!net->pk[i]) net->pk[i].reset(new DevBuf<float>());
-                moved |= net->pk[i]->reserve((size_t)2 * B * net->ld_of(i) * 4);
+                if (!net->ws->pk[i]) net->ws->pk[i].reset(net->ws->fresh_buf());
+                moved |= net->ws->pk[i]->reserve((size_t)2 * B * net->ld_of(i) * 4);
             }
         }
         if (reuse_cert) {
@@ -1112,7 +1200,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     launch_reuse_split(L.dW.p, L.ldw, L.dBias.p, nullptr, L.n_out, L.n_in, L.dSplit[side].p, L.ld_split, 0, side, s);
                 }
             }
-            if (nl >= 3) moved |= net->rc_rows.reserve(2 * (size_t)B * (2 * (size_t)nK - 1) * net->layers[nl - 1]->ld_split);
+            if (nl >= 3) moved |= net->ws->rc_rows.reserve(2 * (size_t)B * (2 * (size_t)nK - 1) * net->layers[nl - 1]->ld_split);
         }
         if (const int terms = contract_split_terms()) {
             for (int i = 1; i <= nl; ++i) {
@@ -1125,12 +1213,12 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 L.wt_terms = terms;
             }
         }
-        moved |= net->cst.reserve(need_rows);
-        moved |= net->stage.reserve(stage_need);
-        if (moved) ++net->ws_epoch;
+        moved |= net->ws->cst.reserve(need_rows);
+        moved |= net->ws->stage.reserve(stage_need);
+        if (moved) ++net->ws->ws_epoch;
 
         if (B == 0) {
-            if (fresh) { *result = fresh.release(); net->live_results++; }
+            if (fresh && !arena) { *result = fresh.release(); net->live_results++; }
             return;
         }
 
@@ -1149,20 +1237,21 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             return at.type == hipMemoryTypeDevice && at.device == net->device;
         };
         const bool resident = B > 0 && on_device(lo) && on_device(hi) && (!label || on_device(label));
-        if (!net->h_flag) DPC_HIP(hipHostMalloc(reinterpret_cast<void**>(&net->h_flag), sizeof(int32_t), hipHostMallocDefault));
+        DPC_REQUIRE(resident || !arena, DPC_EINVAL, "dpc_certify_static: lo, hi and label must be device memory of the network's device");
         *net->h_flag = 0;
         if (resident) {
-            if (!net->dflag.p) {
-                net->dflag.reserve(1);
-                DPC_HIP(hipMemsetAsync(net->dflag.p, 0, sizeof(int32_t), s));
+            if (!net->ws->dflag.p) {
+                // a fill kernel, not a memset: the call may sit inside a caller's graph capture
+                net->ws->dflag.reserve(1);
+                zero_word_enqueue(net->ws->dflag.p, s);
             }
             ingest_enqueue(lo, hi, label, res->l[0], res->u[0], label ? res->label.p : nullptr, B, n0, net->in_spatial ? net->inC : 0,
-                           net->inH, net->inW, nK, net->dflag.p, net->h_flag, s);
+                           net->inH, net->inW, nK, net->ws->dflag.p, net->h_flag, s);
         } else if (net->in_spatial) {
-            DPC_HIP(hipMemcpyAsync(net->stage.p, lo, box * 4, hipMemcpyDefault, s));
-            DPC_HIP(hipMemcpyAsync(net->stage.p + box, hi, box * 4, hipMemcpyDefault, s));
-            launch_chw_to_hwc(net->stage.p, res->l[0], B, net->inC, net->inH, net->inW, s);
-            launch_chw_to_hwc(net->stage.p + box, res->u[0], B, net->inC, net->inH, net->inW, s);
+            DPC_HIP(hipMemcpyAsync(net->ws->stage.p, lo, box * 4, hipMemcpyDefault, s));
+            DPC_HIP(hipMemcpyAsync(net->ws->stage.p + box, hi, box * 4, hipMemcpyDefault, s));
+            launch_chw_to_hwc(net->ws->stage.p, res->l[0], B, net->inC, net->inH, net->inW, s);
+            launch_chw_to_hwc(net->ws->stage.p + box, res->u[0], B, net->inC, net->inH, net->inW, s);
         } else {
             DPC_HIP(hipMemcpyAsync(res->l[0], lo, box * 4, hipMemcpyDefault, s));
             DPC_HIP(hipMemcpyAsync(res->u[0], hi, box * 4, hipMemcpyDefault, s));
@@ -1172,18 +1261,18 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         // synchronised at the end of the call (no round trip in front of the kernels)
         if (!resident)
             check_inputs_enqueue(res->l[0], res->u[0], box, label ? res->label.p : nullptr, B, nK,
-                             reinterpret_cast<int32_t*>(net->stage.p + 2 * box), net->h_flag, s);
+                             reinterpret_cast<int32_t*>(net->ws->stage.p + 2 * box), net->h_flag, s);
 
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
         // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
         const bool graphable = opt.use_graph && s != nullptr && !prof.on && !opt.keep_symbolic && !fresh;
-        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws_epoch};
+        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws->ws_epoch};
         const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
         auto enqueue_reusecert = [&]() {
             Pass P{net, res, &opt, s, &prof, B, -1, false};
-            float* E = net->buf[0].p;            // stored bounds of the current affine layer: [side][b][n][ldE]
-            float* Rr = net->buf[1].p;           // [b][2n + 1][ldE]: the ReLU layer's input-level bounds + unit row
-            double* cst = net->cst.p;
+            float* E = net->ws->buf[0].p;            // stored bounds of the current affine layer: [side][b][n][ldE]
+            float* Rr = net->ws->buf[1].p;           // [b][2n + 1][ldE]: the ReLU layer's input-level bounds + unit row
+            double* cst = net->ws->cst.p;
             // constants travel in column n0 of the rows; the concretisation kernel takes them as fp64 per row
             auto concretise_rows = [&](const float* rows, int R, float* out_l, float* out_u) {
                 const int64_t M = 2 * (int64_t)B * R;
@@ -1231,23 +1320,23 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     // last layer with a property: output rows and margin rows (label-dependent, so per input) in one step
                     const int Rm = 2 * nK - 1;
                     const int64_t rows = 2 * (int64_t)B * Rm;
-                    float* Fr = net->buf[0].p;                                   // rows over the last hidden layer
-                    float* T = net->buf[0].p + (size_t)rows * net->ld_of(nl - 1); // their input-level expressions
+                    float* Fr = net->ws->buf[0].p;                                   // rows over the last hidden layer
+                    float* T = net->ws->buf[0].p + (size_t)rows * net->ld_of(nl - 1); // their input-level expressions
                     prof.begin(P_OTHER);
                     launch_final_rows(L.dW.p, L.ldw, L.dBias.p, res->label.p, B, nK, L.n_in, Fr, net->ld_of(nl - 1), cst, s);
-                    launch_reuse_split(Fr, net->ld_of(nl - 1), nullptr, cst, rows, L.n_in, net->rc_rows.p, L.ld_split, (int64_t)B * Rm, 0, s);
+                    launch_reuse_split(Fr, net->ld_of(nl - 1), nullptr, cst, rows, L.n_in, net->ws->rc_rows.p, L.ld_split, (int64_t)B * Rm, 0, s);
                     prof.end();
                     res->prof.other_launches += 2;
                     prof.begin(P_CONTRACT);
                     for (int side = 0; side < 2; ++side)
-                        launch_contract_batched(net->rc_rows.p + (size_t)side * B * Rm * L.ld_split, (int64_t)Rm * L.ld_split, Rm, K,
+                        launch_contract_batched(net->ws->rc_rows.p + (size_t)side * B * Rm * L.ld_split, (int64_t)Rm * L.ld_split, Rm, K,
                                                 L.ld_split, Rr, (int64_t)K * ldE, n0 + 1, ldE,
                                                 T + (size_t)side * B * Rm * ldE, (int64_t)Rm * ldE, ldE, B, s);
                     prof.end();
                     res->prof.contract_launches += 2;
                     res->prof.contract_flop += 2.0 * 2.0 * B * (double)Rm * K * (n0 + 1);
-                    float* tl = net->stage.p;
-                    float* tu = net->stage.p + (size_t)B * Rm;
+                    float* tl = net->ws->stage.p;
+                    float* tu = net->ws->stage.p + (size_t)B * Rm;
                     concretise_rows(T, Rm, tl, tu);
                     prof.begin(P_OTHER);
                     launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s);
@@ -1258,7 +1347,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         };
         auto enqueue_all = [&]() {
             if (reuse_cert && nl >= 3) { enqueue_reusecert(); return; }
-            if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->pk[0]->p, s);
+            if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->ws->pk[0]->p, s);
             Pass P{net, res, &opt, s, &prof, B, opt.max_backsub_depth, fuse};
             for (int i = 1; i <= nl; ++i) {
                 Layer& L = *net->layers[i - 1];
@@ -1267,10 +1356,10 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                     if (fuse) {
                         // the layer's parameters and their packed forms (for the fused epilogues and the kernels that apply
                         // the ReLU step while they load rows) in one launch
-                        float* pk2 = i == 2 ? net->pk2.p
-                                            : ((int)net->pk2v.size() > i && net->pk2v[i]) ? net->pk2v[i]->p : nullptr;
+                        float* pk2 = i == 2 ? net->ws->pk2.p
+                                            : ((int)net->ws->pk2v.size() > i && net->ws->pk2v[i]) ? net->ws->pk2v[i]->p : nullptr;
                         launch_relax_params_pack(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
-                                                 net->layers[i - 2]->dBias.p, B, L.n_out, net->ld_of(i), net->pk[i]->p, pk2, s);
+                                                 net->layers[i - 2]->dBias.p, B, L.n_out, net->ld_of(i), net->ws->pk[i]->p, pk2, s);
                     } else {
                         launch_relax_params(res->l[i - 1], res->u[i - 1], res->lam[i], res->mu[i], res->nu[i], res->l[i], res->u[i],
                                             (int64_t)B * L.n_out, s);
@@ -1306,11 +1395,11 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                 const int Rm = 2 * nK - 1;
                 // groups padded with zero rows to the fused epilogue's minimum when that route is open
                 const int Rs = (fuse && !opt.keep_symbolic && Rm < 32) ? 32 : Rm;
-                float* tl = net->stage.p;
-                float* tu = net->stage.p + (size_t)B * Rs;
+                float* tl = net->ws->stage.p;
+                float* tu = net->ws->stage.p + (size_t)B * Rs;
                 prof.begin(P_OTHER);
-                launch_final_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
-                                  net->ld_of(nl - 1), net->cst.p, s, Rs);
+                launch_final_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->ws->buf[0].p,
+                                  net->ld_of(nl - 1), net->ws->cst.p, s, Rs);
                 prof.end();
                 res->prof.other_launches++;
                 run_pass(P, nl - 1, 2, Rs, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rs));
@@ -1321,8 +1410,8 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
             } else if (label) {
                 const int nq = nK - 1;
                 prof.begin(P_OTHER);
-                launch_margin_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->buf[0].p,
-                                   net->ld_of(nl - 1), net->cst.p, s);
+                launch_margin_rows(last.dW.p, last.ldw, last.dBias.p, res->label.p, B, nK, last.n_in, net->ws->buf[0].p,
+                                   net->ld_of(nl - 1), net->ws->cst.p, s);
                 prof.end();
                 res->prof.other_launches++;
                 run_pass(P, nl - 1, 1, nq, nullptr, res->margin.p, nullptr, false);
@@ -1360,10 +1449,25 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
         }
         prof.finish();
         if (prof.on) DPC_HIP(hipEventRecord(t1, s));
+        if (so) {
+            // results to the caller's device arrays, in the interface's neuron order
+            const size_t cnt = (size_t)B * nK;
+            if (last.spatial_out) {
+                if (so->l) launch_hwc_to_chw(res->l[nl], so->l, B, last.C, last.H, last.W, s);
+                if (so->u) launch_hwc_to_chw(res->u[nl], so->u, B, last.C, last.H, last.W, s);
+            } else {
+                if (so->l) DPC_HIP(hipMemcpyAsync(so->l, res->l[nl], cnt * sizeof(float), hipMemcpyDeviceToDevice, s));
+                if (so->u) DPC_HIP(hipMemcpyAsync(so->u, res->u[nl], cnt * sizeof(float), hipMemcpyDeviceToDevice, s));
+            }
+            if (label && so->margin)
+                DPC_HIP(hipMemcpyAsync(so->margin, res->margin.p, (size_t)B * (nK - 1) * sizeof(float), hipMemcpyDeviceToDevice, s));
+            if (label && so->verdict)
+                DPC_HIP(hipMemcpyAsync(so->verdict, res->verdict.p, (size_t)B * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+        }
         DPC_HIP(hipStreamSynchronize(s));
         {
             const int32_t h = *static_cast<volatile int32_t*>(net->h_flag);
-            if (h && resident) zero_word_enqueue(net->dflag.p, s);          // the next call expects a clean flag
+            if (h && resident) zero_word_enqueue(net->ws->dflag.p, s);          // the next call expects a clean flag
             DPC_REQUIRE(!(h & 1), DPC_EINVAL, "dpc_certify: lo > hi or a non-finite bound");
             DPC_REQUIRE(!(h & 2), DPC_EINVAL, "dpc_certify: label out of range");
         }
@@ -1377,7 +1481,40 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
                  : r.cls == P_CONC ? res->prof.concretise_ms : r.cls == P_CHAIN ? res->prof.chain_ms : res->prof.other_ms) += ms;
             }
         }
-        if (fresh) { *result = fresh.release(); net->live_results++; }
+        if (fresh && !arena) { *result = fresh.release(); net->live_results++; }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
+                       const dpc_options* opt, dpc_result** result)
+{
+    return guarded([&] { certify_impl(net, batch, lo, hi, label, opt, result, nullptr, nullptr); });
+}
+
+dpc_status dpc_certify_static(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
+                              const dpc_options* opt, float* out_l, float* out_u, float* margin_lb, int32_t* verdict)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net && net->finalized, DPC_ESTATE, "dpc_certify_static: network not finalized");
+        DPC_REQUIRE(label || (!margin_lb && !verdict), DPC_EINVAL, "dpc_certify_static: margins and verdicts need labels");
+        DeviceGuard guard(net->device);
+        Arena arena;
+        arena.base = static_workspace(net->device);
+        arena.size = kStaticWorkspaceBytes;
+        // the call's workspace and result live in the static array; the network's own workspace is put back on every exit
+        Workspace ws(&arena);
+        struct Swap {
+            dpc_network* n; Workspace* old;
+            ~Swap() { n->ws = old; }
+        } swap{net, net->ws};
+        net->ws = &ws;
+        dpc_result* none = nullptr;
+        const StaticOut so{out_l, out_u, margin_lb, verdict};
+        certify_impl(net, batch, lo, hi, label, opt, &none, &arena, &so);
     });
 }
 
