@@ -104,8 +104,11 @@ typedef struct {
                                    iterations (each replaces one layer's neurons, ReLU layers
                                    included), then concretise against the stored l,u of the layer
                                    reached -- the DeepPoly_p family of Section 6.2; 0 = IBP */
-    int32_t keep_symbolic;      /* 0: none; 1: keep the input-level polyhedral bounds of the last layer
-                                   (needs max_backsub_depth = -1) */
+    int32_t keep_symbolic;      /* which neurons' polyhedral bounds L, U (Section 2.1: the symbolic half of the abstract shape),
+                                   back-substituted to the input layer, stay available after the call: 0 none; 1 the
+                                   last layer's and the property rows' (needs final_backsub_depth = -1); 2 those of
+                                   every affine, convolution and Add layer (needs max_backsub_depth = -1 too; every
+                                   traversal then runs step by step: 2*batch*n_layer*n0 floats are kept per layer) */
     int32_t fuse;               /* 1 (default): the ReLU step / concretisation that follows a
                                    contraction runs in that contraction's epilogue where supported;
                                    0: every step is its own kernel */
@@ -131,7 +134,10 @@ enum { DPC_DEEPPOLY = 0, DPC_REUSECERT = 1 };
 /* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, graph replay on, null stream). */
 dpc_status dpc_options_default(dpc_options* opt);
 
-/* Runs the certifier on `batch` boxes.
+/* Runs the certifier on `batch` boxes: the forward flow of Appendix C (DeepPoly) -- layers in order, each affine /
+ * convolution / Add layer bounded by one backward traversal of its neurons' expressions (Section 2.2, traverse;
+ * Sections 3.2 and 4.3 for the tensor form of one iteration), each ReLU layer by its transformer -- then the
+ * property check of Section 2 (psi against the output layer's constraints).
  *   lo, hi : [batch, n0] float32, lo <= hi element-wise (host or device).
  *   label  : [batch] int32 target class in [0, nK), or NULL for bounds only.
  *   *result: NULL -> a new result is allocated; a result returned by an earlier
@@ -165,7 +171,7 @@ dpc_status dpc_certify(dpc_network* net, int32_t batch, const float* lo, const f
 dpc_status dpc_certify_static(dpc_network* net, int32_t batch, const float* lo, const float* hi, const int32_t* label,
                               const dpc_options* opt, float* out_l, float* out_u, float* margin_lb, int32_t* verdict);
 
-/* Concrete bounds l, u of every neuron of `layer` (0 = the box itself):
+/* Concrete bounds l, u of the abstract shape (Section 2.1; Appendix C, DeepPoly shape) of every neuron of `layer` (0 = the box itself):
  * [batch, n_layer] float32 each, caller-allocated (host or device); either may be NULL. */
 dpc_status dpc_result_concrete(const dpc_result* res, int32_t layer, float* l, float* u);
 
@@ -174,12 +180,22 @@ dpc_status dpc_result_concrete(const dpc_result* res, int32_t layer, float* l, f
 dpc_status dpc_result_relaxation(const dpc_result* res, int32_t relu_layer,
                                  float* lambda, float* mu, float* nu);
 
-/* Input-level polyhedral bound of the last layer's neurons (keep_symbolic = 1):
- * side 0 = lower, 1 = upper; coeff [batch, nK, n0], cst [batch, nK]. */
+/* Polyhedral bounds L (side 0) and U (side 1) of the neurons of an affine, convolution or Add layer, in the form the
+ * traversal leaves them in when only input neurons remain (Section 2.2; Appendix C, backsubs_lower / backsubs_upper
+ * before simplify_* is mapped over them):  L_r(x) = cst[b,r] + sum_i coeff[b,r,i] * x_i <= neuron r <= U_r(x) on the box.
+ * coeff [batch, n_layer, n0], cst [batch, n_layer], caller-allocated (host or device); either may be NULL.  Rows and
+ * columns are in the interface's neuron order ((C,H,W) for spatial layers).  Needs keep_symbolic = 1 (last layer) or 2
+ * (any such layer); DPC_ESTATE otherwise; ReLU layers: DPC_EINVAL (their L, U over the predecessor are lambda, mu, nu). */
 dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t side,
                                float* coeff, float* cst);
 
-/* verdict [batch]: 1 = verified, 0 = unknown.  margin_lb [batch, nK-1] (may be
+/* The same for the property rows (keep_symbolic >= 1 and labels): the lower polyhedral bound, over the input, of
+ * logit[label] - logit[o] for o != label in ascending o; coeff [batch, nK-1, n0], cst [batch, nK-1].  Its minimum over
+ * the box is margin_lb of dpc_result_verdict. */
+dpc_status dpc_result_margin_symbolic(const dpc_result* res, float* coeff, float* cst);
+
+/* Outcome of the property check (Section 2: certified, or unknown when the property does not hold or the analysis is too
+ * imprecise).  verdict [batch]: 1 = verified, 0 = unknown.  margin_lb [batch, nK-1] (may be
  * NULL): lower bound of logit[label] - logit[o] for o != label in ascending o.
  * Verified iff every margin lower bound is > 0.  Needs a label at certify time. */
 dpc_status dpc_result_verdict(const dpc_result* res, int32_t* verdict, float* margin_lb);
@@ -202,6 +218,7 @@ typedef struct {
 } dpc_profile;
 dpc_status dpc_result_profile(const dpc_result* res, dpc_profile* out);
 
+/* Frees the result's device and host memory (the abstract shapes of Section 2.1 it holds). */
 dpc_status dpc_result_destroy(dpc_result* res);
 
 /* ---- the three hot kernels on caller-owned DEVICE buffers (unit tests, roofline runs) ---- */

@@ -158,7 +158,8 @@ def run(net, lo, hi, label=None, sym_layer: int = -1, max_depth: int = -1,
 
     sp = [None] * 4
     if sym_layer >= 0:
-        ns = sizes[sym_layer]
+        # nl + 1 names the property's rows (lower expressions of logit[label] - logit[o]; "cu", "ku" stay zero)
+        ns = sizes[sym_layer] if sym_layer <= nl else sizes[-1] - 1
         res.sym = dict(cl=np.zeros((B, ns, n0)), kl=np.zeros((B, ns)),
                        cu=np.zeros((B, ns, n0)), ku=np.zeros((B, ns)))
         sp = [res.sym[k].ctypes.data for k in ("cl", "kl", "cu", "ku")]

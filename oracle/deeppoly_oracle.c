@@ -309,6 +309,8 @@ static double backsubs_multi(const dpo_state* st, int bi, int side, double c0, d
  *   sym_layer     : layer index (>=1, affine/conv) whose input-level expressions
  *                   are exported (needs full traversal), or -1.
  *                   sym_cl/sym_cu: [B, n_sym, n0]; sym_kl/sym_ku: [B, n_sym].
+ *                   nlayers + 1 names the property's rows (with a label): their lower
+ *                   expressions go to sym_cl [B, nK-1, n0], sym_kl [B, nK-1].
  * Returns 0 on success, non-zero on malformed input.
  */
 int dpo_run(int nlayers, const dpo_layer* layers, int B,
@@ -431,6 +433,8 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
                     if (!buf_a || !buf_b || (has_add && !e)) continue;
                     const int t = label[bi];
                     const int o = q < t ? q : q + 1;
+                    const int want_msym = (sym_layer == nlayers + 1);
+                    const size_t mo = (size_t)bi * (nK - 1) + q;
                     /* logit[t] - logit[o] as a polyhedral expression over the last hidden layer */
                     for (int p = 0; p < nP; ++p)
                         buf_a[p] = (double)L->W[(size_t)t * nP + p] - (double)L->W[(size_t)o * nP + p];
@@ -439,11 +443,13 @@ int dpo_run(int nlayers, const dpo_layer* layers, int B,
                         multi_clear(&st, e);
                         memcpy(e->c[nlayers - 1], buf_a, sizeof(double) * (size_t)nP);
                         e->present[nlayers - 1] = 1;
-                        margin[(size_t)bi * (nK - 1) + q] = backsubs_multi(&st, bi, DPO_LOWER, c0, e, max_depth_last, NULL, NULL);
+                        margin[(size_t)bi * (nK - 1) + q] = backsubs_multi(&st, bi, DPO_LOWER, c0, e, max_depth_last,
+                                                                           want_msym ? sym_cl + mo * n0 : NULL, want_msym ? sym_kl + mo : NULL);
                         continue;
                     }
                     margin[(size_t)bi * (nK - 1) + q] =
-                        backsubs(&st, bi, nlayers - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth_last, NULL, NULL);
+                        backsubs(&st, bi, nlayers - 1, DPO_LOWER, c0, buf_a, buf_b, max_depth_last,
+                                 want_msym ? sym_cl + mo * n0 : NULL, want_msym ? sym_kl + mo : NULL);
                 }
             free(buf_a);
             free(buf_b);

@@ -58,6 +58,7 @@ EXPORTS = {
     "dpc_result_concrete": [c_vp, c_i32, c_vp, c_vp],
     "dpc_result_relaxation": [c_vp, c_i32, c_vp, c_vp, c_vp],
     "dpc_result_symbolic": [c_vp, c_i32, c_i32, c_vp, c_vp],
+    "dpc_result_margin_symbolic": [c_vp, c_vp, c_vp],
     "dpc_result_verdict": [c_vp, c_vp, c_vp],
     "dpc_result_profile": [c_vp, ctypes.POINTER(dpc_profile)],
     "dpc_result_destroy": [c_vp],
@@ -229,6 +230,13 @@ class Result:
         coeff = np.empty((self.batch, n, n0), np.float32)
         cst = np.empty((self.batch, n), np.float32)
         _check(_lib.dpc_result_symbolic(self._h, layer, side, _ptr(coeff), _ptr(cst)))
+        return coeff, cst
+
+    def margin_symbolic(self):
+        nq, n0 = self.net.sizes[-1] - 1, self.net.sizes[0]
+        coeff = np.empty((self.batch, nq, n0), np.float32)
+        cst = np.empty((self.batch, nq), np.float32)
+        _check(_lib.dpc_result_margin_symbolic(self._h, _ptr(coeff), _ptr(cst)))
         return coeff, cst
 
     def verdict(self):

@@ -221,13 +221,16 @@ struct dpc_result {
     dpc_network* net = nullptr;
     int batch = 0;
     int keep_symbolic = 0;
-    bool has_label = false, has_symbolic = false;
+    bool has_label = false;
     std::vector<float*> l, u, lam, mu, nu;   // per layer index, device, internal order (sub-allocations)
     DevBuf<float> pool;
     DevBuf<float> margin;                    // [B, nK-1]
     DevBuf<int32_t> verdict, label;
-    DevBuf<float> sym_coeff;                 // [2][B*nK][ld0]
-    DevBuf<double> sym_cst;                  // [2][B*nK]
+    // kept symbolic bounds: per layer index (1..nl; nl + 1 = the property's margin rows, lower side only) the
+    // input-level expressions [side][b][r] x ld0 with their constants, internal neuron orders
+    std::vector<std::unique_ptr<DevBuf<float>>> sym_c;
+    std::vector<std::unique_ptr<DevBuf<double>>> sym_k;
+    std::vector<char> sym_have;
     dpc_profile prof{};
     // the kernel sequence of a certify call on this result, captured once and replayed on reuse
     hipGraphExec_t gexec = nullptr;
@@ -242,7 +245,7 @@ struct dpc_result {
     } gkey;
     dpc_profile gprof{};                   // launch and flop counters of the captured sequence
     dpc_result() = default;
-    explicit dpc_result(Arena* a) : pool(a), margin(a), verdict(a), label(a), sym_coeff(a), sym_cst(a) {}
+    explicit dpc_result(Arena* a) : pool(a), margin(a), verdict(a), label(a) {}
     ~dpc_result() { if (gexec) (void)hipGraphExecDestroy(gexec); }
 };
 
@@ -383,7 +386,7 @@ struct Waiting {
 
 // diag_target >= 0: the expressions are those of an Add layer's neurons, i.e. the rows of `own` (the layer below the Add
 // layer) plus coefficient 1 on the same neuron of layer diag_target.
-void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, bool keep_sym,
+void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l, float* out_u, int sym_idx,      // sym_idx >= 0: keep the input-level expressions there
               double useful = 1.0,       // fraction of the rows whose bounds are used (flop accounting only)
               int diag_target = -1, int depth0 = 0)    // depth0: traverse iterations the starting rows already stand for
 {
@@ -391,6 +394,7 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     dpc_result* res = P.res;
     const int B = P.B;
     const int maxd = P.maxd;
+    const bool keep_sym = sym_idx >= 0;
     float* cur = net->ws->buf[0].p;
     float* nxt = net->ws->buf[1].p;
     double* cst = net->ws->cst.p;
@@ -738,16 +742,24 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     }
     const int n_at = net->size_of(at);
     if (keep_sym) {
-        DPC_REQUIRE(at == 0 && !f.patch, DPC_EUNSUPPORTED, "symbolic bounds are kept for dense rows at the input only");
-        if (!shared) {
-            DPC_HIP(hipMemcpyAsync(res->sym_coeff.p, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
-            DPC_HIP(hipMemcpyAsync(res->sym_cst.p, cst, (size_t)M * sizeof(double), hipMemcpyDeviceToDevice, P.s));
+        DPC_REQUIRE(at == 0, DPC_EUNSUPPORTED, "symbolic bounds are kept at the input only");
+        float* dc = res->sym_c[sym_idx]->p;
+        double* dk = res->sym_k[sym_idx]->p;
+        const int ld0 = net->ld_of(0);
+        if (f.patch) {
+            // rows of a convolution layer reach the input as patches: written out as dense rows over the input
+            launch_fill_zero(dc, M * ld0, P.s);
+            launch_expand_patch_rows(shared ? shared : cur, shared ? ld_shared : f.ld, shared ? f.pg.rows_C : 0, cst, cst_init, M, R,
+                                     f.pg.rows_C, f.pg.rows_W, f.pg.ph, f.pg.pw, f.pg.C, f.pg.S, f.pg.P, f.pg.gh, f.pg.gw, dc, ld0, dk, P.s);
+        } else if (!shared) {
+            DPC_HIP(hipMemcpyAsync(dc, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
+            DPC_HIP(hipMemcpyAsync(dk, cst, (size_t)M * sizeof(double), hipMemcpyDeviceToDevice, P.s));
         } else {
-            // single-layer network: the expression is the weight row itself for every input and side
-            launch_relax_step(res->sym_coeff.p, f.ld, res->sym_cst.p, nsides, B, R, n_at, nullptr, nullptr, nullptr,
+            // first layer: the expression is the weight row itself for every input and side
+            launch_relax_step(dc, f.ld, dk, nsides, B, R, n_at, nullptr, nullptr, nullptr,
                               nullptr, shared, ld_shared, cst_init, P.s);
         }
-        res->has_symbolic = true;
+        res->sym_have[sym_idx] = 1;
     }
     P.prof->begin(P_CONC);
     if (concretised) {
@@ -1057,9 +1069,11 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         DPC_REQUIRE(opt.max_backsub_depth >= -1, DPC_EINVAL, "dpc_certify: max_backsub_depth must be >= -1");
         DPC_REQUIRE(opt.final_backsub_depth >= DPC_SAME_DEPTH, DPC_EINVAL, "dpc_certify: final_backsub_depth must be >= -2");
         if (opt.final_backsub_depth == DPC_SAME_DEPTH) opt.final_backsub_depth = opt.max_backsub_depth;
-        DPC_REQUIRE(opt.keep_symbolic == 0 || opt.keep_symbolic == 1, DPC_EINVAL, "dpc_certify: keep_symbolic must be 0 or 1");
+        DPC_REQUIRE(opt.keep_symbolic >= 0 && opt.keep_symbolic <= 2, DPC_EINVAL, "dpc_certify: keep_symbolic must be 0, 1 or 2");
         DPC_REQUIRE(opt.keep_symbolic == 0 || opt.final_backsub_depth == -1, DPC_EINVAL,
                     "dpc_certify: keep_symbolic needs a full traversal");
+        DPC_REQUIRE(opt.keep_symbolic != 2 || opt.max_backsub_depth == -1, DPC_EINVAL,
+                    "dpc_certify: keep_symbolic = 2 needs full traversals of every layer (max_backsub_depth = -1)");
         const int nl = (int)net->layers.size();
         const Layer& last = *net->layers[nl - 1];
         DPC_REQUIRE(opt.certifier == DPC_DEEPPOLY || opt.certifier == DPC_REUSECERT, DPC_EINVAL, "dpc_certify: unknown certifier %d",
@@ -1120,13 +1134,22 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             res->margin.reserve(std::max<size_t>((size_t)B * (nK - 1), 1));
             res->verdict.reserve(std::max(B, 1));
             res->label.reserve(std::max(B, 1));
-            if (opt.keep_symbolic) {
-                res->sym_coeff.reserve(std::max<size_t>(2 * (size_t)B * nK * net->ld_of(0), 1));
-                res->sym_cst.reserve(std::max<size_t>(2 * (size_t)B * nK, 1));
+            res->sym_c.resize(nl + 2);
+            res->sym_k.resize(nl + 2);
+            res->sym_have.assign(nl + 2, 0);
+            for (int i = 1; i <= nl + 1 && opt.keep_symbolic; ++i) {
+                // 1: the last layer and the property's rows; 2: every affine / convolution / Add layer as well
+                const bool kept = i >= nl || (opt.keep_symbolic == 2 && net->layers[i - 1]->kind != RELU);
+                if (!kept) continue;
+                const size_t rows = i <= nl ? 2 * (size_t)B * net->size_of(i) : (size_t)B * (nK - 1);
+                res->sym_c[i].reset(new DevBuf<float>());
+                res->sym_k[i].reset(new DevBuf<double>());
+                res->sym_c[i]->reserve(std::max<size_t>(rows * net->ld_of(0), 1));
+                res->sym_k[i]->reserve(std::max<size_t>(rows, 1));
             }
         }
         res->has_label = label != nullptr;
-        res->has_symbolic = false;
+        std::fill(res->sym_have.begin(), res->sym_have.end(), 0);
         memset(&res->prof, 0, sizeof res->prof);
         res->prof.struct_size = (int32_t)sizeof(dpc_profile);
 
@@ -1285,7 +1308,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             };
             {   // first layer: L = U = W x + b is already over the input
                 Layer& L1 = *net->layers[0];
-                run_pass(P, 0, 2, L1.n_out, &L1, res->l[1], res->u[1], false);
+                run_pass(P, 0, 2, L1.n_out, &L1, res->l[1], res->u[1], -1);
             }
             for (int i = 2; i <= nl; ++i) {
                 Layer& L = *net->layers[i - 1];
@@ -1383,10 +1406,10 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     // expressions of its neurons: the rows of the layer below (one traverse iteration already taken)
                     // + a unit block on the skip operand
                     Layer& below = *net->layers[i - 2];
-                    run_pass(P, i - 2, 2, L.n_out, &below, res->l[i], res->u[i], opt.keep_symbolic && i == nl, 1.0, L.skip, 1);
+                    run_pass(P, i - 2, 2, L.n_out, &below, res->l[i], res->u[i], res->sym_c[i] ? i : -1, 1.0, L.skip, 1);
                     continue;
                 }
-                run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], opt.keep_symbolic && i == nl);
+                run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], res->sym_c[i] ? i : -1);
             }
             P.maxd = opt.final_backsub_depth;
             if (merge_final) {
@@ -1402,7 +1425,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                                   net->ld_of(nl - 1), net->ws->cst.p, s, Rs);
                 prof.end();
                 res->prof.other_launches++;
-                run_pass(P, nl - 1, 2, Rs, nullptr, tl, tu, false, (double)(2 * nK + nK - 1) / (2.0 * Rs));
+                run_pass(P, nl - 1, 2, Rs, nullptr, tl, tu, -1, (double)(2 * nK + nK - 1) / (2.0 * Rs));
                 prof.begin(P_OTHER);
                 launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s, Rs);
                 prof.end();
@@ -1414,7 +1437,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                                    net->ld_of(nl - 1), net->ws->cst.p, s);
                 prof.end();
                 res->prof.other_launches++;
-                run_pass(P, nl - 1, 1, nq, nullptr, res->margin.p, nullptr, false);
+                run_pass(P, nl - 1, 1, nq, nullptr, res->margin.p, nullptr, res->sym_c[nl + 1] ? nl + 1 : -1);
                 prof.begin(P_OTHER);
                 launch_verdict(res->margin.p, B, nq, res->verdict.p, s);
                 prof.end();
@@ -1575,42 +1598,62 @@ dpc_status dpc_result_relaxation(const dpc_result* res, int32_t relu_layer, floa
     });
 }
 
+namespace {
+
+// Kept input-level expressions of `rows_per_input` rows per input (index `idx` of the result's store, side offset
+// already applied by the caller through `side`) to the caller's arrays, in the interface's neuron orders.
+void export_symbolic(const dpc_result* res, int idx, int side, int rows_per_input, bool rows_spatial, int rC, int rH, int rW,
+                     float* coeff, float* cst)
+{
+    const dpc_network* net = res->net;
+    const int B = res->batch, n0 = net->n0, ld0 = net->ld_of(0), n = rows_per_input;
+    if (B == 0 || n == 0) return;
+    int cC = 0, cH = 0, cW = 0;
+    if (!net->spatial(0, &cC, &cH, &cW)) cC = 0;
+    if (!rows_spatial) rC = 0;
+    DevBuf<float> tmp, tmpk;
+    if (coeff) tmp.reserve((size_t)n * n0);
+    if (cst) tmpk.reserve(n);
+    for (int b = 0; b < B; ++b) {
+        const size_t row0 = ((size_t)side * B + b) * n;
+        launch_sym_export(res->sym_c[idx]->p + row0 * ld0, ld0, res->sym_k[idx]->p + row0, n, n0, rC, rH, rW, cC, cH, cW,
+                          coeff ? tmp.p : nullptr, cst ? tmpk.p : nullptr, nullptr);
+        if (coeff) DPC_HIP(hipMemcpy(coeff + (size_t)b * n * n0, tmp.p, (size_t)n * n0 * sizeof(float), hipMemcpyDefault));
+        if (cst) DPC_HIP(hipMemcpy(cst + (size_t)b * n, tmpk.p, (size_t)n * sizeof(float), hipMemcpyDefault));
+    }
+}
+
+}  // namespace
+
 dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t side, float* coeff, float* cst)
 {
     return guarded([&] {
         require_result(res, "dpc_result_symbolic");
         const dpc_network* net = res->net;
         const int nl = (int)net->layers.size();
-        DPC_REQUIRE(res->keep_symbolic == 1 && res->has_symbolic, DPC_ESTATE,
-                    "dpc_result_symbolic: certify was not run with keep_symbolic = 1");
-        DPC_REQUIRE(layer == nl, DPC_EINVAL, "dpc_result_symbolic: only the last layer (%d) is kept", nl);
+        DPC_REQUIRE(layer >= 1 && layer <= nl, DPC_EINVAL, "dpc_result_symbolic: layer %d out of range [1, %d]", layer, nl);
+        DPC_REQUIRE(net->layers[layer - 1]->kind != RELU, DPC_EINVAL,
+                    "dpc_result_symbolic: layer %d is a ReLU layer (its polyhedral bounds are those of dpc_result_relaxation)", layer);
+        DPC_REQUIRE(res->keep_symbolic >= 1 && res->sym_c[layer] && res->sym_have[layer], DPC_ESTATE,
+                    "dpc_result_symbolic: the bounds of layer %d were not kept (keep_symbolic = 1 keeps the last layer, 2 every layer)", layer);
         DPC_REQUIRE(side == 0 || side == 1, DPC_EINVAL, "dpc_result_symbolic: side must be 0 or 1");
         DeviceGuard guard(net->device);
-        const int B = res->batch, nK = net->size_of(nl), n0 = net->n0, ld0 = net->ld_of(0);
-        const size_t rows = (size_t)B * nK;
-        if (rows == 0) return;
-        if (coeff) {
-            const float* src = res->sym_coeff.p + (size_t)side * rows * ld0;
-            int C, H, W;
-            if (net->spatial(0, &C, &H, &W)) {
-                DevBuf<float> a, b;
-                a.reserve(rows * n0);
-                b.reserve(rows * n0);
-                DPC_HIP(hipMemcpy2D(a.p, (size_t)n0 * 4, src, (size_t)ld0 * 4, (size_t)n0 * 4, rows, hipMemcpyDeviceToDevice));
-                DPC_REQUIRE(rows <= 0x7fffffff, DPC_EINVAL, "dpc_result_symbolic: too many rows");
-                launch_hwc_to_chw(a.p, b.p, (int)rows, C, H, W, nullptr);
-                DPC_HIP(hipMemcpy(coeff, b.p, rows * n0 * sizeof(float), hipMemcpyDefault));
-            } else {
-                DPC_HIP(hipMemcpy2D(coeff, (size_t)n0 * 4, src, (size_t)ld0 * 4, (size_t)n0 * 4, rows, hipMemcpyDefault));
-            }
-        }
-        if (cst) {
-            std::vector<double> h(rows);
-            DPC_HIP(hipMemcpy(h.data(), res->sym_cst.p + (size_t)side * rows, rows * sizeof(double), hipMemcpyDeviceToHost));
-            std::vector<float> hf(rows);
-            for (size_t i = 0; i < rows; ++i) hf[i] = (float)h[i];
-            DPC_HIP(hipMemcpy(cst, hf.data(), rows * sizeof(float), hipMemcpyDefault));
-        }
+        int C = 0, H = 0, W = 0;
+        const bool sp = net->spatial(layer, &C, &H, &W);
+        export_symbolic(res, layer, side, net->size_of(layer), sp, C, H, W, coeff, cst);
+    });
+}
+
+dpc_status dpc_result_margin_symbolic(const dpc_result* res, float* coeff, float* cst)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_margin_symbolic");
+        const dpc_network* net = res->net;
+        const int nl = (int)net->layers.size();
+        DPC_REQUIRE(res->keep_symbolic >= 1 && res->has_label && res->sym_c[nl + 1] && res->sym_have[nl + 1], DPC_ESTATE,
+                    "dpc_result_margin_symbolic: certify was not run with keep_symbolic >= 1 and labels");
+        DeviceGuard guard(net->device);
+        export_symbolic(res, nl + 1, 0, net->size_of(nl) - 1, false, 0, 0, 0, coeff, cst);
     });
 }
 

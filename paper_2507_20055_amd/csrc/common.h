@@ -150,6 +150,13 @@ void launch_merge_block(float* dst, int ld_dst, int64_t M, int R, int rows_C, in
 void launch_block_bound(double* cst, int64_t M, int R, int rows_C, int rows_W, int batch, int nsides, int n, int kind,
                         const float* src, int ld_src, const float* lo, const float* hi, int patch, int ph, int pw, int C, int S,
                         int P, int gh, int gw, hipStream_t s);
+// Patch-form rows at the input layer -> dense rows over the input (dst zero before); see kernels_rows.hip.
+void launch_expand_patch_rows(const float* src, int ld_src, int shared_mod, const double* cst_in, const float* cst_init_c,
+                              int64_t M, int R, int rows_C, int rows_W, int ph, int pw, int C, int S, int P, int gh, int gw,
+                              float* dst, int ld_dst, double* cst_out, hipStream_t s);
+// One input's kept symbolic bounds from internal (H,W,C) row / column orders to (C,H,W); rC / cC = 0: no shape.
+void launch_sym_export(const float* src, int ld_src, const double* cst, int n, int n0, int rC, int rH, int rW, int cC, int cH, int cW,
+                       float* out, float* cst_out, hipStream_t s);
 void launch_add_vectors(const float* a, const float* b, float* out, int64_t n, hipStream_t s);
 void launch_fold_slots(double* cst, const float* part, int nslots, int64_t stride, int64_t M, hipStream_t s, const float* init = nullptr,
                        int init_mod = 0);

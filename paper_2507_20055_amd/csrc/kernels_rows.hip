@@ -902,6 +902,93 @@ void launch_block_bound(double* cst, int64_t M, int R, int rows_C, int rows_W, i
     DPC_HIP(hipGetLastError());
 }
 
+// Patch-form rows that have reached the input layer written out as dense rows over it (kept symbolic bounds of a
+// convolution layer's neurons): row m's ph x pw x C patch sits at grid position (ho*S - P, wo*S - P) of the gh x gw grid;
+// positions off the grid carry no neuron.  shared_mod > 0: the rows are still the layer's own kernel cores,
+// src row = (m % R) % shared_mod, constant = cst_init_c of that channel; else constants are copied.  dst is zero before.
+struct ExpandArgs {
+    const float* src; int ld_src; int shared_mod;
+    const double* cst_in; const float* cst_init_c;
+    float* dst; int ld_dst; double* cst_out;
+    int R, rows_C, rows_W, ph, pw, C, S, P, gh, gw;
+};
+
+__global__ __launch_bounds__(kThreads) void expand_patch_rows_kernel(ExpandArgs a)
+{
+    const size_t m = blockIdx.x;
+    const int r = (int)(m % (size_t)a.R);
+    const size_t srow = a.shared_mod > 0 ? (size_t)(r % a.shared_mod) : m;
+    const float* src = a.src + srow * a.ld_src;
+    float* dst = a.dst + m * a.ld_dst;
+    const int wo = (r / a.rows_C) % a.rows_W, ho = r / (a.rows_C * a.rows_W);
+    const int oy = ho * a.S - a.P, ox = wo * a.S - a.P;
+    const int n1 = a.ph * a.pw * a.C;
+    for (int e = threadIdx.x; e < n1; e += kThreads) {
+        const int pos = e / a.C, c = e - pos * a.C;
+        const int py = pos / a.pw, px = pos - py * a.pw;
+        const int gy = oy + py, gx = ox + px;
+        if (gy < 0 || gy >= a.gh || gx < 0 || gx >= a.gw) continue;
+        dst[(size_t)(gy * a.gw + gx) * a.C + c] = src[e];
+    }
+    if (threadIdx.x == 0) a.cst_out[m] = a.shared_mod > 0 ? (double)a.cst_init_c[r % a.shared_mod] : a.cst_in[m];
+}
+
+void launch_expand_patch_rows(const float* src, int ld_src, int shared_mod, const double* cst_in, const float* cst_init_c,
+                              int64_t M, int R, int rows_C, int rows_W, int ph, int pw, int C, int S, int P, int gh, int gw,
+                              float* dst, int ld_dst, double* cst_out, hipStream_t s)
+{
+    DPC_REQUIRE(src && dst && cst_out && M >= 0 && M <= 0x7fffffff && R >= 1 && rows_C >= 1 && rows_W >= 1 && ph >= 1 && pw >= 1 && C >= 1 &&
+                    S >= 1 && P >= 0 && gh >= 1 && gw >= 1, DPC_EINVAL, "expand_patch_rows: bad arguments");
+    DPC_REQUIRE((int64_t)ph * pw * C <= ld_src && (int64_t)gh * gw * C <= ld_dst, DPC_EINVAL, "expand_patch_rows: rows do not fit");
+    DPC_REQUIRE(shared_mod > 0 ? cst_init_c != nullptr : cst_in != nullptr, DPC_EINVAL, "expand_patch_rows: no constants");
+    if (M == 0) return;
+    ExpandArgs a{src, ld_src, shared_mod, cst_in, cst_init_c, dst, ld_dst, cst_out, R, rows_C, rows_W, ph, pw, C, S, P, gh, gw};
+    hipLaunchKernelGGL(expand_patch_rows_kernel, dim3((unsigned)M), dim3(kThreads), 0, s, a);
+    DPC_HIP(hipGetLastError());
+}
+
+// Kept symbolic bounds of one input, from the internal neuron orders to the interface's: out[r'][j'] = src[r][j] with
+// r' / j' the (C,H,W) positions of the (H,W,C)-ordered row r / column j (rC or cC = 0: that side has no shape);
+// constants double -> float.
+struct SymExportArgs {
+    const float* src; int ld_src; const double* cst;
+    float* out; float* cst_out;
+    int n, n0, rC, rH, rW, cC, cH, cW;
+};
+
+__global__ __launch_bounds__(kThreads) void sym_export_kernel(SymExportArgs a)
+{
+    const int r = blockIdx.x;                      // internal row index
+    int ro = r;
+    if (a.rC > 0) {
+        const int c = r % a.rC, pos = r / a.rC;
+        ro = c * a.rH * a.rW + pos;
+    }
+    if (a.out) {
+        const float* src = a.src + (size_t)r * a.ld_src;
+        float* out = a.out + (size_t)ro * a.n0;
+        for (int j = threadIdx.x; j < a.n0; j += kThreads) {
+            int jo = j;
+            if (a.cC > 0) {
+                const int c = j % a.cC, pos = j / a.cC;
+                jo = c * a.cH * a.cW + pos;
+            }
+            out[jo] = src[j];
+        }
+    }
+    if (a.cst_out && threadIdx.x == 0) a.cst_out[ro] = (float)a.cst[r];
+}
+
+void launch_sym_export(const float* src, int ld_src, const double* cst, int n, int n0, int rC, int rH, int rW, int cC, int cH, int cW,
+                       float* out, float* cst_out, hipStream_t s)
+{
+    DPC_REQUIRE(src && cst && n >= 1 && n0 >= 1 && n0 <= ld_src, DPC_EINVAL, "sym_export: bad arguments");
+    DPC_REQUIRE((rC == 0 || (int64_t)rC * rH * rW == n) && (cC == 0 || (int64_t)cC * cH * cW == n0), DPC_EINVAL, "sym_export: shapes do not match sizes");
+    SymExportArgs a{src, ld_src, cst, out, cst_out, n, n0, rC, rH, rW, cC, cH, cW};
+    hipLaunchKernelGGL(sym_export_kernel, dim3((unsigned)n), dim3(kThreads), 0, s, a);
+    DPC_HIP(hipGetLastError());
+}
+
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* __restrict__ p, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;

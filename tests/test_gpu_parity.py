@@ -150,6 +150,57 @@ def test_symbolic_bounds_of_last_layer(kind):
     gnet.close()
 
 
+@pytest.mark.parametrize("kind", ["fc", "conv", "conv_first_patch", "res_fc", "res_conv"])
+def test_symbolic_bounds_of_every_layer(kind):
+    """keep_symbolic = 2: the input-level polyhedral bounds of every affine / convolution / Add layer and of the property
+    rows against the oracle's (convolution layers' rows arrive at the input as patches and are written out dense; rows
+    and columns come back in (C,H,W) order)."""
+    if kind == "fc":
+        net = wl.random_small_net(141, [9, 40, 33, 36, 6])
+    elif kind == "conv":
+        net = wl.random_small_conv(142, (2, 7, 6), [(4, 3, 1, 1), (8, 4, 2, 1), (8, 3, 1, 0)], [8, 4])
+    elif kind == "conv_first_patch":
+        net = wl.random_small_conv(143, (3, 8, 8), [(8, 4, 2, 1)], [5])
+    elif kind == "res_fc":
+        net = wl.random_small_res(144, 12, 20, 2, 5)
+    else:
+        net = wl.random_small_res_conv(145, (2, 6, 6), 4, 1, 3, [(8, 4, 2, 1)], [6, 3])
+    B = 2
+    x, lo, hi = wl.random_box(146, net.n_in, B, 0.05)
+    nK = net.layers[-1].W.shape[0]
+    label = np.array([0, nK - 1], np.int32)
+    b = _binding()
+    gnet = b.Network(net)
+    nl = len(net.layers)
+    g = gnet.certify(lo, hi, label, keep_symbolic=2)
+    compare_with_oracle(net, lo, hi, g, oracle.run(net, lo, hi, label=label), label)
+
+    def check(c, k, oc, ok):
+        scale = np.abs(oc).max() + 1e-30
+        assert c.shape == oc.shape and k.shape == ok.shape
+        assert np.all(np.abs(c - oc) <= 1e-5 * scale + 1e-4 * np.abs(oc)), np.abs(c - oc).max()
+        assert np.all(np.abs(k - ok) <= 1e-5 + 1e-4 * np.abs(ok))
+
+    for k in range(1, nl + 1):
+        if net.layers[k - 1].kind == "relu":
+            with pytest.raises(b.DpcError):
+                g.symbolic(k, 0)
+            continue
+        o = oracle.run(net, lo, hi, label=label, sym_layer=k)
+        check(*g.symbolic(k, 0), o.sym["cl"], o.sym["kl"])
+        check(*g.symbolic(k, 1), o.sym["cu"], o.sym["ku"])
+    o = oracle.run(net, lo, hi, label=label, sym_layer=nl + 1)
+    check(*g.margin_symbolic(), o.sym["cl"], o.sym["kl"])
+    # keep_symbolic = 1 keeps the last layer and the property rows only
+    g1 = gnet.certify(lo, hi, label, keep_symbolic=1)
+    check(*g1.margin_symbolic(), o.sym["cl"], o.sym["kl"])
+    with pytest.raises(b.DpcError):
+        g1.symbolic(1, 0)
+    with pytest.raises(b.DpcError):
+        gnet.certify(lo, hi, label, keep_symbolic=2, max_backsub_depth=2, final_backsub_depth=-1)
+    gnet.close()
+
+
 @pytest.mark.parametrize("R", [1, 31, 32, 33, 64, 100])
 def test_rows_per_group_around_the_fusion_threshold(R):
     """The fused epilogue needs >= 32 rows per (side, input) group; layers on both sides of that threshold, with

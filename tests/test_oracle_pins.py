@@ -56,6 +56,10 @@ def test_hand_2_2_2():
     np.testing.assert_allclose(r.sym["ku"][0], g["sym_upper_const"], **tol)
     np.testing.assert_allclose(r.margin[0], g["margin"], **tol)
     assert r.verdict[0] == int(g["verdict"][0])
+    # the property row's lower expression over the input (derived in the fixture's header)
+    m = oracle.run(net, g["lo"][None], g["hi"][None], label=g["label"].astype(np.int32), sym_layer=4)
+    np.testing.assert_allclose(m.sym["cl"][0].ravel(), g["margin_sym_coeff"], **tol)
+    np.testing.assert_allclose(m.sym["kl"][0], g["margin_sym_const"], **tol)
 
 
 def test_hand_2_2_2_2():
@@ -367,3 +371,37 @@ def test_rejects_malformed_input():
         oracle.run(net, lo + 1, lo)                       # lo > hi
     with pytest.raises(ValueError):
         oracle.run(net, lo, lo, label=np.array([5], np.int32))
+
+
+def test_symbolic_bounds_of_every_layer_and_of_the_property_rows_hold_pointwise():
+    """Input-level expressions of hidden affine / convolution layers and of the margin rows: their extrema over the box
+    are the layer's l, u (the margins), and they bound the concrete values at sampled points and box corners."""
+    rng = np.random.default_rng(5)
+    for net in (wl.random_small_net(51, [6, 9, 8, 7, 4]), wl.random_small_conv(52, (2, 5, 5), [(3, 3, 1, 1), (4, 3, 2, 0)], [6, 3])):
+        x, lo, hi = wl.random_box(53, net.n_in, 2, 0.2)
+        lab = np.array([1, 2], np.int32)
+        lo64, hi64 = lo.astype(np.float64), hi.astype(np.float64)
+        pts = [lo64[b] + (hi64[b] - lo64[b]) * np.concatenate([rng.uniform(size=(400, net.n_in)), rng.integers(0, 2, size=(64, net.n_in))])
+               for b in range(2)]
+        acts = [wl.forward(net, p) for p in pts]
+        nl = len(net.layers)
+        for k in [i + 1 for i, L in enumerate(net.layers) if L.kind != "relu"] + [nl + 1]:
+            r = oracle.run(net, lo, hi, label=lab, sym_layer=k)
+            cl, kl = r.sym["cl"], r.sym["kl"]
+            ext_l = kl + (np.maximum(cl, 0) * lo64[:, None, :] + np.minimum(cl, 0) * hi64[:, None, :]).sum(-1)
+            if k <= nl:
+                cu, ku = r.sym["cu"], r.sym["ku"]
+                ext_u = ku + (np.maximum(cu, 0) * hi64[:, None, :] + np.minimum(cu, 0) * lo64[:, None, :]).sum(-1)
+                np.testing.assert_allclose(ext_l, r.l[k], rtol=1e-12, atol=1e-12)
+                np.testing.assert_allclose(ext_u, r.u[k], rtol=1e-12, atol=1e-12)
+            else:
+                np.testing.assert_allclose(ext_l, r.margin, rtol=1e-12, atol=1e-12)
+            for b in range(2):
+                if k <= nl:
+                    val = acts[b][k]
+                    assert np.all(pts[b] @ cl[b].T + kl[b] <= val + 1e-9) and np.all(val <= pts[b] @ cu[b].T + ku[b] + 1e-9)
+                else:
+                    out = acts[b][nl]
+                    others = [o for o in range(out.shape[1]) if o != lab[b]]
+                    val = out[:, [lab[b]]] - out[:, others]
+                    assert np.all(pts[b] @ cl[b].T + kl[b] <= val + 1e-9)
