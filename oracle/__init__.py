@@ -6,9 +6,9 @@ imports it.  ``deeppoly_oracle.c`` holds the arithmetic (plain loops following
 the DeepPoly specification of the paper's Appendix C under the map / traverse
 semantics of Sections 2.2 and 3.2); this file only marshals numpy arrays.
 
-``neuron_level.py`` is a second, even more literal pure-Python transcription
-(dictionary-based polyhedral expressions, explicit priority / stop functions)
-used as a brute-force cross-check on tiny networks.
+``neuron_level.py`` is a second, independent pure-Python implementation (a table of
+neurons, sparse expressions, one substitution loop) used as a brute-force
+cross-check on tiny networks.
 
 Networks are duck-typed: an object with ``n_in`` and ``layers``; each layer has
 ``kind`` in {"affine", "conv", "relu", "add"}, ``W``, ``b`` and, for conv, ``stride``,
