@@ -122,6 +122,12 @@ typedef struct {
                                    affine and ReLU layers alternating only; needs max_backsub_depth = -1 and
                                    keep_symbolic = 0.  dpc_result_concrete then returns, for an affine layer, the
                                    concretisation of its stored bounds (the values the next ReLU transformer uses) */
+                                /* DPC_SKIPPOLY (2): DeepPoly whose ReLU neurons carry their polyhedral bounds over the neurons two
+                                   layers back (Appendix C, SkipPoly; Section 6.1): L = lambda * (w . prev2 + b), U = mu * (w . prev2 + b)
+                                   + nu with (w, b) the row of the layer under the ReLU neuron, so a traverse iteration replaces a
+                                   ReLU layer and the layer under it at once (half as many iterations, same bounds).  That is
+                                   the step the fused kernels execute; the certifier selects it and makes the ReLU neurons'
+                                   shape available from dpc_result_relu_symbolic.  Chain networks, full traversals only */
     int32_t final_backsub_depth; /* traversal limit of the LAST layer and of the property (margin) rows: DPC_SAME_DEPTH
                                    (-2, default) = max_backsub_depth; -1 = to the input; p >= 0 as above.
                                    max_backsub_depth = 0 with final_backsub_depth = -1 is CROWN-IBP (Appendix C): interval
@@ -129,7 +135,7 @@ typedef struct {
     void*   stream;             /* hipStream_t all work is enqueued on (NULL = the null stream) */
 } dpc_options;
 enum { DPC_SAME_DEPTH = -2 };
-enum { DPC_DEEPPOLY = 0, DPC_REUSECERT = 1 };
+enum { DPC_DEEPPOLY = 0, DPC_REUSECERT = 1, DPC_SKIPPOLY = 2 };
 
 /* Fills `opt` with the defaults (full traversal, nothing kept, fused, no profile, graph replay on, null stream). */
 dpc_status dpc_options_default(dpc_options* opt);
@@ -188,6 +194,13 @@ dpc_status dpc_result_relaxation(const dpc_result* res, int32_t relu_layer,
  * (any such layer); DPC_ESTATE otherwise; ReLU layers: DPC_EINVAL (their L, U over the predecessor are lambda, mu, nu). */
 dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t side,
                                float* coeff, float* cst);
+
+/* SkipPoly shape of the neurons of ReLU layer `relu_layer` (Appendix C, SkipPoly: relu_n and compute_upper applied to
+ * the L, U of the neuron underneath): their polyhedral bounds over the layer two below, L (side 0) = lambda * (w . prev2
+ * + b), U (side 1) = mu * (w . prev2 + b) + nu.  coeff [batch, n, n_prev2], cst [batch, n] (host or device; either may be
+ * NULL), neuron orders as in dpc_result_symbolic; the layer under the ReLU layer must be fully-connected or a convolution
+ * (its expanded kernel rows are written out).  Needs certifier = DPC_SKIPPOLY at certify time (DPC_ESTATE otherwise). */
+dpc_status dpc_result_relu_symbolic(const dpc_result* res, int32_t relu_layer, int32_t side, float* coeff, float* cst);
 
 /* The same for the property rows (keep_symbolic >= 1 and labels): the lower polyhedral bound, over the input, of
  * logit[label] - logit[o] for o != label in ascending o; coeff [batch, nK-1, n0], cst [batch, nK-1].  Its minimum over

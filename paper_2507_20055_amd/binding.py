@@ -30,7 +30,7 @@ class dpc_options(ctypes.Structure):
                 ("fuse", c_i32), ("profile", c_i32), ("use_graph", c_i32), ("certifier", c_i32), ("final_backsub_depth", c_i32), ("stream", c_vp)]
 
 
-CERTIFIERS = {"deeppoly": 0, "reusecert": 1}
+CERTIFIERS = {"deeppoly": 0, "reusecert": 1, "skippoly": 2}
 
 
 class dpc_profile(ctypes.Structure):
@@ -59,6 +59,7 @@ EXPORTS = {
     "dpc_result_relaxation": [c_vp, c_i32, c_vp, c_vp, c_vp],
     "dpc_result_symbolic": [c_vp, c_i32, c_i32, c_vp, c_vp],
     "dpc_result_margin_symbolic": [c_vp, c_vp, c_vp],
+    "dpc_result_relu_symbolic": [c_vp, c_i32, c_i32, c_vp, c_vp],
     "dpc_result_verdict": [c_vp, c_vp, c_vp],
     "dpc_result_profile": [c_vp, ctypes.POINTER(dpc_profile)],
     "dpc_result_destroy": [c_vp],
@@ -230,6 +231,13 @@ class Result:
         coeff = np.empty((self.batch, n, n0), np.float32)
         cst = np.empty((self.batch, n), np.float32)
         _check(_lib.dpc_result_symbolic(self._h, layer, side, _ptr(coeff), _ptr(cst)))
+        return coeff, cst
+
+    def relu_symbolic(self, layer: int, side: int):
+        n, nb = self.net.sizes[layer], self.net.sizes[layer - 2]
+        coeff = np.empty((self.batch, n, nb), np.float32)
+        cst = np.empty((self.batch, n), np.float32)
+        _check(_lib.dpc_result_relu_symbolic(self._h, layer, side, _ptr(coeff), _ptr(cst)))
         return coeff, cst
 
     def margin_symbolic(self):

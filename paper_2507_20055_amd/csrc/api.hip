@@ -221,6 +221,7 @@ struct dpc_result {
     dpc_network* net = nullptr;
     int batch = 0;
     int keep_symbolic = 0;
+    int certifier = DPC_DEEPPOLY;          // of the last certify call on this result
     bool has_label = false;
     std::vector<float*> l, u, lam, mu, nu;   // per layer index, device, internal order (sub-allocations)
     DevBuf<float> pool;
@@ -1076,8 +1077,15 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     "dpc_certify: keep_symbolic = 2 needs full traversals of every layer (max_backsub_depth = -1)");
         const int nl = (int)net->layers.size();
         const Layer& last = *net->layers[nl - 1];
-        DPC_REQUIRE(opt.certifier == DPC_DEEPPOLY || opt.certifier == DPC_REUSECERT, DPC_EINVAL, "dpc_certify: unknown certifier %d",
-                    opt.certifier);
+        DPC_REQUIRE(opt.certifier == DPC_DEEPPOLY || opt.certifier == DPC_REUSECERT || opt.certifier == DPC_SKIPPOLY, DPC_EINVAL,
+                    "dpc_certify: unknown certifier %d", opt.certifier);
+        if (opt.certifier == DPC_SKIPPOLY) {
+            // ReLU bounds over the neurons two layers back: a traversal replaces a ReLU layer and the layer under it in
+            // one iteration, which is what the fused kernels execute; only the iteration count of a limit would differ
+            DPC_REQUIRE(opt.max_backsub_depth == -1 && opt.final_backsub_depth == -1, DPC_EINVAL,
+                        "dpc_certify: SkipPoly needs full traversals (max_backsub_depth = final_backsub_depth = -1)");
+            DPC_REQUIRE(net->skip_depth == 0, DPC_EUNSUPPORTED, "dpc_certify: SkipPoly is specified for chain networks only");
+        }
         const bool reuse_cert = opt.certifier == DPC_REUSECERT;
         if (arena) {
             DPC_REQUIRE(!reuse_cert && opt.keep_symbolic == 0 && contract_split_terms() == 0, DPC_EUNSUPPORTED,
@@ -1149,6 +1157,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             }
         }
         res->has_label = label != nullptr;
+        res->certifier = opt.certifier;
         std::fill(res->sym_have.begin(), res->sym_have.end(), 0);
         memset(&res->prof, 0, sizeof res->prof);
         res->prof.struct_size = (int32_t)sizeof(dpc_profile);
@@ -1641,6 +1650,50 @@ dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t sid
         int C = 0, H = 0, W = 0;
         const bool sp = net->spatial(layer, &C, &H, &W);
         export_symbolic(res, layer, side, net->size_of(layer), sp, C, H, W, coeff, cst);
+    });
+}
+
+dpc_status dpc_result_relu_symbolic(const dpc_result* res, int32_t relu_layer, int32_t side, float* coeff, float* cst)
+{
+    return guarded([&] {
+        require_result(res, "dpc_result_relu_symbolic");
+        const dpc_network* net = res->net;
+        const int nl = (int)net->layers.size();
+        DPC_REQUIRE(relu_layer >= 2 && relu_layer <= nl && net->layers[relu_layer - 1]->kind == RELU, DPC_EINVAL,
+                    "dpc_result_relu_symbolic: layer %d is not a ReLU layer", relu_layer);
+        DPC_REQUIRE(res->certifier == DPC_SKIPPOLY, DPC_ESTATE, "dpc_result_relu_symbolic: certify was not run with certifier = DPC_SKIPPOLY");
+        DPC_REQUIRE(side == 0 || side == 1, DPC_EINVAL, "dpc_result_relu_symbolic: side must be 0 or 1");
+        const Layer& under = *net->layers[relu_layer - 2];
+        DPC_REQUIRE(under.kind == AFFINE || under.kind == CONV, DPC_EUNSUPPORTED, "dpc_result_relu_symbolic: the layer under the ReLU layer has no weights");
+        DeviceGuard guard(net->device);
+        const int B = res->batch, n = under.n_out, below = relu_layer - 2, nb = net->size_of(below), ldb = net->ld_of(below);
+        if (B == 0) return;
+        int rC = 0, rH = 0, rW = 0, cC = 0, cH = 0, cW = 0;
+        if (!net->spatial(relu_layer, &rC, &rH, &rW)) rC = 0;
+        if (!net->spatial(below, &cC, &cH, &cW)) cC = 0;
+        DevBuf<float> rows, out, outk;
+        DevBuf<double> k;
+        rows.reserve((size_t)n * ldb);
+        k.reserve(n);
+        if (coeff) out.reserve((size_t)n * nb);
+        if (cst) outk.reserve(n);
+        for (int b = 0; b < B; ++b) {
+            // the rows of the layer under the ReLU layer (its own L = U), then scaled by lambda (L) or mu (U), nu added to U
+            if (under.kind == AFFINE) {
+                DPC_HIP(hipMemcpy2DAsync(rows.p, (size_t)ldb * 4, under.dW.p, (size_t)under.ldw * 4, (size_t)ldb * 4, n, hipMemcpyDeviceToDevice, nullptr));
+            } else {
+                const ConvGeom& g = under.g;
+                launch_fill_zero(rows.p, (int64_t)n * ldb, nullptr);
+                launch_expand_patch_rows(under.cw.core, under.cw.ld_core, g.Co, nullptr, under.cw.bias_c, n, n, g.Co, g.Wo, g.kh, g.kw, g.Ci,
+                                         g.stride, g.pad, g.H, g.W, rows.p, ldb, k.p, nullptr);
+            }
+            const float* sc = (side == 0 ? res->lam[relu_layer] : res->mu[relu_layer]) + (size_t)b * n;
+            launch_scale_rows(rows.p, ldb, n, nb, k.p, under.kind == AFFINE ? under.dBias.p : nullptr, sc,
+                              side == 1 ? res->nu[relu_layer] + (size_t)b * n : nullptr, nullptr);
+            launch_sym_export(rows.p, ldb, k.p, n, nb, rC, rH, rW, cC, cH, cW, coeff ? out.p : nullptr, cst ? outk.p : nullptr, nullptr);
+            if (coeff) DPC_HIP(hipMemcpy(coeff + (size_t)b * n * nb, out.p, (size_t)n * nb * sizeof(float), hipMemcpyDefault));
+            if (cst) DPC_HIP(hipMemcpy(cst + (size_t)b * n, outk.p, (size_t)n * sizeof(float), hipMemcpyDefault));
+        }
     });
 }
 

@@ -157,6 +157,9 @@ void launch_expand_patch_rows(const float* src, int ld_src, int shared_mod, cons
 // One input's kept symbolic bounds from internal (H,W,C) row / column orders to (C,H,W); rC / cC = 0: no shape.
 void launch_sym_export(const float* src, int ld_src, const double* cst, int n, int n0, int rC, int rH, int rW, int cC, int cH, int cW,
                        float* out, float* cst_out, hipStream_t s);
+// rows[r][:] *= scale[r]; cst[r] = scale[r] * (bias_f ? bias_f[r] : cst[r]) + (add ? add[r] : 0).
+void launch_scale_rows(float* rows, int ld, int n, int ncols, double* cst, const float* bias_f, const float* scale, const float* add,
+                       hipStream_t s);
 void launch_add_vectors(const float* a, const float* b, float* out, int64_t n, hipStream_t s);
 void launch_fold_slots(double* cst, const float* part, int nslots, int64_t stride, int64_t M, hipStream_t s, const float* init = nullptr,
                        int init_mod = 0);

@@ -989,6 +989,28 @@ void launch_sym_export(const float* src, int ld_src, const double* cst, int n, i
     DPC_HIP(hipGetLastError());
 }
 
+// rows[r][0:ncols] *= scale[r];  cst[r] = scale[r] * (bias_f ? bias_f[r] : cst[r]) + (add ? add[r] : 0): a ReLU neuron's
+// polyhedral bound written over the neurons two layers back (scale = lambda or mu, add = nu) from the rows of the
+// layer under it.
+__global__ __launch_bounds__(kThreads) void scale_rows_kernel(float* __restrict__ rows, int ld, int ncols, double* __restrict__ cst,
+                                                              const float* __restrict__ bias_f, const float* __restrict__ scale,
+                                                              const float* __restrict__ add)
+{
+    const int r = blockIdx.x;
+    const float sc = scale[r];
+    float* row = rows + (size_t)r * ld;
+    for (int j = threadIdx.x; j < ncols; j += kThreads) row[j] *= sc;
+    if (threadIdx.x == 0) cst[r] = (double)sc * (bias_f ? (double)bias_f[r] : cst[r]) + (add ? (double)add[r] : 0.0);
+}
+
+void launch_scale_rows(float* rows, int ld, int n, int ncols, double* cst, const float* bias_f, const float* scale, const float* add,
+                       hipStream_t s)
+{
+    DPC_REQUIRE(rows && cst && scale && n >= 1 && ncols >= 1 && ncols <= ld, DPC_EINVAL, "scale_rows: bad arguments");
+    hipLaunchKernelGGL(scale_rows_kernel, dim3((unsigned)n), dim3(kThreads), 0, s, rows, ld, ncols, cst, bias_f, scale, add);
+    DPC_HIP(hipGetLastError());
+}
+
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* __restrict__ p, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;

@@ -201,6 +201,48 @@ def test_symbolic_bounds_of_every_layer(kind):
     gnet.close()
 
 
+@pytest.mark.parametrize("kind", ["fc", "conv"])
+def test_skippoly_shapes_and_bounds(kind):
+    """certifier = SkipPoly: bounds, margins and verdicts equal DeepPoly's (oracle), and the ReLU neurons' polyhedral
+    bounds over the neurons two layers back equal those of the neuron-level oracle's SkipPoly, term by term."""
+    from oracle import neuron_level
+    if kind == "fc":
+        net = wl.random_small_net(151, [5, 7, 6, 8, 3])
+    else:
+        net = wl.random_small_conv(152, (2, 5, 4), [(3, 3, 1, 1), (4, 3, 2, 0)], [5, 3])
+    B = 2
+    x, lo, hi = wl.random_box(153, net.n_in, B, 0.15)
+    label = np.array([0, 2], np.int32)
+    b = _binding()
+    gnet = b.Network(net)
+    g = gnet.certify(lo, hi, label, certifier="skippoly")
+    compare_with_oracle(net, lo, hi, g, oracle.run(net, lo, hi, label=label), label)
+    sizes = gnet.sizes
+    for bi in range(B):
+        sh, margins, verdict = neuron_level.certify(net, lo[bi], hi[bi], label=int(label[bi]), certifier="skippoly")
+        np.testing.assert_allclose(g.verdict()[1][bi], margins, rtol=1e-4, atol=1e-5)
+        for k, L in enumerate(net.layers, start=1):
+            if L.kind != "relu":
+                continue
+            for side, name in ((0, "L"), (1, "U")):
+                c, cst = g.relu_symbolic(k, side)
+                want = np.zeros((sizes[k], sizes[k - 2]))
+                wcst = np.zeros(sizes[k])
+                for i, s_ in enumerate(sh[k]):
+                    e = getattr(s_, name)
+                    assert all(n[0] == k - 2 for n in e.terms)
+                    for (_, p), v in e.terms.items():
+                        want[i, p] = v
+                    wcst[i] = e.const
+                np.testing.assert_allclose(c[bi], want, rtol=1e-4, atol=1e-6)
+                np.testing.assert_allclose(cst[bi], wcst, rtol=1e-4, atol=1e-6)
+    with pytest.raises(b.DpcError):
+        gnet.certify(lo, hi, label).relu_symbolic(2, 0)                      # not the SkipPoly certifier
+    with pytest.raises(b.DpcError):
+        gnet.certify(lo, hi, label, certifier="skippoly", max_backsub_depth=2)
+    gnet.close()
+
+
 @pytest.mark.parametrize("R", [1, 31, 32, 33, 64, 100])
 def test_rows_per_group_around_the_fusion_threshold(R):
     """The fused epilogue needs >= 32 rows per (side, input) group; layers on both sides of that threshold, with
