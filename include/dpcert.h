@@ -292,7 +292,7 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
  * "conv_half_tiles" = 0 keeps 32 x 32 tiles in the matrix-unit convolution kernel also for layers with at most 16
  * input channels (1, the default, uses 16 x 16 tiles there);
  * "merge_final" = 0 bounds the output layer and the margins in two traversals instead
- * of one; "contract_remap", "rows_per_wave", "rows_stream" select launch shapes of the contraction and
+ * of one; "contract_remap", "rows_per_wave", "rows_stream", "stream_wgs_per_cu" select launch shapes of the contraction and
  * row kernels.  Results do not depend on any of them beyond rounding order.
  * Split-precision experiment (the exception to that sentence): "contract_split" = 2 or 3 (default 0) runs
  * the contractions through fully-connected layers on the bf16 matrix units with both operands written as

@@ -48,6 +48,7 @@ static uint64_t g_tuning_epoch = 1;  // bumped by every dpc_tuning_set: captured
 void set_contract_remap(int v);
 void set_rows_per_wave(int v);
 void set_rows_stream(int v);
+void set_stream_wgs_per_cu(int v);
 
 namespace {
 
@@ -1813,6 +1814,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         }
         else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
         else if (strcmp(key, "rows_stream") == 0) set_rows_stream(value);
+        else if (strcmp(key, "stream_wgs_per_cu") == 0) set_stream_wgs_per_cu(value);
         else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
     });
 }

@@ -60,11 +60,102 @@ __global__ __launch_bounds__(kThreads) void relax_params_kernel(
     ru[i] = uv >= 0.0f ? uv : 0.0f;
 }
 
+// Parameters of the sign-split ReLU step for columns [c0, c0 + cw) of input b into LDS: multiplier for C >= 0, multiplier
+// for C < 0, and the constant picked up per unit of C >= 0 / C < 0 (nu on the side that uses U, plus multiplier * bias).
+// 16-byte loads, all of a thread's loads of a pass issued before the first use (one trip to L2 per 1024 columns), when the
+// arrays allow it; element by element otherwise.  cw and c0 are multiples of 4.
+__device__ __forceinline__ void fill_relax_params(float4* s_pm, float4* s_nm, float4* s_pk, float4* s_nk, int c0, int cw, int n,
+                                                  int side, int b, const float* __restrict__ lambda, const float* __restrict__ mu,
+                                                  const float* __restrict__ nu, const float* __restrict__ bias)
+{
+    const bool vec = (n & 3) == 0 && (!lambda || ((((uintptr_t)(lambda + (size_t)b * n)) | ((uintptr_t)(mu + (size_t)b * n)) |
+                                                   ((uintptr_t)(nu + (size_t)b * n))) & 15) == 0) &&
+                     (!bias || (((uintptr_t)bias) & 15) == 0);
+    if (vec) {
+        const int n4 = n >> 2, c04 = c0 >> 2, cw4 = cw >> 2;
+        const float4* la4 = reinterpret_cast<const float4*>(lambda ? lambda + (size_t)b * n : nullptr);
+        const float4* mu4 = reinterpret_cast<const float4*>(mu ? mu + (size_t)b * n : nullptr);
+        const float4* nu4 = reinterpret_cast<const float4*>(nu ? nu + (size_t)b * n : nullptr);
+        const float4* bi4 = reinterpret_cast<const float4*>(bias);
+        for (int i4 = threadIdx.x; i4 < cw4; i4 += kThreads) {
+            float4 la = make_float4(1.f, 1.f, 1.f, 1.f), m = la, v = make_float4(0.f, 0.f, 0.f, 0.f), bj = v;
+            const bool live = c04 + i4 < n4;
+            if (live) {
+                if (lambda) { la = la4[c04 + i4]; m = mu4[c04 + i4]; v = nu4[c04 + i4]; }
+                if (bias) bj = bi4[c04 + i4];
+            }
+            const float lav[4] = {la.x, la.y, la.z, la.w}, mv[4] = {m.x, m.y, m.z, m.w};
+            const float vv[4] = {v.x, v.y, v.z, v.w}, bv[4] = {bj.x, bj.y, bj.z, bj.w};
+            float pm[4], nm[4], pk[4], nk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                pm[e] = live ? (side == 0 ? lav[e] : mv[e]) : 0.f;      // lower rows: C >= 0 takes L, C < 0 takes U
+                nm[e] = live ? (side == 0 ? mv[e] : lav[e]) : 0.f;
+                pk[e] = live ? (side == 0 ? 0.0f : vv[e]) + pm[e] * bv[e] : 0.f;
+                nk[e] = live ? (side == 0 ? vv[e] : 0.0f) + nm[e] * bv[e] : 0.f;
+            }
+            s_pm[i4] = make_float4(pm[0], pm[1], pm[2], pm[3]);
+            s_nm[i4] = make_float4(nm[0], nm[1], nm[2], nm[3]);
+            s_pk[i4] = make_float4(pk[0], pk[1], pk[2], pk[3]);
+            s_nk[i4] = make_float4(nk[0], nk[1], nk[2], nk[3]);
+        }
+    } else {
+        for (int i = threadIdx.x; i < cw; i += kThreads) {
+            const int col = c0 + i;
+            float pm = 0.f, nm = 0.f, pk = 0.f, nk = 0.f;
+            if (col < n) {
+                const float la = lambda ? lambda[(size_t)b * n + col] : 1.0f;
+                const float m = mu ? mu[(size_t)b * n + col] : 1.0f;
+                const float v = nu ? nu[(size_t)b * n + col] : 0.0f;
+                const float bj = bias ? bias[col] : 0.0f;
+                pm = side == 0 ? la : m;
+                nm = side == 0 ? m : la;
+                pk = (side == 0 ? 0.0f : v) + pm * bj;
+                nk = (side == 0 ? v : 0.0f) + nm * bj;
+            }
+            reinterpret_cast<float*>(s_pm)[i] = pm;
+            reinterpret_cast<float*>(s_nm)[i] = nm;
+            reinterpret_cast<float*>(s_pk)[i] = pk;
+            reinterpret_cast<float*>(s_nk)[i] = nk;
+        }
+    }
+}
+
+// The box of input b for columns [c0, c0 + cw) into LDS: the bound a coefficient >= 0 takes, the bound a negative one takes.
+__device__ __forceinline__ void fill_box_params(float4* s_p, float4* s_n, int c0, int cw, int n, int side, int b,
+                                                const float* __restrict__ lo, const float* __restrict__ hi)
+{
+    const bool vec = (n & 3) == 0 && ((((uintptr_t)(lo + (size_t)b * n)) | ((uintptr_t)(hi + (size_t)b * n))) & 15) == 0;
+    if (vec) {
+        const int n4 = n >> 2, c04 = c0 >> 2, cw4 = cw >> 2;
+        const float4* lo4 = reinterpret_cast<const float4*>(lo + (size_t)b * n);
+        const float4* hi4 = reinterpret_cast<const float4*>(hi + (size_t)b * n);
+        for (int i4 = threadIdx.x; i4 < cw4; i4 += kThreads) {
+            float4 lv = make_float4(0.f, 0.f, 0.f, 0.f), hv = lv;
+            if (c04 + i4 < n4) { lv = lo4[c04 + i4]; hv = hi4[c04 + i4]; }
+            const bool lower = side == 0;
+            s_p[i4] = make_float4(lower ? lv.x : hv.x, lower ? lv.y : hv.y, lower ? lv.z : hv.z, lower ? lv.w : hv.w);
+            s_n[i4] = make_float4(lower ? hv.x : lv.x, lower ? hv.y : lv.y, lower ? hv.z : lv.z, lower ? hv.w : lv.w);
+        }
+    } else {
+        for (int i = threadIdx.x; i < cw; i += kThreads) {
+            const int col = c0 + i;
+            float pv = 0.f, qv = 0.f;
+            if (col < n) {
+                const float lv = lo[(size_t)b * n + col], hv = hi[(size_t)b * n + col];
+                pv = side == 0 ? lv : hv;
+                qv = side == 0 ? hv : lv;
+            }
+            reinterpret_cast<float*>(s_p)[i] = pv;
+            reinterpret_cast<float*>(s_n)[i] = qv;
+        }
+    }
+}
+
 // Sign-split ReLU step + bias fold (replace_lower / replace_upper through a ReLU layer, then the
-// constant part of the affine layer below).  grid = (row tiles, nsides*batch).  LDS per chunk of
-// columns: multiplier for C >= 0, multiplier for C < 0, and the constant picked up per unit of
-// C >= 0 / C < 0 (nu on the side that uses U, plus multiplier * bias).  A wavefront streams two rows
-// at a time so that up to eight 16-byte loads per lane are in flight.
+// constant part of the affine layer below) for rows of any width.  grid = (row tiles, nsides*batch).  The per-input
+// parameters are staged in LDS a chunk of columns at a time.  A wavefront streams two rows at a time so that up to
+// eight 16-byte loads per lane are in flight.
 template <bool SHARED>
 __global__ __launch_bounds__(kThreads) void relax_step_kernel(
     float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
@@ -90,24 +181,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
     for (int c0 = 0; c0 < ldc; c0 += chunk) {
         const int cw = min(chunk, ldc - c0);           // multiple of 4 (ldc is)
         if (c0 > 0) __syncthreads();
-        for (int i = threadIdx.x; i < cw; i += kThreads) {
-            const int col = c0 + i;
-            float pm = 0.f, nm = 0.f, pk = 0.f, nk = 0.f;
-            if (col < n) {
-                const float la = lambda ? lambda[(size_t)b * n + col] : 1.0f;
-                const float m = mu ? mu[(size_t)b * n + col] : 1.0f;
-                const float v = nu ? nu[(size_t)b * n + col] : 0.0f;
-                const float bj = bias ? bias[col] : 0.0f;
-                pm = side == 0 ? la : m;               // lower rows: C>=0 takes L, C<0 takes U
-                nm = side == 0 ? m : la;
-                pk = (side == 0 ? 0.0f : v) + pm * bj;
-                nk = (side == 0 ? v : 0.0f) + nm * bj;
-            }
-            reinterpret_cast<float*>(s_pm)[i] = pm;
-            reinterpret_cast<float*>(s_nm)[i] = nm;
-            reinterpret_cast<float*>(s_pk)[i] = pk;
-            reinterpret_cast<float*>(s_nk)[i] = nk;
-        }
+        fill_relax_params(s_pm, s_nm, s_pk, s_nk, c0, cw, n, side, b, lambda, mu, nu, bias);
         __syncthreads();
         const int cw4 = cw >> 2;
         const int nloc = n - c0;
@@ -198,17 +272,7 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
     for (int c0 = 0; c0 < ldc; c0 += chunk) {
         const int cw = min(chunk, ldc - c0);
         if (c0 > 0) __syncthreads();
-        for (int i = threadIdx.x; i < cw; i += kThreads) {
-            const int col = c0 + i;
-            float p = 0.f, q = 0.f;
-            if (col < n) {
-                const float lv = lo[(size_t)b * n + col], hv = hi[(size_t)b * n + col];
-                p = side == 0 ? lv : hv;
-                q = side == 0 ? hv : lv;
-            }
-            reinterpret_cast<float*>(s_p)[i] = p;
-            reinterpret_cast<float*>(s_n)[i] = q;
-        }
+        fill_box_params(s_p, s_n, c0, cw, n, side, b, lo, hi);
         __syncthreads();
         const int cw4 = cw >> 2;
         const int nloc = n - c0;
@@ -269,16 +333,25 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
     }
 }
 
-// Streaming variants for rows of at most 1024 columns (one 16-byte load per lane covers a quarter of
-// the row): a wavefront owns one pair of rows and issues all of its loads before the per-input
-// parameters are staged in LDS, so the HBM stream does not wait for the parameter fill; small register
-// footprint, so eight wavefronts per SIMD keep loads in flight.
+// Streaming kernels for rows whose per-input parameters fit LDS whole (rows of up to 2048 columns: at most 32 KB for the sign-split
+// ReLU step, 16 KB for the concretisation, so that five or more workgroups fit a compute unit; wider rows go to the
+// kernels above, which walk chunks of 2048 columns and were measured faster there).  Many short workgroups, in row order: a wavefront's work is
+// a unit (pair of rows, segment of 1024 columns) -- one 16-byte load per lane covers a quarter of a segment, a pair
+// shares every LDS read of the parameters -- and with the default launch shape a wavefront owns ONE pair.  Its loads are
+// issued before the group's parameters are staged, and the staging itself is one trip to L2 (16-byte loads, all issued
+// before the first use).  Measured on gfx950: fewer, longer-lived workgroups that walk many pairs (parameters staged once
+// per group, next unit's loads in flight under the current one) were slower at every shape -- the rate of these passes
+// follows the number of resident wavefronts, not the depth of a wavefront's own queue.  Per-lane partial sums of a
+// segment (at most 16 products) are fp32; they are added up per row in fp64, lanes are combined in fp64 by wave shuffles.
+// Pairs of a group are dealt round-robin to the wavefronts of all its workgroups.
+constexpr int kSeg4 = 256;             // float4 per segment of a row (1024 columns)
+
 template <bool SHARED>
 __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
     float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
     const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
     const float* __restrict__ bias, const float* __restrict__ src, int ld_src,
-    const float* __restrict__ cst_init, int rows_per_wave)
+    const float* __restrict__ cst_init, int rows_per_block)
 {
     extern __shared__ float4 s_par[];                  // [4][ldc/4]: pm, nm, pk, nk
     const int cw4 = ldc >> 2;
@@ -289,12 +362,17 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
     const int sb = blockIdx.y;
     const int side = sb / batch, b = sb - side * batch;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rbeg = blockIdx.x * (rows_per_wave * kWaves) + wave * rows_per_wave;
-    const int rend = min(R, rbeg + rows_per_wave);
-    const int npairs = rend > rbeg ? (rend - rbeg + 1) >> 1 : 0;
+    // pairs of the group are dealt round-robin to all wavefronts of all its workgroups, so that at any time the group's
+    // workgroups read one compact window of rows
+    const int rbeg = 0, rend = R;
+    const int npairs = (R + 1) >> 1;
+    const int first = blockIdx.x * kWaves + wave, stride = gridDim.x * kWaves;
+    const int nseg = (cw4 + kSeg4 - 1) / kSeg4;
+    const int nunits = npairs > first ? ((npairs - first + stride - 1) / stride) * nseg : 0;   // of this wavefront
 
     auto row_of = [&](int p, int h) { const int r = rbeg + 2 * p + h; return r < rend ? r : rend - 1; };
-    auto load_pair = [&](int p, float4 (&v)[2][4]) {
+    auto load_unit = [&](int k, float4 (&v)[2][4]) {
+        const int p = first + (k / nseg) * stride, base = (k % nseg) * kSeg4;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int r = row_of(p, h);
@@ -302,17 +380,19 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
                                                                       : C + ((size_t)sb * R + r) * ldc);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const int i4 = t * 64 + lane;
+                const int i4 = base + t * 64 + lane;
                 if (i4 < cw4) v[h][t] = SHARED ? in[i4] : nt_load4(in + i4);
             }
         }
     };
-    auto compute_pair = [&](int p, float4 (&v)[2][4]) {
-        float a[2] = {0.0f, 0.0f};     // a lane adds at most 16 products in fp32; lanes are combined in fp64
+    double ad[2] = {0.0, 0.0};
+    auto compute_unit = [&](int k, float4 (&v)[2][4]) {
+        const int p = first + (k / nseg) * stride, seg = k % nseg, base = seg * kSeg4;
+        float a[2] = {0.0f, 0.0f};
         const bool two = rbeg + 2 * p + 1 < rend;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int i4 = t * 64 + lane;
+            const int i4 = base + t * 64 + lane;
             if (i4 >= cw4) continue;
             const float4 pm = s_pm[i4], nm = s_nm[i4], pk = s_pk[i4], nk = s_nk[i4];
             const float pmv[4] = {pm.x, pm.y, pm.z, pm.w}, nmv[4] = {nm.x, nm.y, nm.z, nm.w};
@@ -333,41 +413,29 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
                 nt_store4(reinterpret_cast<float4*>(C + m * ldc) + i4, y[0], y[1], y[2], y[3]);
             }
         }
+        ad[0] += (double)a[0];
+        ad[1] += (double)a[1];
+        if (seg != nseg - 1) return;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             if (h == 1 && !two) break;
-            const double t = wave_sum((double)a[h]);
+            const double t = wave_sum(ad[h]);
             if (lane == 0) {
                 const int r = row_of(p, h);
                 const size_t m = (size_t)sb * R + r;
                 cst[m] = (cst_init ? (double)cst_init[r] : cst[m]) + t;
             }
         }
+        ad[0] = ad[1] = 0.0;
     };
 
     float4 va[2][4];
-    if (npairs > 0) load_pair(0, va);
-    for (int i = threadIdx.x; i < ldc; i += kThreads) {
-        float pm = 0.f, nm = 0.f, pk = 0.f, nk = 0.f;
-        if (i < n) {
-            const float la = lambda ? lambda[(size_t)b * n + i] : 1.0f;
-            const float m = mu ? mu[(size_t)b * n + i] : 1.0f;
-            const float v = nu ? nu[(size_t)b * n + i] : 0.0f;
-            const float bj = bias ? bias[i] : 0.0f;
-            pm = side == 0 ? la : m;
-            nm = side == 0 ? m : la;
-            pk = (side == 0 ? 0.0f : v) + pm * bj;
-            nk = (side == 0 ? v : 0.0f) + nm * bj;
-        }
-        reinterpret_cast<float*>(s_pm)[i] = pm;
-        reinterpret_cast<float*>(s_nm)[i] = nm;
-        reinterpret_cast<float*>(s_pk)[i] = pk;
-        reinterpret_cast<float*>(s_nk)[i] = nk;
-    }
+    if (nunits > 0) load_unit(0, va);
+    fill_relax_params(s_pm, s_nm, s_pk, s_nk, 0, ldc, n, side, b, lambda, mu, nu, bias);
     __syncthreads();
-    for (int p = 0; p < npairs; ++p) {       // one pair per wavefront in the launch configuration used; more only if forced
-        if (p > 0) load_pair(p, va);
-        compute_pair(p, va);
+    for (int k = 0; k < nunits; ++k) {
+        if (k > 0) load_unit(k, va);
+        compute_unit(k, va);
     }
 }
 
@@ -376,7 +444,7 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
     const float* __restrict__ C, int ldc, const double* __restrict__ cst, int batch, int R, int n,
     const float* __restrict__ lo, const float* __restrict__ hi, float* __restrict__ out_l,
     float* __restrict__ out_u, const float* __restrict__ src, int ld_src,
-    const float* __restrict__ cst_init, int rows_per_wave,
+    const float* __restrict__ cst_init, int rows_per_block,
     const float* __restrict__ part, int nslots, long long part_stride)
 {
     extern __shared__ float4 s_par[];                  // [2][ldc/4]
@@ -386,12 +454,17 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
     const int sb = blockIdx.y;
     const int side = sb / batch, b = sb - side * batch;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rbeg = blockIdx.x * (rows_per_wave * kWaves) + wave * rows_per_wave;
-    const int rend = min(R, rbeg + rows_per_wave);
-    const int npairs = rend > rbeg ? (rend - rbeg + 1) >> 1 : 0;
+    // pairs of the group are dealt round-robin to all wavefronts of all its workgroups, so that at any time the group's
+    // workgroups read one compact window of rows
+    const int rbeg = 0, rend = R;
+    const int npairs = (R + 1) >> 1;
+    const int first = blockIdx.x * kWaves + wave, stride = gridDim.x * kWaves;
+    const int nseg = (cw4 + kSeg4 - 1) / kSeg4;
+    const int nunits = npairs > first ? ((npairs - first + stride - 1) / stride) * nseg : 0;   // of this wavefront
 
     auto row_of = [&](int p, int h) { const int r = rbeg + 2 * p + h; return r < rend ? r : rend - 1; };
-    auto load_pair = [&](int p, float4 (&v)[2][4]) {
+    auto load_unit = [&](int k, float4 (&v)[2][4]) {
+        const int p = first + (k / nseg) * stride, base = (k % nseg) * kSeg4;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int r = row_of(p, h);
@@ -399,17 +472,19 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
                                                                       : C + ((size_t)sb * R + r) * ldc);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const int i4 = t * 64 + lane;
+                const int i4 = base + t * 64 + lane;
                 if (i4 < cw4) v[h][t] = SHARED ? in[i4] : nt_load4(in + i4);
             }
         }
     };
-    auto compute_pair = [&](int p, float4 (&v)[2][4]) {
-        float a[2] = {0.0f, 0.0f};     // a lane adds at most 16 products in fp32; lanes are combined in fp64
+    double ad[2] = {0.0, 0.0};
+    auto compute_unit = [&](int k, float4 (&v)[2][4]) {
+        const int p = first + (k / nseg) * stride, seg = k % nseg, base = seg * kSeg4;
+        float a[2] = {0.0f, 0.0f};
         const bool two = rbeg + 2 * p + 1 < rend;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int i4 = t * 64 + lane;
+            const int i4 = base + t * 64 + lane;
             if (i4 >= cw4) continue;
             const float4 pp = s_p[i4], ng = s_n[i4];
             const float pv[4] = {pp.x, pp.y, pp.z, pp.w}, nv[4] = {ng.x, ng.y, ng.z, ng.w};
@@ -422,6 +497,9 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
                     if (i4 * 4 + e < n) a[h] = fmaf(x[e], x[e] >= 0.0f ? pv[e] : nv[e], a[h]);
             }
         }
+        ad[0] += (double)a[0];
+        ad[1] += (double)a[1];
+        if (seg != nseg - 1) return;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             if (h == 1 && !two) break;
@@ -429,30 +507,22 @@ __global__ __launch_bounds__(kThreads) void concretise_stream_kernel(
             const size_t m = (size_t)sb * R + r;
             double extra = 0.0;
             for (int t = lane; t < nslots; t += 64) extra += (double)part[(size_t)t * part_stride + m];
-            const double t = wave_sum((double)a[h] + extra);
+            const double t = wave_sum(ad[h] + extra);
             if (lane == 0) {
                 const double val = (cst_init ? (double)cst_init[r] : cst[m]) + t;
                 (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)val;
             }
         }
+        ad[0] = ad[1] = 0.0;
     };
 
     float4 va[2][4];
-    if (npairs > 0) load_pair(0, va);
-    for (int i = threadIdx.x; i < ldc; i += kThreads) {
-        float pv = 0.f, qv = 0.f;
-        if (i < n) {
-            const float lv = lo[(size_t)b * n + i], hv = hi[(size_t)b * n + i];
-            pv = side == 0 ? lv : hv;
-            qv = side == 0 ? hv : lv;
-        }
-        reinterpret_cast<float*>(s_p)[i] = pv;
-        reinterpret_cast<float*>(s_n)[i] = qv;
-    }
+    if (nunits > 0) load_unit(0, va);
+    fill_box_params(s_p, s_n, 0, ldc, n, side, b, lo, hi);
     __syncthreads();
-    for (int p = 0; p < npairs; ++p) {       // one pair per wavefront in the launch configuration used; more only if forced
-        if (p > 0) load_pair(p, va);
-        compute_pair(p, va);
+    for (int k = 0; k < nunits; ++k) {
+        if (k > 0) load_unit(k, va);
+        compute_unit(k, va);
     }
 }
 
@@ -740,12 +810,11 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const float* __restri
 
 int g_rows_per_wave = 0;
 int g_stream = 1;
+int g_stream_wgs_per_cu = 0;           // tuning: workgroups per compute unit the streaming kernels' grids aim for (0: default)
 
 int pick_rows_per_wave(int R, int groups, bool streaming_rows)
 {
     if (g_rows_per_wave > 0) return g_rows_per_wave;
-    // Rows streamed from HBM: one pair of rows per wavefront (many small workgroups keep more loads in
-    // flight than few long-running ones; measured on cfg2- and cfg5-sized passes).
     if (streaming_rows) return 2;
     // Rows re-read from a shared (cache-resident) source: enough blocks to cover 256 CUs a few times over,
     // as many rows per block as that allows.
@@ -754,10 +823,24 @@ int pick_rows_per_wave(int R, int groups, bool streaming_rows)
     return rpw;
 }
 
+// Rows per workgroup of the streaming kernels: one pair per wavefront; two for rows of several segments when that
+// still leaves a thousand workgroups (measured: +2..4 % there, -25 % when the grid gets too small).
+int pick_rows_per_block(int R, int groups, int nseg)
+{
+    if (g_rows_per_wave > 0) return g_rows_per_wave * kWaves;
+    if (g_stream_wgs_per_cu > 0) {     // experiment: grid sized to the chip
+        const int blocks_per_group = (int)std::max<int64_t>(1, (int64_t)256 * g_stream_wgs_per_cu / std::max(groups, 1));
+        return (std::max((int)ceil_div(R, blocks_per_group), 2 * kWaves) + 1) & ~1;
+    }
+    if (nseg >= 2 && ceil_div(R, 4 * kWaves) * groups >= 1024) return 4 * kWaves;
+    return 2 * kWaves;
+}
+
 }  // namespace
 
 void set_rows_per_wave(int v) { g_rows_per_wave = v; }
 void set_rows_stream(int v) { g_stream = v; }
+void set_stream_wgs_per_cu(int v) { g_stream_wgs_per_cu = v; }
 
 void launch_relax_params_pack(const float* l, const float* u, float* lambda, float* mu, float* nu, float* rl, float* ru,
                               const float* bias, int batch, int n, int ld, float* pk, float* pk2, hipStream_t s)
@@ -795,20 +878,25 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
                     "relax_step: shared source needs ld_src >= ldc, multiple of 4, 16-byte aligned");
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "relax_step: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
-    const int rpw = pick_rows_per_wave(R, nsides * batch, !shared_src && ldc <= 1024 && g_stream);
-    const int chunk = std::min(ldc, kChunk);
-    const size_t lds = (size_t)chunk * 16;
-    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
-    if (ldc <= 1024 && g_stream) {
-        if (shared_src)
-            hipLaunchKernelGGL(relax_step_stream_kernel<true>, grid, dim3(kThreads), (size_t)ldc * 16, s, C, ldc, cst, batch,
-                               R, n, lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw);
-        else
-            hipLaunchKernelGGL(relax_step_stream_kernel<false>, grid, dim3(kThreads), (size_t)ldc * 16, s, C, ldc, cst, batch,
-                               R, n, lambda, mu, nu, bias, (const float*)nullptr, 0, cst_init, rpw);
+    if (ldc <= 2048 && g_stream) {
+        // parameters of a whole row in LDS (32 KB at most, so that five workgroups fit a compute unit): the streaming kernel
+        const size_t lds_s = (size_t)ldc * 16;
+        const int rpb = pick_rows_per_block(R, nsides * batch, (int)ceil_div(ldc, 1024));
+        dim3 grid_s((unsigned)ceil_div(R, rpb), (unsigned)(nsides * batch));
+        auto go = [&](auto kern) {
+            if (lds_s > 48 * 1024) ensure_dynamic_lds((const void*)kern, 64 * 1024);
+            hipLaunchKernelGGL(kern, grid_s, dim3(kThreads), lds_s, s, C, ldc, cst, batch, R, n, lambda, mu, nu, bias,
+                               shared_src, shared_src ? ld_src : 0, cst_init, rpb);
+        };
+        if (shared_src) go(relax_step_stream_kernel<true>);
+        else go(relax_step_stream_kernel<false>);
         DPC_HIP(hipGetLastError());
         return;
     }
+    const int rpw = pick_rows_per_wave(R, nsides * batch, false);
+    const int chunk = std::min(ldc, kChunk);
+    const size_t lds = (size_t)chunk * 16;
+    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
     if (shared_src)
         hipLaunchKernelGGL(relax_step_kernel<true>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n,
                            lambda, mu, nu, bias, shared_src, ld_src, cst_init, rpw, chunk);
@@ -836,21 +924,24 @@ void launch_concretise(const float* C, int ldc, const double* cst, int nsides, i
         DPC_REQUIRE(C && cst && ((uintptr_t)C % 16) == 0, DPC_EINVAL, "concretise: C/cst missing or misaligned");
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "concretise: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
-    const int rpw = pick_rows_per_wave(R, nsides * batch, !shared_src && ldc <= 1024 && g_stream);
-    const int chunk = std::min(ldc, kChunk);
-    const size_t lds = (size_t)chunk * 8;
-    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
-    if (ldc <= 1024 && g_stream) {
-        if (shared_src)
-            hipLaunchKernelGGL(concretise_stream_kernel<true>, grid, dim3(kThreads), (size_t)ldc * 8, s, C, ldc, cst, batch, R,
-                               n, lo, hi, out_l, out_u, shared_src, ld_src, cst_init, rpw, part, nslots, (long long)part_stride);
-        else
-            hipLaunchKernelGGL(concretise_stream_kernel<false>, grid, dim3(kThreads), (size_t)ldc * 8, s, C, ldc, cst, batch, R,
-                               n, lo, hi, out_l, out_u, (const float*)nullptr, 0, cst_init, rpw, part, nslots,
-                               (long long)part_stride);
+    if (ldc <= 2048 && g_stream) {
+        const size_t lds_s = (size_t)ldc * 8;
+        const int rpb = pick_rows_per_block(R, nsides * batch, (int)ceil_div(ldc, 1024));
+        dim3 grid_s((unsigned)ceil_div(R, rpb), (unsigned)(nsides * batch));
+        auto go = [&](auto kern) {
+            if (lds_s > 48 * 1024) ensure_dynamic_lds((const void*)kern, 64 * 1024);
+            hipLaunchKernelGGL(kern, grid_s, dim3(kThreads), lds_s, s, C, ldc, cst, batch, R, n, lo, hi, out_l, out_u,
+                               shared_src, shared_src ? ld_src : 0, cst_init, rpb, part, nslots, (long long)part_stride);
+        };
+        if (shared_src) go(concretise_stream_kernel<true>);
+        else go(concretise_stream_kernel<false>);
         DPC_HIP(hipGetLastError());
         return;
     }
+    const int rpw = pick_rows_per_wave(R, nsides * batch, false);
+    const int chunk = std::min(ldc, kChunk);
+    const size_t lds = (size_t)chunk * 8;
+    dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
     if (shared_src)
         hipLaunchKernelGGL(concretise_kernel<true>, grid, dim3(kThreads), lds, s, C, ldc, cst, batch, R, n, lo, hi,
                            out_l, out_u, shared_src, ld_src, cst_init, rpw, chunk, part, nslots, (long long)part_stride);
