@@ -118,8 +118,10 @@ typedef struct {
                                    0: always launch kernel by kernel */
     int32_t certifier;          /* DPC_DEEPPOLY (0, default) or DPC_REUSECERT (1): every affine layer keeps its bounds
                                    already back-substituted to the input and later layers reuse them, one replacement
-                                   step per layer (Appendix C, ReuseCert; Section 6.1).  Fully-connected networks with
-                                   affine and ReLU layers alternating only; needs max_backsub_depth = -1 and
+                                   step per layer (Appendix C, ReuseCert; Section 6.1).  Chain networks with affine or
+                                   convolution layers and ReLU layers alternating (the step through a convolution layer
+                                   contracts its split kernel matrix with the stored rows its window touches, held dense
+                                   over the input); needs max_backsub_depth = -1 and
                                    keep_symbolic = 0.  dpc_result_concrete then returns, for an affine layer, the
                                    concretisation of its stored bounds (the values the next ReLU transformer uses) */
                                 /* DPC_SKIPPOLY (2): DeepPoly whose ReLU neurons carry their polyhedral bounds over the neurons two

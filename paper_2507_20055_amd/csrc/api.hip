@@ -149,6 +149,7 @@ struct Layer {
     // ReuseCert: [W+ | W- | b] and [W- | W+ | b], [n_out, ld_split] each, built on first use
     DevBuf<float> dSplit[2];
     int ld_split = 0;
+    DevBuf<float> dDense;                  // ReuseCert, convolution as the first layer: its expanded rows [n_out, ld0]
     // split-precision experiment: bf16 terms of the transposed weights, built when the tuning key is set
     DevBuf<uint16_t> dWt;
     int wt_terms = 0;
@@ -176,9 +177,10 @@ struct Workspace {
     DevBuf<float> part;
     int64_t part_stride = 0;
     DevBuf<float> rc_rows;                 // ReuseCert: split output/margin rows of the last step, per input
+    DevBuf<float> gather;                  // ReuseCert through a convolution: gathered right operands of a chunk of positions
     uint64_t ws_epoch = 1;                 // bumped whenever a workspace buffer moves (captured graphs hold addresses)
     Workspace() = default;
-    explicit Workspace(Arena* a) : arena(a), cst(a), stage(a), pk2(a), rpart(a), dflag(a), part(a), rc_rows(a)
+    explicit Workspace(Arena* a) : arena(a), cst(a), stage(a), pk2(a), rpart(a), dflag(a), part(a), rc_rows(a), gather(a)
     {
         buf[0].arena = a;
         buf[1].arena = a;
@@ -1098,9 +1100,11 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             DPC_REQUIRE(opt.max_backsub_depth == -1 && opt.final_backsub_depth == -1 && opt.keep_symbolic == 0, DPC_EINVAL,
                         "dpc_certify: ReuseCert needs max_backsub_depth = -1 and keep_symbolic = 0");
             DPC_REQUIRE(nl % 2 == 1, DPC_EUNSUPPORTED, "dpc_certify: ReuseCert needs affine and ReLU layers alternating");
-            for (int i = 0; i < nl; ++i)
-                DPC_REQUIRE(net->layers[i]->kind == (i % 2 ? RELU : AFFINE), DPC_EUNSUPPORTED,
-                            "dpc_certify: ReuseCert covers fully-connected networks with affine and ReLU layers alternating");
+            for (int i = 0; i < nl; ++i) {
+                const int kd = net->layers[i]->kind;
+                DPC_REQUIRE(i % 2 ? kd == RELU : (kd == AFFINE || kd == CONV), DPC_EUNSUPPORTED,
+                            "dpc_certify: ReuseCert covers chain networks with affine / convolution and ReLU layers alternating");
+            }
         }
         if (net->skip_depth > 0)
             DPC_REQUIRE(!reuse_cert, DPC_EUNSUPPORTED, "dpc_certify: ReuseCert is specified for chain networks only");
@@ -1224,16 +1228,44 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         }
         if (reuse_cert) {
             // split weights of every affine layer but the first (once), and room for the split rows of the last step
+            size_t gather_need = 0;
             for (int i = 3; i <= nl; i += 2) {
                 Layer& L = *net->layers[i - 1];
+                if (L.kind == CONV) {
+                    // a chunk of output positions at a time: at most 1 GiB of gathered rows, at least one position
+                    const size_t per_pos = (size_t)(2 * L.g.kh * L.g.kw * L.g.Ci + 1) * ldE;
+                    const size_t all = (size_t)B * L.g.Ho * L.g.Wo * per_pos;
+                    gather_need = std::max(gather_need, std::min(all, std::max(per_pos, ((size_t)1 << 28) / per_pos * per_pos)));
+                }
                 if (L.dSplit[0].p) continue;
+                if (L.kind == CONV) {
+                    // the layer's weight matrix is its expanded kernel: [K+ | K- | b] over the (ky, kx, ci) window, per output channel
+                    const int kk = L.g.kh * L.g.kw * L.g.Ci;
+                    L.ld_split = (int)round_up(2 * kk + 1, kLdAlign);
+                    for (int side = 0; side < 2; ++side) {
+                        L.dSplit[side].reserve((size_t)L.g.Co * L.ld_split);
+                        launch_reuse_split(L.cw.core, L.cw.ld_core, L.cw.bias_c, nullptr, L.g.Co, kk, L.dSplit[side].p, L.ld_split, 0, side, s);
+                    }
+                    continue;
+                }
                 L.ld_split = (int)round_up(2 * L.n_in + 1, kLdAlign);
                 for (int side = 0; side < 2; ++side) {
                     L.dSplit[side].reserve((size_t)L.n_out * L.ld_split);
                     launch_reuse_split(L.dW.p, L.ldw, L.dBias.p, nullptr, L.n_out, L.n_in, L.dSplit[side].p, L.ld_split, 0, side, s);
                 }
             }
-            if (nl >= 3) moved |= net->ws->rc_rows.reserve(2 * (size_t)B * (2 * (size_t)nK - 1) * net->layers[nl - 1]->ld_split);
+            if (gather_need) moved |= net->ws->gather.reserve(gather_need);
+            if (nl >= 3 && net->layers[0]->kind == CONV && !net->layers[0]->dDense.p) {
+                // first layer: its neurons' expressions over the input are the expanded kernel rows, written out once
+                Layer& L1 = *net->layers[0];
+                const ConvGeom& g = L1.g;
+                L1.dDense.reserve((size_t)L1.n_out * net->ld_of(0));
+                moved |= net->ws->cst.reserve(L1.n_out);
+                launch_fill_zero(L1.dDense.p, (int64_t)L1.n_out * net->ld_of(0), s);
+                launch_expand_patch_rows(L1.cw.core, L1.cw.ld_core, g.Co, nullptr, L1.cw.bias_c, L1.n_out, L1.n_out, g.Co, g.Wo, g.kh, g.kw, g.Ci,
+                                         g.stride, g.pad, g.H, g.W, L1.dDense.p, net->ld_of(0), net->ws->cst.p, s);
+            }
+            if (nl >= 3 && label) moved |= net->ws->rc_rows.reserve(2 * (size_t)B * (2 * (size_t)nK - 1) * net->layers[nl - 1]->ld_split);
         }
         if (const int terms = contract_split_terms()) {
             for (int i = 1; i <= nl; ++i) {
@@ -1330,11 +1362,37 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     prof.end();
                     res->prof.other_launches++;
                     prof.begin(P_RELAX);
-                    launch_reuse_scale(i == 2 ? nullptr : E, A.dW.p, A.ldw, A.dBias.p, res->lam[i], res->mu[i], res->nu[i], B, L.n_out,
-                                       n0, ldE, Rr, s);
+                    launch_reuse_scale(i == 2 ? nullptr : E, A.kind == CONV ? A.dDense.p : A.dW.p, A.kind == CONV ? net->ld_of(0) : A.ldw,
+                                       A.dBias.p, res->lam[i], res->mu[i], res->nu[i], B, L.n_out, n0, ldE, Rr, s);
                     prof.end();
                     res->prof.relax_launches++;
                     res->prof.relax_bytes += (double)B * (2.0 * L.n_out + 1) * ldE * (i == 2 ? 4.0 : 8.0);
+                    continue;
+                }
+                if (L.kind == CONV) {
+                    // the replacement step through the expanded kernel: per output position (input, ho, wo) the contraction
+                    // [K+ | K- | b] (Co rows) x gathered rows of Rr, a chunk of positions per launch
+                    const int Kp = 2 * L.g.kh * L.g.kw * L.g.Ci + 1;
+                    const int64_t npos = (int64_t)B * L.g.Ho * L.g.Wo;
+                    const int64_t chunk = std::min<int64_t>({npos, (int64_t)(net->ws->gather.count / ((size_t)Kp * ldE)), 65535});
+                    DPC_REQUIRE(chunk >= 1, DPC_ENOMEM, "ReuseCert: gather workspace too small");
+                    for (int64_t z0 = 0; z0 < npos; z0 += chunk) {
+                        const int64_t nz = std::min(chunk, npos - z0);
+                        prof.begin(P_RELAX);
+                        launch_reuse_gather(Rr, L.n_in, ldE, L.g, z0, nz, net->ws->gather.p, s);
+                        prof.end();
+                        res->prof.relax_launches++;
+                        res->prof.relax_bytes += (double)nz * Kp * ldE * 8.0;
+                        prof.begin(P_CONTRACT);
+                        for (int side = 0; side < 2; ++side)
+                            launch_contract_batched(L.dSplit[side].p, 0, L.g.Co, Kp, L.ld_split, net->ws->gather.p, (int64_t)Kp * ldE, n0 + 1, ldE,
+                                                    E + ((size_t)side * B * L.n_out + (size_t)z0 * L.g.Co) * ldE, (int64_t)L.g.Co * ldE, ldE,
+                                                    (int)nz, s);
+                        prof.end();
+                        res->prof.contract_launches += 2;
+                        res->prof.contract_flop += 2.0 * 2.0 * (double)nz * L.g.Co * Kp * (n0 + 1);
+                    }
+                    concretise_rows(E, L.n_out, res->l[i], res->u[i]);
                     continue;
                 }
                 const int K = 2 * L.n_in + 1;

@@ -101,6 +101,10 @@ struct PatchTail {
 };
 bool launch_patch_tail(const PatchTail& d, hipStream_t s);
 
+// ReuseCert through a convolution layer: G[z - z0][k][ldE] for output positions z = (input, ho, wo) in [z0, z0 + nz), rows in
+// the order of the layer's split kernel matrix (see reuse.hip).  Rr: [batch][2n + 1][ldE], n = g.Ci * g.H * g.W.
+void launch_reuse_gather(const float* Rr, int n, int ldE, const ConvGeom& g, int64_t z0, int64_t nz, float* G, hipStream_t s);
+
 void set_conv_algo(int v);
 int conv_algo();
 void set_conv_half_tiles(int v);

@@ -9,6 +9,7 @@
 // ([2 n_{k-1} + 1, ldE] per input: rows Lr, then Ur, then the unit row that carries the bias), batched over
 // the inputs; the helpers here build those two operands.
 #include "common.h"
+#include "conv.h"
 
 namespace dpc {
 
@@ -94,6 +95,38 @@ __global__ __launch_bounds__(kThreads) void reuse_const_kernel(const float* __re
     if (m < rows) cst[m] = (double)C[m * ldc + col];
 }
 
+// Right operand of the replacement step through a convolution layer (the layer's weight matrix is its expanded kernel:
+// neuron (ho, wo, co) reads the kh x kw x Ci window at (ho*S - P, wo*S - P) of the ReLU layer below).  For output
+// position z = (b, ho, wo) the rows of Rr[b] that window touches are gathered in the order of the split kernel matrix
+// [K+ | K- | b] = (ky, kx, ci) over Lr, the same over Ur, then the unit row:
+//   G[z - z0][k] = Lr / Ur row of neuron ((y*W + x)*Ci + ci), zeros where the window hangs over the zero padding.
+// One workgroup per (position, row).
+__global__ __launch_bounds__(kThreads) void reuse_gather_kernel(const float* __restrict__ Rr, int n, int ldE, ConvGeom g,
+                                                               long long z0, float* __restrict__ G, int Kp)
+{
+    const long long z = z0 + blockIdx.x;
+    const int k = blockIdx.y;
+    const int npos = g.Ho * g.Wo, kk = g.kh * g.kw * g.Ci;
+    const int b = (int)(z / npos), pos = (int)(z - (long long)b * npos);
+    const int ho = pos / g.Wo, wo = pos - ho * g.Wo;
+    const float* src = nullptr;
+    const float* base = Rr + (size_t)b * (2 * (size_t)n + 1) * ldE;
+    if (k == 2 * kk) {
+        src = base + (size_t)2 * n * ldE;
+    } else {
+        const int part = k >= kk, kt = part ? k - kk : k;
+        const int ci = kt % g.Ci, kx = (kt / g.Ci) % g.kw, ky = kt / (g.Ci * g.kw);
+        const int y = ho * g.stride - g.pad + ky, x = wo * g.stride - g.pad + kx;
+        if (y >= 0 && y < g.H && x >= 0 && x < g.W) src = base + ((size_t)part * n + ((size_t)y * g.W + x) * g.Ci + ci) * ldE;
+    }
+    float* dst = G + ((size_t)blockIdx.x * Kp + k) * ldE;
+    for (int c = threadIdx.x * 4; c < ldE; c += kThreads * 4) {
+        vf4 v = {0.f, 0.f, 0.f, 0.f};
+        if (src) v = *reinterpret_cast<const vf4*>(src + c);
+        *reinterpret_cast<vf4*>(dst + c) = v;
+    }
+}
+
 }  // namespace
 
 void launch_reuse_scale(const float* E, const float* W1, int ldw, const float* bias, const float* lambda, const float* mu,
@@ -131,6 +164,17 @@ void launch_reuse_const(const float* C, int ldc, int col, int64_t rows, double* 
     if (rows == 0) return;
     hipLaunchKernelGGL(reuse_const_kernel, dim3((unsigned)ceil_div(rows, kThreads)), dim3(kThreads), 0, s, C, ldc, col,
                        (long long)rows, cst);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_reuse_gather(const float* Rr, int n, int ldE, const ConvGeom& g, int64_t z0, int64_t nz, float* G, hipStream_t s)
+{
+    const int Kp = 2 * g.kh * g.kw * g.Ci + 1;
+    DPC_REQUIRE(Rr && G && n == g.Ci * g.H * g.W && ldE % 4 == 0 && z0 >= 0 && nz >= 0 && nz <= 0x7fffffff && Kp <= 65535, DPC_EINVAL,
+                "reuse_gather: bad arguments");
+    DPC_REQUIRE(((uintptr_t)Rr % 16) == 0 && ((uintptr_t)G % 16) == 0, DPC_EINVAL, "reuse_gather: buffers must be 16-byte aligned");
+    if (nz == 0) return;
+    hipLaunchKernelGGL(reuse_gather_kernel, dim3((unsigned)nz, (unsigned)Kp), dim3(kThreads), 0, s, Rr, n, ldE, g, (long long)z0, G, Kp);
     DPC_HIP(hipGetLastError());
 }
 

@@ -466,15 +466,35 @@ def test_reusecert_hand_example_and_errors():
         gnet.certify(gd["lo"][None].astype(np.float32), gd["hi"][None].astype(np.float32), None, certifier="reusecert",
                      max_backsub_depth=2)
     gnet.close()
-    conv = wl.random_small_conv(7, (2, 6, 6), [(3, 3, 1, 1)], [6, 3])
-    cnet = b.Network(conv)
-    x, lo, hi = wl.random_box(8, conv.n_in, 1, 0.05)
+    res = wl.random_small_res(7, 12, 16, 1, 4)
+    rnet = b.Network(res)
+    x, lo, hi = wl.random_box(8, res.n_in, 1, 0.05)
     with pytest.raises(b.DpcError):
-        cnet.certify(lo, hi, None, certifier="reusecert")            # convolution layers are not covered
-    cnet.close()
+        rnet.certify(lo, hi, None, certifier="reusecert")            # specified for chain networks only
+    rnet.close()
 
 
-@pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5])])
+@pytest.mark.parametrize("shape,convs,fcs", [((2, 6, 6), [(3, 3, 1, 1)], [6, 3]),
+                                             ((3, 8, 8), [(4, 4, 2, 1), (8, 4, 2, 1)], [10, 4]),
+                                             ((1, 9, 7), [(4, 3, 1, 0), (6, 3, 2, 1), (8, 2, 1, 0)], [5]),
+                                             ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4])])
+def test_reusecert_through_convolution_layers(shape, convs, fcs):
+    """ReuseCert on convolutional networks: the replacement step through a convolution layer is the contraction of its
+    split kernel matrix with the gathered input-level rows of the ReLU layer below, one output position at a time."""
+    net = wl.random_small_conv(171, shape, convs, fcs)
+    B = 3
+    x, lo, hi = wl.random_box(172, net.n_in, B, 0.04)
+    label = (np.arange(B) % fcs[-1]).astype(np.int32)
+    b = _binding()
+    gnet = b.Network(net)
+    o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
+    g = gnet.certify(lo, hi, label, certifier="reusecert")
+    compare_with_oracle(net, lo, hi, g, o, label, relu_bounds=False)
+    compare_with_oracle(net, lo, hi, gnet.certify(lo, hi, None, certifier="reusecert"), o, None, relu_bounds=False)
+    gnet.close()
+
+
+@pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29])])
 def test_reusecert_full_batch_gpu_sampled_oracle(cfg, idx):
     """ReuseCert at the benchmark's launch configuration (full batch); the oracle on a sample of the inputs."""
     w = wl.make_workload(cfg)

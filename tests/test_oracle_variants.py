@@ -222,3 +222,55 @@ def test_crownibp_structure(seed, dims):
     b = oracle.run(net2, lo, hi, label=lab % dims[-1], max_depth=0, max_depth_last=-1)
     np.testing.assert_allclose(b.l[3], a.l[3], rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(b.margin, a.margin, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------- ReuseCert through convolution layers
+@pytest.mark.parametrize("convs", [[(3, 3, 1, 1), (4, 4, 2, 1)], [(2, 4, 2, 1), (3, 3, 1, 0)], [(3, 3, 2, 0)]])
+def test_reusecert_conv_equals_its_dense_expansion(convs):
+    """A convolution layer is an affine layer whose weight matrix is the expanded kernel (Section 3.3): ReuseCert on a
+    convolutional network equals ReuseCert on the network with every convolution written out as that matrix (built by
+    pushing unit vectors through an ordinary convolution), which the fully-connected pins above cover."""
+    from tests.test_oracle_pins import _conv_as_dense
+    net = wl.random_small_conv(61, (2, 7, 6), convs, [5, 3])
+    dense = wl.Network(n_in=net.n_in)
+    for L in net.layers:
+        if L.kind == "conv":
+            M, b = _conv_as_dense(L)
+            dense.layers.append(wl.Layer("affine", M, b))
+        else:
+            dense.layers.append(L)
+    x, lo, hi = wl.random_box(62, net.n_in, 2, 0.05)
+    lab = np.array([0, 2], np.int32)
+    last = len(net.layers)
+    for sym in range(1, last + 1, 2):
+        a = oracle.run(net, lo, hi, label=lab, certifier="reusecert", sym_layer=sym)
+        d = oracle.run(dense, lo, hi, label=lab, certifier="reusecert", sym_layer=sym)
+        for k in range(1, last + 1, 2):
+            np.testing.assert_allclose(a.l[k], d.l[k], rtol=1e-11, atol=1e-11)
+            np.testing.assert_allclose(a.u[k], d.u[k], rtol=1e-11, atol=1e-11)
+        for key in ("cl", "kl", "cu", "ku"):
+            np.testing.assert_allclose(a.sym[key], d.sym[key], rtol=1e-11, atol=1e-11)
+        np.testing.assert_allclose(a.margin, d.margin, rtol=1e-11, atol=1e-11)
+        assert np.array_equal(a.verdict, d.verdict)
+
+
+def test_reusecert_conv_matches_neuron_level_and_is_sound():
+    net = wl.random_small_conv(63, (1, 5, 4), [(2, 3, 1, 1), (3, 2, 1, 0)], [4, 3])
+    x, lo, hi = wl.random_box(64, net.n_in, 2, 0.3)
+    lab = np.array([1, 2], np.int32)
+    last = len(net.layers)
+    r = oracle.run(net, lo, hi, label=lab, certifier="reusecert")
+    for bi in range(2):
+        sh, m, v = neuron_level.certify(net, lo[bi], hi[bi], label=int(lab[bi]), certifier="reusecert")
+        np.testing.assert_allclose(m, r.margin[bi], rtol=1e-10, atol=1e-12)
+        assert v == r.verdict[bi]
+        for k in (1, last):
+            np.testing.assert_allclose([s.l for s in sh[k]], r.l[k][bi], rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose([s.u for s in sh[k]], r.u[k][bi], rtol=1e-10, atol=1e-12)
+        for k in range(1, last, 2):
+            np.testing.assert_allclose([s.cl for s in sh[k]], r.l[k][bi], rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose([s.cu for s in sh[k]], r.u[k][bi], rtol=1e-10, atol=1e-12)
+        pts = _samples(lo[bi].astype(np.float64), hi[bi].astype(np.float64), 3000, 65)
+        acts = wl.forward(net, pts)
+        for k in range(1, last + 1, 2):
+            assert np.all(acts[k] >= r.l[k][bi] - 1e-9) and np.all(acts[k] <= r.u[k][bi] + 1e-9)
