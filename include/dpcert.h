@@ -83,8 +83,9 @@ dpc_status dpc_network_add_relu(dpc_network* net);
  * l, u by back-substitution.  A polyhedral expression that crosses the layer then has terms on two
  * layers at once: two blocks of one coefficient tensor (Section 5.1), which are summed when the
  * traversal brings them onto the same layer (Section 5.2, overlapping blocks are merged); the
- * deepest layer is always replaced first (Section 4.2).  The previous layer must be fully-connected
- * or a convolution (DPC_EUNSUPPORTED otherwise).  A depth-limited traversal that stops while a
+ * deepest layer is always replaced first (Section 4.2).  The previous layer may be of any kind: above a
+ * fully-connected or convolution layer the traversal starts from that layer's rows, above a ReLU or another
+ * Add layer from coefficient 1 on each operand (two Diagonal blocks, Section 3.3).  A depth-limited traversal that stops while a
  * block still waits on a skip connection concretises the expression over both layers it holds.
  * ReuseCert is specified for chain networks: dpc_certify returns DPC_EUNSUPPORTED. */
 dpc_status dpc_network_add_skip(dpc_network* net, int32_t from_layer);

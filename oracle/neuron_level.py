@@ -146,12 +146,15 @@ def certify(net, lo, hi, label=None, max_iters: int = -1, certifier: str = "deep
                     itself = Expr(0.0, {(k - 1, i): 1.0})
                     base_L, base_U = (p.L, p.U) if certifier == "skippoly" else (itself, itself)
                 # lower: the base expression when l + u >= 0, else 0; upper: the base when the neuron is always active,
-                # 0 when never, else the chord through (l, 0) and (u, u)
-                L = base_L if pl + pu >= 0.0 else Expr(0.0)
+                # 0 when never, else the chord through (l, 0) and (u, u).  A bound that is the constant 0 is held as
+                # coefficient 0 on the base expression's neurons (the expression of a layer is one coefficient tensor over
+                # the layer below, Section 3.2): a depth-limited substitution then still counts that layer as replaced, as
+                # the C oracle's dense rows do.  Only networks with Add layers can tell the difference.
+                L = base_L if pl + pu >= 0.0 else Expr(0.0).plus(base_L, 0.0)
                 if pl >= 0.0:
                     U = base_U
                 elif pu <= 0.0:
-                    U = Expr(0.0)
+                    U = Expr(0.0).plus(base_U, 0.0)
                 else:
                     slope = pu / (pu - pl)
                     U = Expr(-(pu * pl) / (pu - pl)).plus(base_U, slope)

@@ -138,6 +138,7 @@ struct Layer {
     int n_in = 0, n_out = 0;
     ConvGeom g{};                          // CONV only
     int skip = -1;                         // ADD only: layer index (0 = input) of the second operand
+    bool unit_rows = false;                // ADD above a ReLU or another ADD: bounded from unit rows of its own (dW / cw hold an identity)
     bool spatial_out = false;              // neurons of this layer carry a (C,H,W) shape (stored H,W,C)
     int C = 0, H = 0, W = 0;               // that shape
     std::vector<float> hW, hb;             // host copies in the caller's layout
@@ -308,7 +309,7 @@ struct Form {
 Form start_form(const dpc_network* net, int at, const Layer* own)
 {
     Form f;
-    if (own && own->kind == CONV) {
+    if (own && (own->kind == CONV || (own->kind == ADD && own->spatial_out))) {     // (ADD: 1x1 identity cores over its operand)
         const ConvGeom& g = own->g;
         f.patch = true;
         f.pg = PatchGeom{g.Wo, g.Co, g.kh, g.kw, g.Ci, g.stride, g.pad, g.H, g.W};
@@ -342,7 +343,7 @@ size_t workspace_floats(const dpc_network* net, int B, bool with_margin)
     for (int i = 1; i <= nl; ++i) {
         if (net->layers[i - 1]->kind == RELU) continue;
         // an Add layer is bounded through the rows of the layer below it (plus a unit block on the skip operand)
-        const int top = net->layers[i - 1]->kind == ADD ? i - 1 : i;
+        const int top = (net->layers[i - 1]->kind == ADD && !net->layers[i - 1]->unit_rows) ? i - 1 : i;
         const Layer& own = *net->layers[top - 1];
         const size_t rows = 2 * (size_t)B * own.n_out;
         Form f = start_form(net, top - 1, &own);
@@ -522,9 +523,11 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
                 DPC_REQUIRE(!pool.empty(), DPC_EUNSUPPORTED, "skip connections nested deeper than the workspace allows");
                 w.slot = 0;
                 w.ld = f.ld;
-                if (held || blocked(at - 1) || L.skip == at - 1) {
-                    // another block joins the rows at the layer below (in place), or the previous Add layer's buffer is
-                    // still one of the pair: a copy waits
+                const int kind_below = net->layers[at - 2]->kind;
+                if (held || blocked(at - 1) || L.skip == at - 1 || (kind_below != AFFINE && kind_below != CONV)) {
+                    // another block joins the rows at the layer below (in place), the next step rewrites the rows in place
+                    // (a ReLU layer below, directly or under another Add layer), or the previous Add layer's buffer is still
+                    // one of the pair: a copy waits
                     float* dst = pool.back();
                     pool.pop_back();
                     DPC_HIP(hipMemcpyAsync(dst, cur, (size_t)M * f.ld * sizeof(float), hipMemcpyDeviceToDevice, P.s));
@@ -775,7 +778,8 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     } else {
         launch_concretise(cur, f.ld, cst, nsides, B, R, n_at, res->l[at], res->u[at], out_l, out_u,
                           shared, ld_shared, shared ? cst_init : nullptr, P.s, net->ws->part.p, slots, net->ws->part_stride);
-        res->prof.concretise_bytes += (double)M * n_at * 4.0;
+        // rows still shared by all inputs (a first layer) are one weight matrix, read once
+        res->prof.concretise_bytes += (double)(shared ? R : M) * n_at * 4.0;
     }
     P.prof->end();
     res->prof.concretise_launches++;
@@ -924,8 +928,6 @@ dpc_status dpc_network_add_skip(dpc_network* net, int32_t from_layer)
         const int count = (int)net->layers.size();
         DPC_REQUIRE(count >= 1, DPC_EUNSUPPORTED, "dpc_network_add_skip: an Add layer cannot be the first layer");
         const Layer& below = *net->layers.back();
-        DPC_REQUIRE(below.kind == AFFINE || below.kind == CONV, DPC_EUNSUPPORTED,
-                    "dpc_network_add_skip: the layer below an Add layer must be fully-connected or a convolution");
         DPC_REQUIRE(from_layer >= 0 && from_layer <= count - 1, DPC_EINVAL,
                     "dpc_network_add_skip: from_layer %d out of range [0, %d]", from_layer, count - 1);
         int sc = 0, sh = 0, sw = 0;
@@ -963,9 +965,21 @@ dpc_status dpc_network_finalize(dpc_network* net, int32_t device)
                 // no weights; zero biases so that the ReLU step above it can fold "the bias of the layer below" as usual
                 L.dBias.reserve(L.n_out);
                 DPC_HIP(hipMemset(L.dBias.p, 0, (size_t)L.n_out * sizeof(float)));
+                const int kb = net->layers[i - 1]->kind;
+                L.unit_rows = kb != AFFINE && kb != CONV;
                 if (L.spatial_out) {
-                    DPC_HIP(hipMalloc(reinterpret_cast<void**>(&L.cw.bias_c), (size_t)L.C * sizeof(float)));
-                    DPC_HIP(hipMemset(L.cw.bias_c, 0, (size_t)L.C * sizeof(float)));
+                    // a 1x1 identity kernel: as the layer's own "cores" it is the Diagonal block of coefficient 1 on the operand
+                    // below (used when that operand has no weight rows to start from), and it brings the zero channel biases
+                    L.g = ConvGeom{L.C, L.H, L.W, L.C, 1, 1, 1, 0, L.H, L.W};
+                    std::vector<float> eye((size_t)L.C * L.C, 0.0f), zb((size_t)L.C, 0.0f);
+                    for (int c = 0; c < L.C; ++c) eye[(size_t)c * L.C + c] = 1.0f;
+                    upload_conv_weights(L.g, eye.data(), zb.data(), L.cw);
+                } else if (L.unit_rows) {
+                    L.ldw = (int)round_up(L.n_out, kLdAlign);
+                    std::vector<float> eye((size_t)round_up(L.n_out, 8) * L.ldw, 0.0f);
+                    for (int r = 0; r < L.n_out; ++r) eye[(size_t)r * L.ldw + r] = 1.0f;
+                    L.dW.reserve(eye.size());
+                    DPC_HIP(hipMemcpy(L.dW.p, eye.data(), eye.size() * sizeof(float), hipMemcpyHostToDevice));
                 }
                 continue;
             }
@@ -1469,6 +1483,12 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                         launch_add_vectors(res->u[i - 1], res->u[L.skip], res->u[i], (int64_t)B * L.n_out, s);
                         prof.end();
                         res->prof.concretise_launches += 2;
+                        continue;
+                    }
+                    if (L.unit_rows) {
+                        // the operand below is a ReLU or another Add layer: the expressions start as coefficient 1 on its
+                        // neurons (unit rows: two Diagonal blocks with the one on the skip operand) and no iteration is taken yet
+                        run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], res->sym_c[i] ? i : -1, 1.0, L.skip, 0);
                         continue;
                     }
                     // expressions of its neurons: the rows of the layer below (one traverse iteration already taken)

@@ -96,14 +96,16 @@ def test_add_layers_are_validated():
     assert lib.dpc_network_add_skip(h, 0) == 2                                # cannot be the first layer
     assert lib.dpc_network_add_affine(h, 4, 3, W.ctypes.data, b.ctypes.data) == 0
     assert lib.dpc_network_add_relu(h) == 0
-    assert lib.dpc_network_add_skip(h, 1) == 2                                # below an Add layer: affine or convolution
+    assert lib.dpc_network_add_skip(h, 2) == 1                                # the layer directly below is not a skip operand
     assert lib.dpc_network_add_affine(h, 4, 4, W2.ctypes.data, b.ctypes.data) == 0
     assert lib.dpc_network_add_skip(h, 3) == 1                                # the layer directly below is not a skip operand
     assert lib.dpc_network_add_skip(h, -1) == 1
     assert lib.dpc_network_add_skip(h, 0) == 1                                # 3 inputs against 4 neurons
     assert b"neurons" in lib.dpc_last_error()
     assert lib.dpc_network_add_skip(h, 2) == 0
-    assert lib.dpc_network_add_skip(h, 1) == 2                                # Add directly above Add
+    assert lib.dpc_network_add_skip(h, 1) == 0                                # Add directly above Add: unit rows
+    assert lib.dpc_network_add_relu(h) == 0
+    assert lib.dpc_network_add_skip(h, 2) == 0                                # Add directly above ReLU
     assert lib.dpc_network_destroy(h) == 0
 
 

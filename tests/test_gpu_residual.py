@@ -53,6 +53,13 @@ def _variants():
     yield "affine directly above the Add layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=2),
                                                              _mk(rng, 6, n)])
     yield "Add as the last layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=1)])
+    # Add layers whose operand below has no weight rows (a ReLU layer, another Add layer): the expressions start as unit rows
+    yield "Add above a ReLU layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("relu"), Layer("add", skip=2),
+                                                _mk(rng, 5, n)])
+    yield "Add above an Add layer", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("add", skip=2),
+                                                Layer("add", skip=1), Layer("relu"), _mk(rng, 4, n)])
+    yield "pre-activation blocks", Network(n, [_mk(rng, n, n), Layer("relu"), _mk(rng, n, n), Layer("relu"), Layer("add", skip=1),
+                                               _mk(rng, n, n), Layer("relu"), Layer("add", skip=5), _mk(rng, 4, n)])
 
 
 @pytest.mark.parametrize("name,net", list(_variants()))
@@ -73,6 +80,33 @@ def test_small_residual_conv(shape, width, blocks, k, tail, fcs):
     x, lo, hi = wl.random_box(10, net.n_in, B, 0.03)
     label = np.arange(B, dtype=np.int32) % fcs[-1]
     _check(net, lo, hi, label)
+
+
+def _conv_layer(rng, Co, shape, k, s_, p):
+    Wt = (rng.normal(size=(Co, shape[0], k, k)) * np.sqrt(2.0 / (shape[0] * k * k))).astype(np.float32)
+    return Layer("conv", Wt, (rng.normal(size=Co) * 0.1).astype(np.float32), stride=s_, pad=p, in_shape=shape)
+
+
+def test_add_above_relu_on_a_convolutional_network():
+    """Spatial layers: the Add layer's own expressions are 1x1 identity cores over the ReLU layer below it."""
+    rng = np.random.default_rng(17)
+    shape = (2, 7, 6)
+    c1 = _conv_layer(rng, 4, shape, 3, 1, 1)
+    c2 = _conv_layer(rng, 4, c1.out_shape, 3, 1, 1)
+    c3 = _conv_layer(rng, 8, c2.out_shape, 4, 2, 1)
+    n3 = int(np.prod(c3.out_shape))
+    net = Network(int(np.prod(shape)), [c1, Layer("relu"), c2, Layer("relu"), Layer("add", skip=2), c3, Layer("relu"),
+                                        _mk(rng, 6, n3), Layer("relu"), _mk(rng, 3, 6)])
+    x, lo, hi = wl.random_box(18, net.n_in, 3, 0.03)
+    label = np.array([0, 1, 2], np.int32)
+    _check(net, lo, hi, label)
+    b = _binding()
+    gnet = b.Network(net)
+    for depth, last in ((0, None), (1, None), (2, None), (3, None), (2, -1)):
+        o = oracle.run(net, lo, hi, label=label, max_depth=depth, max_depth_last=last)
+        g = gnet.certify(lo, hi, label, max_backsub_depth=depth, final_backsub_depth=-2 if last is None else last)
+        compare_with_oracle(net, lo, hi, g, o, label)
+    gnet.close()
 
 
 def test_reusecert_is_refused_on_residual_networks():

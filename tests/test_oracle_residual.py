@@ -80,6 +80,11 @@ def _skip_variants():
     yield "nested skips", Network(n, [mk(), Layer("relu"), mk(), Layer("relu"), mk(), Layer("add", skip=4), mk(),
                                       Layer("add", skip=2), Layer("relu"), mk()])
     yield "the layer below added twice", Network(n, [mk(), Layer("relu"), mk(), Layer("add", skip=3), mk()])
+    # Add layers whose operand below is a ReLU layer or another Add layer (no weight rows to start from)
+    yield "Add above a ReLU layer", Network(n, [mk(), Layer("relu"), mk(), Layer("relu"), Layer("add", skip=2), mk()])
+    yield "Add above an Add layer", Network(n, [mk(), Layer("relu"), mk(), Layer("add", skip=2), Layer("add", skip=1),
+                                                Layer("relu"), mk()])
+    yield "ReLU layer added to itself", Network(n, [mk(), Layer("relu"), Layer("add", skip=2), Layer("relu"), mk()])
 
 
 @pytest.mark.parametrize("name,net", list(_skip_variants()))
@@ -146,3 +151,23 @@ def test_malformed_add_layers_are_rejected():
         oracle.run(bad, *_box(52, 3, 1, 0.1)[1:])
     with pytest.raises((ValueError, AssertionError)):
         oracle.run(net, *_box(52, 3, 1, 0.1)[1:], certifier="reusecert")
+
+
+def test_relu_layer_added_to_itself_is_twice_the_layer():
+    """ReLU(h) + ReLU(h) = 2 ReLU(h): the network equals the chain network with the affine layer 2 I in place of the Add
+    layer (an Add layer whose operand below is a ReLU layer starts from coefficient 1 on each operand)."""
+    rng = np.random.default_rng(41)
+    n0, m, k = 4, 5, 3
+    A1 = Layer("affine", rng.normal(size=(m, n0)).astype(np.float32), rng.normal(size=m).astype(np.float32))
+    A2 = Layer("affine", rng.normal(size=(k, m)).astype(np.float32), rng.normal(size=k).astype(np.float32))
+    res = Network(n0, [A1, Layer("relu"), Layer("add", skip=2), Layer("relu"), A2])
+    twice = Layer("affine", 2 * np.eye(m, dtype=np.float32), np.zeros(m, np.float32))
+    chain = Network(n0, [A1, Layer("relu"), twice, Layer("relu"), A2])
+    x, lo, hi = _box(42, n0, 3, 0.4)
+    label = np.array([0, 1, 2], np.int32)
+    a = oracle.run(res, lo, hi, label=label)
+    c = oracle.run(chain, lo, hi, label=label)
+    for k_ in range(1, 6):
+        np.testing.assert_allclose(a.l[k_], c.l[k_], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(a.u[k_], c.u[k_], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(a.margin, c.margin, rtol=1e-12, atol=1e-12)
