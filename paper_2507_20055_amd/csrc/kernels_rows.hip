@@ -812,14 +812,14 @@ int g_rows_per_wave = 0;
 int g_stream = 1;
 int g_stream_wgs_per_cu = 0;           // tuning: workgroups per compute unit the streaming kernels' grids aim for (0: default)
 
-int pick_rows_per_wave(int R, int groups, bool streaming_rows)
+int pick_rows_per_wave(int R, int groups)
 {
     if (g_rows_per_wave > 0) return g_rows_per_wave;
-    if (streaming_rows) return 2;
-    // Rows re-read from a shared (cache-resident) source: enough blocks to cover 256 CUs a few times over,
-    // as many rows per block as that allows.
+    // Kernels that walk chunks of columns: enough blocks to cover 256 CUs a few times over, as many rows per block as
+    // that allows, but at least one PAIR per wavefront (a pair shares every LDS read of the parameters: single rows
+    // measured 4 % slower even where they double the number of workgroups).
     int rpw = kMaxRowsPerWave;
-    while (rpw > 1 && ceil_div(R, rpw * kWaves) * groups < 2048) rpw >>= 1;
+    while (rpw > 2 && ceil_div(R, rpw * kWaves) * groups < 2048) rpw >>= 1;
     return rpw;
 }
 
@@ -893,7 +893,7 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
         DPC_HIP(hipGetLastError());
         return;
     }
-    const int rpw = pick_rows_per_wave(R, nsides * batch, false);
+    const int rpw = pick_rows_per_wave(R, nsides * batch);
     const int chunk = std::min(ldc, kChunk);
     const size_t lds = (size_t)chunk * 16;
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
@@ -938,7 +938,7 @@ void launch_concretise(const float* C, int ldc, const double* cst, int nsides, i
         DPC_HIP(hipGetLastError());
         return;
     }
-    const int rpw = pick_rows_per_wave(R, nsides * batch, false);
+    const int rpw = pick_rows_per_wave(R, nsides * batch);
     const int chunk = std::min(ldc, kChunk);
     const size_t lds = (size_t)chunk * 8;
     dim3 grid((unsigned)ceil_div(R, rpw * kWaves), (unsigned)(nsides * batch));
