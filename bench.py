@@ -237,6 +237,26 @@ def measure(workload, args, steps, warmup, cpu_baseline):
     return out
 
 
+def verdict_check():
+    """Both verdicts in one line: the cfg2 network at eps = 0.001 -- a perturbation small enough that most inputs are
+    certified (NOT one of the named settings, whose bounds are too wide to certify anything on untrained networks) --
+    through the GPU path and through the oracle."""
+    import numpy as np
+    import oracle
+    from paper_2507_20055_amd import binding, workloads as wl
+    w = wl.make_workload("cfg2")
+    eps = 0.001
+    lo = np.clip(w.x - eps, 0.0, 1.0).astype(np.float32)
+    hi = np.clip(w.x + eps, 0.0, 1.0).astype(np.float32)
+    net = binding.Network(w.net, device=0)
+    v, m = net.certify(lo, hi, w.label).verdict()
+    net.close()
+    o = oracle.run(w.net, lo, hi, label=w.label)
+    return {"workload": "cfg2 network, B=32, eps=0.001 (not a named setting)", "inputs": int(v.size), "verified": int(v.sum()),
+            "oracle_verified": int(o.verdict.sum()), "verdicts_identical": bool(np.array_equal(v, o.verdict)),
+            "min_margin": float(m.min()), "max_margin": float(m.max())}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -282,6 +302,8 @@ def main():
                 rec["cpu_baseline"] = r["cpu_baseline"]
             per.append(rec)
         out["per_config"] = per
+        if not args.no_cpu_baseline and args.certifier == "deeppoly" and args.max_depth < 0:
+            out["verdict_check"] = verdict_check()
     print(json.dumps(out))
 
 

@@ -43,6 +43,7 @@ void set_error(const char* fmt, ...)
 }
 
 void set_contract_variant(int v);
+static int g_reuse_patch = 1;     // 1: ReuseCert keeps the stored bounds of convolution layers over their receptive fields only
 static int g_merge_final = 1;     // 1: output-layer bounds and margins share one traversal
 static uint64_t g_tuning_epoch = 1;  // bumped by every dpc_tuning_set: captured launch sequences are keyed on it
 void set_contract_remap(int v);
@@ -1192,6 +1193,21 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         need_rows = std::max(need_rows, 2 * (size_t)B * RsMax);   // output + margin rows of the last pass
         size_t need = workspace_floats(net, B, label != nullptr);
         const int ldE = (int)round_up(n0 + 1, kLdAlign);          // ReuseCert: input-level expression rows
+        // ReuseCert on a convolutional front: the stored bounds of convolution layer i reach only its neurons' receptive
+        // field, rwin[i] (ld == 0: rows over the whole input).  Kept while the window is smaller than the input.
+        std::vector<ReuseWindow> rwin(nl + 2, ReuseWindow{0, 0, 0, 0, 0, 0});
+        if (reuse_cert && g_reuse_patch && net->in_spatial) {
+            ReuseWindow w{0, 0, net->inC, 1, 0, 0};
+            w.ph = w.pw = 1;
+            for (int i = 1; i <= nl && net->layers[i - 1]->kind == CONV; i += 2) {
+                const ConvGeom& g = net->layers[i - 1]->g;
+                ReuseWindow o{(g.kh - 1) * w.S + w.ph, (g.kw - 1) * w.S + w.pw, w.C0, g.stride * w.S, g.pad * w.S + w.P, 0};
+                if ((size_t)o.ph * o.pw * o.C0 >= (size_t)n0) break;
+                o.ld = (int)round_up((size_t)o.ph * o.pw * o.C0 + 1, kLdAlign);
+                rwin[i] = o;
+                w = o;
+            }
+        }
         if (reuse_cert) {
             size_t nmax = 1;
             for (int i = 1; i <= nl; i += 2) nmax = std::max<size_t>(nmax, net->size_of(i));
@@ -1247,7 +1263,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                 Layer& L = *net->layers[i - 1];
                 if (L.kind == CONV) {
                     // a chunk of output positions at a time: at most 1 GiB of gathered rows, at least one position
-                    const size_t per_pos = (size_t)(2 * L.g.kh * L.g.kw * L.g.Ci + 1) * ldE;
+                    const size_t per_pos = (size_t)(2 * L.g.kh * L.g.kw * L.g.Ci + 1) * (rwin[i].ld ? rwin[i].ld : ldE);
                     const size_t all = (size_t)B * L.g.Ho * L.g.Wo * per_pos;
                     gather_need = std::max(gather_need, std::min(all, std::max(per_pos, ((size_t)1 << 28) / per_pos * per_pos)));
                 }
@@ -1269,7 +1285,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                 }
             }
             if (gather_need) moved |= net->ws->gather.reserve(gather_need);
-            if (nl >= 3 && net->layers[0]->kind == CONV && !net->layers[0]->dDense.p) {
+            if (nl >= 3 && net->layers[0]->kind == CONV && !rwin[1].ld && !net->layers[0]->dDense.p) {
                 // first layer: its neurons' expressions over the input are the expanded kernel rows, written out once
                 Layer& L1 = *net->layers[0];
                 const ConvGeom& g = L1.g;
@@ -1362,6 +1378,18 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                 res->prof.concretise_launches++;
                 res->prof.concretise_bytes += (double)M * n0 * 4.0;
             };
+            auto concretise_window_rows = [&](const float* rows, const ReuseWindow& w, const ConvGeom& g, float* out_l, float* out_u) {
+                const int R = g.Co * g.Ho * g.Wo;
+                const int64_t M = 2 * (int64_t)B * R;
+                const int elems = w.ph * w.pw * w.C0;
+                prof.begin(P_CONC);
+                launch_reuse_const(rows, w.ld, elems, M, cst, s);
+                launch_concretise_patch(rows, w.ld, cst, 2, B, R, PatchGeom{g.Wo, g.Co, w.ph, w.pw, w.C0, w.S, w.P, net->inH, net->inW}, res->l[0],
+                                        res->u[0], out_l, out_u, nullptr, 0, nullptr, s);
+                prof.end();
+                res->prof.concretise_launches++;
+                res->prof.concretise_bytes += (double)M * elems * 4.0;
+            };
             {   // first layer: L = U = W x + b is already over the input
                 Layer& L1 = *net->layers[0];
                 run_pass(P, 0, 2, L1.n_out, &L1, res->l[1], res->u[1], -1);
@@ -1376,11 +1404,26 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     prof.end();
                     res->prof.other_launches++;
                     prof.begin(P_RELAX);
-                    launch_reuse_scale(i == 2 ? nullptr : E, A.kind == CONV ? A.dDense.p : A.dW.p, A.kind == CONV ? net->ld_of(0) : A.ldw,
-                                       A.dBias.p, res->lam[i], res->mu[i], res->nu[i], B, L.n_out, n0, ldE, Rr, s);
+                    const ReuseWindow& w = rwin[i - 1];
+                    const bool next_window = w.ld && i < nl && rwin[i + 1].ld;
+                    if (next_window) {
+                        // rows stay over the receptive field (the layer above is a convolution that keeps a window)
+                        const int elems = w.ph * w.pw * w.C0;
+                        launch_reuse_scale(i == 2 ? nullptr : E, A.cw.core, A.cw.ld_core, A.cw.bias_c, res->lam[i], res->mu[i], res->nu[i], B, L.n_out,
+                                           elems, w.ld, Rr, s, A.g.Co);
+                        res->prof.relax_bytes += (double)B * (2.0 * L.n_out + 1) * w.ld * (i == 2 ? 4.0 : 8.0);
+                    } else if (w.ld) {
+                        // the layer above needs rows over the whole input: written out while they are scaled
+                        launch_reuse_scale_expand(i == 2 ? nullptr : E, A.cw.core, A.cw.ld_core, A.cw.bias_c, A.g.Co, res->lam[i], res->mu[i],
+                                                  res->nu[i], B, L.n_out, w, A.g.Wo, A.g.Co, net->inH, net->inW, n0, ldE, Rr, s);
+                        res->prof.relax_bytes += (double)B * (2.0 * L.n_out + 1) * (ldE + w.ld) * 4.0;
+                    } else {
+                        launch_reuse_scale(i == 2 ? nullptr : E, A.kind == CONV ? A.dDense.p : A.dW.p, A.kind == CONV ? net->ld_of(0) : A.ldw,
+                                           A.dBias.p, res->lam[i], res->mu[i], res->nu[i], B, L.n_out, n0, ldE, Rr, s);
+                        res->prof.relax_bytes += (double)B * (2.0 * L.n_out + 1) * ldE * (i == 2 ? 4.0 : 8.0);
+                    }
                     prof.end();
                     res->prof.relax_launches++;
-                    res->prof.relax_bytes += (double)B * (2.0 * L.n_out + 1) * ldE * (i == 2 ? 4.0 : 8.0);
                     continue;
                 }
                 if (L.kind == CONV) {
@@ -1388,25 +1431,30 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     // [K+ | K- | b] (Co rows) x gathered rows of Rr, a chunk of positions per launch
                     const int Kp = 2 * L.g.kh * L.g.kw * L.g.Ci + 1;
                     const int64_t npos = (int64_t)B * L.g.Ho * L.g.Wo;
-                    const int64_t chunk = std::min<int64_t>({npos, (int64_t)(net->ws->gather.count / ((size_t)Kp * ldE)), 65535});
+                    const ReuseWindow& wo = rwin[i];
+                    const int ldR = wo.ld ? wo.ld : ldE;                                  // floats per stored row of this layer
+                    const int ncol = wo.ld ? wo.ph * wo.pw * wo.C0 + 1 : n0 + 1;
+                    const int64_t chunk = std::min<int64_t>({npos, (int64_t)(net->ws->gather.count / ((size_t)Kp * ldR)), 65535});
                     DPC_REQUIRE(chunk >= 1, DPC_ENOMEM, "ReuseCert: gather workspace too small");
                     for (int64_t z0 = 0; z0 < npos; z0 += chunk) {
                         const int64_t nz = std::min(chunk, npos - z0);
                         prof.begin(P_RELAX);
-                        launch_reuse_gather(Rr, L.n_in, ldE, L.g, z0, nz, net->ws->gather.p, s);
+                        if (wo.ld) launch_reuse_gather_patch(Rr, L.n_in, rwin[i - 2], wo, L.g, z0, nz, net->ws->gather.p, s);
+                        else launch_reuse_gather(Rr, L.n_in, ldE, L.g, z0, nz, net->ws->gather.p, s);
                         prof.end();
                         res->prof.relax_launches++;
-                        res->prof.relax_bytes += (double)nz * Kp * ldE * 8.0;
+                        res->prof.relax_bytes += (double)nz * Kp * ldR * 8.0;
                         prof.begin(P_CONTRACT);
                         for (int side = 0; side < 2; ++side)
-                            launch_contract_batched(L.dSplit[side].p, 0, L.g.Co, Kp, L.ld_split, net->ws->gather.p, (int64_t)Kp * ldE, n0 + 1, ldE,
-                                                    E + ((size_t)side * B * L.n_out + (size_t)z0 * L.g.Co) * ldE, (int64_t)L.g.Co * ldE, ldE,
+                            launch_contract_batched(L.dSplit[side].p, 0, L.g.Co, Kp, L.ld_split, net->ws->gather.p, (int64_t)Kp * ldR, ncol, ldR,
+                                                    E + ((size_t)side * B * L.n_out + (size_t)z0 * L.g.Co) * ldR, (int64_t)L.g.Co * ldR, ldR,
                                                     (int)nz, s);
                         prof.end();
                         res->prof.contract_launches += 2;
-                        res->prof.contract_flop += 2.0 * 2.0 * (double)nz * L.g.Co * Kp * (n0 + 1);
+                        res->prof.contract_flop += 2.0 * 2.0 * (double)nz * L.g.Co * Kp * ncol;
                     }
-                    concretise_rows(E, L.n_out, res->l[i], res->u[i]);
+                    if (wo.ld) concretise_window_rows(E, wo, L.g, res->l[i], res->u[i]);
+                    else concretise_rows(E, L.n_out, res->l[i], res->u[i]);
                     continue;
                 }
                 const int K = 2 * L.n_in + 1;
@@ -1882,6 +1930,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
         else if (strcmp(key, "conv_half_tiles") == 0) set_conv_half_tiles(value);
         else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
+        else if (strcmp(key, "reuse_patch") == 0) g_reuse_patch = value;
         else if (strcmp(key, "chain") == 0) set_chain_mode(value);
         else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);
         else if (strcmp(key, "contract_split_wide") == 0) {

@@ -116,8 +116,9 @@ void set_chain_rows(int v);          // 32 or 64: row block for panels up to 512
 // ---- ReuseCert helpers (Appendix C, ReuseCert): see reuse.hip for the layout -------------------
 // Rr[b] = [lambda * L ; mu * U + nu ; unit row] from the stored bounds E[side][b][n][ldE] of the layer below the ReLU
 // layer, or (E == NULL) from the first layer's shared rows (W1 [n][ldw], bias [n]).
+// (mod > 0: the shared rows repeat every mod rows -- the cores of a first convolution layer, bias per channel.)
 void launch_reuse_scale(const float* E, const float* W1, int ldw, const float* bias, const float* lambda, const float* mu,
-                        const float* nu, int batch, int n, int n0, int ldE, float* Rr, hipStream_t s);
+                        const float* nu, int batch, int n, int n0, int ldE, float* Rr, hipStream_t s, int mod = 0);
 // dst[m] = [c+ | c- | constant] (side 0) or [c- | c+ | constant] (side 1) of row m of src ([rows][ld_src], n columns);
 // constant = bias_d[m] if given, else bias_f[m]; side = m / rows_per_side (rows_per_side > 0) or side0.
 void launch_reuse_split(const float* src, int ld_src, const float* bias_f, const double* bias_d, int64_t rows, int n,

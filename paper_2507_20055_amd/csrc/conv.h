@@ -105,6 +105,19 @@ bool launch_patch_tail(const PatchTail& d, hipStream_t s);
 // the order of the layer's split kernel matrix (see reuse.hip).  Rr: [batch][2n + 1][ldE], n = g.Ci * g.H * g.W.
 void launch_reuse_gather(const float* Rr, int n, int ldE, const ConvGeom& g, int64_t z0, int64_t nz, float* G, hipStream_t s);
 
+// Stored bounds of a convolution layer in patch form: the window of input positions a neuron's bounds reach
+// (ph x pw x C0, corner of neuron (y, x) at (y*S - P, x*S - P)), ld floats per row, constant in column ph*pw*C0.
+struct ReuseWindow { int ph, pw, C0, S, P, ld; };
+// As launch_reuse_gather, for rows in patch form: window fi of the ReLU layer below g, window fo of g's neurons.
+void launch_reuse_gather_patch(const float* Rr, int n, const ReuseWindow& fi, const ReuseWindow& fo, const ConvGeom& g, int64_t z0,
+                               int64_t nz, float* G, hipStream_t s);
+// Rr[b] = [lambda * L ; mu * U + nu ; unit row] as DENSE rows over the input (n0 = gh*gw*C0 columns + constant, ldE floats) from
+// stored bounds in patch form (E [side][batch][n][fi.ld], or E == NULL: the shared cores [mod][ld_core] with bias [mod]);
+// neuron j sits at position ((j / rows_C) / rows_W, (j / rows_C) % rows_W).
+void launch_reuse_scale_expand(const float* E, const float* core, int ld_core, const float* bias, int mod, const float* lambda,
+                               const float* mu, const float* nu, int batch, int n, const ReuseWindow& fi, int rows_W, int rows_C, int gh,
+                               int gw, int n0, int ldE, float* Rr, hipStream_t s);
+
 void set_conv_algo(int v);
 int conv_algo();
 void set_conv_half_tiles(int v);

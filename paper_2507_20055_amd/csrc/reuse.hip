@@ -26,7 +26,7 @@ template <bool SHARED>
 __global__ __launch_bounds__(kThreads) void reuse_scale_kernel(
     const float* __restrict__ E, const float* __restrict__ W1, int ldw, const float* __restrict__ bias,
     const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
-    int batch, int n, int n0, int ldE, float* __restrict__ Rr)
+    int batch, int n, int n0, int ldE, float* __restrict__ Rr, int mod)
 {
     const int b = blockIdx.y;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -44,8 +44,8 @@ __global__ __launch_bounds__(kThreads) void reuse_scale_kernel(
     const int side = j >= n, jj = side ? j - n : j;
     const float scale = side ? mu[(size_t)b * n + jj] : lambda[(size_t)b * n + jj];
     const float add = side ? nu[(size_t)b * n + jj] : 0.0f;
-    const float* src = SHARED ? W1 + (size_t)jj * ldw : E + (((size_t)side * batch + b) * n + jj) * ldE;
-    const float cst = SHARED ? bias[jj] : 0.0f;
+    const float* src = SHARED ? W1 + (size_t)(jj % mod) * ldw : E + (((size_t)side * batch + b) * n + jj) * ldE;
+    const float cst = SHARED ? bias[jj % mod] : 0.0f;
     for (int c = lane * 4; c < ldE; c += 256) {
         vf4 x = {0.f, 0.f, 0.f, 0.f};
         if (SHARED) {
@@ -127,11 +127,94 @@ __global__ __launch_bounds__(kThreads) void reuse_gather_kernel(const float* __r
     }
 }
 
+// ---- stored bounds of convolution layers in patch form -------------------------------------------------------
+// The stored input-level bounds of a convolution neuron (y, x, c) only reach its receptive field: a window of
+// ph x pw x C0 input positions whose corner is (y*S - P, x*S - P) (C0 = channels of the network input; positions off the
+// image carry no input and are ignored by every consumer).  A row holds the window's coefficients followed by the
+// constant in column ph*pw*C0.  All neurons of one position share a window, so the replacement step through the next
+// convolution layer is again one contraction per output position, with the rows it gathers embedded in the (larger)
+// window of that position: tap (ky, kx) of the layer sits at offset (ky*S, kx*S) of it.
+struct RWin { int ph, pw, C0, S, P, ld; };      // ld: floats per row (>= ph*pw*C0 + 1)
+
+__global__ __launch_bounds__(kThreads) void reuse_gather_patch_kernel(const float* __restrict__ Rr, int n, RWin fi, RWin fo, ConvGeom g,
+                                                                     long long z0, float* __restrict__ G, int Kp)
+{
+    const long long z = z0 + blockIdx.x;
+    const int k = blockIdx.y;
+    const int npos = g.Ho * g.Wo, kk = g.kh * g.kw * g.Ci;
+    const int b = (int)(z / npos), pos = (int)(z - (long long)b * npos);
+    const int ho = pos / g.Wo, wo = pos - ho * g.Wo;
+    const float* base = Rr + (size_t)b * (2 * (size_t)n + 1) * fi.ld;
+    const int ei = fi.ph * fi.pw * fi.C0, eo = fo.ph * fo.pw * fo.C0;
+    float* dst = G + ((size_t)blockIdx.x * Kp + k) * fo.ld;
+    if (k == 2 * kk) {                                               // unit row: carries the bias
+        for (int e = threadIdx.x; e < fo.ld; e += kThreads) dst[e] = e == eo ? 1.0f : 0.0f;
+        return;
+    }
+    const int part = k >= kk, kt = part ? k - kk : k;
+    const int ci = kt % g.Ci, kx = (kt / g.Ci) % g.kw, ky = kt / (g.Ci * g.kw);
+    const int y = ho * g.stride - g.pad + ky, x = wo * g.stride - g.pad + kx;
+    const bool on = y >= 0 && y < g.H && x >= 0 && x < g.W;          // off the layer's grid: zero padding, no neuron
+    const float* src = base + ((size_t)part * n + ((size_t)y * g.W + x) * g.Ci + ci) * fi.ld;
+    const int dy = ky * fi.S, dx = kx * fi.S;
+    for (int e = threadIdx.x; e < fo.ld; e += kThreads) {
+        float v = 0.0f;
+        if (on) {
+            if (e < eo) {
+                const int c = e % fo.C0, q = e / fo.C0;
+                const int qx = q % fo.pw, qy = q / fo.pw;
+                const int py = qy - dy, px = qx - dx;
+                if (py >= 0 && py < fi.ph && px >= 0 && px < fi.pw) v = src[(py * fi.pw + px) * fi.C0 + c];
+            } else if (e == eo) {
+                v = src[ei];
+            }
+        }
+        dst[e] = v;
+    }
+}
+
+// Rr[b][j] (dense rows over the input, constant in column n0) from stored bounds in patch form: row j < n is
+// lambda * L_j, row n + j is mu * U_j + nu, row 2n the unit row, written out over the whole input for the
+// fully-connected layer that follows the last convolution.  SHARED: L_j = U_j = (core[j % mod], bias[j % mod]).
+template <bool SHARED>
+__global__ __launch_bounds__(kThreads) void reuse_scale_expand_kernel(
+    const float* __restrict__ E, const float* __restrict__ core, int ld_core, const float* __restrict__ bias, int mod,
+    const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu, int batch, int n, RWin fi,
+    int rows_W, int rows_C, int gh, int gw, int n0, int ldE, float* __restrict__ Rr)
+{
+    const int b = blockIdx.y, j = blockIdx.x;
+    float* dst = Rr + ((size_t)b * (2 * n + 1) + j) * ldE;
+    if (j == 2 * n) {
+        for (int e = threadIdx.x; e < ldE; e += kThreads) dst[e] = e == n0 ? 1.0f : 0.0f;
+        return;
+    }
+    const int side = j >= n, jj = side ? j - n : j;
+    const float scale = side ? mu[(size_t)b * n + jj] : lambda[(size_t)b * n + jj];
+    const float add = side ? nu[(size_t)b * n + jj] : 0.0f;
+    const float* src = SHARED ? core + (size_t)(jj % mod) * ld_core : E + (((size_t)side * batch + b) * n + jj) * fi.ld;
+    const float cst = SHARED ? bias[jj % mod] : src[fi.ph * fi.pw * fi.C0];
+    const int wo = (jj / rows_C) % rows_W, ho = jj / (rows_C * rows_W);
+    const int oy = ho * fi.S - fi.P, ox = wo * fi.S - fi.P;
+    for (int e = threadIdx.x; e < ldE; e += kThreads) {
+        float v = 0.0f;
+        if (e < n0) {
+            const int c = e % fi.C0, q = e / fi.C0;
+            const int gx = q % gw, gy = q / gw;
+            const int py = gy - oy, px = gx - ox;
+            if (py >= 0 && py < fi.ph && px >= 0 && px < fi.pw) v = scale * src[(py * fi.pw + px) * fi.C0 + c];
+        } else if (e == n0) {
+            v = scale * cst + add;
+        }
+        dst[e] = v;
+    }
+}
+
 }  // namespace
 
 void launch_reuse_scale(const float* E, const float* W1, int ldw, const float* bias, const float* lambda, const float* mu,
-                        const float* nu, int batch, int n, int n0, int ldE, float* Rr, hipStream_t s)
+                        const float* nu, int batch, int n, int n0, int ldE, float* Rr, hipStream_t s, int mod)
 {
+    if (mod <= 0) mod = n;
     DPC_REQUIRE(lambda && mu && nu && Rr && (E || (W1 && bias)) && n >= 1 && n0 >= 1 && ldE > n0 && ldE % 4 == 0 &&
                     batch >= 0 && batch <= 65535, DPC_EINVAL, "reuse_scale: bad arguments");
     DPC_REQUIRE(E || ldw >= n0, DPC_EINVAL, "reuse_scale: weight rows too short");
@@ -140,10 +223,10 @@ void launch_reuse_scale(const float* E, const float* W1, int ldw, const float* b
     dim3 grid((unsigned)ceil_div(2 * n + 1, kThreads / 64), (unsigned)batch);
     if (E)
         hipLaunchKernelGGL(reuse_scale_kernel<false>, grid, dim3(kThreads), 0, s, E, (const float*)nullptr, 0, (const float*)nullptr,
-                           lambda, mu, nu, batch, n, n0, ldE, Rr);
+                           lambda, mu, nu, batch, n, n0, ldE, Rr, mod);
     else
         hipLaunchKernelGGL(reuse_scale_kernel<true>, grid, dim3(kThreads), 0, s, (const float*)nullptr, W1, ldw, bias, lambda, mu,
-                           nu, batch, n, n0, ldE, Rr);
+                           nu, batch, n, n0, ldE, Rr, mod);
     DPC_HIP(hipGetLastError());
 }
 
@@ -175,6 +258,38 @@ void launch_reuse_gather(const float* Rr, int n, int ldE, const ConvGeom& g, int
     DPC_REQUIRE(((uintptr_t)Rr % 16) == 0 && ((uintptr_t)G % 16) == 0, DPC_EINVAL, "reuse_gather: buffers must be 16-byte aligned");
     if (nz == 0) return;
     hipLaunchKernelGGL(reuse_gather_kernel, dim3((unsigned)nz, (unsigned)Kp), dim3(kThreads), 0, s, Rr, n, ldE, g, (long long)z0, G, Kp);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_reuse_gather_patch(const float* Rr, int n, const ReuseWindow& fi, const ReuseWindow& fo, const ConvGeom& g, int64_t z0,
+                               int64_t nz, float* G, hipStream_t s)
+{
+    const int Kp = 2 * g.kh * g.kw * g.Ci + 1;
+    DPC_REQUIRE(Rr && G && n == g.Ci * g.H * g.W && z0 >= 0 && nz >= 0 && nz <= 0x7fffffff && Kp <= 65535, DPC_EINVAL,
+                "reuse_gather_patch: bad arguments");
+    DPC_REQUIRE(fi.C0 == fo.C0 && fo.ph == (g.kh - 1) * fi.S + fi.ph && fo.pw == (g.kw - 1) * fi.S + fi.pw &&
+                    fi.ld > fi.ph * fi.pw * fi.C0 && fo.ld > fo.ph * fo.pw * fo.C0, DPC_EINVAL, "reuse_gather_patch: windows do not fit");
+    if (nz == 0) return;
+    const RWin a{fi.ph, fi.pw, fi.C0, fi.S, fi.P, fi.ld}, o{fo.ph, fo.pw, fo.C0, fo.S, fo.P, fo.ld};
+    hipLaunchKernelGGL(reuse_gather_patch_kernel, dim3((unsigned)nz, (unsigned)Kp), dim3(kThreads), 0, s, Rr, n, a, o, g, (long long)z0, G, Kp);
+    DPC_HIP(hipGetLastError());
+}
+
+void launch_reuse_scale_expand(const float* E, const float* core, int ld_core, const float* bias, int mod, const float* lambda,
+                               const float* mu, const float* nu, int batch, int n, const ReuseWindow& fi, int rows_W, int rows_C, int gh,
+                               int gw, int n0, int ldE, float* Rr, hipStream_t s)
+{
+    DPC_REQUIRE(lambda && mu && nu && Rr && (E || (core && bias && mod >= 1)) && n >= 1 && n0 == gh * gw * fi.C0 && ldE > n0 && batch >= 0 &&
+                    batch <= 65535 && n == (n / (rows_W * rows_C)) * rows_W * rows_C, DPC_EINVAL, "reuse_scale_expand: bad arguments");
+    if (batch == 0) return;
+    const RWin a{fi.ph, fi.pw, fi.C0, fi.S, fi.P, fi.ld};
+    dim3 grid((unsigned)(2 * n + 1), (unsigned)batch);
+    if (E)
+        hipLaunchKernelGGL(reuse_scale_expand_kernel<false>, grid, dim3(kThreads), 0, s, E, (const float*)nullptr, 0, (const float*)nullptr, 1,
+                           lambda, mu, nu, batch, n, a, rows_W, rows_C, gh, gw, n0, ldE, Rr);
+    else
+        hipLaunchKernelGGL(reuse_scale_expand_kernel<true>, grid, dim3(kThreads), 0, s, (const float*)nullptr, core, ld_core, bias, mod, lambda,
+                           mu, nu, batch, n, a, rows_W, rows_C, gh, gw, n0, ldE, Rr);
     DPC_HIP(hipGetLastError());
 }
 

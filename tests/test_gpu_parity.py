@@ -478,20 +478,27 @@ def test_reusecert_hand_example_and_errors():
                                              ((3, 8, 8), [(4, 4, 2, 1), (8, 4, 2, 1)], [10, 4]),
                                              ((1, 9, 7), [(4, 3, 1, 0), (6, 3, 2, 1), (8, 2, 1, 0)], [5]),
                                              ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4])])
-def test_reusecert_through_convolution_layers(shape, convs, fcs):
+@pytest.mark.parametrize("window", [1, 0])
+def test_reusecert_through_convolution_layers(shape, convs, fcs, window):
     """ReuseCert on convolutional networks: the replacement step through a convolution layer is the contraction of its
-    split kernel matrix with the gathered input-level rows of the ReLU layer below, one output position at a time."""
+    split kernel matrix with the gathered input-level rows of the ReLU layer below, one output position at a time.
+    window=1: the stored rows of the leading convolution layers cover their receptive field only (while that is smaller
+    than the input -- the four shapes mix both forms and every hand-over between them); window=0: rows over the whole input."""
     net = wl.random_small_conv(171, shape, convs, fcs)
     B = 3
     x, lo, hi = wl.random_box(172, net.n_in, B, 0.04)
     label = (np.arange(B) % fcs[-1]).astype(np.int32)
     b = _binding()
-    gnet = b.Network(net)
-    o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
-    g = gnet.certify(lo, hi, label, certifier="reusecert")
-    compare_with_oracle(net, lo, hi, g, o, label, relu_bounds=False)
-    compare_with_oracle(net, lo, hi, gnet.certify(lo, hi, None, certifier="reusecert"), o, None, relu_bounds=False)
-    gnet.close()
+    b.dpc_tuning_set("reuse_patch", window)
+    try:
+        gnet = b.Network(net)
+        o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
+        g = gnet.certify(lo, hi, label, certifier="reusecert")
+        compare_with_oracle(net, lo, hi, g, o, label, relu_bounds=False)
+        compare_with_oracle(net, lo, hi, gnet.certify(lo, hi, None, certifier="reusecert"), o, None, relu_bounds=False)
+        gnet.close()
+    finally:
+        b.dpc_tuning_set("reuse_patch", 1)
 
 
 @pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29])])
@@ -615,6 +622,20 @@ def _named_config(cfg, idx=None, eps_index=0, check_samples=200):
 @pytest.mark.parametrize("eps_index", [0, 1, 2])
 def test_cfg2_full_batch(eps_index):
     _named_config("cfg2", eps_index=eps_index)
+
+
+def test_cfg2_network_at_a_perturbation_that_certifies():
+    """The named settings certify nothing on untrained networks; at eps = 0.001 most inputs of the cfg2 network are
+    certified and some are not: both verdicts, identical to the oracle's, on the full batch."""
+    w = wl.make_workload("cfg2")
+    lo = np.clip(w.x - 0.001, 0.0, 1.0).astype(np.float32)
+    hi = np.clip(w.x + 0.001, 0.0, 1.0).astype(np.float32)
+    gnet, g, o = _run_both(w.net, lo, hi, w.label)
+    flipped, worst = compare_with_oracle(w.net, lo, hi, g, o, w.label, check_samples=100)
+    v, m = g.verdict()
+    assert np.array_equal(v, o.verdict) and 0 < int(v.sum()) < v.size
+    print("cfg2 @ eps 0.001: verified", int(v.sum()), "of", v.size, "worst err/tol", worst)
+    gnet.close()
 
 
 def test_cfg3_full_batch():
