@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdpcert.so")
-SOURCES = ["api.hip", "kernels_rows.hip", "contract.hip", "contract_split.hip", "chain.hip", "reuse.hip", "conv.hip", "conv_mfma.hip", "conv_tail.hip"]
+SOURCES = ["api.hip", "kernels_rows.hip", "contract.hip", "contract_split.hip", "chain.hip", "reuse.hip", "reuse_window.hip", "conv.hip", "conv_mfma.hip", "conv_tail.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fgpu-rdc-",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

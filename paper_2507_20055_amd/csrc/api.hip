@@ -44,6 +44,7 @@ void set_error(const char* fmt, ...)
 
 void set_contract_variant(int v);
 static int g_reuse_patch = 1;     // 1: ReuseCert keeps the stored bounds of convolution layers over their receptive fields only
+static int g_reuse_window = 1;    // 1: ReuseCert's steps above a convolutional front run as implicit contractions (no gathered operand)
 static int g_merge_final = 1;     // 1: output-layer bounds and margins share one traversal
 static uint64_t g_tuning_epoch = 1;  // bumped by every dpc_tuning_set: captured launch sequences are keyed on it
 void set_contract_remap(int v);
@@ -1208,6 +1209,14 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                 w = o;
             }
         }
+        // layers whose replacement step runs as an implicit contraction over the rows of the convolution layer two below
+        auto implicit_step = [&](int k) {
+            if (!reuse_cert || !g_reuse_window || k < 3 || k > nl || !net->in_spatial) return false;
+            const Layer& Lk = *net->layers[k - 1];
+            const Layer& Lb = *net->layers[k - 3];
+            if (Lk.kind == CONV) return reuse_window_covers(Lk.g.Ci);
+            return Lk.kind == AFFINE && Lb.kind == CONV && rwin[k - 2].ld != 0 && reuse_window_covers(Lb.g.Co) && !(k == nl && label);
+        };
         if (reuse_cert) {
             size_t nmax = 1;
             for (int i = 1; i <= nl; i += 2) nmax = std::max<size_t>(nmax, net->size_of(i));
@@ -1261,7 +1270,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             size_t gather_need = 0;
             for (int i = 3; i <= nl; i += 2) {
                 Layer& L = *net->layers[i - 1];
-                if (L.kind == CONV) {
+                if (L.kind == CONV && !implicit_step(i)) {
                     // a chunk of output positions at a time: at most 1 GiB of gathered rows, at least one position
                     const size_t per_pos = (size_t)(2 * L.g.kh * L.g.kw * L.g.Ci + 1) * (rwin[i].ld ? rwin[i].ld : ldE);
                     const size_t all = (size_t)B * L.g.Ho * L.g.Wo * per_pos;
@@ -1405,7 +1414,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     res->prof.other_launches++;
                     prof.begin(P_RELAX);
                     const ReuseWindow& w = rwin[i - 1];
-                    const bool next_window = w.ld && i < nl && rwin[i + 1].ld;
+                    const bool next_window = w.ld && i < nl && (rwin[i + 1].ld || implicit_step(i + 1));
                     if (next_window) {
                         // rows stay over the receptive field (the layer above is a convolution that keeps a window)
                         const int elems = w.ph * w.pw * w.C0;
@@ -1434,6 +1443,21 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     const ReuseWindow& wo = rwin[i];
                     const int ldR = wo.ld ? wo.ld : ldE;                                  // floats per stored row of this layer
                     const int ncol = wo.ld ? wo.ph * wo.pw * wo.C0 + 1 : n0 + 1;
+                    if (implicit_step(i)) {
+                        // rows of the ReLU layer below as they are (windows, or rows over the image), placed inside the frame of
+                        // each output position while they are contracted
+                        const ReuseWindow image{net->inH, net->inW, net->inC, 0, 0, ldE};
+                        const ReuseWindow& wi = rwin[i - 2].ld ? rwin[i - 2] : image;
+                        prof.begin(P_CONTRACT);
+                        res->prof.contract_flop += launch_reuse_window(L.dSplit[0].p, L.dSplit[1].p, L.ld_split, L.g.Co, Rr, L.n_in, wi, L.g,
+                                                                       wo.ld ? wo.ph : net->inH, wo.ld ? wo.pw : net->inW, ldR, wo.S, wo.P, !wo.ld, B,
+                                                                       E, s);
+                        prof.end();
+                        res->prof.contract_launches++;
+                        if (wo.ld) concretise_window_rows(E, wo, L.g, res->l[i], res->u[i]);
+                        else concretise_rows(E, L.n_out, res->l[i], res->u[i]);
+                        continue;
+                    }
                     const int64_t chunk = std::min<int64_t>({npos, (int64_t)(net->ws->gather.count / ((size_t)Kp * ldR)), 65535});
                     DPC_REQUIRE(chunk >= 1, DPC_ENOMEM, "ReuseCert: gather workspace too small");
                     for (int64_t z0 = 0; z0 < npos; z0 += chunk) {
@@ -1459,6 +1483,18 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                 }
                 const int K = 2 * L.n_in + 1;
                 const bool is_last = i == nl;
+                if (implicit_step(i)) {
+                    // first fully-connected layer above the convolutions: a convolution whose kernel covers the whole grid
+                    const Layer& cv = *net->layers[i - 3];
+                    const ConvGeom fc{cv.g.Co, cv.g.Ho, cv.g.Wo, L.n_out, cv.g.Ho, cv.g.Wo, 1, 0, 1, 1};
+                    prof.begin(P_CONTRACT);
+                    res->prof.contract_flop += launch_reuse_window(L.dSplit[0].p, L.dSplit[1].p, L.ld_split, L.n_out, Rr, L.n_in, rwin[i - 2], fc,
+                                                                   net->inH, net->inW, ldE, 0, 0, true, B, E, s);
+                    prof.end();
+                    res->prof.contract_launches++;
+                    concretise_rows(E, L.n_out, res->l[i], res->u[i]);
+                    continue;
+                }
                 if (!is_last || !label) {
                     // stored bounds of the layer: [W+ | W- | b] Rr[b] (lower), [W- | W+ | b] Rr[b] (upper)
                     prof.begin(P_CONTRACT);
@@ -1931,6 +1967,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         else if (strcmp(key, "conv_half_tiles") == 0) set_conv_half_tiles(value);
         else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
         else if (strcmp(key, "reuse_patch") == 0) g_reuse_patch = value;
+        else if (strcmp(key, "reuse_window") == 0) g_reuse_window = value;
         else if (strcmp(key, "chain") == 0) set_chain_mode(value);
         else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);
         else if (strcmp(key, "contract_split_wide") == 0) {

@@ -118,6 +118,16 @@ void launch_reuse_scale_expand(const float* E, const float* core, int ld_core, c
                                const float* mu, const float* nu, int batch, int n, const ReuseWindow& fi, int rows_W, int rows_C, int gh,
                                int gw, int n0, int ldE, float* Rr, hipStream_t s);
 
+// The replacement step through a layer above rows in window form (or dense rows: the window is the image, S = P = 0) as an
+// implicit contraction: E[side][(z, m)] = sum over taps and channels of the split weights A0 / A1 [M][ld_split] (lower / upper
+// side, columns [part][tap][ci], bias in column 2*taps*Ci) times the rows of Rr [batch][2n+1][fi.ld], each row placed at its
+// offset inside the output frame (fh x fw x C0 + constant, ld_o floats; frame_image: the whole image, else the window of the
+// output position with origin index * S_o - P_o).  g describes the taps (a fully-connected layer: kh x kw = its input grid,
+// one output position).  Returns the multiply-add count * 2.  reuse_window_covers: channel counts the kernel takes.
+bool reuse_window_covers(int Ci);
+double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M, const float* Rr, int n, const ReuseWindow& fi, const ConvGeom& g,
+                           int fh, int fw, int ld_o, int S_o, int P_o, bool frame_image, int batch, float* E, hipStream_t s);
+
 void set_conv_algo(int v);
 int conv_algo();
 void set_conv_half_tiles(int v);

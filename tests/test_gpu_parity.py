@@ -477,19 +477,23 @@ def test_reusecert_hand_example_and_errors():
 @pytest.mark.parametrize("shape,convs,fcs", [((2, 6, 6), [(3, 3, 1, 1)], [6, 3]),
                                              ((3, 8, 8), [(4, 4, 2, 1), (8, 4, 2, 1)], [10, 4]),
                                              ((1, 9, 7), [(4, 3, 1, 0), (6, 3, 2, 1), (8, 2, 1, 0)], [5]),
-                                             ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4])])
-@pytest.mark.parametrize("window", [1, 0])
-def test_reusecert_through_convolution_layers(shape, convs, fcs, window):
+                                             ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4]),
+                                             ((3, 12, 12), [(8, 3, 1, 1), (16, 4, 2, 1), (16, 3, 1, 1)], [10, 4])])
+@pytest.mark.parametrize("window,implicit", [(1, 1), (0, 1), (1, 0), (0, 0)])
+def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implicit):
     """ReuseCert on convolutional networks: the replacement step through a convolution layer is the contraction of its
-    split kernel matrix with the gathered input-level rows of the ReLU layer below, one output position at a time.
+    split kernel matrix with the input-level rows of the ReLU layer below, one output position at a time.
     window=1: the stored rows of the leading convolution layers cover their receptive field only (while that is smaller
-    than the input -- the four shapes mix both forms and every hand-over between them); window=0: rows over the whole input."""
+    than the input -- the shapes mix both forms and every hand-over between them); window=0: rows over the whole input.
+    implicit=1: layers whose channel count the implicit contraction takes (multiples of 8) read the rows in place, the
+    others gather them first; implicit=0: all gather."""
     net = wl.random_small_conv(171, shape, convs, fcs)
     B = 3
     x, lo, hi = wl.random_box(172, net.n_in, B, 0.04)
     label = (np.arange(B) % fcs[-1]).astype(np.int32)
     b = _binding()
     b.dpc_tuning_set("reuse_patch", window)
+    b.dpc_tuning_set("reuse_window", implicit)
     try:
         gnet = b.Network(net)
         o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
@@ -499,6 +503,7 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window):
         gnet.close()
     finally:
         b.dpc_tuning_set("reuse_patch", 1)
+        b.dpc_tuning_set("reuse_window", 1)
 
 
 @pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29])])
