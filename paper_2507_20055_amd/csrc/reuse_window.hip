@@ -20,6 +20,7 @@
 // frame rows are skipped by the whole workgroup, taps that miss a wavefront's 32 columns by that wavefront.
 // Summation order is fixed (taps in order, channels in order), so results are reproducible.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "conv.h"
@@ -49,8 +50,8 @@ struct RwArgs {
     int CK;                             // channels per staged chunk (divides Ci, multiple of 8)
 };
 
-template <int MT>
-__global__ __launch_bounds__(kRwThreads) void reuse_window_kernel(RwArgs a)
+template <int MT, int NTW>
+__global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
 {
     extern __shared__ float4 lds4[];
     float* sA = reinterpret_cast<float*>(lds4);                    // [32*MT][2*CK + 4]
@@ -61,18 +62,27 @@ __global__ __launch_bounds__(kRwThreads) void reuse_window_kernel(RwArgs a)
     const int elems_o = a.fh * a.fw * a.C0, elems_i = a.ph_i * a.pw_i * a.C0;
     const int astride = 2 * a.CK + 4;
     const int mbase = blockIdx.y * 32 * MT;
+    constexpr int kCols = kRwCols * NTW;                           // frame columns per workgroup
 
-    // this lane's frame column
-    const int col0 = blockIdx.x * kRwCols;
-    const int ncol = col0 + wave * 32 + l32;
-    const bool is_const = ncol == elems_o, in_frame = ncol < elems_o;
-    const int q = ncol / a.C0, qc = ncol - q * a.C0;
-    const int qy = q / a.fw, qx = q - qy * a.fw;
+    // this lane's frame columns: sub-tile nt of the wavefront is 32-column block nt*4 + wave of the workgroup's columns
+    const int col0 = blockIdx.x * kCols;
+    int ncol[NTW], qy[NTW], qx[NTW], qc[NTW];
+    bool is_const[NTW], in_frame[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+        ncol[nt] = col0 + (nt * 4 + wave) * 32 + l32;
+        is_const[nt] = ncol[nt] == elems_o;
+        in_frame[nt] = ncol[nt] < elems_o;
+        const int q = ncol[nt] / a.C0;
+        qc[nt] = ncol[nt] - q * a.C0;
+        qy[nt] = q / a.fw;
+        qx[nt] = q - qy[nt] * a.fw;
+    }
     const int fy0 = a.frame_image ? 0 : ho * a.S_o - a.P_o, fx0 = a.frame_image ? 0 : wo * a.S_o - a.P_o;
     // frame rows the workgroup's columns touch (the constant column takes part in every tap)
     const int rowlen = a.fw * a.C0;
-    const bool has_const = col0 <= elems_o && elems_o < col0 + kRwCols;
-    const int ty_lo = col0 / rowlen, ty_hi = (std::min(col0 + kRwCols, elems_o) - 1) / rowlen;
+    const bool has_const = col0 <= elems_o && elems_o < col0 + kCols;
+    const int ty_lo = col0 / rowlen, ty_hi = (std::min(col0 + kCols, elems_o) - 1) / rowlen;
     const bool has_coeff = col0 < elems_o;
 
     constexpr int kOutside = (int)0x80000000;
@@ -80,11 +90,13 @@ __global__ __launch_bounds__(kRwThreads) void reuse_window_kernel(RwArgs a)
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.Rr + (size_t)b * a.rr_block), 0, (int)(a.rr_block * 4), 0x00020000);
     const int part_off = kq * a.n * a.ld_i * 4;                    // bytes from an Lr row to the Ur row of the same neuron
 
-    floatx16 acc[MT];
+    floatx16 acc[NTW][MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mt][v] = 0.0f;
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.0f;
 
     for (int ky = 0; ky < a.kh; ++ky) {
         const int y = ho * a.stride - a.pad + ky;
@@ -97,74 +109,118 @@ __global__ __launch_bounds__(kRwThreads) void reuse_window_kernel(RwArgs a)
             const int ox = x * a.S_i - a.P_i - fx0;
             const int t = ky * a.kw + kx;
             const int nrow0 = (y * a.W + x) * a.Ci;                // first of the neuron rows of this tap
-            const int py = qy - oy, px = qx - ox;
-            const bool valid = in_frame && py >= 0 && py < a.ph_i && px >= 0 && px < a.pw_i;
-            const int voff = valid ? ((py * a.pw_i + px) * a.C0 + qc) * 4 + part_off : is_const ? elems_i * 4 + part_off : kOutside;
-            const bool wave_live = __ballot(valid || is_const) != 0ull;
+            int voff[NTW];
+            bool any_live = false;
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                const int py = qy[nt] - oy, px = qx[nt] - ox;
+                const bool valid = in_frame[nt] && py >= 0 && py < a.ph_i && px >= 0 && px < a.pw_i;
+                voff[nt] = valid ? ((py * a.pw_i + px) * a.C0 + qc[nt]) * 4 + part_off : is_const[nt] ? elems_i * 4 + part_off : kOutside;
+                any_live |= __ballot(valid || is_const[nt]) != 0ull;
+            }
             for (int c0 = 0; c0 < a.Ci; c0 += a.CK) {
-                float bcur[8], bnxt[8];
-                auto load_b = [&](float (&bb)[8], int s0) __attribute__((always_inline)) {
+                float bcur[NTW][8], bnxt[NTW][8];
+                auto load_b = [&](float (&bb)[8], int nt, int s0) __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
-                        bb[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(bres, voff, (nrow0 + c0 + s0 + u) * a.ld_i * 4, 0));
+                        bb[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(bres, voff[nt], (nrow0 + c0 + s0 + u) * a.ld_i * 4, 0));
                 };
-                if (wave_live) load_b(bcur, 0);                    // in flight while the A chunk is staged
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt)
+                    if (any_live) load_b(bcur[nt], nt, 0);         // in flight while the A chunk is staged (a dead sub-tile reads zeros)
                 __syncthreads();                                   // every wavefront is done with the previous chunk
                 {
+                    // several 16-byte loads in flight per thread before the first LDS write
+                    constexpr int kU = 4;
                     const int q4n = a.CK >> 1;                     // 16-byte pieces per row: 2 parts x CK / 4
-                    for (int idx = tid; idx < 32 * MT * q4n; idx += kRwThreads) {
-                        const int row = idx / q4n, q4 = idx - row * q4n;
-                        const int part = q4 >= (a.CK >> 2), c4 = q4 - part * (a.CK >> 2);
-                        const int m = mbase + row;
-                        const int side = m >= a.M, r = m - side * a.M;
-                        vf4 v = {0.f, 0.f, 0.f, 0.f};
-                        if (m < 2 * a.M)
-                            v = *reinterpret_cast<const vf4*>((side ? a.A1 : a.A0) + (size_t)r * a.ld_split + part * a.kk + t * a.Ci + c0 + c4 * 4);
-                        *reinterpret_cast<vf4*>(sA + row * astride + part * a.CK + c4 * 4) = v;
+                    const int total = 32 * MT * q4n;
+                    for (int idx0 = tid; idx0 < total; idx0 += kRwThreads * kU) {
+                        vf4 v[kU];
+                        int dsto[kU];
+#pragma unroll
+                        for (int u = 0; u < kU; ++u) {
+                            const int idx = idx0 + u * kRwThreads;
+                            const int row = idx / q4n, q4 = idx - row * q4n;
+                            const int part = q4 >= (a.CK >> 2), c4 = q4 - part * (a.CK >> 2);
+                            const int m = mbase + row;
+                            const int side = m >= a.M, r = m - side * a.M;
+                            v[u] = vf4{0.f, 0.f, 0.f, 0.f};
+                            if (idx < total && m < 2 * a.M)
+                                v[u] = *reinterpret_cast<const vf4*>((side ? a.A1 : a.A0) + (size_t)r * a.ld_split + part * a.kk + t * a.Ci + c0 + c4 * 4);
+                            dsto[u] = idx < total ? row * astride + part * a.CK + c4 * 4 : -1;
+                        }
+#pragma unroll
+                        for (int u = 0; u < kU; ++u)
+                            if (dsto[u] >= 0) *reinterpret_cast<vf4*>(sA + dsto[u]) = v[u];
                     }
                 }
                 __syncthreads();
-                if (!wave_live) continue;
+                if (!any_live) continue;
                 const float* arow = sA + l32 * astride + kq * a.CK;
-                for (int s0 = 0; s0 < a.CK; s0 += 8) {
-                    if (s0 + 8 < a.CK) load_b(bnxt, s0 + 8);
+                // the sub-tiles that are live share the A reads; one code path per combination so that the loop has no branches
+                auto run = [&](auto mask) __attribute__((always_inline)) {
+                    constexpr int MASK = decltype(mask)::value;
+                    for (int s0 = 0; s0 < a.CK; s0 += 8) {
+                        if (s0 + 8 < a.CK) {
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        vf4 av[MT];
+                            for (int nt = 0; nt < NTW; ++nt)
+                                if (MASK >> nt & 1) load_b(bnxt[nt], nt, s0 + 8);
+                        }
 #pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) av[mt] = *reinterpret_cast<const vf4*>(arow + mt * 32 * astride + s0 + 4 * h);
+                        for (int h = 0; h < 2; ++h) {
+                            vf4 av[MT];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
+                            for (int mt = 0; mt < MT; ++mt) av[mt] = *reinterpret_cast<const vf4*>(arow + mt * 32 * astride + s0 + 4 * h);
 #pragma unroll
-                            for (int mt = 0; mt < MT; ++mt)
-                                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt][u], bcur[4 * h + u], acc[mt], 0, 0, 0);
+                            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                                for (int nt = 0; nt < NTW; ++nt)
+                                    if (MASK >> nt & 1) {
+#pragma unroll
+                                        for (int mt = 0; mt < MT; ++mt)
+                                            acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt][u], bcur[nt][4 * h + u], acc[nt][mt], 0, 0, 0);
+                                    }
+                        }
+#pragma unroll
+                        for (int nt = 0; nt < NTW; ++nt)
+                            if (MASK >> nt & 1) {
+#pragma unroll
+                                for (int u = 0; u < 8; ++u) bcur[nt][u] = bnxt[nt][u];
+                            }
                     }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) bcur[u] = bnxt[u];
-                }
+                };
+                // (a wavefront with one live sub-tile still runs both: the dead one reads zeros.  Separate code paths per
+                // combination cost more registers than the file has at two workgroups per compute unit.)
+                run(std::integral_constant<int, (1 << NTW) - 1>{});
             }
         }
     }
 
     // ---- epilogue: accumulator register 4*i + j of a lane is row 8*i + 4*kq + j, column l32 ----
-    if (ncol >= a.ld_o) return;
-    float* Eb = a.E + ((size_t)z * a.M) * a.ld_o + ncol;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int nt = 0; nt < NTW; ++nt) {
+        if (ncol[nt] >= a.ld_o) continue;
+        float* Eb = a.E + ((size_t)z * a.M) * a.ld_o + ncol[nt];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int m = mbase + mt * 32 + 8 * i + 4 * kq + j;
-                if (m >= 2 * a.M) continue;
-                const int side = m >= a.M, r = m - side * a.M;
-                float v = acc[mt][4 * i + j];
-                if (is_const) v += (side ? a.A1 : a.A0)[(size_t)r * a.ld_split + 2 * a.kk];      // the unit row carries the bias
-                Eb[(size_t)side * a.side_stride + (size_t)r * a.ld_o] = v;
-            }
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = mbase + mt * 32 + 8 * i + 4 * kq + j;
+                    if (m >= 2 * a.M) continue;
+                    const int side = m >= a.M, r = m - side * a.M;
+                    float v = acc[nt][mt][4 * i + j];
+                    if (is_const[nt]) v += (side ? a.A1 : a.A0)[(size_t)r * a.ld_split + 2 * a.kk];      // the unit row carries the bias
+                    Eb[(size_t)side * a.side_stride + (size_t)r * a.ld_o] = v;
+                }
+    }
 }
 
 }  // namespace
+
+static int g_rw_ntw = 0;          // tuning: 32-column sub-tiles per wavefront (0: by shape)
+void set_reuse_window_ntw(int v) { g_rw_ntw = v; }
 
 bool reuse_window_covers(int Ci) { return Ci >= 8 && Ci % 8 == 0; }
 
@@ -190,18 +246,24 @@ double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M
     a.CK = g.Ci <= 64 ? g.Ci : g.Ci % 64 == 0 ? 64 : g.Ci % 32 == 0 ? 32 : g.Ci % 16 == 0 ? 16 : 8;
     const int rows = 2 * M;
     const int MT = rows > 64 ? 4 : rows > 32 ? 2 : 1;
+    // (two 32-column sub-tiles per wavefront measured slower at every shape tried: a wavefront can then no longer skip a tap
+    // that misses one of its blocks, and the staging of A it saves was not the limit)
+    const int NTW = MT == 1 ? 1 : (g_rw_ntw == 1 || g_rw_ntw == 2) ? g_rw_ntw : 1;
     const size_t lds = (size_t)32 * MT * (2 * a.CK + 4) * 4;
-    const unsigned gx = (unsigned)ceil_div(ld_o, kRwCols), gy = (unsigned)ceil_div(rows, 32 * MT);
+    const unsigned gx = (unsigned)ceil_div(ld_o, kRwCols * NTW), gy = (unsigned)ceil_div(rows, 32 * MT);
     constexpr int kMaxLds = 32 * 4 * (2 * 64 + 4) * 4;
-    ensure_dynamic_lds(reinterpret_cast<const void*>(&reuse_window_kernel<4>), kMaxLds);
-    ensure_dynamic_lds(reinterpret_cast<const void*>(&reuse_window_kernel<2>), kMaxLds);
-    ensure_dynamic_lds(reinterpret_cast<const void*>(&reuse_window_kernel<1>), kMaxLds);
+    auto go = [&](auto kern, const dim3& grid) {
+        ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kMaxLds);
+        hipLaunchKernelGGL(kern, grid, dim3(kRwThreads), lds, s, a);
+    };
     for (int64_t z0 = 0; z0 < nz; z0 += 65535) {
         a.z0 = z0;
         const dim3 grid(gx, gy, (unsigned)std::min<int64_t>(65535, nz - z0));
-        if (MT == 4) hipLaunchKernelGGL(reuse_window_kernel<4>, grid, dim3(kRwThreads), lds, s, a);
-        else if (MT == 2) hipLaunchKernelGGL(reuse_window_kernel<2>, grid, dim3(kRwThreads), lds, s, a);
-        else hipLaunchKernelGGL(reuse_window_kernel<1>, grid, dim3(kRwThreads), lds, s, a);
+        if (MT == 4 && NTW == 2) go(&reuse_window_kernel<4, 2>, grid);
+        else if (MT == 4) go(&reuse_window_kernel<4, 1>, grid);
+        else if (MT == 2 && NTW == 2) go(&reuse_window_kernel<2, 2>, grid);
+        else if (MT == 2) go(&reuse_window_kernel<2, 1>, grid);
+        else go(&reuse_window_kernel<1, 1>, grid);
         DPC_HIP(hipGetLastError());
     }
     // multiply-adds of the taps that exist, over whole windows (what the step computes; skipped lanes do not count)
