@@ -1968,7 +1968,7 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
         else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
         else if (strcmp(key, "reuse_patch") == 0) g_reuse_patch = value;
         else if (strcmp(key, "reuse_window") == 0) g_reuse_window = value;
-        else if (strcmp(key, "reuse_window_ntw") == 0) set_reuse_window_ntw(value);
+        else if (strcmp(key, "reuse_window_ck") == 0) set_reuse_window_ck(value);
         else if (strcmp(key, "chain") == 0) set_chain_mode(value);
         else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);
         else if (strcmp(key, "contract_split_wide") == 0) {

@@ -33,7 +33,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float vf4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRwThreads = 256;
-constexpr int kRwCols = 128;            // frame columns per workgroup
 
 struct RwArgs {
     const float* A0; const float* A1;   // split weights of the lower / upper side [M][ld_split]
@@ -48,9 +47,11 @@ struct RwArgs {
     long long side_stride;              // floats between the two sides of E
     long long z0;                       // first output position (input-major) of this launch
     int CK;                             // channels per staged chunk (divides Ci, multiple of 8)
+    int n_xt;                           // 32-float blocks per frame row
+    int flat;                           // tiles over the flattened frame instead of over frame rows
 };
 
-template <int MT, int NTW>
+template <int MT>
 __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
 {
     extern __shared__ float4 lds4[];
@@ -62,72 +63,87 @@ __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
     const int elems_o = a.fh * a.fw * a.C0, elems_i = a.ph_i * a.pw_i * a.C0;
     const int astride = 2 * a.CK + 4;
     const int mbase = blockIdx.y * 32 * MT;
-    constexpr int kCols = kRwCols * NTW;                           // frame columns per workgroup
 
-    // this lane's frame columns: sub-tile nt of the wavefront is 32-column block nt*4 + wave of the workgroup's columns
-    const int col0 = blockIdx.x * kCols;
-    int ncol[NTW], qy[NTW], qx[NTW], qc[NTW];
-    bool is_const[NTW], in_frame[NTW];
-#pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-        ncol[nt] = col0 + (nt * 4 + wave) * 32 + l32;
-        is_const[nt] = ncol[nt] == elems_o;
-        in_frame[nt] = ncol[nt] < elems_o;
-        const int q = ncol[nt] / a.C0;
-        qc[nt] = ncol[nt] - q * a.C0;
-        qy[nt] = q / a.fw;
-        qx[nt] = q - qy[nt] * a.fw;
+    // The workgroup's tile, one 32-column block per wavefront.
+    // Row tiles: block xt of four consecutive frame rows, so the four wavefronts meet the same taps (a tap's window covers
+    // the same columns in every row) and finish together; the constant column counts as one more frame row with a single
+    // column, the rest of that row's block being the padding of the stored row.
+    // Flat tiles (frames whose rows would leave many lanes of a 32-column block empty): 128 consecutive columns of the
+    // flattened frame, constant and padding included; the wavefronts then differ in the taps they can skip.
+    const int rowlen = a.fw * a.C0;
+    int qy, qx, qc, ncol, ty_lo, ty_hi, tx_lo, tx_hi;
+    bool is_const, in_frame, wg_const, stores;
+    if (a.flat) {
+        const int col0 = blockIdx.x * 128;
+        ncol = col0 + wave * 32 + l32;
+        is_const = ncol == elems_o;
+        in_frame = ncol < elems_o;
+        const int q = ncol / a.C0;
+        qc = ncol - q * a.C0;
+        qy = q / a.fw;
+        qx = q - qy * a.fw;
+        wg_const = col0 <= elems_o && elems_o < col0 + 128;
+        ty_lo = col0 / rowlen;
+        ty_hi = col0 < elems_o ? (std::min(col0 + 128, elems_o) - 1) / rowlen : -1;
+        tx_lo = 0;
+        tx_hi = rowlen - 1;
+        stores = ncol < a.ld_o;
+    } else {
+        const int xt = blockIdx.x % a.n_xt, rg = blockIdx.x / a.n_xt;
+        const int xcol = xt * 32 + l32;
+        qy = rg * 4 + wave;                                        // frame row of this wavefront (fh: the constant's row)
+        const bool const_row = qy == a.fh;
+        is_const = const_row && xcol == 0;
+        in_frame = qy < a.fh && xcol < rowlen;
+        qx = xcol / a.C0;
+        qc = xcol - qx * a.C0;
+        wg_const = rg * 4 <= a.fh && a.fh < rg * 4 + 4 && xt == 0;
+        ty_lo = rg * 4;
+        ty_hi = std::min(rg * 4 + 3, a.fh - 1);
+        tx_lo = xt * 32;
+        tx_hi = std::min(xt * 32 + 31, rowlen - 1);
+        ncol = const_row ? elems_o + l32 : qy * rowlen + xcol;
+        stores = in_frame || (const_row && xt == 0 && ncol < a.ld_o);
     }
     const int fy0 = a.frame_image ? 0 : ho * a.S_o - a.P_o, fx0 = a.frame_image ? 0 : wo * a.S_o - a.P_o;
-    // frame rows the workgroup's columns touch (the constant column takes part in every tap)
-    const int rowlen = a.fw * a.C0;
-    const bool has_const = col0 <= elems_o && elems_o < col0 + kCols;
-    const int ty_lo = col0 / rowlen, ty_hi = (std::min(col0 + kCols, elems_o) - 1) / rowlen;
-    const bool has_coeff = col0 < elems_o;
 
     constexpr int kOutside = (int)0x80000000;
     const __amdgpu_buffer_rsrc_t bres =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.Rr + (size_t)b * a.rr_block), 0, (int)(a.rr_block * 4), 0x00020000);
     const int part_off = kq * a.n * a.ld_i * 4;                    // bytes from an Lr row to the Ur row of the same neuron
 
-    floatx16 acc[NTW][MT];
+    floatx16 acc[MT];
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[mt][v] = 0.0f;
 
     for (int ky = 0; ky < a.kh; ++ky) {
         const int y = ho * a.stride - a.pad + ky;
         if (y < 0 || y >= a.H) continue;                           // zero padding: no neuron
         const int oy = y * a.S_i - a.P_i - fy0;                    // frame row of the window's first row
-        if (!has_const && (!has_coeff || oy > ty_hi || oy + a.ph_i <= ty_lo)) continue;
+        if (!wg_const && (ty_hi < ty_lo || oy > ty_hi || oy + a.ph_i <= ty_lo)) continue;
+        const int py = qy - oy;
+        const bool row_ok = py >= 0 && py < a.ph_i;
         for (int kx = 0; kx < a.kw; ++kx) {
             const int x = wo * a.stride - a.pad + kx;
             if (x < 0 || x >= a.W) continue;
             const int ox = x * a.S_i - a.P_i - fx0;
+            if (!wg_const && (tx_hi < tx_lo || ox * a.C0 > tx_hi || (ox + a.pw_i) * a.C0 <= tx_lo)) continue;
             const int t = ky * a.kw + kx;
             const int nrow0 = (y * a.W + x) * a.Ci;                // first of the neuron rows of this tap
-            int voff[NTW];
-            bool any_live = false;
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                const int py = qy[nt] - oy, px = qx[nt] - ox;
-                const bool valid = in_frame[nt] && py >= 0 && py < a.ph_i && px >= 0 && px < a.pw_i;
-                voff[nt] = valid ? ((py * a.pw_i + px) * a.C0 + qc[nt]) * 4 + part_off : is_const[nt] ? elems_i * 4 + part_off : kOutside;
-                any_live |= __ballot(valid || is_const[nt]) != 0ull;
-            }
+            const int px = qx - ox;
+            const bool valid = in_frame && row_ok && px >= 0 && px < a.pw_i;
+            const int voff = valid ? ((py * a.pw_i + px) * a.C0 + qc) * 4 + part_off : is_const ? elems_i * 4 + part_off : kOutside;
+            const bool wave_live = __ballot(valid || is_const) != 0ull;
             for (int c0 = 0; c0 < a.Ci; c0 += a.CK) {
-                float bcur[NTW][8], bnxt[NTW][8];
-                auto load_b = [&](float (&bb)[8], int nt, int s0) __attribute__((always_inline)) {
+                float bcur[8], bnxt[8];
+                auto load_b = [&](float (&bb)[8], int s0) __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
-                        bb[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(bres, voff[nt], (nrow0 + c0 + s0 + u) * a.ld_i * 4, 0));
+                        bb[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(bres, voff, (nrow0 + c0 + s0 + u) * a.ld_i * 4, 0));
                 };
-#pragma unroll
-                for (int nt = 0; nt < NTW; ++nt)
-                    if (any_live) load_b(bcur[nt], nt, 0);         // in flight while the A chunk is staged (a dead sub-tile reads zeros)
+                if (wave_live) load_b(bcur, 0);                    // in flight while the A chunk is staged
                 __syncthreads();                                   // every wavefront is done with the previous chunk
                 {
                     // several 16-byte loads in flight per thread before the first LDS write
@@ -155,72 +171,53 @@ __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
                     }
                 }
                 __syncthreads();
-                if (!any_live) continue;
+                if (!wave_live) continue;
                 const float* arow = sA + l32 * astride + kq * a.CK;
-                // the sub-tiles that are live share the A reads; one code path per combination so that the loop has no branches
-                auto run = [&](auto mask) __attribute__((always_inline)) {
-                    constexpr int MASK = decltype(mask)::value;
-                    for (int s0 = 0; s0 < a.CK; s0 += 8) {
-                        if (s0 + 8 < a.CK) {
+                for (int s0 = 0; s0 < a.CK; s0 += 8) {
+                    if (s0 + 8 < a.CK) load_b(bnxt, s0 + 8);
 #pragma unroll
-                            for (int nt = 0; nt < NTW; ++nt)
-                                if (MASK >> nt & 1) load_b(bnxt[nt], nt, s0 + 8);
-                        }
+                    for (int h = 0; h < 2; ++h) {
+                        vf4 av[MT];
 #pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            vf4 av[MT];
+                        for (int mt = 0; mt < MT; ++mt) av[mt] = *reinterpret_cast<const vf4*>(arow + mt * 32 * astride + s0 + 4 * h);
 #pragma unroll
-                            for (int mt = 0; mt < MT; ++mt) av[mt] = *reinterpret_cast<const vf4*>(arow + mt * 32 * astride + s0 + 4 * h);
+                        for (int u = 0; u < 4; ++u)
 #pragma unroll
-                            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                                for (int nt = 0; nt < NTW; ++nt)
-                                    if (MASK >> nt & 1) {
-#pragma unroll
-                                        for (int mt = 0; mt < MT; ++mt)
-                                            acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt][u], bcur[nt][4 * h + u], acc[nt][mt], 0, 0, 0);
-                                    }
-                        }
-#pragma unroll
-                        for (int nt = 0; nt < NTW; ++nt)
-                            if (MASK >> nt & 1) {
-#pragma unroll
-                                for (int u = 0; u < 8; ++u) bcur[nt][u] = bnxt[nt][u];
-                            }
+                            for (int mt = 0; mt < MT; ++mt)
+                                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mt][u], bcur[4 * h + u], acc[mt], 0, 0, 0);
                     }
-                };
-                // (a wavefront with one live sub-tile still runs both: the dead one reads zeros.  Separate code paths per
-                // combination cost more registers than the file has at two workgroups per compute unit.)
-                run(std::integral_constant<int, (1 << NTW) - 1>{});
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) bcur[u] = bnxt[u];
+                }
             }
         }
     }
 
     // ---- epilogue: accumulator register 4*i + j of a lane is row 8*i + 4*kq + j, column l32 ----
+    // (lanes on the padding of the stored rows hold zeros)
+    if (!stores) return;
+    float* Eb = a.E + ((size_t)z * a.M) * a.ld_o + ncol;
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-        if (ncol[nt] >= a.ld_o) continue;
-        float* Eb = a.E + ((size_t)z * a.M) * a.ld_o + ncol[nt];
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int m = mbase + mt * 32 + 8 * i + 4 * kq + j;
-                    if (m >= 2 * a.M) continue;
-                    const int side = m >= a.M, r = m - side * a.M;
-                    float v = acc[nt][mt][4 * i + j];
-                    if (is_const[nt]) v += (side ? a.A1 : a.A0)[(size_t)r * a.ld_split + 2 * a.kk];      // the unit row carries the bias
-                    Eb[(size_t)side * a.side_stride + (size_t)r * a.ld_o] = v;
-                }
-    }
+            for (int j = 0; j < 4; ++j) {
+                const int m = mbase + mt * 32 + 8 * i + 4 * kq + j;
+                if (m >= 2 * a.M) continue;
+                const int side = m >= a.M, r = m - side * a.M;
+                float v = acc[mt][4 * i + j];
+                if (is_const) v += (side ? a.A1 : a.A0)[(size_t)r * a.ld_split + 2 * a.kk];      // the unit row carries the bias
+                Eb[(size_t)side * a.side_stride + (size_t)r * a.ld_o] = v;
+            }
 }
 
 }  // namespace
 
-static int g_rw_ntw = 0;          // tuning: 32-column sub-tiles per wavefront (0: by shape)
-void set_reuse_window_ntw(int v) { g_rw_ntw = v; }
+static int g_rw_ck = 0;           // tuning: channels per staged chunk (0: by shape)
+static int g_rw_flat = -1;        // tuning: tile shape (-1: by shape, 0: row tiles, 1: flat tiles)
+void set_reuse_window_ck(int v) { if (v >= 100) g_rw_flat = v - 101; else g_rw_ck = v; }
+
 
 bool reuse_window_covers(int Ci) { return Ci >= 8 && Ci % 8 == 0; }
 
@@ -243,14 +240,15 @@ double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M
     a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad; a.H = g.H; a.W = g.W; a.Wo = g.Wo; a.npos = (int)npos;
     a.fh = fh; a.fw = fw; a.ld_o = ld_o; a.S_o = S_o; a.P_o = P_o; a.frame_image = frame_image ? 1 : 0;
     a.E = E; a.side_stride = nz * M * ld_o;
-    a.CK = g.Ci <= 64 ? g.Ci : g.Ci % 64 == 0 ? 64 : g.Ci % 32 == 0 ? 32 : g.Ci % 16 == 0 ? 16 : 8;
+    a.CK = (g_rw_ck >= 8 && g_rw_ck <= 64 && g_rw_ck % 8 == 0 && g.Ci % g_rw_ck == 0) ? g_rw_ck : g.Ci <= 32 ? g.Ci : g.Ci % 32 == 0 ? 32 : g.Ci % 16 == 0 ? 16 : 8;
     const int rows = 2 * M;
     const int MT = rows > 64 ? 4 : rows > 32 ? 2 : 1;
-    // (two 32-column sub-tiles per wavefront measured slower at every shape tried: a wavefront can then no longer skip a tap
-    // that misses one of its blocks, and the staging of A it saves was not the limit)
-    const int NTW = MT == 1 ? 1 : (g_rw_ntw == 1 || g_rw_ntw == 2) ? g_rw_ntw : 1;
+    a.n_xt = ceil_div(fw * fi.C0, 32);
+    const int n_rg = fh / 4 + 1;                                  // row groups: the constant's row fh is one of the rows
+    // row tiles when at least 9 of 10 lanes of a row's blocks hold a column
+    a.flat = g_rw_flat >= 0 ? g_rw_flat : (fw * fi.C0 * 10 < a.n_xt * 32 * 9);
     const size_t lds = (size_t)32 * MT * (2 * a.CK + 4) * 4;
-    const unsigned gx = (unsigned)ceil_div(ld_o, kRwCols * NTW), gy = (unsigned)ceil_div(rows, 32 * MT);
+    const unsigned gx = a.flat ? (unsigned)ceil_div(ld_o, 128) : (unsigned)(a.n_xt * n_rg), gy = (unsigned)ceil_div(rows, 32 * MT);
     constexpr int kMaxLds = 32 * 4 * (2 * 64 + 4) * 4;
     auto go = [&](auto kern, const dim3& grid) {
         ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kMaxLds);
@@ -259,11 +257,9 @@ double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M
     for (int64_t z0 = 0; z0 < nz; z0 += 65535) {
         a.z0 = z0;
         const dim3 grid(gx, gy, (unsigned)std::min<int64_t>(65535, nz - z0));
-        if (MT == 4 && NTW == 2) go(&reuse_window_kernel<4, 2>, grid);
-        else if (MT == 4) go(&reuse_window_kernel<4, 1>, grid);
-        else if (MT == 2 && NTW == 2) go(&reuse_window_kernel<2, 2>, grid);
-        else if (MT == 2) go(&reuse_window_kernel<2, 1>, grid);
-        else go(&reuse_window_kernel<1, 1>, grid);
+        if (MT == 4) go(&reuse_window_kernel<4>, grid);
+        else if (MT == 2) go(&reuse_window_kernel<2>, grid);
+        else go(&reuse_window_kernel<1>, grid);
         DPC_HIP(hipGetLastError());
     }
     // multiply-adds of the taps that exist, over whole windows (what the step computes; skipped lanes do not count)

@@ -479,15 +479,16 @@ def test_reusecert_hand_example_and_errors():
                                              ((1, 9, 7), [(4, 3, 1, 0), (6, 3, 2, 1), (8, 2, 1, 0)], [5]),
                                              ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4]),
                                              ((3, 12, 12), [(8, 3, 1, 1), (16, 4, 2, 1), (16, 3, 1, 1)], [10, 4])])
-@pytest.mark.parametrize("window,implicit,ntw", [(1, 1, 0), (0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 1, 2), (0, 1, 2)])
-def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implicit, ntw):
+@pytest.mark.parametrize("window,implicit,ck", [(1, 1, 0), (0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 1, 8), (0, 1, 8), (1, 1, 101), (0, 1, 101), (1, 1, 102), (0, 1, 102)])
+def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implicit, ck):
     """ReuseCert on convolutional networks: the replacement step through a convolution layer is the contraction of its
     split kernel matrix with the input-level rows of the ReLU layer below, one output position at a time.
     window=1: the stored rows of the leading convolution layers cover their receptive field only (while that is smaller
     than the input -- the shapes mix both forms and every hand-over between them); window=0: rows over the whole input.
     implicit=1: layers whose channel count the implicit contraction takes (multiples of 8) read the rows in place, the
-    others gather them first; implicit=0: all gather.  ntw=2: the implicit contraction's wide tile (two 32-column blocks per
-    wavefront), which these small frames would not pick by themselves."""
+    others gather them first; implicit=0: all gather.  ck=8: the implicit contraction stages 8 channels at a time, so that layers with 16
+    channels take more than one chunk per tap; ck=101 / 102: its tiles run over frame rows / over the flattened frame at
+    every layer (by itself it picks one of the two per layer)."""
     net = wl.random_small_conv(171, shape, convs, fcs)
     B = 3
     x, lo, hi = wl.random_box(172, net.n_in, B, 0.04)
@@ -495,7 +496,7 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implici
     b = _binding()
     b.dpc_tuning_set("reuse_patch", window)
     b.dpc_tuning_set("reuse_window", implicit)
-    b.dpc_tuning_set("reuse_window_ntw", ntw)
+    b.dpc_tuning_set("reuse_window_ck", ck)
     try:
         gnet = b.Network(net)
         o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
@@ -506,7 +507,8 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implici
     finally:
         b.dpc_tuning_set("reuse_patch", 1)
         b.dpc_tuning_set("reuse_window", 1)
-        b.dpc_tuning_set("reuse_window_ntw", 0)
+        b.dpc_tuning_set("reuse_window_ck", 0)
+        b.dpc_tuning_set("reuse_window_ck", 100)
 
 
 @pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29])])
