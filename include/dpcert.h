@@ -296,7 +296,9 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
  * input channels (1, the default, uses 16 x 16 tiles there);
  * "merge_final" = 0 bounds the output layer and the margins in two traversals instead
  * of one; "contract_remap", "rows_per_wave", "rows_stream", "stream_wgs_per_cu" select launch shapes of the contraction and
- * row kernels.  Results do not depend on any of them beyond rounding order.
+ * row kernels; "reuse_patch" = 0 keeps ReuseCert's stored bounds of convolution layers as rows over the whole input,
+ * "reuse_window" = 0 gathers the rows a convolution layer reads before contracting them, "reuse_window_ck" (8..64)
+ * and "reuse_window_tiles" (0 rows, 1 flat) select the chunk and tile shape of the implicit contraction.  Results do not depend on any of them beyond rounding order.
  * Split-precision experiment (the exception to that sentence): "contract_split" = 2 or 3 (default 0) runs
  * the contractions through fully-connected layers on the bf16 matrix units with both operands written as
  * sums of 2 or 3 bf16 terms and the 3 or 6 largest partial products accumulated in fp32 ("bf16x3": about
@@ -304,6 +306,16 @@ dpc_status dpc_op_conv_transpose(const float* in, int64_t M, int32_t ld_in, int3
  * convolutions stay on the fp32 kernels; the resident traversal kernel is not used.  "contract_split_wide"
  * (-1 by shape, 0, 1) selects its 128 x 256 tile. */
 dpc_status dpc_tuning_set(const char* key, int32_t value);
+
+/* The same knobs for one network: calls on `net` (and reads of its results) use `value` for `key` whatever the
+ * process-wide value is; DPC_TUNING_DEFAULT as the value removes the override.  The process-wide values are read
+ * atomically and the values in force for a call are fixed when it starts, so dpc_tuning_set on one thread does not
+ * disturb a call running on another, and calls on different networks from different threads do not share knob
+ * state.  (Calls on one network still must not overlap: they share its workspace.)  For callers that cannot
+ * serialise process-wide settings: services that certify several networks from several threads.
+ * DPC_EINVAL for an unknown key. */
+#define DPC_TUNING_DEFAULT INT32_MIN
+dpc_status dpc_network_tuning_set(dpc_network* net, const char* key, int32_t value);
 
 /* Text of the last error raised on the calling thread ("" if none). */
 const char* dpc_last_error(void);

@@ -69,6 +69,7 @@ EXPORTS = {
     "dpc_op_conv_transpose": [c_vp, c_i64, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32, c_vp,
                               c_vp, c_i32, c_i32, c_i32, c_vp],
     "dpc_tuning_set": [ctypes.c_char_p, c_i32],
+    "dpc_network_tuning_set": [c_vp, ctypes.c_char_p, c_i32],
 }
 for _name, _args in EXPORTS.items():
     _f = getattr(_lib, _name)
@@ -99,6 +100,9 @@ def dpc_version() -> str:
 
 def dpc_tuning_set(key: str, value: int):
     _check(_lib.dpc_tuning_set(key.encode(), value))
+
+
+TUNING_DEFAULT = -2 ** 31          # DPC_TUNING_DEFAULT: removes a network's override
 
 
 def _ptr(a):
@@ -157,6 +161,10 @@ class Network:
             self._h = None
             raise
         self._results = []
+
+    def tuning_set(self, key: str, value: int = TUNING_DEFAULT):
+        """dpc_network_tuning_set: this network's value of a tuning knob (TUNING_DEFAULT: back to the process-wide one)."""
+        _check(_lib.dpc_network_tuning_set(self._h, key.encode(), value))
 
     def certify(self, lo, hi, label=None, *, max_backsub_depth: int = -1, keep_symbolic: int = 0,
                 fuse: int = 1, profile: int = 0, use_graph: int = 1, stream: int = 0,

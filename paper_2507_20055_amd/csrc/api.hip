@@ -13,6 +13,9 @@
 #include <utility>
 #include <vector>
 
+#include <atomic>
+#include <climits>
+
 #include "common.h"
 #include "conv.h"
 
@@ -42,15 +45,36 @@ void set_error(const char* fmt, ...)
     g_error = buf;
 }
 
-void set_contract_variant(int v);
-static int g_reuse_patch = 1;     // 1: ReuseCert keeps the stored bounds of convolution layers over their receptive fields only
-static int g_reuse_window = 1;    // 1: ReuseCert's steps above a convolutional front run as implicit contractions (no gathered operand)
-static int g_merge_final = 1;     // 1: output-layer bounds and margins share one traversal
-static uint64_t g_tuning_epoch = 1;  // bumped by every dpc_tuning_set: captured launch sequences are keyed on it
-void set_contract_remap(int v);
-void set_rows_per_wave(int v);
-void set_rows_stream(int v);
-void set_stream_wgs_per_cu(int v);
+// ---- tuning knobs: process-wide values, per-network overrides, the values in force on the calling thread ----
+namespace {
+struct TuneInfo { const char* name; int def; };
+constexpr TuneInfo kTune[TK_COUNT] = {
+    {"contract_variant", -1}, {"contract_remap", 1}, {"conv_algo", 0}, {"conv_half_tiles", 1},
+    {"merge_final", 1},           // 1: output-layer bounds and margins share one traversal
+    {"reuse_patch", 1},           // 1: ReuseCert keeps the stored bounds of convolution layers over their receptive fields only
+    {"reuse_window", 1},          // 1: ReuseCert's steps above a convolutional front run as implicit contractions
+    {"reuse_window_ck", 0}, {"reuse_window_tiles", -1}, {"chain", -1}, {"chain_rows", 64}, {"contract_split_wide", -1},
+    {"contract_split", 0}, {"rows_per_wave", 0}, {"rows_stream", 1}, {"stream_wgs_per_cu", 0},
+};
+struct TuneTable {
+    std::atomic<int> v[TK_COUNT];
+    TuneTable() { for (int k = 0; k < TK_COUNT; ++k) v[k].store(kTune[k].def, std::memory_order_relaxed); }
+};
+TuneTable g_tune;
+std::atomic<uint64_t> g_tuning_epoch{1};   // bumped by every dpc_tuning_set: captured launch sequences are keyed on it
+thread_local const Tuning* t_tuning = nullptr;
+constexpr int kTuneUnset = INT32_MIN;
+int tune_key(const char* key)
+{
+    for (int k = 0; k < TK_COUNT; ++k)
+        if (strcmp(key, kTune[k].name) == 0) return k;
+    return -1;
+}
+}  // namespace
+
+int tune(TuneKey k) { return t_tuning ? t_tuning->v[k] : g_tune.v[k].load(std::memory_order_relaxed); }
+TuningScope::TuningScope(const Tuning* t) : prev_(t_tuning) { t_tuning = t; }
+TuningScope::~TuningScope() { t_tuning = prev_; }
 
 namespace {
 
@@ -208,6 +232,16 @@ struct dpc_network {
     Workspace own_ws;
     Workspace* ws = &own_ws;
     int32_t* h_flag = nullptr;             // pinned host word the input validation reports into (allocated by finalize)
+    int tune_override[TK_COUNT];           // kTuneUnset: the process-wide value applies
+    uint64_t tuning_epoch = 0;
+    dpc_network() { for (int& v : tune_override) v = kTuneUnset; }
+    Tuning tuning() const
+    {
+        Tuning t;
+        for (int k = 0; k < TK_COUNT; ++k)
+            t.v[k] = tune_override[k] != kTuneUnset ? tune_override[k] : g_tune.v[k].load(std::memory_order_relaxed);
+        return t;
+    }
     ~dpc_network() { if (h_flag) (void)hipHostFree(h_flag); }
     int skip_depth = 0;                    // how many skip connections span one layer at most
     static constexpr int kMaxSlots = 96;
@@ -1077,6 +1111,8 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
     {
         DPC_REQUIRE(net && lo && hi && result, DPC_EINVAL, "dpc_certify: NULL argument");
         DPC_REQUIRE(net->finalized, DPC_ESTATE, "dpc_certify: network not finalized");
+        const Tuning tuning = net->tuning();          // this network's knobs are the ones in force for the whole call
+        TuningScope tuning_scope(&tuning);
         dpc_options opt;
         if (opt_in) {
             DPC_REQUIRE(opt_in->struct_size == (int32_t)sizeof(dpc_options), DPC_EINVAL,
@@ -1197,7 +1233,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         // ReuseCert on a convolutional front: the stored bounds of convolution layer i reach only its neurons' receptive
         // field, rwin[i] (ld == 0: rows over the whole input).  Kept while the window is smaller than the input.
         std::vector<ReuseWindow> rwin(nl + 2, ReuseWindow{0, 0, 0, 0, 0, 0});
-        if (reuse_cert && g_reuse_patch && net->in_spatial) {
+        if (reuse_cert && tune(TK_REUSE_PATCH) && net->in_spatial) {
             ReuseWindow w{0, 0, net->inC, 1, 0, 0};
             w.ph = w.pw = 1;
             for (int i = 1; i <= nl && net->layers[i - 1]->kind == CONV; i += 2) {
@@ -1211,7 +1247,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         }
         // layers whose replacement step runs as an implicit contraction over the rows of the convolution layer two below
         auto implicit_step = [&](int k) {
-            if (!reuse_cert || !g_reuse_window || k < 3 || k > nl || !net->in_spatial) return false;
+            if (!reuse_cert || !tune(TK_REUSE_WINDOW) || k < 3 || k > nl || !net->in_spatial) return false;
             const Layer& Lk = *net->layers[k - 1];
             const Layer& Lb = *net->layers[k - 3];
             if (Lk.kind == CONV) return reuse_window_covers(Lk.g.Ci);
@@ -1370,8 +1406,8 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
         // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
         const bool graphable = opt.use_graph && s != nullptr && !prof.on && !opt.keep_symbolic && !fresh;
-        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch, net->ws->ws_epoch};
-        const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && g_merge_final;
+        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch.load() + (net->tuning_epoch << 32), net->ws->ws_epoch};
+        const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && tune(TK_MERGE_FINAL);
         auto enqueue_reusecert = [&]() {
             Pass P{net, res, &opt, s, &prof, B, -1, false};
             float* E = net->ws->buf[0].p;            // stored bounds of the current affine layer: [side][b][n][ldE]
@@ -1801,6 +1837,8 @@ dpc_status dpc_result_symbolic(const dpc_result* res, int32_t layer, int32_t sid
 {
     return guarded([&] {
         require_result(res, "dpc_result_symbolic");
+        const Tuning tuning = res->net->tuning();
+        TuningScope tuning_scope(&tuning);
         const dpc_network* net = res->net;
         const int nl = (int)net->layers.size();
         DPC_REQUIRE(layer >= 1 && layer <= nl, DPC_EINVAL, "dpc_result_symbolic: layer %d out of range [1, %d]", layer, nl);
@@ -1820,6 +1858,8 @@ dpc_status dpc_result_relu_symbolic(const dpc_result* res, int32_t relu_layer, i
 {
     return guarded([&] {
         require_result(res, "dpc_result_relu_symbolic");
+        const Tuning tuning = res->net->tuning();
+        TuningScope tuning_scope(&tuning);
         const dpc_network* net = res->net;
         const int nl = (int)net->layers.size();
         DPC_REQUIRE(relu_layer >= 2 && relu_layer <= nl && net->layers[relu_layer - 1]->kind == RELU, DPC_EINVAL,
@@ -1864,6 +1904,8 @@ dpc_status dpc_result_margin_symbolic(const dpc_result* res, float* coeff, float
 {
     return guarded([&] {
         require_result(res, "dpc_result_margin_symbolic");
+        const Tuning tuning = res->net->tuning();
+        TuningScope tuning_scope(&tuning);
         const dpc_network* net = res->net;
         const int nl = (int)net->layers.size();
         DPC_REQUIRE(res->keep_symbolic >= 1 && res->has_label && res->sym_c[nl + 1] && res->sym_have[nl + 1], DPC_ESTATE,
@@ -1960,27 +2002,25 @@ dpc_status dpc_tuning_set(const char* key, int32_t value)
 {
     return guarded([&] {
         DPC_REQUIRE(key, DPC_EINVAL, "dpc_tuning_set: NULL key");
+        const int k = tune_key(key);
+        DPC_REQUIRE(k >= 0, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
+        DPC_REQUIRE(k != TK_CONTRACT_SPLIT || value == 0 || value == 2 || value == 3, DPC_EINVAL,
+                    "dpc_tuning_set: contract_split takes 0, 2 or 3");
+        g_tune.v[k].store(value, std::memory_order_relaxed);
         ++g_tuning_epoch;
-        if (strcmp(key, "contract_variant") == 0) set_contract_variant(value);
-        else if (strcmp(key, "contract_remap") == 0) set_contract_remap(value);
-        else if (strcmp(key, "conv_algo") == 0) set_conv_algo(value);
-        else if (strcmp(key, "conv_half_tiles") == 0) set_conv_half_tiles(value);
-        else if (strcmp(key, "merge_final") == 0) g_merge_final = value;
-        else if (strcmp(key, "reuse_patch") == 0) g_reuse_patch = value;
-        else if (strcmp(key, "reuse_window") == 0) g_reuse_window = value;
-        else if (strcmp(key, "reuse_window_ck") == 0) set_reuse_window_ck(value);
-        else if (strcmp(key, "chain") == 0) set_chain_mode(value);
-        else if (strcmp(key, "chain_rows") == 0) set_chain_rows(value);
-        else if (strcmp(key, "contract_split_wide") == 0) {
-            set_contract_split_wide(value);
-        } else if (strcmp(key, "contract_split") == 0) {
-            DPC_REQUIRE(value == 0 || value == 2 || value == 3, DPC_EINVAL, "dpc_tuning_set: contract_split takes 0, 2 or 3");
-            set_contract_split(value);
-        }
-        else if (strcmp(key, "rows_per_wave") == 0) set_rows_per_wave(value);
-        else if (strcmp(key, "rows_stream") == 0) set_rows_stream(value);
-        else if (strcmp(key, "stream_wgs_per_cu") == 0) set_stream_wgs_per_cu(value);
-        else DPC_REQUIRE(false, DPC_EINVAL, "dpc_tuning_set: unknown key '%s'", key);
+    });
+}
+
+dpc_status dpc_network_tuning_set(dpc_network* net, const char* key, int32_t value)
+{
+    return guarded([&] {
+        DPC_REQUIRE(net && key, DPC_EINVAL, "dpc_network_tuning_set: NULL argument");
+        const int k = tune_key(key);
+        DPC_REQUIRE(k >= 0, DPC_EINVAL, "dpc_network_tuning_set: unknown key '%s'", key);
+        DPC_REQUIRE(k != TK_CONTRACT_SPLIT || value == kTuneUnset || value == 0 || value == 2 || value == 3, DPC_EINVAL,
+                    "dpc_network_tuning_set: contract_split takes 0, 2 or 3");
+        net->tune_override[k] = value;
+        ++net->tuning_epoch;
     });
 }
 

@@ -340,8 +340,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void chain_kernel(ChainArgs a)
 template <int BM, int KMAX, int WAVES>
 constexpr size_t chain_lds_bytes() { return (size_t)BM * (KMAX + 4) * 4 + (size_t)BM * 8 + (size_t)WAVES * BM * 4; }
 
-int g_chain = -1;          // -1: by shape, 0: never, 1: whenever the shape is covered
-int g_chain_rows = 64;     // row block of the variant for panels up to 512 columns: 64, or 32 (two workgroups per CU)
 
 template <int BM, int KMAX, int WAVES, int MBS, int NBS, int MBF, int NBF>
 void launch_chain_variant(const ChainArgs& a, int groups, hipStream_t s)
@@ -355,13 +353,14 @@ void launch_chain_variant(const ChainArgs& a, int groups, hipStream_t s)
 
 }  // namespace
 
-void set_chain_mode(int v) { g_chain = v; }
-void set_chain_rows(int v) { g_chain_rows = v == 32 ? 32 : 64; }
 
 // See common.h.  Returns false (nothing launched) when the shape is not covered or not worth it.
 bool launch_chain(const ChainDesc& d, hipStream_t s)
 {
     DPC_REQUIRE(d.W0 && d.bias0 && d.pk0 && d.out_l && d.out_u && d.nsteps >= 1 && d.steps, DPC_EINVAL, "chain: bad arguments");
+    // tuning "chain": -1 by shape, 0 never, 1 whenever the shape is covered; "chain_rows": row block of the variant for
+    // panels up to 512 columns, 64 or 32 (two workgroups per CU)
+    const int g_chain = tune(TK_CHAIN), g_chain_rows = tune(TK_CHAIN_ROWS) == 32 ? 32 : 64;
     if (g_chain == 0 || d.nsteps > kChainMaxSteps || d.R < 1 || d.B < 1) return false;
     // widths: every panel (the initial one and the output of every storing step) and every K
     int wmax = d.width0;

@@ -110,8 +110,6 @@ struct ChainDesc {
     float* out_u;
 };
 bool launch_chain(const ChainDesc& d, hipStream_t s);
-void set_chain_mode(int v);          // -1: by shape, 0: never, 1: whenever covered
-void set_chain_rows(int v);          // 32 or 64: row block for panels up to 512 columns
 
 // ---- ReuseCert helpers (Appendix C, ReuseCert): see reuse.hip for the layout -------------------
 // Rr[b] = [lambda * L ; mu * U + nu ; unit row] from the stored bounds E[side][b][n][ldE] of the layer below the ReLU
@@ -138,9 +136,25 @@ void launch_contract_split(const float* A, int64_t M, int K, int lda, const void
                            hipStream_t s);
 int launch_contract_split_fused(const float* A, int64_t M, int K, int lda, const void* Wt, int terms, int N, float* C, int ldc,
                                 const ContractEpilogue& e, hipStream_t s);
-void set_contract_split(int v);
-void set_contract_split_wide(int v);
 int contract_split_terms();
+
+// Tuning knobs.  Process-wide values (dpc_tuning_set) can be overridden per network (dpc_network_tuning_set); the values in
+// force on a thread are those of the network whose call is running on it (TuningScope), else the process-wide ones.
+enum TuneKey {
+    TK_CONTRACT_VARIANT, TK_CONTRACT_REMAP, TK_CONV_ALGO, TK_CONV_HALF_TILES, TK_MERGE_FINAL, TK_REUSE_PATCH, TK_REUSE_WINDOW,
+    TK_REUSE_WINDOW_CK, TK_REUSE_WINDOW_TILES, TK_CHAIN, TK_CHAIN_ROWS, TK_CONTRACT_SPLIT_WIDE, TK_CONTRACT_SPLIT, TK_ROWS_PER_WAVE,
+    TK_ROWS_STREAM, TK_STREAM_WGS_PER_CU, TK_COUNT
+};
+struct Tuning { int v[TK_COUNT]; };
+int tune(TuneKey k);
+struct TuningScope {
+    explicit TuningScope(const Tuning* t);
+    ~TuningScope();
+    TuningScope(const TuningScope&) = delete;
+    TuningScope& operator=(const TuningScope&) = delete;
+private:
+    const Tuning* prev_;
+};
 // dst rows += a block of the same expression that waited on a skip connection (residual networks); rows are
 // [M][ph2*pw2*C] patches (dense rows: ph2 = pw2 = 1, C = n), the block is ph1 x pw1 x C at offset (d, d).
 // kind 0: src[m][..]; kind 1: src[r % rows_C][..] (r = m % R); kind 2: += 1 on channel r % rows_C of position (d, d).

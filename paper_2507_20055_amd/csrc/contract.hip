@@ -377,7 +377,6 @@ int launch_variant(const float* A, int64_t M, int K, int lda, const float* W, in
     return tiles_n;
 }
 
-int g_variant = -1;      // -1: chosen from the problem shape
 
 // Tile choice from the problem shape (measured on cfg2- and cfg5-sized contractions):
 //  * fewer than 512 tiles of 128x128: 64x64 tiles, so that the grid still covers the 256 CUs;
@@ -391,12 +390,9 @@ int pick_variant(int64_t M, int ldc, int K)
     const int rem = ldc % 256;
     return (rem != 0 && rem <= 128) ? 17 : 7;
 }
-int g_remap = 1;
 
 }  // namespace
 
-void set_contract_variant(int v) { g_variant = v; }
-void set_contract_remap(int v) { g_remap = v; }
 
 void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, int N, int ldw,
                      float* Cout, int ldc, hipStream_t s)
@@ -407,29 +403,29 @@ void launch_contract(const float* A, int64_t M, int K, int lda, const float* W, 
     DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0, DPC_EINVAL,
                 "contract: buffers must be 16-byte aligned");
     if (M == 0) return;
-    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc, K);
+    const int variant = tune(TK_CONTRACT_VARIANT) >= 0 ? tune(TK_CONTRACT_VARIANT) : pick_variant(M, ldc, K);
     switch (variant) {
-        case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 3:  launch_variant<Tile<256, 128, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 4:  launch_variant<Tile<128, 256, 16, 64, 128>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 10: launch_variant<Tile<128, 128, 8, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 16: launch_variant<Tile<128, 128, 8, 64, 64, 4>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 18: launch_variant<Tile<64, 64, 64, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 19: launch_variant<Tile<64, 64, 32, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 20: launch_variant<Tile<32, 64, 32, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 11: launch_variant<Tile<64, 64, 8, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 12: launch_variant<Tile<128, 64, 16, 64, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 13: launch_variant<Tile<64, 128, 8, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 14: launch_variant<Tile<128, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        case 15: launch_variant<Tile<256, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
-        default: launch_variant<Tile<128, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap}, 0, s); break;
+        case 1:  launch_variant<Tile<256, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 2:  launch_variant<Tile<128, 128, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 3:  launch_variant<Tile<256, 128, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 4:  launch_variant<Tile<128, 256, 16, 64, 128>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 5:  launch_variant<Tile<256, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 6:  launch_variant<Tile<256, 256, 16, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 8:  launch_variant<Tile<64, 128, 16, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 9:  launch_variant<Tile<64, 64, 16, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 10: launch_variant<Tile<128, 128, 8, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 16: launch_variant<Tile<128, 128, 8, 64, 64, 4>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 18: launch_variant<Tile<64, 64, 64, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 19: launch_variant<Tile<64, 64, 32, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 20: launch_variant<Tile<32, 64, 32, 32, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 11: launch_variant<Tile<64, 64, 8, 32, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 12: launch_variant<Tile<128, 64, 16, 64, 32>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 13: launch_variant<Tile<64, 128, 8, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 14: launch_variant<Tile<128, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        case 15: launch_variant<Tile<256, 128, 8, 128, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
+        default: launch_variant<Tile<128, 128, 32, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, EpiArgs{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP)}, 0, s); break;
     }
 }
 
@@ -445,10 +441,10 @@ void launch_contract_batched(const float* A, int64_t strideA, int64_t M, int K, 
     DPC_REQUIRE(((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)Cout % 16) == 0, DPC_EINVAL,
                 "contract_batched: buffers must be 16-byte aligned");
     if (M == 0 || batches == 0) return;
-    EpiArgs ep{nullptr, 0, 0, 0, nullptr, 0, 0, g_remap, (long long)strideA, (long long)strideW, (long long)strideC};
+    EpiArgs ep{nullptr, 0, 0, 0, nullptr, 0, 0, tune(TK_CONTRACT_REMAP), (long long)strideA, (long long)strideW, (long long)strideC};
     // tile choice as for one problem of batches * M rows; problems of at most 512 rows tile better with 64x64
     // (measured on the 500-row steps of ReuseCert)
-    const int variant = g_variant >= 0 ? g_variant : M <= 512 ? 9 : pick_variant(M * batches, ldc, 0);
+    const int variant = tune(TK_CONTRACT_VARIANT) >= 0 ? tune(TK_CONTRACT_VARIANT) : M <= 512 ? 9 : pick_variant(M * batches, ldc, 0);
     switch (variant) {
         case 7:  launch_variant<Tile<128, 256, 16, 64, 64>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
         case 17: launch_variant<Tile<128, 128, 16, 64, 64, 3>, 0>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, 0, s, batches); break;
@@ -468,8 +464,8 @@ int launch_contract_fused(const float* A, int64_t M, int K, int lda, const float
     DPC_REQUIRE(e.ldpk >= ldc && e.R >= 32 && e.nsb >= 1 && (int64_t)e.nsb * e.R == M && e.part_stride >= M, DPC_EINVAL,
                 "contract_fused: epilogue geometry does not match the rows");
     if (M == 0) return 0;
-    const int variant = g_variant >= 0 ? g_variant : pick_variant(M, ldc, K);
-    EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store, g_remap};
+    const int variant = tune(TK_CONTRACT_VARIANT) >= 0 ? tune(TK_CONTRACT_VARIANT) : pick_variant(M, ldc, K);
+    EpiArgs ep{reinterpret_cast<const float4*>(e.pk), e.ldpk, e.R, e.nsb, e.part, e.part_stride, e.store, tune(TK_CONTRACT_REMAP)};
     switch (variant) {      // the fused epilogue is instantiated for the tiles the shape heuristic can pick
         case 17: return launch_variant<Tile<128, 128, 16, 64, 64, 3>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);
         case 7:  return launch_variant<Tile<128, 256, 16, 64, 64>, 1>(A, M, K, lda, W, N, ldw, Cout, ldc, ep, e.max_slots, s);

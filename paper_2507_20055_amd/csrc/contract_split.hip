@@ -17,11 +17,7 @@
 
 namespace dpc {
 
-static int g_split_terms = 0;
-static int g_split_wide = -1;         // -1: 256-column tiles chosen from the shape; 0 / 1: never / always
-void set_contract_split_wide(int v) { g_split_wide = v; }
-void set_contract_split(int v) { g_split_terms = v; }
-int contract_split_terms() { return g_split_terms; }
+int contract_split_terms() { return tune(TK_CONTRACT_SPLIT); }
 
 namespace {
 
@@ -329,7 +325,7 @@ namespace {
 // 256-column tiles unless the last one would be at most half used (e.g. 784 columns)
 int pick_ntw(int ldc)
 {
-    if (g_split_wide >= 0) return g_split_wide ? 4 : 2;
+    if (tune(TK_CONTRACT_SPLIT_WIDE) >= 0) return tune(TK_CONTRACT_SPLIT_WIDE) ? 4 : 2;     // -1: 256-column tiles by shape
     const int rem = ldc % 256;
     return (rem != 0 && rem <= 128) ? 2 : 4;
 }

@@ -125,13 +125,10 @@ void launch_reuse_scale_expand(const float* E, const float* core, int ld_core, c
 // output position with origin index * S_o - P_o).  g describes the taps (a fully-connected layer: kh x kw = its input grid,
 // one output position).  Returns the multiply-add count * 2.  reuse_window_covers: channel counts the kernel takes.
 bool reuse_window_covers(int Ci);
-void set_reuse_window_ck(int v);
 double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M, const float* Rr, int n, const ReuseWindow& fi, const ConvGeom& g,
                            int fh, int fw, int ld_o, int S_o, int P_o, bool frame_image, int batch, float* E, hipStream_t s);
 
-void set_conv_algo(int v);
 int conv_algo();
-void set_conv_half_tiles(int v);
 int conv_half_tiles();
 
 // Validation of certify inputs on the device.  Returns 0 = fine, 1 = lo > hi or non-finite, 2 = bad label.

@@ -243,9 +243,6 @@ int rows_per_wave_for(int R, int groups)
 
 }  // namespace
 
-int g_conv_algo = 0;       // 0: MFMA kernels where they apply; 1: always the generic gather kernel; 2: as 0, but few
-                          // input channels go to the plain-ALU kernel instead of the MFMA one
-
 ConvWeights::~ConvWeights()
 {
     if (core) (void)hipFree(core);
@@ -334,7 +331,7 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
     DPC_REQUIRE(M < ((int64_t)1 << 31), DPC_EINVAL, "conv_transpose_rows: too many rows");
     if (M == 0) return 0.0;
     const double flop = 2.0 * (double)M * ih * iw * g.Co * g.Ci * g.kh * g.kw;
-    if (g_conv_algo != 1 && launch_conv_transpose_fast(in, M, ld_in, ih, iw, g, w, out, ld_out, oh, ow, off, s)) return flop;
+    if (conv_algo() != 1 && launch_conv_transpose_fast(in, M, ld_in, ih, iw, g, w, out, ld_out, oh, ow, off, s)) return flop;
     dim3 grid((unsigned)M, (unsigned)ceil_div(ld_out, kThreads));
     hipLaunchKernelGGL(conv_transpose_rows_kernel, grid, dim3(kThreads), 0, s, in, ld_in, ih, iw, g.Co, g.Ci, g.kh, g.kw,
                        g.stride, w.taps, out, ld_out, oh, ow, off);
@@ -342,11 +339,11 @@ double launch_conv_transpose_rows(const float* in, int64_t M, int ld_in, int ih,
     return flop;
 }
 
-void set_conv_algo(int v) { g_conv_algo = v; }
-int conv_algo() { return g_conv_algo; }
-static int g_conv_half_tiles = 1;   // 1: 16 x 16 tiles in the MFMA kernel for layers with at most 16 input channels; 0: 32 x 32 always
-void set_conv_half_tiles(int v) { g_conv_half_tiles = v; }
-int conv_half_tiles() { return g_conv_half_tiles; }
+// 0: MFMA kernels where they apply; 1: always the generic gather kernel; 2: as 0, but few input channels go to the plain-ALU
+// kernel instead of the MFMA one
+int conv_algo() { return tune(TK_CONV_ALGO); }
+// 1: 16 x 16 tiles in the MFMA kernel for layers with at most 16 input channels; 0: 32 x 32 always
+int conv_half_tiles() { return tune(TK_CONV_HALF_TILES); }
 
 int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,
                  int32_t* flag, hipStream_t s)

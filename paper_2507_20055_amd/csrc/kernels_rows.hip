@@ -808,13 +808,10 @@ __global__ __launch_bounds__(kThreads) void permute_kernel(const float* __restri
     if (TO_HWC) dst[hwc] = src[i]; else dst[i] = src[hwc];
 }
 
-int g_rows_per_wave = 0;
-int g_stream = 1;
-int g_stream_wgs_per_cu = 0;           // tuning: workgroups per compute unit the streaming kernels' grids aim for (0: default)
 
 int pick_rows_per_wave(int R, int groups)
 {
-    if (g_rows_per_wave > 0) return g_rows_per_wave;
+    if (tune(TK_ROWS_PER_WAVE) > 0) return tune(TK_ROWS_PER_WAVE);
     // Kernels that walk chunks of columns: enough blocks to cover 256 CUs a few times over, as many rows per block as
     // that allows, but at least one PAIR per wavefront (a pair shares every LDS read of the parameters: single rows
     // measured 4 % slower even where they double the number of workgroups).
@@ -827,9 +824,9 @@ int pick_rows_per_wave(int R, int groups)
 // still leaves a thousand workgroups (measured: +2..4 % there, -25 % when the grid gets too small).
 int pick_rows_per_block(int R, int groups, int nseg)
 {
-    if (g_rows_per_wave > 0) return g_rows_per_wave * kWaves;
-    if (g_stream_wgs_per_cu > 0) {     // experiment: grid sized to the chip
-        const int blocks_per_group = (int)std::max<int64_t>(1, (int64_t)256 * g_stream_wgs_per_cu / std::max(groups, 1));
+    if (tune(TK_ROWS_PER_WAVE) > 0) return tune(TK_ROWS_PER_WAVE) * kWaves;
+    if (tune(TK_STREAM_WGS_PER_CU) > 0) {     // experiment: grid sized to the chip
+        const int blocks_per_group = (int)std::max<int64_t>(1, (int64_t)256 * tune(TK_STREAM_WGS_PER_CU) / std::max(groups, 1));
         return (std::max((int)ceil_div(R, blocks_per_group), 2 * kWaves) + 1) & ~1;
     }
     if (nseg >= 2 && ceil_div(R, 4 * kWaves) * groups >= 1024) return 4 * kWaves;
@@ -838,9 +835,6 @@ int pick_rows_per_block(int R, int groups, int nseg)
 
 }  // namespace
 
-void set_rows_per_wave(int v) { g_rows_per_wave = v; }
-void set_rows_stream(int v) { g_stream = v; }
-void set_stream_wgs_per_cu(int v) { g_stream_wgs_per_cu = v; }
 
 void launch_relax_params_pack(const float* l, const float* u, float* lambda, float* mu, float* nu, float* rl, float* ru,
                               const float* bias, int batch, int n, int ld, float* pk, float* pk2, hipStream_t s)
@@ -878,7 +872,7 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
                     "relax_step: shared source needs ld_src >= ldc, multiple of 4, 16-byte aligned");
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "relax_step: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
-    if (ldc <= 2048 && g_stream) {
+    if (ldc <= 2048 && tune(TK_ROWS_STREAM)) {
         // parameters of a whole row in LDS (32 KB at most, so that five workgroups fit a compute unit): the streaming kernel
         const size_t lds_s = (size_t)ldc * 16;
         const int rpb = pick_rows_per_block(R, nsides * batch, (int)ceil_div(ldc, 1024));
@@ -924,7 +918,7 @@ void launch_concretise(const float* C, int ldc, const double* cst, int nsides, i
         DPC_REQUIRE(C && cst && ((uintptr_t)C % 16) == 0, DPC_EINVAL, "concretise: C/cst missing or misaligned");
     DPC_REQUIRE((int64_t)nsides * batch <= 65535, DPC_EINVAL, "concretise: nsides*batch exceeds 65535");
     if (batch == 0 || R == 0) return;
-    if (ldc <= 2048 && g_stream) {
+    if (ldc <= 2048 && tune(TK_ROWS_STREAM)) {
         const size_t lds_s = (size_t)ldc * 8;
         const int rpb = pick_rows_per_block(R, nsides * batch, (int)ceil_div(ldc, 1024));
         dim3 grid_s((unsigned)ceil_div(R, rpb), (unsigned)(nsides * batch));

@@ -12,12 +12,16 @@
 // (qy - oy_t, qx - ox_t, c) of that row, or nothing when that falls outside the window.
 //
 // Work split: a workgroup (4 wavefronts) owns 32*MT rows m (both sides stacked: m < M is the lower side, the rest the upper
-// side) x 128 frame columns of one output position; each wavefront owns 32 of those columns for all the rows.  The A operand
-// of one (tap, channel chunk) goes through LDS, k-contiguous per row so that four reduction steps come from one 16-byte
-// read; the B operand comes straight from global memory (L2), one float per lane per step through a buffer resource whose
+// side) x four 32-column blocks of the frame of one output position, one block per wavefront for all the rows.  Where a frame
+// row fills its 32-column blocks (at least 9 lanes of 10), the four blocks are the same block of four consecutive frame
+// rows: a tap's window covers the same columns in every row, so the wavefronts meet the same taps and finish together, and
+// taps that miss the tile in either direction are skipped by the whole workgroup; the constant column is then one more
+// frame row.  Narrow frames take 128 consecutive columns of the flattened frame instead (taps are skipped by frame rows for
+// the workgroup and by block for a wavefront).  The A operand of one (tap, chunk of 32 channels) goes through LDS,
+// k-contiguous per row so that four reduction steps come from one 16-byte read (row stride 2*CK + 4 floats: conflict-free);
+// the B operand comes straight from global memory (L2), one float per lane per step through a buffer resource whose
 // out-of-range offsets read zeros (so a lane outside the window needs no branch), fetched eight steps ahead.  One MFMA step
-// consumes Lr row ci (lanes 0-31, k = 0) and Ur row ci (lanes 32-63, k = 1).  Taps whose window misses the workgroup's
-// frame rows are skipped by the whole workgroup, taps that miss a wavefront's 32 columns by that wavefront.
+// consumes Lr row ci (lanes 0-31, k = 0) and Ur row ci (lanes 32-63, k = 1).
 // Summation order is fixed (taps in order, channels in order), so results are reproducible.
 #include <algorithm>
 #include <type_traits>
@@ -214,9 +218,6 @@ __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
 
 }  // namespace
 
-static int g_rw_ck = 0;           // tuning: channels per staged chunk (0: by shape)
-static int g_rw_flat = -1;        // tuning: tile shape (-1: by shape, 0: row tiles, 1: flat tiles)
-void set_reuse_window_ck(int v) { if (v >= 100) g_rw_flat = v - 101; else g_rw_ck = v; }
 
 
 bool reuse_window_covers(int Ci) { return Ci >= 8 && Ci % 8 == 0; }
@@ -240,6 +241,7 @@ double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M
     a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad; a.H = g.H; a.W = g.W; a.Wo = g.Wo; a.npos = (int)npos;
     a.fh = fh; a.fw = fw; a.ld_o = ld_o; a.S_o = S_o; a.P_o = P_o; a.frame_image = frame_image ? 1 : 0;
     a.E = E; a.side_stride = nz * M * ld_o;
+    const int g_rw_ck = tune(TK_REUSE_WINDOW_CK), g_rw_flat = tune(TK_REUSE_WINDOW_TILES);   // 0 / -1: by shape
     a.CK = (g_rw_ck >= 8 && g_rw_ck <= 64 && g_rw_ck % 8 == 0 && g.Ci % g_rw_ck == 0) ? g_rw_ck : g.Ci <= 32 ? g.Ci : g.Ci % 32 == 0 ? 32 : g.Ci % 16 == 0 ? 16 : 8;
     const int rows = 2 * M;
     const int MT = rows > 64 ? 4 : rows > 32 ? 2 : 1;

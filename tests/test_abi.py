@@ -81,10 +81,16 @@ def test_host_side_error_paths():
     lo = np.zeros((1, 4), np.float32)
     r = ctypes.c_void_p()
     assert lib.dpc_certify(h, 1, lo.ctypes.data, lo.ctypes.data, None, None, ctypes.byref(r)) == 5
+    assert lib.dpc_network_tuning_set(h, b"chain", 0) == 0                    # per-network knob: before or after finalize
+    assert lib.dpc_network_tuning_set(h, b"chain", binding.TUNING_DEFAULT) == 0
+    assert lib.dpc_network_tuning_set(h, b"no_such_key", 1) == 1
+    assert lib.dpc_network_tuning_set(h, b"contract_split", 5) == 1
+    assert lib.dpc_network_tuning_set(None, b"chain", 0) == 1
     assert lib.dpc_network_destroy(h) == 0
     assert lib.dpc_network_destroy(None) == 0
     assert lib.dpc_result_destroy(None) == 0
     assert lib.dpc_tuning_set(b"no_such_key", 1) == 1
+    assert lib.dpc_tuning_set(b"contract_split", 5) == 1
 
 
 def test_add_layers_are_validated():

@@ -421,6 +421,41 @@ def test_resident_traversal_kernel(seed, dims, B, rows):
     gnet.close()
 
 
+def test_tuning_knobs_per_network():
+    """dpc_network_tuning_set: a knob set on one network holds for that network only, whatever the process-wide value
+    is, and DPC_TUNING_DEFAULT removes it.  Seen through the profile: the resident traversal kernel runs (or not)."""
+    b = _binding()
+    dims = [20, 33, 65, 40, 10]
+    net = wl.random_small_net(91, dims)
+    x, lo, hi = wl.random_box(92, dims[0], 4, 0.05)
+    label = np.arange(4, dtype=np.int32) % dims[-1]
+    o = oracle.run(net, lo, hi, label=label)
+    forced, never, plain = b.Network(net), b.Network(net), b.Network(net)
+    forced.tuning_set("chain", 1)
+    never.tuning_set("chain", 0)
+
+    def chain_launches(gnet):
+        g = gnet.certify(lo, hi, label, profile=1)
+        compare_with_oracle(net, lo, hi, g, o, label)
+        return g.profile()["chain_launches"]
+
+    try:
+        for process_wide in (-1, 0, 1):
+            b.dpc_tuning_set("chain", process_wide)
+            assert chain_launches(forced) == len(dims) - 3
+            assert chain_launches(never) == 0
+            assert chain_launches(plain) == (len(dims) - 3 if process_wide == 1 else 0)      # by shape: too small for it
+        forced.tuning_set("chain")                 # override removed: follows the process-wide value again
+        b.dpc_tuning_set("chain", 0)
+        assert chain_launches(forced) == 0
+        with pytest.raises(b.DpcError):
+            forced.tuning_set("no_such_key", 1)
+    finally:
+        b.dpc_tuning_set("chain", -1)
+    for n in (forced, never, plain):
+        n.close()
+
+
 @pytest.mark.parametrize("seed,dims,B,eps", [(81, [5, 7, 6, 3], 3, 0.3), (82, [20, 33, 65, 40, 10], 4, 0.1), (83, [7, 130, 5], 2, 0.2),
                                              (84, [64, 257, 129, 70, 10], 5, 0.05), (85, [31, 40, 40, 40, 40, 2], 2, 0.1),
                                              (86, [1030, 48, 36, 4], 2, 0.02)])
@@ -479,7 +514,7 @@ def test_reusecert_hand_example_and_errors():
                                              ((1, 9, 7), [(4, 3, 1, 0), (6, 3, 2, 1), (8, 2, 1, 0)], [5]),
                                              ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4]),
                                              ((3, 12, 12), [(8, 3, 1, 1), (16, 4, 2, 1), (16, 3, 1, 1)], [10, 4])])
-@pytest.mark.parametrize("window,implicit,ck", [(1, 1, 0), (0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 1, 8), (0, 1, 8), (1, 1, 101), (0, 1, 101), (1, 1, 102), (0, 1, 102)])
+@pytest.mark.parametrize("window,implicit,ck", [(1, 1, 0), (0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 1, 8), (0, 1, 8), (1, 1, 100), (0, 1, 100), (1, 1, 101), (0, 1, 101)])
 def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implicit, ck):
     """ReuseCert on convolutional networks: the replacement step through a convolution layer is the contraction of its
     split kernel matrix with the input-level rows of the ReLU layer below, one output position at a time.
@@ -487,7 +522,7 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implici
     than the input -- the shapes mix both forms and every hand-over between them); window=0: rows over the whole input.
     implicit=1: layers whose channel count the implicit contraction takes (multiples of 8) read the rows in place, the
     others gather them first; implicit=0: all gather.  ck=8: the implicit contraction stages 8 channels at a time, so that layers with 16
-    channels take more than one chunk per tap; ck=101 / 102: its tiles run over frame rows / over the flattened frame at
+    channels take more than one chunk per tap; ck=100 / 101: its tiles run over frame rows / over the flattened frame at
     every layer (by itself it picks one of the two per layer)."""
     net = wl.random_small_conv(171, shape, convs, fcs)
     B = 3
@@ -496,7 +531,8 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implici
     b = _binding()
     b.dpc_tuning_set("reuse_patch", window)
     b.dpc_tuning_set("reuse_window", implicit)
-    b.dpc_tuning_set("reuse_window_ck", ck)
+    b.dpc_tuning_set("reuse_window_ck", ck if ck < 100 else 0)
+    b.dpc_tuning_set("reuse_window_tiles", ck - 100 if ck >= 100 else -1)
     try:
         gnet = b.Network(net)
         o = oracle.run(net, lo, hi, label=label, certifier="reusecert")
@@ -508,7 +544,7 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implici
         b.dpc_tuning_set("reuse_patch", 1)
         b.dpc_tuning_set("reuse_window", 1)
         b.dpc_tuning_set("reuse_window_ck", 0)
-        b.dpc_tuning_set("reuse_window_ck", 100)
+        b.dpc_tuning_set("reuse_window_tiles", -1)
 
 
 @pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29])])
