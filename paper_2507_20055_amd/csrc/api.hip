@@ -411,6 +411,13 @@ struct Pass {
     int maxd;             // traversal limit of this pass (-1: to the input)
     bool fuse;            // the call filled the packed ReLU parameters (pk, pk2, pk2v) of every layer: only then may a
                           // kernel that applies a ReLU step from them be chosen (an earlier call's are stale)
+    // Work that can ride on the pass's last kernel when that kernel is the fold of the partial sums (no launch of its own):
+    // the parameters of the ReLU layer above the bounded layer, or the split of the merged last pass.
+    struct NextRelu { float *lam, *mu, *nu, *rl, *ru; const float* bias; int n, ld; float *pk, *pk2; };
+    struct FinalSplit { int nK, Rs; float *l, *u, *margin; int32_t* verdict; };
+    const NextRelu* next = nullptr;
+    const FinalSplit* fin = nullptr;
+    bool rider_done = false;      // set by the pass when it did that work
 };
 
 // A block of the expression that waits on a skip connection until the traversal reaches the layer it is over
@@ -806,7 +813,17 @@ void run_pass(Pass& P, int at, int nsides, int R, const Layer* own, float* out_l
     }
     P.prof->begin(P_CONC);
     if (concretised) {
-        launch_finalize_bounds(cst, net->ws->part.p, slots, net->ws->part_stride, nsides, B, R, out_l, out_u, P.s);
+        if (P.next && nsides == 2 && R == P.next->n) {
+            launch_finalize_relax_pack(cst, net->ws->part.p, slots, net->ws->part_stride, out_l, out_u, P.next->lam, P.next->mu, P.next->nu,
+                                       P.next->rl, P.next->ru, P.next->bias, B, R, P.next->ld, P.next->pk, P.next->pk2, P.s);
+            P.rider_done = true;
+        } else if (P.fin && nsides == 2 && R == P.fin->Rs &&
+                   launch_finalize_split_final(cst, net->ws->part.p, slots, net->ws->part_stride, B, P.fin->nK, R, P.fin->l, P.fin->u,
+                                               P.fin->margin, P.fin->verdict, P.s)) {
+            P.rider_done = true;
+        } else {
+            launch_finalize_bounds(cst, net->ws->part.p, slots, net->ws->part_stride, nsides, B, R, out_l, out_u, P.s);
+        }
     } else if (f.patch) {
         launch_concretise_patch(cur, f.ld, cst, nsides, B, R, f.pg, res->l[at], res->u[at], out_l, out_u,
                                 shared, ld_shared, cst_init, P.s);
@@ -1377,6 +1394,9 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             return at.type == hipMemoryTypeDevice && at.device == net->device;
         };
         const bool resident = B > 0 && on_device(lo) && on_device(hi) && (!label || on_device(label));
+        // the packed form of the box (for the fused concretisation epilogues) is written by the kernel that takes the box in
+        const bool packed0 = resident && fuse && !(reuse_cert && (int)net->layers.size() >= 3) && !net->ws->pk.empty() && net->ws->pk[0] &&
+                             net->ws->pk[0]->p;
         DPC_REQUIRE(resident || !arena, DPC_EINVAL, "dpc_certify_static: lo, hi and label must be device memory of the network's device");
         *net->h_flag = 0;
         if (resident) {
@@ -1386,7 +1406,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                 zero_word_enqueue(net->ws->dflag.p, s);
             }
             ingest_enqueue(lo, hi, label, res->l[0], res->u[0], label ? res->label.p : nullptr, B, n0, net->in_spatial ? net->inC : 0,
-                           net->inH, net->inW, nK, net->ws->dflag.p, net->h_flag, s);
+                           net->inH, net->inW, nK, net->ws->dflag.p, net->h_flag, s, packed0 ? net->ws->pk[0]->p : nullptr, net->ld_of(0));
         } else if (net->in_spatial) {
             DPC_HIP(hipMemcpyAsync(net->ws->stage.p, lo, box * 4, hipMemcpyDefault, s));
             DPC_HIP(hipMemcpyAsync(net->ws->stage.p + box, hi, box * 4, hipMemcpyDefault, s));
@@ -1406,7 +1426,7 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         // Launch-bound workloads (small networks: tens of short kernels) replay the whole kernel sequence as one
         // HIP graph: captured the first time a result object is reused, keyed on everything that shapes it.
         const bool graphable = opt.use_graph && s != nullptr && !prof.on && !opt.keep_symbolic && !fresh;
-        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1), label != nullptr, g_tuning_epoch.load() + (net->tuning_epoch << 32), net->ws->ws_epoch};
+        const dpc_result::GraphKey gkey{(opt.max_backsub_depth + 2) * 65536 + opt.final_backsub_depth + 2, (opt.fuse != 0) | (opt.certifier << 1) | (packed0 ? 256 : 0), label != nullptr, g_tuning_epoch.load() + (net->tuning_epoch << 32), net->ws->ws_epoch};
         const bool merge_final = label && !opt.keep_symbolic && nl >= 2 && tune(TK_MERGE_FINAL);
         auto enqueue_reusecert = [&]() {
             Pass P{net, res, &opt, s, &prof, B, -1, false};
@@ -1572,10 +1592,22 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
         };
         auto enqueue_all = [&]() {
             if (reuse_cert && nl >= 3) { enqueue_reusecert(); return; }
-            if (fuse) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->ws->pk[0]->p, s);
+            if (fuse && !packed0) launch_pack_bounds(res->l[0], res->u[0], B, n0, net->ld_of(0), net->ws->pk[0]->p, s);
             Pass P{net, res, &opt, s, &prof, B, opt.max_backsub_depth, fuse};
+            bool relu_done = false;           // the pass below this ReLU layer has written its parameters already
+            Pass::NextRelu next{};
             for (int i = 1; i <= nl; ++i) {
                 Layer& L = *net->layers[i - 1];
+                if (L.kind == RELU && relu_done) { relu_done = false; continue; }
+                P.next = nullptr;
+                P.rider_done = false;
+                if (fuse && L.kind == AFFINE && i < nl && net->layers[i]->kind == RELU) {
+                    float* pk2 = i + 1 == 2 ? net->ws->pk2.p
+                                            : ((int)net->ws->pk2v.size() > i + 1 && net->ws->pk2v[i + 1]) ? net->ws->pk2v[i + 1]->p : nullptr;
+                    next = Pass::NextRelu{res->lam[i + 1], res->mu[i + 1], res->nu[i + 1], res->l[i + 1], res->u[i + 1], L.dBias.p, L.n_out,
+                                          net->ld_of(i + 1), net->ws->pk[i + 1]->p, pk2};
+                    P.next = &next;
+                }
                 if (L.kind == RELU) {
                     prof.begin(P_OTHER);
                     if (fuse) {
@@ -1618,7 +1650,10 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                     continue;
                 }
                 run_pass(P, i - 1, 2, L.n_out, &L, res->l[i], res->u[i], res->sym_c[i] ? i : -1);
+                relu_done = P.rider_done;
             }
+            P.next = nullptr;
+            P.rider_done = false;
             P.maxd = opt.final_backsub_depth;
             if (merge_final) {
                 // Output-layer rows and margin rows walk the same layers: one pass of 2*nK-1 rows per (side, input)
@@ -1633,11 +1668,16 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
                                   net->ld_of(nl - 1), net->ws->cst.p, s, Rs);
                 prof.end();
                 res->prof.other_launches++;
+                const Pass::FinalSplit fin{nK, Rs, res->l[nl], res->u[nl], res->margin.p, res->verdict.p};
+                P.fin = &fin;
                 run_pass(P, nl - 1, 2, Rs, nullptr, tl, tu, -1, (double)(2 * nK + nK - 1) / (2.0 * Rs));
-                prof.begin(P_OTHER);
-                launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s, Rs);
-                prof.end();
-                res->prof.other_launches++;
+                P.fin = nullptr;
+                if (!P.rider_done) {
+                    prof.begin(P_OTHER);
+                    launch_split_final(tl, tu, B, nK, res->l[nl], res->u[nl], res->margin.p, res->verdict.p, s, Rs);
+                    prof.end();
+                    res->prof.other_launches++;
+                }
             } else if (label) {
                 const int nq = nK - 1;
                 prof.begin(P_OTHER);

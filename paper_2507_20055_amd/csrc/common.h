@@ -185,6 +185,14 @@ void launch_pack_relax2(const float* lambda, const float* mu, const float* nu, i
 // pk[side][b][c] = (0, 0, bound taken by C >= 0, bound taken by C < 0) for the concretisation.
 void launch_pack_bounds(const float* lo, const float* hi, int batch, int n, int ld, float* pk, hipStream_t s);
 // out[b, r] = float(cst[m] + sum over slots of part[slot][m]), m = (side*batch + b)*R + r.
+// launch_finalize_bounds (both sides, R = n) and launch_relax_params_pack of the ReLU layer above in one launch.
+void launch_finalize_relax_pack(const double* cst, const float* part, int nslots, int64_t part_stride, float* out_l, float* out_u,
+                                float* lambda, float* mu, float* nu, float* rl, float* ru, const float* bias, int batch, int n, int ld,
+                                float* pk, float* pk2, hipStream_t s);
+// launch_finalize_bounds and launch_split_final of the merged last pass in one launch; false (nothing launched) when a
+// group has more than 64 rows.
+bool launch_finalize_split_final(const double* cst, const float* part, int nslots, int64_t part_stride, int batch, int nK, int Rs, float* l,
+                                 float* u, float* margin, int32_t* verdict, hipStream_t s);
 void launch_finalize_bounds(const double* cst, const float* part, int nslots, int64_t part_stride, int nsides, int batch,
                             int R, float* out_l, float* out_u, hipStream_t s);
 

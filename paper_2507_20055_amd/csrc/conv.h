@@ -136,7 +136,7 @@ int conv_half_tiles();
 // Device-resident boxes and labels: copy into the result's buffers (Cc > 0: (C,H,W) -> (H,W,C)) and validate in one
 // kernel; *flag must be zero before (zero_word_enqueue after a call that found an error).
 void ingest_enqueue(const float* lo, const float* hi, const int32_t* label, float* l0, float* u0, int32_t* lab, int batch, int n0,
-                    int Cc, int H, int W, int nK, int32_t* flag, int32_t* pinned_host_flag, hipStream_t s);
+                    int Cc, int H, int W, int nK, int32_t* flag, int32_t* pinned_host_flag, hipStream_t s, float* pk = nullptr, int ld = 0);
 void zero_word_enqueue(int32_t* flag, hipStream_t s);
 // The same checks without waiting: the flag word lands in pinned host memory once the stream reaches the copy.
 void check_inputs_enqueue(const float* lo, const float* hi, size_t count, const int32_t* label, int batch, int nK,

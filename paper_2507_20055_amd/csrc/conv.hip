@@ -201,22 +201,35 @@ __global__ void check_inputs_kernel(const float* __restrict__ lo, const float* _
 // when the kernel starts.
 __global__ void ingest_kernel(const float* __restrict__ lo, const float* __restrict__ hi, const int32_t* __restrict__ label,
                               float* __restrict__ l0, float* __restrict__ u0, int32_t* __restrict__ lab, int batch, int n0,
-                              int Cc, int H, int W, int nK, int32_t* __restrict__ flag)
+                              int Cc, int H, int W, int nK, int32_t* __restrict__ flag, float4* __restrict__ pk, int ld)
 {
+    // one destination element per step: (input, column of the internal order); with pk the box is also written in the
+    // packed form of launch_pack_bounds ([side][input][ld] of (0, 0, bound the side takes under a coefficient >= 0, the
+    // other bound), padding columns zero), which then needs no launch of its own
     int bad = 0;
-    const size_t count = (size_t)batch * n0;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
-        const float a = lo[i], b = hi[i];
-        if (!(a <= b) || !isfinite(a) || !isfinite(b)) bad |= 1;
-        size_t d = i;
-        if (Cc > 0) {
-            const size_t bi = i / n0;
-            const int e = (int)(i - bi * n0);
-            const int w = e % W, h = (e / W) % H, c = e / (W * H);
-            d = bi * n0 + ((size_t)h * W + w) * Cc + c;
+    const size_t count = (size_t)batch * ld;
+    for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < count; j += (size_t)gridDim.x * blockDim.x) {
+        const size_t bi = j / ld;
+        const int col = (int)(j - bi * ld);
+        float4 lo4 = make_float4(0.f, 0.f, 0.f, 0.f), up4 = lo4;
+        if (col < n0) {
+            size_t si = bi * n0 + col;
+            if (Cc > 0) {
+                const int c = col % Cc, hw = col / Cc;
+                const int w = hw % W, h = hw / W;
+                si = bi * n0 + ((size_t)c * H + h) * W + w;
+            }
+            const float a = lo[si], b = hi[si];
+            if (!(a <= b) || !isfinite(a) || !isfinite(b)) bad |= 1;
+            l0[bi * n0 + col] = a;
+            u0[bi * n0 + col] = b;
+            lo4.z = a; lo4.w = b;
+            up4.z = b; up4.w = a;
         }
-        l0[d] = a;
-        u0[d] = b;
+        if (pk) {
+            pk[j] = lo4;
+            pk[count + j] = up4;
+        }
     }
     if (label)
         for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)batch; i += (size_t)gridDim.x * blockDim.x) {
@@ -359,11 +372,14 @@ int check_inputs(const float* lo, const float* hi, size_t count, const int32_t* 
 }
 
 void ingest_enqueue(const float* lo, const float* hi, const int32_t* label, float* l0, float* u0, int32_t* lab, int batch, int n0,
-                    int Cc, int H, int W, int nK, int32_t* flag, int32_t* pinned_host_flag, hipStream_t s)
+                    int Cc, int H, int W, int nK, int32_t* flag, int32_t* pinned_host_flag, hipStream_t s, float* pk, int ld)
 {
-    const size_t count = (size_t)batch * n0;
+    if (!pk) ld = n0;
+    DPC_REQUIRE(ld >= n0 && ((uintptr_t)pk % 16) == 0, DPC_EINVAL, "ingest: bad arguments");
+    const size_t count = (size_t)batch * ld;
     const unsigned blocks = (unsigned)std::min<size_t>(1024, ceil_div((int64_t)std::max<size_t>(count, 1), 256));
-    hipLaunchKernelGGL(ingest_kernel, dim3(blocks), dim3(256), 0, s, lo, hi, label, l0, u0, lab, batch, n0, Cc, H, W, nK, flag);
+    hipLaunchKernelGGL(ingest_kernel, dim3(blocks), dim3(256), 0, s, lo, hi, label, l0, u0, lab, batch, n0, Cc, H, W, nK, flag,
+                       reinterpret_cast<float4*>(pk), ld);
     DPC_HIP(hipGetLastError());
     DPC_HIP(hipMemcpyAsync(pinned_host_flag, flag, sizeof(int32_t), hipMemcpyDeviceToHost, s));
 }

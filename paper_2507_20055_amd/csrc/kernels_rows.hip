@@ -725,6 +725,92 @@ __global__ __launch_bounds__(kThreads) void finalize_bounds_kernel(
     (side == 0 ? out_l : out_u)[(size_t)b * R + r] = (float)v;
 }
 
+// The constant + the partial sums of row m, slots added in index order (finalize_bounds_kernel's order).
+__device__ __forceinline__ float folded_bound(const double* __restrict__ cst, const float* __restrict__ part, int nslots,
+                                              long long part_stride, long long m)
+{
+    double v = cst[m];
+    int t = 0;
+    for (; t + 8 <= nslots; t += 8) {
+        float p[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p[k] = part[(size_t)(t + k) * part_stride + m];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v += (double)p[k];
+    }
+    for (; t < nslots; ++t) v += (double)part[(size_t)t * part_stride + m];
+    return (float)v;
+}
+
+// finalize_bounds_kernel for an affine layer (both sides, R = n rows per group) and relax_params_pack_kernel for the ReLU
+// layer above it in one launch, value by value the same arithmetic: one thread per (input, padded column).
+__global__ __launch_bounds__(kThreads) void finalize_relax_pack_kernel(
+    const double* __restrict__ cst, const float* __restrict__ part, int nslots, long long part_stride,
+    float* __restrict__ out_l, float* __restrict__ out_u, float* __restrict__ lambda, float* __restrict__ mu,
+    float* __restrict__ nu, float* __restrict__ rl, float* __restrict__ ru, const float* __restrict__ bias, int batch, int n,
+    int ld, float4* __restrict__ pk, float2* __restrict__ pk2)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;       // over [batch][ld]
+    if (i >= (int64_t)batch * ld) return;
+    const int col = (int)(i % ld), b = (int)(i / ld);
+    float4 lo4 = make_float4(0.f, 0.f, 0.f, 0.f), up4 = lo4;
+    float2 o2 = make_float2(0.f, 0.f);
+    if (col < n) {
+        const size_t k = (size_t)b * n + col;
+        const float lv = folded_bound(cst, part, nslots, part_stride, (long long)b * n + col);
+        const float uv = folded_bound(cst, part, nslots, part_stride, ((long long)batch + b) * n + col);
+        out_l[k] = lv;
+        out_u[k] = uv;
+        const float la = (lv + uv >= 0.0f) ? 1.0f : 0.0f;
+        float m, v;
+        if (lv >= 0.0f) { m = 1.0f; v = 0.0f; }
+        else if (uv <= 0.0f) { m = 0.0f; v = 0.0f; }
+        else {
+            const float d = uv - lv;
+            m = uv / d;
+            v = -(uv * lv) / d;
+        }
+        lambda[k] = la;
+        mu[k] = m;
+        nu[k] = v;
+        rl[k] = lv >= 0.0f ? lv : 0.0f;
+        ru[k] = uv >= 0.0f ? uv : 0.0f;
+        const float bj = bias ? bias[col] : 0.0f;
+        lo4 = make_float4(la, m, 0.0f + la * bj, v + m * bj);
+        up4 = make_float4(m, la, v + m * bj, 0.0f + la * bj);
+        const float av = fabsf(v);
+        o2 = make_float2(m, la != 0.0f ? -av : av);
+    }
+    if (pk) {
+        pk[i] = lo4;
+        pk[(size_t)batch * ld + i] = up4;
+    }
+    if (pk2) pk2[i] = o2;
+}
+
+// finalize_bounds_kernel and split_final_kernel for the merged last pass in one launch: one wavefront per input, lane r
+// takes row r of the input's two groups (Rs <= 64 rows each).
+__global__ __launch_bounds__(64) void finalize_split_final_kernel(
+    const double* __restrict__ cst, const float* __restrict__ part, int nslots, long long part_stride, int batch, int nK, int Rs,
+    float* __restrict__ l, float* __restrict__ u, float* __restrict__ margin, int32_t* __restrict__ verdict)
+{
+    const int b = blockIdx.x, r = threadIdx.x;
+    const int Rm = 2 * nK - 1;
+    bool fails = false;
+    if (r < Rm) {
+        const float lv = folded_bound(cst, part, nslots, part_stride, (long long)b * Rs + r);
+        if (r < nK) {
+            l[(size_t)b * nK + r] = lv;
+            u[(size_t)b * nK + r] = folded_bound(cst, part, nslots, part_stride, ((long long)batch + b) * Rs + r);
+        } else {
+            margin[(size_t)b * (nK - 1) + (r - nK)] = lv;
+            fails = !(lv > 0.0f);
+        }
+    }
+    const unsigned long long any = __ballot(fails);
+    if (r == 0) verdict[b] = any == 0ull ? 1 : 0;
+}
+
 __global__ __launch_bounds__(kThreads) void margin_rows_kernel(
     const float* __restrict__ W, int ldw, const float* __restrict__ bias, const int32_t* __restrict__ label,
     int nK, int n, float* __restrict__ C, int ldc, double* __restrict__ cst)
@@ -1178,6 +1264,33 @@ void launch_finalize_bounds(const double* cst, const float* part, int nslots, in
     hipLaunchKernelGGL(finalize_bounds_kernel, dim3((unsigned)ceil_div(M, kThreads)), dim3(kThreads), 0, s, cst, part, nslots,
                        (long long)part_stride, batch, R, (long long)M, out_l, out_u);
     DPC_HIP(hipGetLastError());
+}
+
+void launch_finalize_relax_pack(const double* cst, const float* part, int nslots, int64_t part_stride, float* out_l, float* out_u,
+                                float* lambda, float* mu, float* nu, float* rl, float* ru, const float* bias, int batch, int n, int ld,
+                                float* pk, float* pk2, hipStream_t s)
+{
+    DPC_REQUIRE(cst && out_l && out_u && lambda && mu && nu && rl && ru && ld >= n && ((uintptr_t)pk % 16) == 0 && ((uintptr_t)pk2 % 8) == 0 &&
+                    (nslots == 0 || (part && part_stride >= (int64_t)2 * batch * n)), DPC_EINVAL, "finalize_relax_pack: bad arguments");
+    const int64_t tot = (int64_t)batch * ld;
+    if (tot <= 0) return;
+    hipLaunchKernelGGL(finalize_relax_pack_kernel, dim3((unsigned)ceil_div(tot, kThreads)), dim3(kThreads), 0, s, cst, part, nslots,
+                       (long long)part_stride, out_l, out_u, lambda, mu, nu, rl, ru, bias, batch, n, ld, reinterpret_cast<float4*>(pk),
+                       reinterpret_cast<float2*>(pk2));
+    DPC_HIP(hipGetLastError());
+}
+
+bool launch_finalize_split_final(const double* cst, const float* part, int nslots, int64_t part_stride, int batch, int nK, int Rs, float* l,
+                                 float* u, float* margin, int32_t* verdict, hipStream_t s)
+{
+    if (Rs > 64 || Rs < 2 * nK - 1 || nK < 2) return false;
+    DPC_REQUIRE(cst && l && u && margin && verdict && (nslots == 0 || (part && part_stride >= (int64_t)2 * batch * Rs)), DPC_EINVAL,
+                "finalize_split_final: bad arguments");
+    if (batch == 0) return true;
+    hipLaunchKernelGGL(finalize_split_final_kernel, dim3((unsigned)batch), dim3(64), 0, s, cst, part, nslots, (long long)part_stride, batch,
+                       nK, Rs, l, u, margin, verdict);
+    DPC_HIP(hipGetLastError());
+    return true;
 }
 
 void launch_margin_rows(const float* W, int ldw, const float* bias, const int32_t* label, int batch,
