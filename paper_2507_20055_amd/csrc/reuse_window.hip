@@ -49,10 +49,11 @@ struct RwArgs {
     int fh, fw, ld_o, S_o, P_o, frame_image;   // output frame: window of the output position (origin ho*S_o - P_o), or the image
     float* E;                           // [side][batch * npos * M][ld_o]
     long long side_stride;              // floats between the two sides of E
-    long long z0;                       // first output position (input-major) of this launch
     int CK;                             // channels per staged chunk (divides Ci, multiple of 8)
     int n_xt;                           // 32-float blocks per frame row
     int flat;                           // tiles over the flattened frame instead of over frame rows
+    int gx, gy;                         // column tiles and row blocks per output position
+    long long total;                    // workgroups with work: gx * gy * output positions
 };
 
 template <int MT>
@@ -61,12 +62,21 @@ __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
     extern __shared__ float4 lds4[];
     float* sA = reinterpret_cast<float*>(lds4);                    // [32*MT][2*CK + 4]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kq = lane >> 5;
-    const long long z = a.z0 + blockIdx.z;
+    // Workgroup -> (row block, column tile, output position), row block fastest.  Workgroups are dealt to the 8 XCDs round
+    // robin, so consecutive indices ON ONE XCD (blockIdx.x = xcd + 8 * slot) take consecutive work items: the row blocks of one
+    // tile, then the neighbouring tiles and positions, which read the same rows of Rr, share that XCD's L2.
+    const long long per = (a.total + 7) >> 3;
+    const long long item = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    if (item >= a.total) return;
+    const int by = (int)(item % a.gy);
+    const long long rest = item / a.gy;
+    const int bx = (int)(rest % a.gx);
+    const long long z = rest / a.gx;
     const int b = (int)(z / a.npos), pos = (int)(z - (long long)b * a.npos);
     const int ho = pos / a.Wo, wo = pos - ho * a.Wo;
     const int elems_o = a.fh * a.fw * a.C0, elems_i = a.ph_i * a.pw_i * a.C0;
     const int astride = 2 * a.CK + 4;
-    const int mbase = blockIdx.y * 32 * MT;
+    const int mbase = by * 32 * MT;
 
     // The workgroup's tile, one 32-column block per wavefront.
     // Row tiles: block xt of four consecutive frame rows, so the four wavefronts meet the same taps (a tap's window covers
@@ -78,7 +88,7 @@ __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
     int qy, qx, qc, ncol, ty_lo, ty_hi, tx_lo, tx_hi;
     bool is_const, in_frame, wg_const, stores;
     if (a.flat) {
-        const int col0 = blockIdx.x * 128;
+        const int col0 = bx * 128;
         ncol = col0 + wave * 32 + l32;
         is_const = ncol == elems_o;
         in_frame = ncol < elems_o;
@@ -93,7 +103,7 @@ __global__ __launch_bounds__(kRwThreads, 2) void reuse_window_kernel(RwArgs a)
         tx_hi = rowlen - 1;
         stores = ncol < a.ld_o;
     } else {
-        const int xt = blockIdx.x % a.n_xt, rg = blockIdx.x / a.n_xt;
+        const int xt = bx % a.n_xt, rg = bx / a.n_xt;
         const int xcol = xt * 32 + l32;
         qy = rg * 4 + wave;                                        // frame row of this wavefront (fh: the constant's row)
         const bool const_row = qy == a.fh;
@@ -256,14 +266,15 @@ double launch_reuse_window(const float* A0, const float* A1, int ld_split, int M
         ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kMaxLds);
         hipLaunchKernelGGL(kern, grid, dim3(kRwThreads), lds, s, a);
     };
-    for (int64_t z0 = 0; z0 < nz; z0 += 65535) {
-        a.z0 = z0;
-        const dim3 grid(gx, gy, (unsigned)std::min<int64_t>(65535, nz - z0));
-        if (MT == 4) go(&reuse_window_kernel<4>, grid);
-        else if (MT == 2) go(&reuse_window_kernel<2>, grid);
-        else go(&reuse_window_kernel<1>, grid);
-        DPC_HIP(hipGetLastError());
-    }
+    a.gx = (int)gx;
+    a.gy = (int)gy;
+    a.total = (int64_t)gx * gy * nz;
+    DPC_REQUIRE(a.total + 8 < ((int64_t)1 << 31), DPC_EINVAL, "reuse_window: too many workgroups");
+    const dim3 grid((unsigned)(ceil_div(a.total, 8) * 8));
+    if (MT == 4) go(&reuse_window_kernel<4>, grid);
+    else if (MT == 2) go(&reuse_window_kernel<2>, grid);
+    else go(&reuse_window_kernel<1>, grid);
+    DPC_HIP(hipGetLastError());
     // multiply-adds of the taps that exist, over whole windows (what the step computes; skipped lanes do not count)
     double taps = 0.0;
     for (int ho = 0; ho < g.Ho; ++ho)
