@@ -1267,6 +1267,12 @@ void certify_impl(dpc_network* net, int32_t batch, const float* lo, const float*
             if (!reuse_cert || !tune(TK_REUSE_WINDOW) || k < 3 || k > nl || !net->in_spatial) return false;
             const Layer& Lk = *net->layers[k - 1];
             const Layer& Lb = *net->layers[k - 3];
+            // the rows it reads: windows of the convolution layer two below, else rows over the image; 32-bit offsets inside
+            // one input's block of rows and inside the workgroup index bound what the kernel takes
+            const int64_t ld_in = rwin[k - 2].ld ? rwin[k - 2].ld : ldE;
+            const int64_t positions = Lk.kind == CONV ? (int64_t)Lk.g.Ho * Lk.g.Wo : 1;
+            const int64_t rows_m = Lk.kind == CONV ? Lk.g.Co : Lk.n_out;
+            if ((2 * (int64_t)Lk.n_in + 1) * ld_in * 4 >= ((int64_t)1 << 31) || (int64_t)B * positions * rows_m >= ((int64_t)1 << 28)) return false;
             if (Lk.kind == CONV) return reuse_window_covers(Lk.g.Ci);
             return Lk.kind == AFFINE && Lb.kind == CONV && rwin[k - 2].ld != 0 && reuse_window_covers(Lb.g.Co) && !(k == nl && label);
         };
