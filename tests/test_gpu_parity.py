@@ -547,7 +547,7 @@ def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implici
         b.dpc_tuning_set("reuse_window_tiles", -1)
 
 
-@pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29])])
+@pytest.mark.parametrize("cfg,idx", [("cfg2", [0, 17, 31]), ("cfg5", [5]), ("cfg3", [4, 29]), ("cfg4", [3])])
 def test_reusecert_full_batch_gpu_sampled_oracle(cfg, idx):
     """ReuseCert at the benchmark's launch configuration (full batch); the oracle on a sample of the inputs."""
     w = wl.make_workload(cfg)
