@@ -218,12 +218,19 @@ def measure(workload, args, steps, warmup, cpu_baseline):
 
             t_relax = timed(lambda: binding.dpc_op_relax_step(C, cst, 2, B, R, n, lam, mu, nu, bias, stream=stream.cuda_stream))
             t_conc = timed(lambda: binding.dpc_op_concretise(C, cst, 2, B, R, n, lo_, hi_, ol, ou, stream=stream.cuda_stream))
+            # what a plain device-to-device copy of the same rows reaches at this size (the runtime's copy kernel; the same
+            # bytes as the ReLU step: every row read once and written once): launch ramp and tail weigh the same on it
+            C2 = torch.empty_like(C)
+            t_copy = timed(lambda: C2.copy_(C))
+            del C2
         out["hbm_passes_standalone"] = {
             "shape": {"rows": M, "columns": n},
             "relax_step": {"achieved": M * n * 8 / t_relax / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": M * n * 8 / t_relax / 1e9 / PEAK_HBM_GBS, "us_per_launch": t_relax * 1e6},
             "concretise": {"achieved": M * n * 4 / t_conc / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": M * n * 4 / t_conc / 1e9 / PEAK_HBM_GBS, "us_per_launch": t_conc * 1e6},
+            "plain_copy_same_rows": {"achieved": M * ld * 8 / t_copy / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                     "frac": M * ld * 8 / t_copy / 1e9 / PEAK_HBM_GBS, "us_per_launch": t_copy * 1e6},
         }
         del C, cst
 
