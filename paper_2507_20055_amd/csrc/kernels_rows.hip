@@ -205,8 +205,8 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
                 for (int t = 0; t < 4; ++t) {
                     const int i4 = base + t * 64 + lane;
                     if (i4 < cw4) {
-                        v[0][t] = SHARED ? in[0][i4] : nt_load4(in[0] + i4);
-                        if (two) v[1][t] = SHARED ? in[1][i4] : nt_load4(in[1] + i4);
+                        v[0][t] = SHARED ? in[0][i4] : in[0][i4];
+                        if (two) v[1][t] = SHARED ? in[1][i4] : in[1][i4];
                     }
                 }
 #pragma unroll
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_kernel(
                             y[e] = live ? x[e] * (pos ? pmv[e] : nmv[e]) : 0.0f;
                             a[h] = live ? fmaf(x[e], pos ? pkv[e] : nkv[e], a[h]) : a[h];
                         }
-                        nt_store4(out[h] + i4, y[0], y[1], y[2], y[3]);
+                        *(out[h] + i4) = make_float4(y[0], y[1], y[2], y[3]);
                     }
                 }
             }
@@ -294,8 +294,8 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
                 for (int t = 0; t < 4; ++t) {
                     const int i4 = base + t * 64 + lane;
                     if (i4 < cw4) {
-                        v[0][t] = SHARED ? in[0][i4] : nt_load4(in[0] + i4);
-                        if (two) v[1][t] = SHARED ? in[1][i4] : nt_load4(in[1] + i4);
+                        v[0][t] = SHARED ? in[0][i4] : in[0][i4];
+                        if (two) v[1][t] = SHARED ? in[1][i4] : in[1][i4];
                     }
                 }
 #pragma unroll
@@ -346,7 +346,11 @@ __global__ __launch_bounds__(kThreads) void concretise_kernel(
 // Pairs of a group are dealt round-robin to the wavefronts of all its workgroups.
 constexpr int kSeg4 = 256;             // float4 per segment of a row (1024 columns)
 
-template <bool SHARED>
+// NT: the rows are read and written with non-temporal accesses.  Measured: better when the rows are larger than the 256 MB
+// Infinity Cache (1 GB of rows: 0.71 against 0.68 of the HBM rate), worse when a following kernel could still find them
+// there (100-270 MB: 0.66-0.72 against 0.72-0.74); the launcher picks by size.  The kernels that walk wide rows in chunks use
+// plain accesses (measured better at both of their shapes), the streaming concretisation non-temporal loads (better at both).
+template <bool SHARED, bool NT>
 __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
     float* __restrict__ C, int ldc, double* __restrict__ cst, int batch, int R, int n,
     const float* __restrict__ lambda, const float* __restrict__ mu, const float* __restrict__ nu,
@@ -381,7 +385,7 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int i4 = base + t * 64 + lane;
-                if (i4 < cw4) v[h][t] = SHARED ? in[i4] : nt_load4(in + i4);
+                if (i4 < cw4) v[h][t] = (SHARED || !NT) ? in[i4] : nt_load4(in + i4);
             }
         }
     };
@@ -410,7 +414,8 @@ __global__ __launch_bounds__(kThreads) void relax_step_stream_kernel(
                     a[h] = live ? fmaf(x[e], pos ? pkv[e] : nkv[e], a[h]) : a[h];
                 }
                 const size_t m = (size_t)sb * R + row_of(p, h);
-                nt_store4(reinterpret_cast<float4*>(C + m * ldc) + i4, y[0], y[1], y[2], y[3]);
+                if constexpr (NT) nt_store4(reinterpret_cast<float4*>(C + m * ldc) + i4, y[0], y[1], y[2], y[3]);
+                else reinterpret_cast<float4*>(C + m * ldc)[i4] = make_float4(y[0], y[1], y[2], y[3]);
             }
         }
         ad[0] += (double)a[0];
@@ -968,8 +973,10 @@ void launch_relax_step(float* C, int ldc, double* cst, int nsides, int batch, in
             hipLaunchKernelGGL(kern, grid_s, dim3(kThreads), lds_s, s, C, ldc, cst, batch, R, n, lambda, mu, nu, bias,
                                shared_src, shared_src ? ld_src : 0, cst_init, rpb);
         };
-        if (shared_src) go(relax_step_stream_kernel<true>);
-        else go(relax_step_stream_kernel<false>);
+        // rows larger than the Infinity Cache stream past the caches
+        const bool nt = (int64_t)nsides * batch * R * ldc * 4 > ((int64_t)384 << 20);
+        if (shared_src) { if (nt) go(relax_step_stream_kernel<true, true>); else go(relax_step_stream_kernel<true, false>); }
+        else { if (nt) go(relax_step_stream_kernel<false, true>); else go(relax_step_stream_kernel<false, false>); }
         DPC_HIP(hipGetLastError());
         return;
     }
