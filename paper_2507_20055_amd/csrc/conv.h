@@ -24,6 +24,8 @@ struct ConvWeights {
     float* core = nullptr;      // [Co][kh][kw][Ci] padded rows: row co has ld_core floats (the layer's own expressions)
     int ld_core = 0;
     float* taps = nullptr;      // [kh][kw][Co][Ci]  (transposed-convolution operand, Ci fastest)
+    float* taps4 = nullptr;     // [kh][kw][Co/4][Ci][4]: the same values with four consecutive output channels innermost (Co % 4 == 0),
+                                // so that a lane of the MFMA kernel fetches the four values it feeds with one 16-byte load
     float* bias_c = nullptr;    // [Co]
     ~ConvWeights();
     ConvWeights() = default;

@@ -260,6 +260,7 @@ ConvWeights::~ConvWeights()
 {
     if (core) (void)hipFree(core);
     if (taps) (void)hipFree(taps);
+    if (taps4) (void)hipFree(taps4);
     if (bias_c) (void)hipFree(bias_c);
 }
 
@@ -282,6 +283,15 @@ void upload_conv_weights(const ConvGeom& g, const float* K, const float* b, Conv
     DPC_HIP(hipMemcpy(out.core, core.data(), core.size() * sizeof(float), hipMemcpyHostToDevice));
     DPC_HIP(hipMemcpy(out.taps, taps.data(), taps.size() * sizeof(float), hipMemcpyHostToDevice));
     DPC_HIP(hipMemcpy(out.bias_c, b, (size_t)g.Co * sizeof(float), hipMemcpyHostToDevice));
+    if (g.Co % 4 == 0) {
+        std::vector<float> t4(taps.size());
+        for (int t = 0; t < g.kh * g.kw; ++t)
+            for (int co = 0; co < g.Co; ++co)
+                for (int ci = 0; ci < g.Ci; ++ci)
+                    t4[((((size_t)t * (g.Co / 4) + co / 4) * g.Ci + ci) << 2) + (co & 3)] = taps[((size_t)t * g.Co + co) * g.Ci + ci];
+        DPC_HIP(hipMalloc(reinterpret_cast<void**>(&out.taps4), t4.size() * sizeof(float)));
+        DPC_HIP(hipMemcpy(out.taps4, t4.data(), t4.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
 }
 
 void launch_relax_step_patch(float* C, int ldc, double* cst, int nsides, int batch, int R, const PatchGeom& pg,

@@ -36,7 +36,7 @@ constexpr int kCtEntries = 256;          // list entries per class per workgroup
 
 struct CtArgs {
     const float* in; long long M; int ld_in; int ih, iw, Co;
-    const float* taps; int Ci, kh, kw, s, off;
+    const float* taps; int Ci, kh, kw, s, off;      // conv_transpose_mfma_kernel: the [kh][kw][Co/4][Ci][4] layout
     float* out; int ld_out; int oh, ow;
     int RB;          // rows per workgroup
     int CC;          // channels of the reduction staged in LDS at a time (divides Co, multiple of 8)
@@ -250,13 +250,14 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
     if (nchunks == 1) { add_consts(true); consts_pending = false; }
 
     // kernel values straight from global memory (the whole kernel is a few hundred KB and is read by every
-    // workgroup, so it lives in L2): lane (kq, l32) needs K[tap][co = 8g+4kq+s][ci = 32n + l32], s = 0..3
+    // workgroup, so it lives in L2): lane (kq, l32) needs K[tap][co = 8g+4kq+s][ci = 32n + l32], s = 0..3, which the
+    // [tap][co / 4][ci][co % 4] layout holds in 16 consecutive bytes
     bool ci_ok[NTN];
     int kvoff[NTN];                                   // byte offset of this lane's kernel column (clamped into range)
 #pragma unroll
     for (int n = 0; n < NTN; ++n) {
         ci_ok[n] = n * 32 + l32 < a.Ci;
-        kvoff[n] = (4 * kq * a.Ci + min(n * 32 + l32, a.Ci - 1)) * 4;
+        kvoff[n] = (kq * a.Ci + min(n * 32 + l32, a.Ci - 1)) * 16;
     }
     const __amdgpu_buffer_rsrc_t kres =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.taps), 0, a.kh * a.kw * a.Co * a.Ci * 4, 0x00020000);
@@ -338,14 +339,13 @@ __global__ __launch_bounds__(kCtThreads) void conv_transpose_mfma_kernel(CtArgs 
                 auto load_b = [&](float (&bb)[4][NTN]) __attribute__((always_inline)) {
                     const int so = lbase + lg * GC * a.Ci * 4;
 #pragma unroll
-                    for (int s = 0; s < 4; ++s)
+                    for (int n = 0; n < NTN; ++n) {
+                        // columns past Ci read a clamped (valid) column: they only feed accumulator columns that
+                        // are never stored, and touching the value here would force a wait right behind the load
+                        const vf4 b4 = __builtin_bit_cast(vf4, __builtin_amdgcn_raw_buffer_load_b128(kres, kvoff[n], so, 0));
 #pragma unroll
-                        for (int n = 0; n < NTN; ++n) {
-                            // columns past Ci read a clamped (valid) column: they only feed accumulator columns that
-                            // are never stored, and touching the value here would force a wait right behind the load
-                            bb[s][n] = __builtin_bit_cast(
-                                float, __builtin_amdgcn_raw_buffer_load_b32(kres, kvoff[n], so + s * a.Ci * 4, 0));
-                        }
+                        for (int s = 0; s < 4; ++s) bb[s][n] = b4[s];
+                    }
                     if (++lg == ngr) {
                         lg = 0;
                         if (++ljx == nkx) { ljx = 0; ++ljy; }
@@ -911,7 +911,8 @@ bool launch_conv_transpose_fast(const float* in, int64_t M, int ld_in, int ih, i
         return true;
     }
 
-    if (g.Ci > 64) return false;
+    if (g.Ci > 64 || !w.taps4) return false;
+    a.taps = w.taps4;
     // at most 16 input channels (and reduction channels in groups of 16): half-width tiles
     const bool half = g.Ci <= 16 && g.Co % 16 == 0 && conv_half_tiles() != 0;
     const int NT = half ? 0 : (g.Ci + 31) / 32;
