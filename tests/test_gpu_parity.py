@@ -513,7 +513,8 @@ def test_reusecert_hand_example_and_errors():
                                              ((3, 8, 8), [(4, 4, 2, 1), (8, 4, 2, 1)], [10, 4]),
                                              ((1, 9, 7), [(4, 3, 1, 0), (6, 3, 2, 1), (8, 2, 1, 0)], [5]),
                                              ((3, 10, 10), [(8, 3, 1, 1), (8, 4, 2, 1), (16, 3, 1, 1)], [12, 4]),
-                                             ((3, 12, 12), [(8, 3, 1, 1), (16, 4, 2, 1), (16, 3, 1, 1)], [10, 4])])
+                                             ((3, 12, 12), [(8, 3, 1, 1), (16, 4, 2, 1), (16, 3, 1, 1)], [10, 4]),
+                                             ((2, 13, 11), [(8, 5, 3, 2), (16, 3, 1, 1)], [7])])
 @pytest.mark.parametrize("window,implicit,ck", [(1, 1, 0), (0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 1, 8), (0, 1, 8), (1, 1, 100), (0, 1, 100), (1, 1, 101), (0, 1, 101)])
 def test_reusecert_through_convolution_layers(shape, convs, fcs, window, implicit, ck):
     """ReuseCert on convolutional networks: the replacement step through a convolution layer is the contraction of its
